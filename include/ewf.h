@@ -1,0 +1,209 @@
+/*
+ * ewf.h -- C ABI of the fused element-wise + reduce library for MI355X (gfx950).
+ *
+ * The library evaluates, in ONE pass over n-d tensors, a directed acyclic graph of scalar
+ * operations (the result of the paper's "Specialize" stage, section 2.2.1: successive
+ * element-wise operations fused so the tensor is traversed once), with the typing rules of
+ * section 2.1.1 (data type, rank and broadcastable pattern belong to a variable's type;
+ * shape and strides do not) and the strided views of section 2.2.1 "Inplace" (transposes
+ * and basic slices are views).  Reductions over chosen axes (sum, max, min, prod, arg-max)
+ * are fused into the same pass.
+ *
+ * Life cycle, following section 2.2 (describe symbolically, compile once, call many times):
+ *   ewf_graph_create -> ewf_input / ewf_scalar / ewf_const / ewf_iota / ewf_apply / ewf_cast /
+ *   ewf_reduce / ewf_output      describe the typed scalar graph            (host only)
+ *   ewf_compile                   type-check, freeze into an executable      (host only)
+ *   ewf_plan                      canonicalise shapes/strides, generate and compile the
+ *                                 gfx950 kernel for this layout class, cache it (no launch)
+ *   ewf_run                       launch on the caller's stream              (asynchronous)
+ *
+ * Conventions
+ *   - Every function returns 0 (EWF_OK) or a negative ewf_status.  No C++ exception crosses
+ *     this boundary.  ewf_last_error() gives a thread-local message for the last failure on
+ *     the calling thread (including the run-time compiler's log), valid until the next call.
+ *   - Value ids are >= 0; a negative return from a graph-building call is an ewf_status.
+ *   - All tensors of one graph have the same rank `ndim` (<= EWF_MAX_DIMS).  A dimension
+ *     flagged broadcastable must have extent 1; an unflagged one must have the full extent
+ *     of the iteration space, otherwise EWF_ESHAPE (the pattern is a guarantee, section 2.1.1).
+ *   - Strides are in ELEMENTS, must be >= 0.  Shapes/strides arrays are host memory, read
+ *     during the call only.
+ *   - `ptr` members are DEVICE pointers owned by the caller: inputs, outputs and workspace.
+ *     ewf_run neither allocates, frees nor synchronises (section 3.1.3: freeing device memory
+ *     synchronises, so the hot path must not).
+ *   - An output may alias an input only exactly (same pointer, shape and strides; section
+ *     2.2.1: element-wise operations may overwrite an input); any other overlap between an
+ *     output and an input or another output is EWF_EALIAS.
+ *   - A tensor with a zero extent is legal: success, nothing launched (sum / prod outputs
+ *     of an empty reduction are filled with the identity; max / min / argmax are EWF_ESHAPE).
+ *   - Thread safety: different ewf_exec handles may be used concurrently; one handle must be
+ *     externally synchronised.
+ */
+#ifndef EWF_H
+#define EWF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EWF_MAX_DIMS 8
+
+typedef int32_t ewf_status;
+enum {
+    EWF_OK = 0,
+    EWF_EINVAL = -1,        /* malformed argument or graph                                  */
+    EWF_ETYPE = -2,         /* value/storage type rule violated                             */
+    EWF_ESHAPE = -3,        /* shape does not match the broadcastable pattern               */
+    EWF_EALIAS = -4,        /* output overlaps an input or another output                   */
+    EWF_ECOMPILE = -5,      /* run-time compilation failed (log in ewf_last_error)          */
+    EWF_EHIP = -6,          /* a HIP runtime call failed                                    */
+    EWF_ENOMEM = -7,        /* host allocation failed or workspace too small                */
+    EWF_EUNSUPPORTED = -8   /* graph/layout combination no kernel class covers              */
+};
+
+/* Storage types of tensors; value types of scalar nodes are EWF_F32 or EWF_I32 only
+ * (float16 is a storage format: it is widened to float32 on load, rounded to nearest even
+ * on store; section 3.1.5 of the paper: half-precision storage in the new back-end). */
+typedef enum { EWF_F32 = 0, EWF_F16 = 1, EWF_I32 = 2 } ewf_dtype;
+
+/* Scalar operations.  Arithmetic needs operands of equal value type; there is no implicit
+ * promotion (use ewf_cast).  Comparisons return int32 0/1.  EWF_WHERE(c,a,b) = a if c != 0
+ * (a NaN condition counts as true) else b.  EWF_MAX / EWF_MIN propagate NaN. */
+typedef enum {
+    EWF_ADD = 0, EWF_SUB, EWF_MUL, EWF_DIV, EWF_NEG, EWF_ABS, EWF_EXP, EWF_LOG, EWF_LOG1P,
+    EWF_SQRT, EWF_TANH, EWF_SIGMOID, EWF_MAX, EWF_MIN, EWF_POW, EWF_WHERE, EWF_GT, EWF_GE,
+    EWF_LT, EWF_LE, EWF_EQ, EWF_NE, EWF_EXPM1, EWF_SQR, EWF_RECIP, EWF_OP_COUNT
+} ewf_op;
+
+/* Reductions.  EWF_ARGMAX takes exactly one axis and returns the int32 index of the first
+ * occurrence of the maximum along it. */
+typedef enum { EWF_RSUM = 0, EWF_RMAX, EWF_RMIN, EWF_RPROD, EWF_RARGMAX } ewf_redop;
+
+typedef int32_t ewf_value;
+typedef struct ewf_graph ewf_graph;
+typedef struct ewf_exec ewf_exec;
+
+/* Compile options; zero-initialise for defaults. */
+typedef struct {
+    int32_t math_mode;      /* 0 auto (native-rate transcendentals iff every output is stored
+                               as float16), 1 accurate float32 routines, 2 native-rate        */
+    int32_t force_scalar;   /* 1: never use vector (multi-element) memory accesses           */
+    int32_t force_index64;  /* 1: 64-bit offset arithmetic even when 32 bits suffice         */
+    int32_t block_threads;  /* 0 = library default                                           */
+    int32_t unroll;         /* vectors per thread per tile; 0 = library default              */
+    int32_t max_blocks;     /* cap on the grid; 0 = library default                          */
+    int32_t no_lds_staging; /* 1: never stage permuted operands through LDS                  */
+    int32_t reserved[9];
+} ewf_options;
+
+/* A strided n-d view of caller-owned device memory.  rank is implied by the graph (inputs:
+ * ndim; outputs: ndim minus the axes dropped by reductions, see ewf_reduce). */
+typedef struct {
+    void *ptr;                /* device pointer                                             */
+    const int64_t *shape;     /* host array, extents                                        */
+    const int64_t *strides;   /* host array, element strides                                */
+} ewf_tensor;
+
+/* ---- graph description (host only; section 2.1.1: typed variables, apply nodes, SSA) ---- */
+
+/* Creates an empty graph whose tensors all have rank ndim (0..EWF_MAX_DIMS). */
+ewf_status ewf_graph_create(int32_t ndim, ewf_graph **g);
+void ewf_graph_destroy(ewf_graph *g);
+
+/* Tensor input number k (k counts ewf_input calls).  bcast_flags: ndim bytes, non-zero =
+ * the dimension is broadcastable (extent 1, value repeated along it). */
+ewf_value ewf_input(ewf_graph *g, ewf_dtype storage, const uint8_t *bcast_flags);
+/* Run-time scalar number k (k counts ewf_scalar calls), passed by value to ewf_run so that
+ * changing it needs no recompilation (section 5.3: pass information at run time instead of
+ * hard-coding it in generated code).  dtype: EWF_F32 or EWF_I32. */
+ewf_value ewf_scalar(ewf_graph *g, ewf_dtype dtype);
+/* Literal baked into the kernel; rounded to dtype (EWF_F32 or EWF_I32). */
+ewf_value ewf_const(ewf_graph *g, ewf_dtype dtype, double value);
+/* int32 coordinate along `axis` of the iteration space. */
+ewf_value ewf_iota(ewf_graph *g, int32_t axis);
+/* Applies a scalar operation point-wise. */
+ewf_value ewf_apply(ewf_graph *g, ewf_op op, const ewf_value *args, int32_t nargs);
+/* Explicit conversion: to EWF_F32 (int32 -> float32, nearest even; float32 -> itself),
+ * to EWF_F16 (rounds the value to the nearest float16, result stays a float32 value),
+ * to EWF_I32 (truncation toward zero, saturating, NaN -> 0). */
+ewf_value ewf_cast(ewf_graph *g, ewf_value v, ewf_dtype to);
+/* Folds v over `axes` (numbered in the rank-ndim space).  The result is broadcastable along
+ * the reduced axes and can be combined with full-rank values.  With keep_as_bcast == 0 the
+ * reduced axes are removed from the shape of any output computed from the result alone. */
+ewf_value ewf_reduce(ewf_graph *g, ewf_redop op, ewf_value v, const int32_t *axes, int32_t naxes,
+                     int32_t keep_as_bcast);
+/* Declares output number k (k counts ewf_output calls) stored as `storage`. */
+ewf_status ewf_output(ewf_graph *g, ewf_value v, ewf_dtype storage);
+
+/* ---- compile / plan / run (section 2.2: compile once into a callable) ---- */
+
+/* Type-level compilation.  opts may be NULL.  The graph may be destroyed afterwards. */
+ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **out);
+void ewf_exec_destroy(ewf_exec *e);
+
+/* Shape inference for caller-side allocation: given the input tensors (ptr ignored), writes
+ * rank and extents of output k.  shape_out must hold EWF_MAX_DIMS entries. */
+ewf_status ewf_output_shape(ewf_exec *e, const ewf_tensor *in, int32_t nin, int32_t k,
+                            int32_t *rank_out, int64_t *shape_out);
+
+/* Canonicalises the layout, generates + compiles (hipRTC, gfx950) + caches the kernel for it.
+ * Launches nothing; pointers are inspected for alignment and aliasing only.  Writes the
+ * workspace size ewf_run will need for this layout (0 if none).  Needs a current HIP device. */
+ewf_status ewf_plan(ewf_exec *e, const ewf_tensor *in, int32_t nin, const ewf_tensor *out,
+                    int32_t nout, size_t *workspace_bytes);
+
+/* Zeroes the bookkeeping part of a freshly allocated workspace (asynchronous, on `stream`).
+ * A workspace must be initialised once before its first use; every ewf_run leaves it ready
+ * for the next.  Concurrent runs must not share a workspace. */
+ewf_status ewf_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Launches the planned kernel(s) on hip_stream (a hipStream_t; NULL = the null stream).
+ * scalars: host array, one double per ewf_scalar in creation order (converted to the
+ * scalar's type).  Plans implicitly if this layout has not been planned.
+ * workspace may be NULL when the plan needs none. */
+ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double *scalars,
+                   int32_t nscalars, const ewf_tensor *out, int32_t nout, void *workspace,
+                   size_t workspace_bytes, void *hip_stream);
+
+const char *ewf_last_error(void);
+
+/* ---- introspection, used by host-only tests and tools ---- */
+
+typedef struct {
+    int32_t kernel_class;     /* 0 none (empty), 1 tile element-wise, 2 tile + split reduce,
+                                 3 row-resident reduce                                       */
+    int32_t rank;             /* canonical rank after dropping/merging dimensions            */
+    int64_t extent[EWF_MAX_DIMS];
+    int32_t reduced[EWF_MAX_DIMS];  /* 1 if the canonical dimension is reduced                */
+    int32_t vec;              /* elements per memory access along the innermost dimension    */
+    int32_t index_bits;       /* 32 or 64                                                    */
+    int32_t noperands;        /* inputs then outputs                                         */
+    int32_t block_threads;
+    int32_t grid_blocks;
+    int32_t lds_bytes;
+    int32_t staged_operands;  /* number of operands staged through LDS                       */
+    int64_t tile[EWF_MAX_DIMS];
+} ewf_plan_info;
+
+/* Describes the most recent plan made (or looked up) on this executable. */
+ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info);
+/* Canonical element strides of operand k (inputs first, then outputs) of the last plan. */
+ewf_status ewf_debug_operand_strides(ewf_exec *e, int32_t k, int64_t *strides_out);
+/* Generated HIP source of the last plan (library-owned, valid until the next plan). */
+const char *ewf_debug_source(ewf_exec *e);
+/* Number of kernels compiled so far by this executable (cache misses). */
+int32_t ewf_debug_compile_count(ewf_exec *e);
+
+/* ---- measurement aid ---- */
+
+/* Plain device-to-device copy of nbytes (multiple of 16, 16-byte aligned pointers) with the
+ * library's own dwordx4 grid-stride kernel: the measured ceiling that bandwidth figures and
+ * hardware-counter scale factors are quoted against. */
+ewf_status ewf_copy_bytes(void *dst, const void *src, size_t nbytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EWF_H */

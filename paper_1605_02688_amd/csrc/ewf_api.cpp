@@ -1,0 +1,331 @@
+// C ABI: compile / plan / run, the per-layout plan cache and the introspection calls.
+//
+// ewf_run follows the rule the paper draws from its allocator experience (section 3.1.3:
+// freeing device memory synchronises the device): the hot call allocates nothing on the
+// device, frees nothing and never synchronises; it only patches pointers and scalars into a
+// prepared argument block and enqueues one kernel on the caller's stream (section 3.1.5:
+// computations are asynchronous so the host can run ahead).
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "ewf_internal.h"
+
+namespace ewf {
+const Graph &graph_of(const ewf_graph *g);
+void aux_fill_zero(void *ptr, size_t nbytes, hipStream_t stream);
+void aux_copy(void *dst, const void *src, size_t nbytes, hipStream_t stream);
+}  // namespace ewf
+
+using namespace ewf;
+
+struct ewf_exec { Exec e; };
+
+namespace {
+
+std::string layout_signature(const Graph &g, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout)
+{
+    std::string s;
+    auto put = [&](int64_t v) { s.append(reinterpret_cast<const char *>(&v), 8); };
+    for (int k = 0; k < nin; k++) {
+        for (int d = 0; d < g.ndim; d++) { put(in[k].shape[d]); put(in[k].strides[d]); }
+        put((int64_t)((uintptr_t)in[k].ptr & 15));
+    }
+    for (int k = 0; k < nout; k++) {
+        const Node &v = g.nodes[g.outputs[k].value];
+        int orank = g.ndim - __builtin_popcount(v.dropped);
+        for (int d = 0; d < orank; d++) { put(out[k].shape[d]); put(out[k].strides[d]); }
+        put((int64_t)((uintptr_t)out[k].ptr & 15));
+        // exact aliasing of an input changes nothing in the kernel but must be re-validated
+        int alias = -1;
+        for (int j = 0; j < nin; j++) if (in[j].ptr == out[k].ptr) alias = j;
+        put(alias);
+    }
+    return s;
+}
+
+bool args_present(const Graph &g, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout)
+{
+    if (nin != g.ninputs || nout != (int)g.outputs.size()) return false;
+    if ((nin > 0 && !in) || (nout > 0 && !out)) return false;
+    for (int k = 0; k < nin; k++) if (g.ndim > 0 && (!in[k].shape || !in[k].strides)) return false;
+    for (int k = 0; k < nout; k++) {
+        const Node &v = g.nodes[g.outputs[k].value];
+        int orank = g.ndim - __builtin_popcount(v.dropped);
+        if (orank > 0 && (!out[k].shape || !out[k].strides)) return false;
+    }
+    return true;
+}
+
+ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result)
+{
+    if (!args_present(e.g, in, nin, out, nout)) {
+        set_error("expected %d input and %d output tensors with shape and strides", e.g.ninputs, (int)e.g.outputs.size());
+        return EWF_EINVAL;
+    }
+    std::string sig = layout_signature(e.g, in, nin, out, nout);
+    auto it = e.plans.find(sig);
+    if (it != e.plans.end()) {
+        // pointers may differ from the planning call: aliasing rules depend on them
+        Canon tmp;
+        int64_t full[kMaxDims];
+        ewf_status st = canonicalize(e, it->second->red, in, nin, out, nout, true, tmp, full);
+        if (st != EWF_OK) return st;
+        e.last = it->second.get();
+        *result = e.last;
+        return EWF_OK;
+    }
+
+    std::unique_ptr<Plan> plan(new Plan());
+    int64_t full[kMaxDims];
+    ewf_status st = infer_full_extents(e.g, in, nin, full);
+    if (st != EWF_OK) return st;
+    uint32_t unit = 0;
+    bool empty = false;
+    for (int d = 0; d < e.g.ndim; d++) { if (full[d] == 1) unit |= 1u << d; if (full[d] == 0) empty = true; }
+    plan->red = analyse_reductions(e.g, unit);
+    st = canonicalize(e, plan->red, in, nin, out, nout, true, plan->canon, full);
+    if (st != EWF_OK) return st;
+
+    if (empty) {
+        // nothing to traverse; reductions over an empty axis still define their outputs
+        for (size_t k = 0; k < e.g.outputs.size(); k++) {
+            const Node &v = e.g.nodes[e.g.outputs[k].value];
+            bool out_empty = false;
+            for (int d = 0; d < e.g.ndim; d++)
+                if (!(v.bcast & (1u << d)) && full[d] == 0) out_empty = true;
+            if (!out_empty) {
+                set_error("output %d is a reduction over an empty axis; not supported", (int)k);
+                return EWF_ESHAPE;
+            }
+        }
+        plan->empty = true;
+        plan->kclass = KernelClass::None;
+        e.last = plan.get();
+        *result = e.last;
+        e.plans.emplace(sig, std::move(plan));
+        return EWF_OK;
+    }
+
+    const Canon &c = plan->canon;
+    if (!plan->red.has_reduce) {
+        plan->kclass = KernelClass::Tile;
+    } else {
+        if (!plan->red.unsupported.empty()) { set_error("unsupported reduction structure: %s", plan->red.unsupported.c_str()); return EWF_EUNSUPPORTED; }
+        int nred = 0;
+        for (int d = 0; d < c.rank; d++) nred += c.reduced[d];
+        const bool inner_only = nred == 1 && c.reduced[c.rank - 1];
+        int64_t rows = 1;
+        for (int d = 0; d < c.rank - 1; d++) rows *= c.extent[d];
+        const bool needs_row = plan->red.max_depth > 1 || !plan->red.cross_nodes.empty();
+        bool full_dep_out = false;             // an output that varies along the row and uses a reduction
+        for (const OutputDecl &od : e.g.outputs)
+            if (plan->red.edepth[od.value] >= 1 && (e.g.nodes[od.value].bcast & plan->red.axes) != plan->red.axes) full_dep_out = true;
+        if (!c.reduced[c.rank - 1]) {
+            set_error("unsupported layout: the reduced axes are not the fastest-varying ones in memory");
+            return EWF_EUNSUPPORTED;
+        }
+        if (needs_row || full_dep_out) {
+            if (!inner_only) {
+                set_error("unsupported: chained or cross-group reductions need the reduced axes to form the innermost contiguous dimension");
+                return EWF_EUNSUPPORTED;
+            }
+            if (!plan->red.cross_nodes.empty()) {
+                // the cross-group reduction must fold every remaining group
+                for (int d = 0; d < e.g.ndim; d++) {
+                    bool varies = full[d] > 1 && !(plan->red.axes & (1u << d));
+                    if (varies && !(plan->red.cross_axes & (1u << d))) {
+                        set_error("unsupported: the second reduction must cover every axis the first one keeps");
+                        return EWF_EUNSUPPORTED;
+                    }
+                }
+            }
+            plan->kclass = KernelClass::Row;
+        } else if (inner_only && rows >= 512 && c.extent[c.rank - 1] <= 65536) {
+            plan->kclass = KernelClass::Row;
+        } else {
+            plan->kclass = KernelClass::TileReduce;
+        }
+    }
+
+    st = generate(e, *plan);
+    if (st != EWF_OK) return st;
+    bool cached = false;
+    st = compile_source(plan->source, plan->code, &cached);
+    if (st != EWF_OK) return st;
+    if (!cached) e.compile_count++;
+    e.last = plan.get();
+    *result = e.last;
+    e.plans.emplace(sig, std::move(plan));
+    return EWF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **out)
+{
+    if (!g || !out) { set_error("null argument"); return EWF_EINVAL; }
+    ewf_exec *x = new (std::nothrow) ewf_exec();
+    if (!x) return EWF_ENOMEM;
+    x->e.g = graph_of(g);
+    if (opts) x->e.opts = *opts;
+    ewf_status st = finalize_graph(x->e.g);
+    if (st != EWF_OK) { delete x; return st; }
+    bool all_f16 = true;
+    for (const OutputDecl &o : x->e.g.outputs) if (o.storage != EWF_F16) all_f16 = false;
+    x->e.fast_math = x->e.opts.math_mode == 2 || (x->e.opts.math_mode == 0 && all_f16);
+    *out = x;
+    return EWF_OK;
+}
+
+void ewf_exec_destroy(ewf_exec *e) { delete e; }
+
+ewf_status ewf_output_shape(ewf_exec *e, const ewf_tensor *in, int32_t nin, int32_t k, int32_t *rank_out,
+                            int64_t *shape_out)
+{
+    if (!e || !rank_out || !shape_out) { set_error("null argument"); return EWF_EINVAL; }
+    const Graph &g = e->e.g;
+    if (k < 0 || k >= (int)g.outputs.size()) { set_error("no such output"); return EWF_EINVAL; }
+    int64_t full[kMaxDims];
+    ewf_status st = infer_full_extents(g, in, nin, full);
+    if (st != EWF_OK) return st;
+    const Node &v = g.nodes[g.outputs[k].value];
+    int r = 0;
+    for (int d = 0; d < g.ndim; d++) {
+        if (v.dropped & (1u << d)) continue;
+        shape_out[r++] = (v.bcast & (1u << d)) ? 1 : full[d];
+    }
+    *rank_out = r;
+    return EWF_OK;
+}
+
+ewf_status ewf_plan(ewf_exec *e, const ewf_tensor *in, int32_t nin, const ewf_tensor *out, int32_t nout,
+                    size_t *workspace_bytes)
+{
+    if (!e) { set_error("null executable"); return EWF_EINVAL; }
+    Plan *p = nullptr;
+    ewf_status st = make_plan(e->e, in, nin, out, nout, &p);
+    if (st != EWF_OK) return st;
+    if (workspace_bytes) *workspace_bytes = p->workspace_bytes;
+    return EWF_OK;
+}
+
+ewf_status ewf_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (workspace_bytes == 0) return EWF_OK;
+    if (!workspace || ((uintptr_t)workspace & 15)) { set_error("workspace must be a 16-byte aligned device pointer"); return EWF_EINVAL; }
+    aux_fill_zero(workspace, workspace_bytes, (hipStream_t)hip_stream);
+    hipError_t he = hipGetLastError();
+    if (he != hipSuccess) { set_error("workspace fill: %s", hipGetErrorString(he)); return EWF_EHIP; }
+    return EWF_OK;
+}
+
+ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
+                   const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!e) { set_error("null executable"); return EWF_EINVAL; }
+    Exec &x = e->e;
+    if (nscalars != x.g.nscalars || (nscalars > 0 && !scalars)) {
+        set_error("expected %d run-time scalar(s), got %d", x.g.nscalars, nscalars);
+        return EWF_EINVAL;
+    }
+    Plan *p = nullptr;
+    ewf_status st = make_plan(x, in, nin, out, nout, &p);
+    if (st != EWF_OK) return st;
+    if (p->empty) return EWF_OK;
+    if (p->workspace_bytes > 0) {
+        if (!workspace || workspace_bytes < p->workspace_bytes) {
+            set_error("workspace of %zu bytes needed, %zu given", p->workspace_bytes, workspace ? workspace_bytes : (size_t)0);
+            return EWF_ENOMEM;
+        }
+        if ((uintptr_t)workspace & 15) { set_error("workspace must be 16-byte aligned"); return EWF_EINVAL; }
+    }
+    int dev = -1;
+    if (!p->function || hipGetDevice(&dev) != hipSuccess || dev != p->function_device) {
+        st = load_function(p->code, "ewf_kernel", &p->function, &p->function_device);
+        if (st != EWF_OK) return st;
+    }
+
+    // patch pointers and scalars into a copy of the prepared argument block
+    uint8_t stack_args[1024];
+    std::vector<uint8_t> heap_args;
+    uint8_t *args = stack_args;
+    if (p->args.size() > sizeof stack_args) { heap_args = p->args; args = heap_args.data(); }
+    else memcpy(args, p->args.data(), p->args.size());
+    const ParamLayout &L = p->layout;
+    size_t f = 0;
+    for (int k = 0; k < nin; k++, f++) memcpy(args + L.offsets[f], &in[k].ptr, 8);
+    for (int k = 0; k < nout; k++, f++) memcpy(args + L.offsets[f], &out[k].ptr, 8);
+    void *counters = workspace;
+    void *partials = workspace ? (char *)workspace + p->counter_bytes : nullptr;
+    memcpy(args + L.offsets[f++], &counters, 8);
+    memcpy(args + L.offsets[f++], &partials, 8);
+    for (int k = 0; k < nscalars; k++) {
+        size_t fi = L.fields.size() - (size_t)nscalars + (size_t)k;
+        if (L.fields[fi].type == ParamField::I32) { int32_t v = (int32_t)scalars[k]; memcpy(args + L.offsets[fi], &v, 4); }
+        else { float v = (float)scalars[k]; memcpy(args + L.offsets[fi], &v, 4); }
+    }
+    size_t arg_size = p->args.size();
+    void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
+    hipError_t he = hipModuleLaunchKernel((hipFunction_t)p->function, (unsigned)p->grid, 1, 1, (unsigned)p->block, 1, 1,
+                                          (unsigned)p->lds_bytes, (hipStream_t)hip_stream, nullptr, config);
+    if (he != hipSuccess) { set_error("kernel launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
+    return EWF_OK;
+}
+
+ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info)
+{
+    if (!e || !info) { set_error("null argument"); return EWF_EINVAL; }
+    const Plan *p = e->e.last;
+    if (!p) { set_error("no plan yet"); return EWF_EINVAL; }
+    memset(info, 0, sizeof *info);
+    info->kernel_class = (int)p->kclass;
+    info->rank = p->canon.rank;
+    for (int d = 0; d < p->canon.rank; d++) {
+        info->extent[d] = p->canon.extent[d];
+        info->reduced[d] = p->canon.reduced[d];
+        info->tile[d] = p->tile[d];
+    }
+    info->vec = p->canon.vec;
+    info->index_bits = p->canon.idx64 ? 64 : 32;
+    info->noperands = (int)p->canon.ops.size();
+    info->block_threads = p->block;
+    info->grid_blocks = (int)p->grid;
+    info->lds_bytes = p->lds_bytes;
+    info->staged_operands = p->staged;
+    return EWF_OK;
+}
+
+ewf_status ewf_debug_operand_strides(ewf_exec *e, int32_t k, int64_t *strides_out)
+{
+    if (!e || !strides_out) { set_error("null argument"); return EWF_EINVAL; }
+    const Plan *p = e->e.last;
+    if (!p || k < 0 || k >= (int)p->canon.ops.size()) { set_error("no such operand"); return EWF_EINVAL; }
+    for (int d = 0; d < p->canon.rank; d++) strides_out[d] = p->canon.ops[k].stride[d];
+    return EWF_OK;
+}
+
+const char *ewf_debug_source(ewf_exec *e)
+{
+    if (!e || !e->e.last) return "";
+    return e->e.last->source.c_str();
+}
+
+int32_t ewf_debug_compile_count(ewf_exec *e) { return e ? e->e.compile_count : 0; }
+
+ewf_status ewf_copy_bytes(void *dst, const void *src, size_t nbytes, void *hip_stream)
+{
+    if (nbytes == 0) return EWF_OK;
+    if (!dst || !src || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) {
+        set_error("copy needs 16-byte aligned pointers and a multiple of 16 bytes");
+        return EWF_EINVAL;
+    }
+    aux_copy(dst, src, nbytes, (hipStream_t)hip_stream);
+    hipError_t he = hipGetLastError();
+    if (he != hipSuccess) { set_error("copy launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
+    return EWF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,58 @@
+// Two small ahead-of-time kernels for gfx950: a zero fill for workspace bookkeeping (a fill
+// kernel rather than a memset so that callers may record it into a HIP graph) and the plain
+// dwordx4 grid-stride copy that bandwidth figures are quoted against.
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+namespace ewf {
+
+__global__ void __launch_bounds__(256) k_fill_zero(uint4 *p, size_t n16, unsigned char *tail, size_t ntail)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+    if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+// Each thread moves UNROLL 16-byte pieces per step, all loads issued before the stores.
+template <int UNROLL>
+__global__ void __launch_bounds__(256) k_copy(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16)
+{
+    const size_t per_block = (size_t)256 * UNROLL;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n16; base += (size_t)gridDim.x * per_block) {
+        uint4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; u++) {
+            size_t i = base + (size_t)u * 256 + threadIdx.x;
+            if (i < n16) v[u] = src[i];
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; u++) {
+            size_t i = base + (size_t)u * 256 + threadIdx.x;
+            if (i < n16) dst[i] = v[u];
+        }
+    }
+}
+
+void aux_fill_zero(void *ptr, size_t nbytes, hipStream_t stream)
+{
+    size_t n16 = nbytes / 16, ntail = nbytes % 16;
+    unsigned blocks = (unsigned)((n16 + 255) / 256);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, stream, (uint4 *)ptr, n16,
+                       (unsigned char *)ptr + n16 * 16, ntail);
+}
+
+void aux_copy(void *dst, const void *src, size_t nbytes, hipStream_t stream)
+{
+    size_t n16 = nbytes / 16;
+    size_t per_block = 256 * 4;
+    size_t blocks = (n16 + per_block - 1) / per_block;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_copy<4>, dim3((unsigned)blocks), dim3(256), 0, stream, (uint4 *)dst, (const uint4 *)src, n16);
+}
+
+}  // namespace ewf

@@ -1,0 +1,185 @@
+// Internal data structures of the fused element-wise + reduce library (host side).
+//
+// Pipeline (paper section 2.2 reduced to one fused node): typed scalar graph -> frozen
+// executable -> per-layout plan (canonical dimensions, kernel class, generated source,
+// compiled code object) -> launch.
+#pragma once
+
+#include <cstdint>
+#include <map>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "ewf.h"
+
+namespace ewf {
+
+constexpr int kMaxDims = EWF_MAX_DIMS;
+
+enum class NodeKind : int { Input, Scalar, Const, Iota, Apply, Cast, Reduce };
+
+struct Node {
+    NodeKind kind = NodeKind::Const;
+    int op = 0;                 // Apply: ewf_op; Reduce: ewf_redop; Cast: target ewf_dtype
+    int nargs = 0;
+    int args[3] = {-1, -1, -1};
+    int index = 0;              // Input / Scalar: ordinal; Iota: axis
+    uint32_t axes = 0;          // Reduce: mask of reduced axes
+    bool keep = false;          // Reduce: keep reduced axes in output shapes
+    double cval = 0.0;          // Const
+    // derived by the builder
+    ewf_dtype vtype = EWF_F32;  // value type: EWF_F32 or EWF_I32
+    ewf_dtype storage = EWF_F32;// Input: storage type
+    uint32_t bcast = 0;         // bit d: value does not vary along d
+    uint32_t dropped = 0;       // bit d: d is removed from the shape of an output of this value
+    int depth = 0;              // number of reduce nodes on the longest path from the inputs
+};
+
+struct OutputDecl {
+    int value;
+    ewf_dtype storage;
+};
+
+struct Graph {
+    int ndim = 0;
+    std::vector<Node> nodes;
+    std::vector<OutputDecl> outputs;
+    int ninputs = 0;
+    int nscalars = 0;
+    std::vector<int> input_node;   // node id of input k
+    std::vector<int> scalar_node;  // node id of scalar k
+};
+
+// ---------------------------------------------------------------------------------------
+// Canonical layout
+
+enum class Access : int {
+    Vector,   // unit stride along the innermost canonical dimension, aligned: one wide access
+    Splat,    // stride 0 along the innermost dimension: one element repeated
+    Gather,   // anything else: one access per element
+    Staged    // gathered through an LDS tile filled along the operand's own fastest dimension
+};
+
+struct Operand {
+    bool is_output = false;
+    int index = 0;                    // input / output ordinal
+    ewf_dtype storage = EWF_F32;
+    uint32_t bcast = 0;               // original-rank mask (inputs: declared; outputs: value's)
+    int64_t stride[kMaxDims] = {0};   // canonical, in elements
+    uint64_t addr = 0;
+    Access access = Access::Gather;
+    int alias_of = -1;                // outputs: operand number of the input it aliases exactly
+};
+
+struct Canon {
+    int rank = 0;
+    int64_t extent[kMaxDims] = {0};
+    bool reduced[kMaxDims] = {false};     // member of the reduce axes of the fused reduction
+    int orig_of_axis[kMaxDims];           // for iota: canonical dim that carries original axis d (-1: extent 1)
+    std::vector<Operand> ops;             // inputs then outputs
+    int vec = 1;
+    bool idx64 = false;
+    int64_t total = 0;                    // product of extents
+};
+
+// ---------------------------------------------------------------------------------------
+// Reduce structure of a graph (which kernel class can run it)
+
+enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3 };
+
+struct ReduceInfo {
+    bool has_reduce = false;
+    uint32_t axes = 0;                   // axes of the fused (first-level) reductions
+    std::vector<int> level_nodes;        // reduce nodes over `axes` whose argument varies on them
+    int max_depth = 0;                   // deepest chained level among level_nodes
+    std::vector<int> cross_nodes;        // reductions of per-group values over the kept axes
+    uint32_t cross_axes = 0;
+    std::vector<int> edepth;             // per node: fused reductions on the longest path to it
+    std::string unsupported;             // non-empty: why no single kernel covers the graph
+};
+
+struct KernelSource {
+    std::string source;
+    std::string entry;                   // kernel symbol
+    std::string finish_entry;            // optional second kernel (empty if unused)
+};
+
+struct ParamField {
+    enum Type { Ptr, I64, I32, F32 } type;
+    std::string name;
+    int count;
+};
+
+struct Plan;
+struct Exec;
+
+// Packs kernel arguments with C layout rules for the struct the generator declares.
+struct ParamLayout {
+    std::vector<ParamField> fields;
+    std::vector<size_t> offsets;
+    size_t size = 0;
+    void add(ParamField::Type t, const std::string &name, int count = 1);
+    int find(const std::string &name) const;
+    std::string declare(const std::string &struct_name, bool idx64) const;
+};
+
+struct Plan {
+    KernelClass kclass = KernelClass::None;
+    Canon canon;
+    ReduceInfo red;
+    ParamLayout layout;
+    std::vector<uint8_t> args;           // packed argument block (pointers patched per run)
+    std::string source;
+    std::vector<char> code;              // compiled code object
+    void *function = nullptr;            // hipFunction_t, loaded on first launch
+    int function_device = -1;
+    int block = 256;
+    int64_t grid = 0;
+    int lds_bytes = 0;
+    int staged = 0;
+    int64_t tile[kMaxDims] = {0};
+    size_t workspace_bytes = 0;
+    size_t counter_bytes = 0;
+    // fill kernels for empty reductions etc. are not needed: handled on the host by memset-free
+    // identity stores through a tiny generated kernel
+    bool empty = false;                  // zero-size iteration space: nothing to launch
+};
+
+struct Exec {
+    Graph g;
+    ewf_options opts{};
+    bool fast_math = false;
+    std::map<std::string, std::unique_ptr<Plan>> plans;  // keyed by layout signature
+    Plan *last = nullptr;
+    int compile_count = 0;
+};
+
+// ---- ewf_ir.cpp
+void set_error(const char *fmt, ...);
+const char *get_error();
+ewf_status finalize_graph(Graph &g);     // recompute derived fields, validate outputs
+// unit_mask: axes whose extent is 1 in this call (reducing over them is the identity)
+ReduceInfo analyse_reductions(const Graph &g, uint32_t unit_mask);
+void set_error_str(const std::string &s);
+uint32_t all_mask(int ndim);
+
+// ---- ewf_canon.cpp
+// Builds the canonical layout.  `in`/`out` give shapes and strides in the original rank
+// (outputs: rank minus dropped axes).  Returns EWF_OK or an error (message set).
+ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *in, int nin,
+                        const ewf_tensor *out, int nout, bool check_ptrs, Canon &c,
+                        int64_t full_out[kMaxDims]);
+ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int64_t full[kMaxDims]);
+
+// ---- ewf_codegen.cpp
+ewf_status generate(const Exec &e, Plan &p);
+
+// ---- ewf_rtc.cpp
+// Compiles HIP source for gfx950 (no device needed); identical sources share one code object.
+ewf_status compile_source(const std::string &source, std::vector<char> &code, bool *was_cached);
+// Loads `entry` from a code object on the current device (cached per device and code object).
+ewf_status load_function(const std::vector<char> &code, const std::string &entry, void **function, int *device);
+const char *prelude_source();
+
+}  // namespace ewf

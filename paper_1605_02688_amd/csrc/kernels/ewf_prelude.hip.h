@@ -1,0 +1,230 @@
+// Device-side helpers shared by every generated kernel (gfx950, wave64).
+//
+// This text is compiled at run time, in front of the per-expression code the generator
+// emits.  It holds: wide aligned memory accesses, storage <-> value conversions, the scalar
+// operations in an accurate float32 flavour and a native-rate flavour, and the wavefront /
+// workgroup reduction used by the fused reduce kernels (cross-lane DPP inside a row of 16
+// lanes, lane permutes across rows, LDS across wavefronts).
+#ifndef EWF_PRELUDE_H
+#define EWF_PRELUDE_H
+
+typedef _Float16 ewf_half;
+typedef unsigned int ewf_u32;
+
+#define EWF_DEV __device__ __forceinline__
+
+// ------------------------------------------------------------------ wide memory accesses
+
+template <int B> struct ewf_align { static constexpr int value = B >= 16 ? 16 : B; };
+
+template <typename T, int N>
+struct alignas(ewf_align<N * (int)sizeof(T)>::value) ewf_vec {
+    T e[N];
+};
+
+// One aligned access of N elements (N * sizeof(T) bytes, in 16-byte pieces when larger).
+template <typename T, int N>
+EWF_DEV ewf_vec<T, N> ewf_ld(const T *p)
+{
+    return *reinterpret_cast<const ewf_vec<T, N> *>(p);
+}
+
+template <typename T, int N>
+EWF_DEV void ewf_st(T *p, const ewf_vec<T, N> &v)
+{
+    *reinterpret_cast<ewf_vec<T, N> *>(p) = v;
+}
+
+// ------------------------------------------------------------------ storage <-> value
+
+EWF_DEV float ewf_in(float x) { return x; }
+EWF_DEV float ewf_in(ewf_half x) { return (float)x; }
+EWF_DEV int ewf_in(int x) { return x; }
+
+EWF_DEV float ewf_out_f32(float x) { return x; }
+EWF_DEV ewf_half ewf_out_f16(float x) { return (ewf_half)x; }   // round to nearest even
+EWF_DEV int ewf_out_i32(int x) { return x; }
+
+EWF_DEV float ewf_round_f16(float x) { return (float)(ewf_half)x; }
+EWF_DEV int ewf_f2i(float x)
+{
+    // truncation toward zero, saturating, NaN -> 0
+    if (!(x == x)) return 0;
+    if (x >= 2147483648.0f) return 2147483647;
+    if (x <= -2147483648.0f) return (-2147483647 - 1);
+    return (int)x;
+}
+
+EWF_DEV float ewf_bits_f32(ewf_u32 b) { return __uint_as_float(b); }
+
+// ------------------------------------------------------------------ scalar operations
+
+// max / min propagate NaN from either operand
+EWF_DEV float ewf_max(float a, float b) { return (a > b || a != a) ? a : b; }
+EWF_DEV float ewf_min(float a, float b) { return (a < b || a != a) ? a : b; }
+EWF_DEV int ewf_max(int a, int b) { return a > b ? a : b; }
+EWF_DEV int ewf_min(int a, int b) { return a < b ? a : b; }
+EWF_DEV float ewf_abs(float a) { return fabsf(a); }
+EWF_DEV int ewf_abs(int a) { return a < 0 ? (int)(0u - (ewf_u32)a) : a; }
+EWF_DEV int ewf_addi(int a, int b) { return (int)((ewf_u32)a + (ewf_u32)b); }
+EWF_DEV int ewf_subi(int a, int b) { return (int)((ewf_u32)a - (ewf_u32)b); }
+EWF_DEV int ewf_muli(int a, int b) { return (int)((ewf_u32)a * (ewf_u32)b); }
+EWF_DEV int ewf_negi(int a) { return (int)(0u - (ewf_u32)a); }
+
+// where(c, a, b): a when c != 0; a NaN condition is "not equal to zero"
+EWF_DEV bool ewf_truth(float c) { return c != 0.0f; }
+EWF_DEV bool ewf_truth(int c) { return c != 0; }
+
+// accurate float32 flavour (library routines, about one unit in the last place)
+struct ewf_acc {
+    static EWF_DEV float exp(float x) { return expf(x); }
+    static EWF_DEV float log(float x) { return logf(x); }
+    static EWF_DEV float log1p(float x) { return log1pf(x); }
+    static EWF_DEV float expm1(float x) { return expm1f(x); }
+    static EWF_DEV float sqrt(float x) { return sqrtf(x); }
+    static EWF_DEV float tanh(float x) { return tanhf(x); }
+    static EWF_DEV float sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
+    static EWF_DEV float pow(float x, float y) { return powf(x, y); }
+    static EWF_DEV float div(float x, float y) { return x / y; }
+    static EWF_DEV float recip(float x) { return 1.0f / x; }
+};
+
+// native-rate flavour: hardware exp2 / log2 / rcp / sqrt with minimal fix-ups.  Relative
+// error is a few float32 units for moderate arguments; meant for float16-stored results.
+struct ewf_fast {
+    static EWF_DEV float exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
+    static EWF_DEV float log(float x) { return __builtin_amdgcn_logf(x) * 0.69314718055994530942f; }
+    static EWF_DEV float recip(float x) { return __builtin_amdgcn_rcpf(x); }
+    static EWF_DEV float log1p(float x)
+    {
+        // log(u) * x / (u - 1) with u = fl(1 + x) cancels the rounding of 1 + x
+        float u = 1.0f + x;
+        float d = u - 1.0f;
+        float l = log(u);
+        return (d == 0.0f) ? x : l * (x * recip(d));
+    }
+    static EWF_DEV float expm1(float x)
+    {
+        float e = exp(x);
+        return (fabsf(x) < 0.25f) ? x * (1.0f + x * (0.5f + x * (0.16666667f + x * (0.041666668f + x * 0.0083333338f))))
+                                   : e - 1.0f;
+    }
+    static EWF_DEV float sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+    static EWF_DEV float sigmoid(float x) { return recip(1.0f + exp(-x)); }
+    static EWF_DEV float tanh(float x)
+    {
+        float a = fminf(fabsf(x), 15.0f);
+        float e = exp(-2.0f * a);
+        float t = (1.0f - e) * recip(1.0f + e);
+        t = (a < 0.03125f) ? a * (1.0f - a * a * 0.33333334f) : t;
+        return copysignf(t, x);
+    }
+    static EWF_DEV float pow(float x, float y)
+    {
+        // positive bases only get the fast path; everything else the library routine
+        if (x > 0.0f) return __builtin_amdgcn_exp2f(y * __builtin_amdgcn_logf(x));
+        return powf(x, y);
+    }
+    static EWF_DEV float div(float x, float y) { return x * recip(y); }
+};
+
+// ------------------------------------------------------------------ reductions
+
+// Moves every 32-bit word of v through a DPP lane pattern.
+template <int CTRL, typename T>
+EWF_DEV T ewf_dpp(const T &v)
+{
+    static_assert(sizeof(T) % 4 == 0, "accumulator must be made of 32-bit words");
+    T r;
+    const int *src = reinterpret_cast<const int *>(&v);
+    int *dst = reinterpret_cast<int *>(&r);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) / 4); i++)
+        dst[i] = __builtin_amdgcn_update_dpp(src[i], src[i], CTRL, 0xf, 0xf, false);
+    return r;
+}
+
+template <typename T>
+EWF_DEV T ewf_lane_xor(const T &v, int mask)
+{
+    T r;
+    const int *src = reinterpret_cast<const int *>(&v);
+    int *dst = reinterpret_cast<int *>(&r);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) / 4); i++) dst[i] = __shfl_xor(src[i], mask, 64);
+    return r;
+}
+
+// All 64 lanes end with the combination of all 64 inputs.  The butterfly combines the same
+// pairs on both partners, so with a commutative `op` every lane holds identical bits.
+template <typename T, typename F>
+EWF_DEV T ewf_wave_reduce(T v, F op)
+{
+    v = op(v, ewf_dpp<0xB1>(v));    // quad_perm [1,0,3,2]   : lane ^ 1
+    v = op(v, ewf_dpp<0x4E>(v));    // quad_perm [2,3,0,1]   : lane ^ 2
+    v = op(v, ewf_dpp<0x141>(v));   // row_half_mirror       : quads 0<->1, 2<->3
+    v = op(v, ewf_dpp<0x140>(v));   // row_mirror            : half rows
+    v = op(v, ewf_lane_xor(v, 16)); // rows 0<->1, 2<->3
+    v = op(v, ewf_lane_xor(v, 32)); // row pairs
+    return v;
+}
+
+// Workgroup reduction: wave butterflies, then the per-wave results are combined in wave
+// order by every thread from LDS.  `smem` must hold NWAVES elements of T and may be reused
+// after the call returns.
+template <int NWAVES, typename T, typename F>
+EWF_DEV T ewf_block_reduce(T v, F op, T *smem, int tid)
+{
+    v = ewf_wave_reduce(v, op);
+    if (NWAVES == 1) return v;
+    if ((tid & 63) == 0) smem[tid >> 6] = v;
+    __syncthreads();
+    T r = smem[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; w++) r = op(r, smem[w]);
+    __syncthreads();
+    return r;
+}
+
+// Agent-scope coherent accesses for partial results exchanged between workgroups
+EWF_DEV int ewf_ld_coherent(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+EWF_DEV void ewf_st_coherent(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+template <typename T>
+EWF_DEV T ewf_ld_partial(const T *p)
+{
+    T r;
+    const int *src = reinterpret_cast<const int *>(p);
+    int *dst = reinterpret_cast<int *>(&r);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) / 4); i++) dst[i] = ewf_ld_coherent(src + i);
+    return r;
+}
+
+template <typename T>
+EWF_DEV void ewf_st_partial(T *p, const T &v)
+{
+    const int *src = reinterpret_cast<const int *>(&v);
+    int *dst = reinterpret_cast<int *>(p);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) / 4); i++) ewf_st_coherent(dst + i, src[i]);
+}
+
+// Takes a ticket on `counter`; true in every thread of the workgroup that arrives last of
+// `expected`.  Publishes this workgroup's earlier global writes before the ticket and makes
+// the other workgroups' writes visible after it.
+EWF_DEV bool ewf_last_arrival(int *counter, int expected, int *flag_lds, int tid)
+{
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        int t = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *flag_lds = (t == expected - 1);
+    }
+    __syncthreads();
+    bool last = (*flag_lds != 0);
+    if (last) __threadfence();
+    return last;
+}
+
+#endif  // EWF_PRELUDE_H

@@ -1,0 +1,40 @@
+"""GPU parity of the five workloads against the oracle, at sizes the oracle finishes in
+seconds that still span several tiles and a ragged tail."""
+import pytest
+
+from workloads import configs as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import tests.harness as h
+    return h
+
+
+CASES = {
+    "c1_full": lambda: wl.c1_affine_tanh(),
+    "c1_ragged": lambda: wl.c1_affine_tanh(rows=333, cols=77),
+    "c1_const_a": lambda: wl.c1_affine_tanh(rows=130, cols=256, a_form="const"),
+    "c1_tensor_a": lambda: wl.c1_affine_tanh(rows=130, cols=256, a_form="tensor"),
+    "c2_full": lambda: wl.c2_lstm_cell(),
+    "c2_ragged": lambda: wl.c2_lstm_cell(batch=7, hidden=250),
+    "c3_rows64": lambda: wl.c3_softmax_xent(rows=64, vocab=10000),
+    "c3_ragged": lambda: wl.c3_softmax_xent(rows=37, vocab=1003),
+    "c3_short_rows": lambda: wl.c3_softmax_xent(rows=300, vocab=40),
+    "c4_small": lambda: wl.c4_bias_relu_chansum(n=4, c=64, h=112, w=112),
+    "c4_ragged": lambda: wl.c4_bias_relu_chansum(n=3, c=5, h=13, w=17),
+    "c5a_small": lambda: wl.c5_stress(n=2, c=256, h=56, w=56, reading="A"),
+    "c5b_small": lambda: wl.c5_stress(n=2, c=256, h=56, w=56, reading="B"),
+    "c5a_ragged": lambda: wl.c5_stress(n=2, c=10, h=7, w=9, reading="A"),
+    "c5b_ragged_c": lambda: wl.c5_stress(n=3, c=6, h=5, w=12, reading="B", bcast="c"),
+}
+
+
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_config_parity(case, oracle, H):
+    w = CASES[case]()
+    print(f"[case] {case} {w.name} elements={w.elements}", flush=True)
+    expr, stats = H.check_workload(w, oracle)
+    print(f"[ok] {case} {expr.info()['kernel_class']} {stats}", flush=True)

@@ -77,13 +77,40 @@ def _gen(seed: int) -> torch.Generator:
     return g
 
 
-def _uniform(g, shape, lo, hi, dtype=torch.float32) -> np.ndarray:
+class Placeholder:
+    """Stands in for a host buffer when only the layout is wanted (``data=False``)."""
+
+    def __init__(self, shape, dtype):
+        self.shape = tuple(shape)
+        self.dtype = np.dtype(dtype)
+        self.itemsize = self.dtype.itemsize
+        self.nbytes = int(np.prod(self.shape)) * self.itemsize
+
+
+_DATA = True
+
+
+def _uniform(g, shape, lo, hi, dtype=torch.float32):
+    if not _DATA:
+        return Placeholder(shape, np.float16 if dtype == torch.float16 else np.float32)
     t = torch.rand(tuple(shape), generator=g, dtype=torch.float32) * (hi - lo) + lo
     return t.to(dtype).numpy()
 
 
-def _normal(g, shape, std=1.0) -> np.ndarray:
+def _normal(g, shape, std=1.0):
+    if not _DATA:
+        return Placeholder(shape, np.float32)
     return (torch.randn(tuple(shape), generator=g, dtype=torch.float32) * std).numpy()
+
+
+def layout_only(make, *args, **kw) -> "Workload":
+    """Builds a workload description without drawing its tensors."""
+    global _DATA
+    _DATA = False
+    try:
+        return make(*args, **kw)
+    finally:
+        _DATA = True
 
 
 def _full_view(buf_index: int, shape: Sequence[int]) -> View:
@@ -155,7 +182,8 @@ def c3_softmax_xent(rows: int = 1280, vocab: int = 10000, std: float = 2.0) -> W
     """Row max, arg-max, exp-sum, log-softmax at the target, per-row loss and mean loss."""
     g = _gen(SEED0 + 3)
     logits = _normal(g, (rows, vocab), std)
-    targets = torch.randint(0, vocab, (rows, 1), generator=g, dtype=torch.int32).numpy()
+    targets = (torch.randint(0, vocab, (rows, 1), generator=g, dtype=torch.int32).numpy()
+               if _DATA else Placeholder((rows, 1), np.int32))
     s = GraphSpec(2)
     x = s.input("f32", (False, False))
     t = s.input("i32", (False, True))
