@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused element-wise + reduce path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu]
+
+One "step" is one pass of the whole hot path (canonicalised layout -> one fused kernel:
+element-wise body + reduce epilogue) over one batch of the headline workload: the convnet
+bias+ReLU with per-channel sum on float32 NCHW [128,64,112,112].  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line; the other workloads ride along under
+"per_config" (rotating buffer sets > 512 MB for the small ones so that they measure HBM, not
+the on-chip cache).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def _stats(ms):
+    s = sorted(ms)
+    return {"avg_us": 1e3 * sum(s) / len(s), "median_us": 1e3 * s[len(s) // 2], "min_us": 1e3 * s[0]}
+
+
+class Case:
+    """One workload bound to device memory, with `nsets` rotating buffer sets."""
+
+    def __init__(self, w, nsets=1, **opts):
+        import torch
+        import tests.harness as h
+        from paper_1605_02688_amd import ewf
+        self.w = w
+        self.expr = ewf.Expression(w.spec, **opts)
+        self.sets = []
+        self.stream = torch.cuda.current_stream().cuda_stream
+        for _ in range(nsets):
+            bufs, ins = h.device_inputs(w)
+            outs = h.alloc_outputs(self.expr, w.spec, ins)
+            self.sets.append((bufs, ins, outs))
+        self.ws = h.make_workspace(self.expr, self.sets[0][1], self.sets[0][2])
+        self.info = self.expr.info()
+        self.calls = [self.expr.bind(ins, outs, w.scalars, self.ws, self.stream) for _b, ins, outs in self.sets]
+        self.k = 0
+
+    def launch(self):
+        self.calls[self.k % len(self.calls)].launch()
+        self.k += 1
+
+    def time(self, steps, warmup):
+        """Returns (wall ms for `steps` launches, per-launch event durations in ms)."""
+        import torch
+        for _ in range(warmup):
+            self.launch()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            self.launch()
+            b.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return wall, [a.elapsed_time(b) for a, b in ev]
+
+
+def copy_ceiling(nbytes, steps=20):
+    import torch
+    from paper_1605_02688_amd import ewf
+    src = torch.empty(nbytes // 4, dtype=torch.int32, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(3):
+        ewf.copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, st)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        ewf.copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, st)
+    b.record()
+    torch.cuda.synchronize()
+    return 2 * nbytes * steps / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
+def cpu_baseline(budget_s=15.0):
+    """The oracle, as it stands, on a bounded sample of the headline workload."""
+    from oracle import oracle as orc
+    from workloads import configs as wl
+    cores = min(16, len(os.sched_getaffinity(0)))
+    probe = wl.c4_bias_relu_chansum(n=1)
+    t0 = time.perf_counter()
+    orc.evaluate(probe.spec, wl.host_inputs(probe), nthreads=cores)
+    per_n = time.perf_counter() - t0
+    n = max(1, min(128, int(budget_s / max(per_n, 1e-3))))
+    w = wl.c4_bias_relu_chansum(n=n)
+    ins = wl.host_inputs(w)
+    t0 = time.perf_counter()
+    orc.evaluate(w.spec, ins, nthreads=cores)
+    dt = time.perf_counter() - t0
+    return {"value": w.algorithmic_bytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"same workload at batch {n} of 128 ([{n},64,112,112], {w.elements} elements), "
+                      f"{dt:.2f} s wall on {cores} threads",
+            "gelem_per_s": w.elements / dt / 1e9}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default="", help="time one workload (c1,c2,c3,c4,c5a,c5b) as the headline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from workloads import configs as wl
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+
+    head_name = args.only or "c4"
+    head = Case(wl.FULL_SIZE[head_name]())
+    wall_ms, per = head.time(args.steps, args.warmup)
+    st = _stats(per)
+    w = head.w
+    ms_per_step = wall_ms / args.steps
+    gbps = w.algorithmic_bytes / (ms_per_step * 1e-3) / 1e9
+    kern_gbps = w.algorithmic_bytes / (st["avg_us"] * 1e-6) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(head_name)
+
+    out = {
+        "metric": "fused Elemwise/CAReduce effective HBM GB/s",
+        "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if not head_name.startswith("c5") else "f32 (f16 storage)",
+        "data": "synthetic",
+        "config": {"workload": f"{head_name}: {w.name}", "elements": w.elements,
+                   "algorithmic_bytes": w.algorithmic_bytes, "kernel_class": head.info["kernel_class"],
+                   "block_threads": head.info["block_threads"], "grid_blocks": head.info["grid_blocks"],
+                   "vec": head.info["vec"]},
+        "gelem_per_s": round(w.elements / (ms_per_step * 1e-3) / 1e9, 2),
+        "pct_of_peak": round(100 * gbps / PEAK_HBM_GBPS, 1),
+        "roofline": {"bound": "hbm", "achieved": round(kern_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": round(kern_gbps / PEAK_HBM_GBPS, 4), "traffic": traffic,
+                     "kernel_avg_us": round(st["avg_us"], 2), "kernel_median_us": round(st["median_us"], 2),
+                     "kernel_min_us": round(st["min_us"], 2)},
+    }
+    out["copy_ceiling_gbps"] = round(copy_ceiling(w.algorithmic_bytes // 2 // 16 * 16), 1)
+    del head
+    torch.cuda.empty_cache()
+
+    if not args.no_extra:
+        per_config = {}
+        for name in ("c1", "c2", "c3", "c4", "c5a", "c5b"):
+            if name == head_name:
+                continue
+            wk = wl.FULL_SIZE[name]()
+            nsets = max(1, min(300, int(600e6 // max(1, wk.algorithmic_bytes)) + 1)) if wk.algorithmic_bytes < 300e6 else 1
+            case = Case(wk, nsets=nsets)
+            steps = 200 if wk.algorithmic_bytes < 300e6 else 50
+            _wall, per = case.time(steps, 20)
+            s = _stats(per)
+            wall2, _ = case.time(steps, 0)
+            res = {"elements": wk.elements, "algorithmic_bytes": wk.algorithmic_bytes,
+                   "kernel_class": case.info["kernel_class"], "buffer_sets": nsets,
+                   "mode": "rotating" if nsets > 1 else "single set (exceeds on-chip cache)",
+                   "kernel_avg_us": round(s["avg_us"], 2), "kernel_min_us": round(s["min_us"], 2),
+                   "us_per_step_back_to_back": round(1e3 * wall2 / steps, 2),
+                   "gbps": round(wk.algorithmic_bytes / (s["avg_us"] * 1e-6) / 1e9, 1),
+                   "pct_of_peak": round(100 * wk.algorithmic_bytes / (s["avg_us"] * 1e-6) / 1e9 / PEAK_HBM_GBPS, 1),
+                   "gelem_per_s": round(wk.elements / (s["avg_us"] * 1e-6) / 1e9, 2)}
+            if nsets > 1:
+                warm = Case(wk, nsets=1)
+                _w, perw = warm.time(steps, 20)
+                res["warm_kernel_avg_us"] = round(_stats(perw)["avg_us"], 2)
+                del warm
+            per_config[name] = res
+            del case
+            torch.cuda.empty_cache()
+        out["per_config"] = per_config
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -66,13 +66,23 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
     std::string sig = layout_signature(e.g, in, nin, out, nout);
     auto it = e.plans.find(sig);
     if (it != e.plans.end()) {
-        // pointers may differ from the planning call: aliasing rules depend on them
-        Canon tmp;
-        int64_t full[kMaxDims];
-        ewf_status st = canonicalize(e, it->second->red, in, nin, out, nout, true, tmp, full);
-        if (st != EWF_OK) return st;
-        e.last = it->second.get();
-        *result = e.last;
+        // same shapes, strides and alignment; only the pointers may differ from the planning
+        // call, and the aliasing rules depend on them
+        Plan *p = it->second.get();
+        bool same = true;
+        for (int k = 0; k < nin; k++) same = same && p->raw[k].addr == (uint64_t)(uintptr_t)in[k].ptr;
+        for (int k = 0; k < nout; k++) same = same && p->raw[nin + k].addr == (uint64_t)(uintptr_t)out[k].ptr;
+        if (!same) {
+            for (int k = 0; k < nin; k++) p->raw[k].addr = (uint64_t)(uintptr_t)in[k].ptr;
+            for (int k = 0; k < nout; k++) p->raw[nin + k].addr = (uint64_t)(uintptr_t)out[k].ptr;
+            if (!p->empty)
+                for (int k = 0; k < nin + nout; k++)
+                    if (!p->raw[k].addr) { p->raw[0].addr = ~(uint64_t)0; set_error("operand %d: null pointer", k); return EWF_EINVAL; }
+            ewf_status st = check_aliasing(p->raw, nin, nout);
+            if (st != EWF_OK) { p->raw[0].addr = ~(uint64_t)0; return st; }
+        }
+        e.last = p;
+        *result = p;
         return EWF_OK;
     }
 
@@ -84,7 +94,7 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
     bool empty = false;
     for (int d = 0; d < e.g.ndim; d++) { if (full[d] == 1) unit |= 1u << d; if (full[d] == 0) empty = true; }
     plan->red = analyse_reductions(e.g, unit);
-    st = canonicalize(e, plan->red, in, nin, out, nout, true, plan->canon, full);
+    st = canonicalize(e, plan->red, in, nin, out, nout, true, plan->canon, full, &plan->raw);
     if (st != EWF_OK) return st;
 
     if (empty) {

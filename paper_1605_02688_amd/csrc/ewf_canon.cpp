@@ -45,14 +45,6 @@ ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int
     return EWF_OK;
 }
 
-struct RawView {
-    uint64_t addr;
-    int isz;
-    int64_t ext[kMaxDims];
-    int64_t str[kMaxDims];
-    int rank;
-};
-
 static void byte_range(const RawView &v, uint64_t &lo, uint64_t &hi)
 {
     int64_t span = 0;
@@ -120,9 +112,23 @@ static bool same_view(const RawView &a, const RawView &b)
     return true;
 }
 
+ewf_status check_aliasing(const std::vector<RawView> &raw, int nin, int nout)
+{
+    for (int o = nin; o < nin + nout; o++) {
+        for (int k = 0; k < o; k++) {
+            if (!views_overlap(raw[k], raw[o])) continue;
+            if (k < nin && same_view(raw[k], raw[o])) continue;
+            set_error("%s %d overlaps output %d (only an exact alias of an input is allowed)",
+                      k < nin ? "input" : "output", k < nin ? k : k - nin, o - nin);
+            return EWF_EALIAS;
+        }
+    }
+    return EWF_OK;
+}
+
 ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *in, int nin,
                         const ewf_tensor *out, int nout, bool check_ptrs, Canon &c,
-                        int64_t full[kMaxDims])
+                        int64_t full[kMaxDims], std::vector<RawView> *raw_out)
 {
     const Graph &g = e.g;
     const int nd = g.ndim;
@@ -194,16 +200,10 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
 
     // ---- aliasing (section 2.2.1: an element-wise result may overwrite an input, exactly)
     if (check_ptrs) {
-        for (int o = nin; o < nin + nout; o++) {
-            for (int k = 0; k < o; k++) {
-                if (!views_overlap(raw[k], raw[o])) continue;
-                if (k < nin && same_view(raw[k], raw[o])) { c.ops[o].alias_of = k; continue; }
-                set_error("%s %d overlaps output %d (only an exact alias of an input is allowed)",
-                          k < nin ? "input" : "output", k < nin ? k : k - nin, o - nin);
-                return EWF_EALIAS;
-            }
-        }
+        st = check_aliasing(raw, nin, nout);
+        if (st != EWF_OK) return st;
     }
+    if (raw_out) *raw_out = raw;
 
     // ---- iteration space
     c.total = 1;

@@ -72,6 +72,15 @@ struct Operand {
     int alias_of = -1;                // outputs: operand number of the input it aliases exactly
 };
 
+// An operand as the caller passed it (original rank), for overlap checks.
+struct RawView {
+    uint64_t addr;
+    int isz;
+    int64_t ext[kMaxDims];
+    int64_t str[kMaxDims];
+    int rank;
+};
+
 struct Canon {
     int rank = 0;
     int64_t extent[kMaxDims] = {0};
@@ -130,6 +139,8 @@ struct Plan {
     ReduceInfo red;
     ParamLayout layout;
     std::vector<uint8_t> args;           // packed argument block (pointers patched per run)
+    std::vector<RawView> raw;            // the caller's views at planning time
+    std::vector<char> may_be_null;       // operand may legally have a null pointer (empty)
     std::string source;
     std::vector<char> code;              // compiled code object
     void *function = nullptr;            // hipFunction_t, loaded on first launch
@@ -169,7 +180,9 @@ uint32_t all_mask(int ndim);
 // (outputs: rank minus dropped axes).  Returns EWF_OK or an error (message set).
 ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *in, int nin,
                         const ewf_tensor *out, int nout, bool check_ptrs, Canon &c,
-                        int64_t full_out[kMaxDims]);
+                        int64_t full_out[kMaxDims], std::vector<RawView> *raw_out = nullptr);
+// Overlap rules between outputs and inputs / other outputs, on the caller's views.
+ewf_status check_aliasing(const std::vector<RawView> &raw, int nin, int nout);
 ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int64_t full[kMaxDims]);
 
 // ---- ewf_codegen.cpp

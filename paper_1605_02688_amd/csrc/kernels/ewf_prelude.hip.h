@@ -211,19 +211,31 @@ EWF_DEV void ewf_st_partial(T *p, const T &v)
 }
 
 // Takes a ticket on `counter`; true in every thread of the workgroup that arrives last of
-// `expected`.  Publishes this workgroup's earlier global writes before the ticket and makes
-// the other workgroups' writes visible after it.
+// `expected`.
+//
+// Protocol (thread 0 of each workgroup has just written its partial with ewf_st_partial):
+// partials are written and read only with agent-scope atomic accesses, which are coherent
+// across the chip's L2 slices by themselves, so no cache write-back or invalidate is needed
+// -- a full agent-scope fence would write back and invalidate a whole L2 per call, which
+// costs far more than the kernels' own traffic.  What remains is ordering: the writer waits
+// for its partial stores to complete before taking the ticket (workgroup-scope release:
+// a wait on the memory counters, no cache maintenance), and the reader issues its partial
+// loads only after the ticket value has come back (control dependence + workgroup-scope
+// acquire).  Ordinary element-wise stores of the same kernel are not part of the exchange.
 EWF_DEV bool ewf_last_arrival(int *counter, int expected, int *flag_lds, int tid)
 {
-    __threadfence();
-    __syncthreads();
     if (tid == 0) {
-        int t = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        // stores and the ticket go to different L2 channels: wait until the partial stores
+        // have been acknowledged (stores count in vmcnt on this architecture)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        int t = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         *flag_lds = (t == expected - 1);
     }
     __syncthreads();
     bool last = (*flag_lds != 0);
-    if (last) __threadfence();
+    __syncthreads();
     return last;
 }
 

@@ -321,8 +321,34 @@ class Expression:
         wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
         run(self.handle, inputs, scalars, outputs, wptr, wbytes, stream)
 
+    def bind(self, inputs, outputs, scalars=(), workspace=None, stream: int = 0) -> "BoundCall":
+        """Marshals the arguments once; ``BoundCall.launch()`` is then a single ewf_run call."""
+        return BoundCall(self, inputs, outputs, scalars, workspace, stream)
+
     def info(self) -> dict:
         return debug_plan_info(self.handle)
 
     def source(self) -> str:
         return debug_source(self.handle)
+
+
+class BoundCall:
+    """ewf_run with its argument arrays prepared once (for launch loops: the Python-side
+    marshalling otherwise costs more than a small kernel).  Keeps the tensors alive."""
+
+    def __init__(self, expr: Expression, inputs, outputs, scalars=(), workspace=None, stream: int = 0):
+        self.expr = expr
+        self._tensors = (list(inputs), list(outputs), workspace)
+        self._tin, self._k1 = _marshal(inputs)
+        self._tout, self._k2 = _marshal(outputs)
+        self._sc = (ctypes.c_double * max(1, len(scalars)))(*[float(s) for s in scalars])
+        self._n = (len(inputs), len(scalars), len(outputs))
+        self._ws = ctypes.c_void_p(workspace.data_ptr() if workspace is not None else None)
+        self._wsb = ctypes.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0)
+        self._stream = ctypes.c_void_p(stream or None)
+
+    def launch(self) -> None:
+        st = _lib.ewf_run(self.expr.handle, self._tin, self._n[0], self._sc, self._n[1], self._tout, self._n[2],
+                          self._ws, self._wsb, self._stream)
+        if st < 0:
+            raise EwfError(st, last_error())
