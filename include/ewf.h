@@ -95,7 +95,10 @@ typedef struct {
     int32_t unroll;         /* vectors per thread per tile; 0 = library default              */
     int32_t max_blocks;     /* cap on the grid; 0 = library default                          */
     int32_t no_lds_staging; /* 1: never stage permuted operands through LDS                  */
-    int32_t reserved[9];
+    int32_t streaming;      /* non-temporal accesses for operands touched once: 0 auto (operands
+                               of 32 MiB or more), 1 always, 2 never                          */
+    int32_t tile_elems;     /* elements per tile (per workgroup and loop trip); 0 = default  */
+    int32_t reserved[7];
 } ewf_options;
 
 /* A strided n-d view of caller-owned device memory.  rank is implied by the graph (inputs:
@@ -154,9 +157,10 @@ ewf_status ewf_output_shape(ewf_exec *e, const ewf_tensor *in, int32_t nin, int3
 ewf_status ewf_plan(ewf_exec *e, const ewf_tensor *in, int32_t nin, const ewf_tensor *out,
                     int32_t nout, size_t *workspace_bytes);
 
-/* Zeroes the bookkeeping part of a freshly allocated workspace (asynchronous, on `stream`).
- * A workspace must be initialised once before its first use; every ewf_run leaves it ready
- * for the next.  Concurrent runs must not share a workspace. */
+/* Zero-fills a workspace with a fill kernel (asynchronous, on `stream`; safe to record into
+ * a HIP graph).  Optional: the kernels write every workspace word before reading it, so a
+ * workspace needs no initialisation; its contents after a run are unspecified.  Runs that may
+ * overlap in time must not share a workspace. */
 ewf_status ewf_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Launches the planned kernel(s) on hip_stream (a hipStream_t; NULL = the null stream).

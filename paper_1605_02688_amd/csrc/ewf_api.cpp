@@ -256,6 +256,10 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
     if (!p->function || hipGetDevice(&dev) != hipSuccess || dev != p->function_device) {
         st = load_function(p->code, "ewf_kernel", &p->function, &p->function_device);
         if (st != EWF_OK) return st;
+        if (p->finish_grid > 0) {
+            st = load_function(p->code, "ewf_finish", &p->finish_function, &p->function_device);
+            if (st != EWF_OK) { p->function = nullptr; return st; }
+        }
     }
 
     // patch pointers and scalars into a copy of the prepared argument block
@@ -282,6 +286,12 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
     hipError_t he = hipModuleLaunchKernel((hipFunction_t)p->function, (unsigned)p->grid, 1, 1, (unsigned)p->block, 1, 1,
                                           (unsigned)p->lds_bytes, (hipStream_t)hip_stream, nullptr, config);
     if (he != hipSuccess) { set_error("kernel launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
+    if (p->finish_grid > 0) {
+        // partial results are folded by a second kernel on the same stream
+        he = hipModuleLaunchKernel((hipFunction_t)p->finish_function, (unsigned)p->finish_grid, 1, 1,
+                                   (unsigned)p->finish_block, 1, 1, 0, (hipStream_t)hip_stream, nullptr, config);
+        if (he != hipSuccess) { set_error("kernel launch (fold): %s", hipGetErrorString(he)); return EWF_EHIP; }
+    }
     return EWF_OK;
 }
 

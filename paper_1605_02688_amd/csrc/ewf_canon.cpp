@@ -308,6 +308,14 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
         else if (op.stride[in_d] == 0) op.access = Access::Splat;
         else op.access = Access::Gather;
         if (c.extent[in_d] == 1 && op.stride[in_d] == 0) op.access = Access::Splat;
+        // streaming hint: every element is touched once and the operand is far larger than
+        // what the caches could keep for a later consumer
+        int64_t footprint = itemsize(op.storage);
+        bool once = true;
+        for (int i = 0; i < c.rank; i++) { if (op.stride[i] != 0) footprint *= c.extent[i]; else if (!(op.is_output && c.reduced[i])) once = false; }
+        if (op.is_output) once = true;
+        op.stream = op.access == Access::Vector && once &&
+                    (e.opts.streaming == 1 || (e.opts.streaming == 0 && footprint >= ((int64_t)32 << 20)));
     }
     return EWF_OK;
 }

@@ -11,12 +11,12 @@
 //               all of its wide loads, then evaluates the scalar graph in registers, then
 //               stores.
 //   TileReduce  Tile plus per-thread accumulators; one tile never leaves its reduction
-//               group; partial results go to the workspace and the last workgroup of a
-//               group (ticket counter) folds them in a fixed order.
+//               group; every wavefront stores one partial result to the workspace and a
+//               second small kernel folds the partials of each group in a fixed order.
 //   Row         one workgroup owns whole rows of the innermost (reduced) dimension, keeps
 //               the row in registers and runs the chained reduction levels over it
-//               (row max, then sum of exp(x - max), ...); optional cross-row reduction
-//               through the workspace.
+//               (row max, then sum of exp(x - max), ...); an optional cross-row reduction
+//               goes through the workspace and the same kind of second kernel.
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -344,6 +344,7 @@ struct Gen {
         o << "#define EWF_BLOCK " << block << "\n";
         o << "#define EWF_NWAVES " << (block / 64) << "\n";
         o << "#define EWF_VEC " << VEC << "\n";
+        o << "#define EWF_FIN_BLOCK 256\n";
         o << "typedef " << (c.idx64 ? "long long" : "int") << " idx_t;\n";
     }
 
@@ -403,7 +404,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
 {
     const int block = e.opts.block_threads > 0 ? e.opts.block_threads : 256;
     if (block % 64 || block > 1024) return fail("block_threads must be a multiple of 64, at most 1024");
-    const int U = e.opts.unroll > 0 ? e.opts.unroll : 4;
+    const int U = e.opts.unroll > 0 ? e.opts.unroll : 2;
     p.block = block;
 
     // ---- outputs by role
@@ -421,6 +422,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     int64_t T[kMaxDims];
     for (int d = 0; d < kMaxDims; d++) T[d] = 1;
     int64_t target = (int64_t)block * VEC * U * (with_reduce ? 4 : 1);
+    if (e.opts.tile_elems > 0) target = e.opts.tile_elems;
     {
         int64_t rem = target;
         for (int d = R - 1; d >= 0 && rem > 1; d--) {
@@ -458,10 +460,14 @@ ewf_status Gen::gen_tile(bool with_reduce)
 
     o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) ewf_kernel(const Params p)\n{\n";
     o << "    const int tid = threadIdx.x;\n";
-    if (with_reduce) {
-        o << "    __shared__ Acc sm_acc[EWF_NWAVES];\n    __shared__ int sm_flag;\n";
-        o << "    Acc *const partials = (Acc *)p.ws_partials;\n    int *const counters = (int *)p.ws_counters;\n";
-    }
+    std::vector<int> all_dims;
+    for (int d = 0; d < R; d++) all_dims.push_back(d);
+    std::vector<int> load_ops;                         // operand numbers read per element
+    for (int k : used_inputs) load_ops.push_back(k);
+    std::string ind = "        ";
+    if (with_reduce) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
+    // tiles are numbered in canonical (memory) order so that the workgroups resident at any
+    // moment stream neighbouring addresses
     o << "    for (idx_t tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {\n";
     o << "        idx_t t_ = tile;\n";
     for (int d = R - 1; d >= 0; d--) {
@@ -469,16 +475,12 @@ ewf_status Gen::gen_tile(bool with_reduce)
         else o << "        const idx_t ti0 = t_;\n";
         o << "        const idx_t o" << d << " = ti" << d << " * " << T[d] << ";\n";
     }
-    std::vector<int> all_dims;
-    for (int d = 0; d < R; d++) all_dims.push_back(d);
-    std::vector<int> load_ops;                         // operand numbers read per element
-    for (int k : used_inputs) load_ops.push_back(k);
-    for (int k : load_ops) emit_base(k, all_dims, "        ");
-    for (int k : ew_out_ops) emit_base(k, all_dims, "        ");
     if (with_reduce) o << "        Acc acc = Acc_identity();\n";
+    for (int k : load_ops) emit_base(k, all_dims, ind);
+    for (int k : ew_out_ops) emit_base(k, all_dims, ind);
 
     const bool looped = TE > step;
-    std::string ind = "        ";
+    const std::string ind0 = ind;
     if (looped) { o << ind << "for (int L0 = 0; L0 < " << TE << "; L0 += " << step << ") {\n"; ind += "    "; }
     else o << ind << "const int L0 = 0;\n";
 
@@ -520,7 +522,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         const Operand &op = c.ops[k];
         std::string nm = opname(k);
         if (op.access == Access::Vector)
-            o << ind << "        x_" << nm << "[u] = ewf_ld<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + (" << offset_expr(k, false) << "));\n";
+            o << ind << "        x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + (" << offset_expr(k, false) << "));\n";
         else if (op.access == Access::Splat)
             o << ind << "        x_" << nm << "[u] = q_" << nm << "[" << offset_expr(k, true) << "];\n";
         else {
@@ -562,7 +564,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         const Operand &op = c.ops[k];
         std::string nm = opname(k);
         if (op.access == Access::Vector)
-            o << ind << "    ewf_st<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + (" << offset_expr(k, false) << "), y_" << nm << ");\n";
+            o << ind << "    " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + (" << offset_expr(k, false) << "), y_" << nm << ");\n";
         else {
             o << ind << "    { const idx_t b_ = " << offset_expr(k, op.access == Access::Splat) << ";\n";
             o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) q_" << nm << "[b_ + (idx_t)e_ * p.st_" << nm
@@ -570,62 +572,79 @@ ewf_status Gen::gen_tile(bool with_reduce)
         }
     }
     o << ind << "}\n";
-    if (looped) { ind = "        "; o << ind << "}\n"; }
+    if (looped) { ind = ind0; o << ind << "}\n"; }
 
     if (with_reduce) {
-        // group = mixed-radix number of the kept coordinates; slot = of the reduced tile indices
+        // Every wavefront folds its own lanes with cross-lane moves and stores one partial:
+        // no LDS, no barrier, no atomic -- the waves of a workgroup never wait for each other
+        // and the kernel streams like a copy.  A second, tiny kernel folds the partials of a
+        // group in a fixed order (deterministic, and ordered by the kernel boundary alone).
         o << ind << "idx_t group = 0, slot = 0;\n";
         for (int d = 0; d < R; d++) {
             if (c.reduced[d]) o << ind << "slot = slot * p.ntile[" << d << "] + ti" << d << ";\n";
             else o << ind << "group = group * p.ext[" << d << "] + o" << d << ";\n";
         }
-        o << ind << "acc = ewf_block_reduce<EWF_NWAVES>(acc, Acc_combine(), sm_acc, tid);\n";
-        o << ind << "if (tid == 0) ewf_st_partial(&partials[group * p.nslots + slot], acc);\n";
-        o << ind << "if (ewf_last_arrival(&counters[group], (int)p.nslots, &sm_flag, tid)) {\n";
-        o << ind << "    Acc tot = Acc_identity();\n";
-        o << ind << "    for (idx_t i = tid; i < p.nslots; i += EWF_BLOCK) tot = Acc_combine()(tot, ewf_ld_partial(&partials[group * p.nslots + i]));\n";
-        o << ind << "    tot = ewf_block_reduce<EWF_NWAVES>(tot, Acc_combine(), sm_acc, tid);\n";
-        o << ind << "    if (tid == 0) {\n";
-        emit_results("tot", level, ind + "        ");
+        o << ind << "acc = ewf_wave_reduce(acc, Acc_combine());\n";
+        o << ind << "if ((tid & 63) == 0) partials[((size_t)group * (size_t)p.nslots + (size_t)slot) * EWF_NWAVES + (tid >> 6)] = acc;\n";
+    }
+    o << "    }\n}\n";
+
+    if (with_reduce) {
+        o << "\n// folds the partials of each reduction group, one wavefront per group\n";
+        o << "extern \"C\" __global__ void __launch_bounds__(64) ewf_finish(const Params p)\n{\n";
+        o << "    const int lane = threadIdx.x;\n";
+        o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
+        o << "    const idx_t nparts = p.nslots * EWF_NWAVES;\n";
+        o << "    for (idx_t group = blockIdx.x; group < p.nrows; group += gridDim.x) {\n";
+        o << "        const Acc *const gpart = partials + (size_t)group * (size_t)nparts;\n";
+        o << "        Acc tot = Acc_identity();\n";
+        o << "        for (idx_t i = lane; i < nparts; i += 64) tot = Acc_combine()(tot, gpart[i]);\n";
+        o << "        tot = ewf_wave_reduce(tot, Acc_combine());\n";
+        o << "        if (lane != 0) continue;\n";
+        o << "        idx_t g_ = group;\n";
+        for (int d = R - 1; d >= 0; d--) {
+            if (c.reduced[d]) { o << "        const idx_t o" << d << " = 0;\n"; continue; }
+            bool last_kept = true;
+            for (int d2 = d - 1; d2 >= 0; d2--) if (!c.reduced[d2]) last_kept = false;
+            if (!last_kept) o << "        const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
+            else o << "        const idx_t o" << d << " = g_;\n";
+        }
+        for (int d = 0; d < R; d++) o << "        (void)o" << d << ";\n";
+        emit_results("tot", level, "        ");
         std::vector<int> gt;
         for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
         std::vector<char> gneed = needed(gt);
-        std::vector<int> ginputs = inputs_of(gneed);
-        for (int k : ginputs) if (std::find(load_ops.begin(), load_ops.end(), k) == load_ops.end()) emit_base(k, all_dims, ind + "        ");
+        for (int k : inputs_of(gneed)) emit_base(k, all_dims, "        ");
         EmitCtx gx;
         gx.input = [&](int k) { return "ewf_in(q_" + opname(k) + "[0])"; };
         gx.coord = [&](int d) { return "o" + std::to_string(d); };
-        emit_values(gneed, gx, ind + "        ");
+        emit_values(gneed, gx, "        ");
         for (int k : group_out_ops) {
             const Operand &op = c.ops[k];
             int v = g.outputs[op.index].value;
             const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
-            emit_base(k, all_dims, ind + "        ");
-            o << ind << "        q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
+            emit_base(k, all_dims, "        ");
+            o << "        q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
         }
-        o << ind << "        counters[group] = 0;\n";
-        o << ind << "    }\n";
-        o << ind << "}\n";
+        o << "    }\n}\n";
     }
-    o << "    }\n}\n";
 
     // ---- launch geometry and argument block
-    p.grid = ntiles;
-    int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (with_reduce ? ntiles : (int64_t)256 * 16);
-    if (with_reduce) cap = ntiles;       // the last-arrival protocol takes one ticket per tile
+    int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)1 << 22;
     p.grid = std::max<int64_t>(1, std::min(ntiles, cap));
     p.lds_bytes = 0;
     int64_t ngroups = 1, nslots = 1;
     for (int d = 0; d < R; d++) { if (c.reduced[d]) nslots *= ntile[d]; else ngroups *= c.extent[d]; }
+    p.counter_bytes = 0;
+    p.workspace_bytes = 0;
+    p.finish_grid = 0;
     if (with_reduce) {
         if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31)) return fail("too many reduction groups");
         size_t acc_bytes = 0;
         for (int n : level) acc_bytes += (g.nodes[n].op == EWF_RARGMAX) ? 8 : 4;
-        p.counter_bytes = ((size_t)ngroups * 4 + 255) / 256 * 256;
-        p.workspace_bytes = p.counter_bytes + (size_t)ngroups * (size_t)nslots * acc_bytes;
-    } else {
-        p.counter_bytes = 0;
-        p.workspace_bytes = 0;
+        p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(block / 64) * acc_bytes;
+        p.finish_grid = std::min<int64_t>(ngroups, (int64_t)1 << 20);
+        p.finish_block = 64;
     }
     p.args.assign(p.layout.size, 0);
     auto put_idx = [&](const std::string &name, int i, int64_t v) {
@@ -702,10 +721,7 @@ ewf_status Gen::gen_row()
     o << "    const int tid = threadIdx.x;\n";
     o << "    const idx_t cols = p.ext[" << in_d << "];\n";
     for (int l = 1; l <= D; l++) o << "    __shared__ Acc" << l << " sm_acc" << l << "[EWF_NWAVES];\n";
-    if (has_cross) {
-        o << "    __shared__ AccX sm_accx[EWF_NWAVES];\n    __shared__ int sm_flag;\n";
-        o << "    AccX *const partials = (AccX *)p.ws_partials;\n    int *const counters = (int *)p.ws_counters;\n";
-    }
+    if (has_cross) o << "    AccX *const partials = (AccX *)p.ws_partials;\n";
     o << "    for (idx_t row = blockIdx.x; row < p.nrows; row += gridDim.x) {\n";
     o << "        idx_t t_ = row;\n";
     std::vector<int> outer;
@@ -746,7 +762,7 @@ ewf_status Gen::gen_row()
         const Operand &op = c.ops[k];
         std::string nm = opname(k);
         if (op.access == Access::Vector)
-            o << ind << dst << " = ewf_ld<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col);\n";
+            o << ind << dst << " = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col);\n";
         else
             o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) " << dst << ".e[e_] = q_" << nm
               << "[(col + e_) * p.st_" << nm << "[" << in_d << "]];\n";
@@ -814,7 +830,7 @@ ewf_status Gen::gen_row()
             const Operand &op = c.ops[k];
             std::string nm = opname(k);
             if (op.access == Access::Vector)
-                o << "            ewf_st<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col, y_" << nm << ");\n";
+                o << "            " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col, y_" << nm << ");\n";
             else
                 o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) q_" << nm << "[(col + e_) * p.st_" << nm
                   << "[" << in_d << "]] = y_" << nm << ".e[e_];\n";
@@ -856,36 +872,40 @@ ewf_status Gen::gen_row()
                         o << "            ax.i" << i << " = (int)(" << (cd < 0 ? std::string("0") : "o" + std::to_string(cd)) << ");\n";
                     }
                 }
-                o << "            ewf_st_partial(&partials[row], ax);\n";
+                o << "            partials[row] = ax;\n";
             }
             o << "        }\n";
         }
     }
     o << "    }\n";
 
+    o << "}\n";
     if (has_cross) {
-        o << "    if (ewf_last_arrival(&counters[0], (int)gridDim.x, &sm_flag, tid)) {\n";
-        o << "        AccX tot = AccX_identity();\n";
-        o << "        for (idx_t i = tid; i < p.nrows; i += EWF_BLOCK) tot = AccX_combine()(tot, ewf_ld_partial(&partials[i]));\n";
-        o << "        tot = ewf_block_reduce<EWF_NWAVES>(tot, AccX_combine(), sm_accx, tid);\n";
-        o << "        if (tid == 0) {\n";
-        emit_results("tot", red.cross_nodes, "            ");
+        // the per-row values are folded by a second, single-workgroup kernel: ordered by the
+        // kernel boundary, deterministic, and free of atomics
+        o << "\nextern \"C\" __global__ void __launch_bounds__(EWF_FIN_BLOCK) ewf_finish(const Params p)\n{\n";
+        o << "    const int tid = threadIdx.x;\n";
+        o << "    __shared__ AccX sm_accx[EWF_FIN_BLOCK / 64];\n";
+        o << "    const AccX *const partials = (const AccX *)p.ws_partials;\n";
+        o << "    AccX tot = AccX_identity();\n";
+        o << "    for (idx_t i = tid; i < p.nrows; i += EWF_FIN_BLOCK) tot = AccX_combine()(tot, partials[i]);\n";
+        o << "    tot = ewf_block_reduce<EWF_FIN_BLOCK / 64>(tot, AccX_combine(), sm_accx, tid);\n";
+        o << "    if (tid == 0) {\n";
+        emit_results("tot", red.cross_nodes, "        ");
         std::vector<int> tg;
         for (int k : final_out_ops) tg.push_back(g.outputs[c.ops[k].index].value);
         std::vector<char> need = needed(tg);
         EmitCtx fx;
         fx.input = [&](int k) { return "ewf_in(((const " + std::string(ctype(c.ops[k].storage)) + " *)p." + opname(k) + ")[0])"; };
         fx.coord = [&](int) { return std::string("0"); };
-        emit_values(need, fx, "            ");
+        emit_values(need, fx, "        ");
         for (int k : final_out_ops) {
             const Operand &op = c.ops[k];
             const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
-            o << "            ((" << ctype(op.storage) << " *)p." << opname(k) << ")[0] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
+            o << "        ((" << ctype(op.storage) << " *)p." << opname(k) << ")[0] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
         }
-        o << "            counters[0] = 0;\n";
-        o << "        }\n    }\n";
+        o << "    }\n}\n";
     }
-    o << "}\n";
 
     // ---- launch geometry and argument block
     int64_t nrows = 1;
@@ -894,14 +914,15 @@ ewf_status Gen::gen_row()
     int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)256 * 32;
     p.grid = std::max<int64_t>(1, std::min(nrows, cap));
     p.lds_bytes = 0;
+    p.counter_bytes = 0;
+    p.workspace_bytes = 0;
+    p.finish_grid = 0;
     if (has_cross) {
         size_t acc_bytes = 0;
         for (int n : red.cross_nodes) acc_bytes += (g.nodes[n].op == EWF_RARGMAX) ? 8 : 4;
-        p.counter_bytes = 256;
-        p.workspace_bytes = p.counter_bytes + (size_t)nrows * acc_bytes;
-    } else {
-        p.counter_bytes = 0;
-        p.workspace_bytes = 0;
+        p.workspace_bytes = (size_t)nrows * acc_bytes;
+        p.finish_grid = 1;
+        p.finish_block = 256;
     }
     p.args.assign(p.layout.size, 0);
     auto put_idx = [&](const std::string &name, int i, int64_t v) {

@@ -69,6 +69,7 @@ struct Operand {
     int64_t stride[kMaxDims] = {0};   // canonical, in elements
     uint64_t addr = 0;
     Access access = Access::Gather;
+    bool stream = false;              // touched once and large: non-temporal accesses
     int alias_of = -1;                // outputs: operand number of the input it aliases exactly
 };
 
@@ -147,6 +148,9 @@ struct Plan {
     int function_device = -1;
     int block = 256;
     int64_t grid = 0;
+    void *finish_function = nullptr;     // second kernel folding partial results (0 grid: none)
+    int64_t finish_grid = 0;
+    int finish_block = 64;
     int lds_bytes = 0;
     int staged = 0;
     int64_t tile[kMaxDims] = {0};

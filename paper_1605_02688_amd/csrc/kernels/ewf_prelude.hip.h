@@ -4,7 +4,10 @@
 // emits.  It holds: wide aligned memory accesses, storage <-> value conversions, the scalar
 // operations in an accurate float32 flavour and a native-rate flavour, and the wavefront /
 // workgroup reduction used by the fused reduce kernels (cross-lane DPP inside a row of 16
-// lanes, lane permutes across rows, LDS across wavefronts).
+// lanes, lane permutes across rows, LDS across wavefronts).  Results that span workgroups
+// are exchanged through the workspace and folded by a second kernel: on this chip an
+// agent-scope fence writes back and invalidates a whole L2 slice, and contended global
+// atomics cost a memory round trip each, so the kernels use neither.
 #ifndef EWF_PRELUDE_H
 #define EWF_PRELUDE_H
 
@@ -33,6 +36,50 @@ template <typename T, int N>
 EWF_DEV void ewf_st(T *p, const ewf_vec<T, N> &v)
 {
     *reinterpret_cast<ewf_vec<T, N> *>(p) = v;
+}
+
+// Streaming flavour of the same accesses for operands that are touched exactly once and
+// are much larger than the caches: the non-temporal hint keeps them from displacing the
+// broadcast operands and measurably raises sustained HBM throughput.
+typedef unsigned int ewf_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int ewf_u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename T, int N>
+EWF_DEV ewf_vec<T, N> ewf_ld_nt(const T *p)
+{
+    constexpr int B = N * (int)sizeof(T);
+    ewf_vec<T, N> r;
+    if constexpr (B % 16 == 0) {
+        const ewf_u32x4 *s = reinterpret_cast<const ewf_u32x4 *>(p);
+        ewf_u32x4 *d = reinterpret_cast<ewf_u32x4 *>(&r);
+#pragma unroll
+        for (int i = 0; i < B / 16; i++) d[i] = __builtin_nontemporal_load(s + i);
+    } else if constexpr (B == 8) {
+        *reinterpret_cast<ewf_u32x2 *>(&r) = __builtin_nontemporal_load(reinterpret_cast<const ewf_u32x2 *>(p));
+    } else if constexpr (B == 4) {
+        *reinterpret_cast<unsigned int *>(&r) = __builtin_nontemporal_load(reinterpret_cast<const unsigned int *>(p));
+    } else {
+        *reinterpret_cast<unsigned short *>(&r) = __builtin_nontemporal_load(reinterpret_cast<const unsigned short *>(p));
+    }
+    return r;
+}
+
+template <typename T, int N>
+EWF_DEV void ewf_st_nt(T *p, const ewf_vec<T, N> &v)
+{
+    constexpr int B = N * (int)sizeof(T);
+    if constexpr (B % 16 == 0) {
+        ewf_u32x4 *d = reinterpret_cast<ewf_u32x4 *>(p);
+        const ewf_u32x4 *s = reinterpret_cast<const ewf_u32x4 *>(&v);
+#pragma unroll
+        for (int i = 0; i < B / 16; i++) __builtin_nontemporal_store(s[i], d + i);
+    } else if constexpr (B == 8) {
+        __builtin_nontemporal_store(*reinterpret_cast<const ewf_u32x2 *>(&v), reinterpret_cast<ewf_u32x2 *>(p));
+    } else if constexpr (B == 4) {
+        __builtin_nontemporal_store(*reinterpret_cast<const unsigned int *>(&v), reinterpret_cast<unsigned int *>(p));
+    } else {
+        __builtin_nontemporal_store(*reinterpret_cast<const unsigned short *>(&v), reinterpret_cast<unsigned short *>(p));
+    }
 }
 
 // ------------------------------------------------------------------ storage <-> value
@@ -184,59 +231,6 @@ EWF_DEV T ewf_block_reduce(T v, F op, T *smem, int tid)
     for (int w = 1; w < NWAVES; w++) r = op(r, smem[w]);
     __syncthreads();
     return r;
-}
-
-// Agent-scope coherent accesses for partial results exchanged between workgroups
-EWF_DEV int ewf_ld_coherent(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-EWF_DEV void ewf_st_coherent(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
-template <typename T>
-EWF_DEV T ewf_ld_partial(const T *p)
-{
-    T r;
-    const int *src = reinterpret_cast<const int *>(p);
-    int *dst = reinterpret_cast<int *>(&r);
-#pragma unroll
-    for (int i = 0; i < (int)(sizeof(T) / 4); i++) dst[i] = ewf_ld_coherent(src + i);
-    return r;
-}
-
-template <typename T>
-EWF_DEV void ewf_st_partial(T *p, const T &v)
-{
-    const int *src = reinterpret_cast<const int *>(&v);
-    int *dst = reinterpret_cast<int *>(p);
-#pragma unroll
-    for (int i = 0; i < (int)(sizeof(T) / 4); i++) ewf_st_coherent(dst + i, src[i]);
-}
-
-// Takes a ticket on `counter`; true in every thread of the workgroup that arrives last of
-// `expected`.
-//
-// Protocol (thread 0 of each workgroup has just written its partial with ewf_st_partial):
-// partials are written and read only with agent-scope atomic accesses, which are coherent
-// across the chip's L2 slices by themselves, so no cache write-back or invalidate is needed
-// -- a full agent-scope fence would write back and invalidate a whole L2 per call, which
-// costs far more than the kernels' own traffic.  What remains is ordering: the writer waits
-// for its partial stores to complete before taking the ticket (workgroup-scope release:
-// a wait on the memory counters, no cache maintenance), and the reader issues its partial
-// loads only after the ticket value has come back (control dependence + workgroup-scope
-// acquire).  Ordinary element-wise stores of the same kernel are not part of the exchange.
-EWF_DEV bool ewf_last_arrival(int *counter, int expected, int *flag_lds, int tid)
-{
-    if (tid == 0) {
-        // stores and the ticket go to different L2 channels: wait until the partial stores
-        // have been acknowledged (stores count in vmcnt on this architecture)
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        int t = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        *flag_lds = (t == expected - 1);
-    }
-    __syncthreads();
-    bool last = (*flag_lds != 0);
-    __syncthreads();
-    return last;
 }
 
 #endif  // EWF_PRELUDE_H

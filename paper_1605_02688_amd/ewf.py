@@ -41,7 +41,8 @@ class ewf_options(ctypes.Structure):
     _fields_ = [("math_mode", ctypes.c_int32), ("force_scalar", ctypes.c_int32),
                 ("force_index64", ctypes.c_int32), ("block_threads", ctypes.c_int32),
                 ("unroll", ctypes.c_int32), ("max_blocks", ctypes.c_int32),
-                ("no_lds_staging", ctypes.c_int32), ("reserved", ctypes.c_int32 * 9)]
+                ("no_lds_staging", ctypes.c_int32), ("streaming", ctypes.c_int32),
+                ("tile_elems", ctypes.c_int32), ("reserved", ctypes.c_int32 * 7)]
 
 
 class ewf_tensor(ctypes.Structure):
