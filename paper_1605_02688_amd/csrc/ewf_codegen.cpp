@@ -31,6 +31,7 @@ namespace ewf {
 
 void ParamLayout::add(ParamField::Type t, const std::string &name, int count)
 {
+    // count 0 declares a scalar member, any other count an array of that many
     fields.push_back({t, name, count});
 }
 
@@ -50,7 +51,7 @@ std::string ParamLayout::declare(const std::string &struct_name, bool) const
         const char *ty = f.type == ParamField::Ptr ? "void *" : f.type == ParamField::I64 ? "long long " :
                          f.type == ParamField::I32 ? "int " : "float ";
         o << "    " << ty << f.name;
-        if (f.count > 1) o << "[" << f.count << "]";
+        if (f.count > 0) o << "[" << f.count << "]";
         o << ";\n";
     }
     o << "};\n";
@@ -66,7 +67,7 @@ static void finish_layout(ParamLayout &L)
         maxal = std::max(maxal, sz);
         off = (off + sz - 1) / sz * sz;
         L.offsets.push_back(off);
-        off += sz * (size_t)f.count;
+        off += sz * (size_t)std::max(1, f.count);
     }
     L.size = (off + maxal - 1) / maxal * maxal;
 }
@@ -353,17 +354,17 @@ struct Gen {
         ParamLayout &L = p.layout;
         L.fields.clear();
         const ParamField::Type IDX = c.idx64 ? ParamField::I64 : ParamField::I32;
-        for (size_t k = 0; k < c.ops.size(); k++) L.add(ParamField::Ptr, opname((int)k));
-        L.add(ParamField::Ptr, "ws_counters");
-        L.add(ParamField::Ptr, "ws_partials");
+        for (size_t k = 0; k < c.ops.size(); k++) L.add(ParamField::Ptr, opname((int)k), 0);
+        L.add(ParamField::Ptr, "ws_counters", 0);
+        L.add(ParamField::Ptr, "ws_partials", 0);
         L.add(IDX, "ext", std::max(1, R));
         L.add(IDX, "ntile", std::max(1, R));
-        L.add(IDX, "ntiles");
-        L.add(IDX, "nrows");
-        L.add(IDX, "nslots");
+        L.add(IDX, "ntiles", 0);
+        L.add(IDX, "nrows", 0);
+        L.add(IDX, "nslots", 0);
         for (size_t k = 0; k < c.ops.size(); k++) L.add(IDX, "st_" + opname((int)k), std::max(1, R));
         for (int k = 0; k < g.nscalars; k++)
-            L.add(g.nodes[g.scalar_node[k]].vtype == EWF_I32 ? ParamField::I32 : ParamField::F32, "s" + std::to_string(k));
+            L.add(g.nodes[g.scalar_node[k]].vtype == EWF_I32 ? ParamField::I32 : ParamField::F32, "s" + std::to_string(k), 0);
         finish_layout(L);
         o << L.declare("Params", c.idx64);
     }

@@ -1,0 +1,417 @@
+"""GPU parity, part 2: every scalar operation on its own, and randomly generated graphs over
+random shapes, broadcast patterns and strided views -- all against the CPU oracle on the same
+seeded inputs.  Launches go through the C ABI binding."""
+import numpy as np
+import pytest
+
+from workloads import GraphSpec
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    import tests.harness as h
+    from paper_1605_02688_amd import ewf
+
+    class Ctx:
+        pass
+    c = Ctx()
+    c.torch, c.h, c.ewf = torch, h, ewf
+    return c
+
+
+def run_spec(G, spec, host_inputs, scalars=(), **opts):
+    """host_inputs: numpy arrays (possibly strided views).  The device tensors reproduce the
+    same strides over a copy of each view's underlying buffer."""
+    torch = G.torch
+    dev = []
+    for a in host_inputs:
+        base = a if a.base is None else a.base
+        while base.base is not None:
+            base = base.base
+        tb = torch.from_numpy(np.ascontiguousarray(base).reshape(-1).copy()).cuda()
+        off = (a.__array_interface__["data"][0] - base.__array_interface__["data"][0]) // a.itemsize
+        dev.append(torch.as_strided(tb, a.shape, tuple(s // a.itemsize for s in a.strides), off))
+    expr = G.ewf.Expression(spec, **opts)
+    outs = G.h.alloc_outputs(expr, spec, dev)
+    ws = G.h.make_workspace(expr, dev, outs)
+    expr.run(dev, outs, scalars, ws, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return expr, [o.cpu().numpy() for o in outs]
+
+
+# ------------------------------------------------------------------ single operations
+
+UNARY = {
+    # name: (low, high, rtol, atol) -- float32 element-wise bar unless the op amplifies input error
+    "neg": (-4, 4, 0, 0), "abs": (-4, 4, 0, 0), "sqr": (-4, 4, 2e-6, 1e-6), "exp": (-20, 20, 2e-6, 1e-6),
+    "log": (1e-3, 50, 2e-6, 1e-6), "log1p": (-0.9, 50, 2e-6, 1e-6), "sqrt": (0, 50, 2e-6, 1e-6),
+    "tanh": (-12, 12, 2e-6, 1e-6), "sigmoid": (-30, 30, 2e-6, 1e-6), "expm1": (-10, 10, 2e-6, 1e-6),
+    "recip": (0.05, 50, 2e-6, 1e-6),
+}
+
+
+@pytest.mark.parametrize("op", sorted(UNARY))
+def test_unary_op_accurate_mode(op, oracle, G):
+    lo, hi, rtol, atol = UNARY[op]
+    rng = np.random.default_rng(hash(op) % 1000)
+    x = rng.uniform(lo, hi, 5003).astype(np.float32)
+    x[:7] = np.float32([lo, hi, (lo + hi) / 2, lo + 1e-4, hi - 1e-4, lo + 1e-7 * (hi - lo), 1.0])
+    s = GraphSpec(1)
+    s.output(s.apply(op, s.input("f32", (False,))), "f32")
+    print(f"[case] unary {op}", flush=True)
+    _, (got,) = run_spec(G, s, [x])
+    want = oracle.evaluate(s, [x])[0]
+    G.h.compare(op, got, want, rtol, atol)
+
+
+def test_log1p_keeps_small_arguments(oracle, G):
+    x = np.float32([1e-7, -1e-7, 3e-10, 1e-5, -1e-5])
+    s = GraphSpec(1)
+    s.output(s.apply("log1p", s.input("f32", (False,))), "f32")
+    for mode in (1, 2):
+        _, (got,) = run_spec(G, s, [x], math_mode=mode)
+        assert np.allclose(got, x.astype(np.float64), rtol=1e-4), mode   # log(1+x) in float32 would give 0
+
+
+BINARY = ["add", "sub", "mul", "div", "max", "min", "pow"]
+
+
+@pytest.mark.parametrize("op", BINARY)
+def test_binary_op_accurate_mode(op, oracle, G):
+    rng = np.random.default_rng(5 + len(op))
+    a = rng.uniform(-3, 3, 4099).astype(np.float32)
+    b = rng.uniform(-3, 3, 4099).astype(np.float32)
+    if op == "pow":
+        a = np.abs(a) + np.float32(0.1)
+    if op == "div":
+        b = np.where(np.abs(b) < 0.05, np.float32(0.5), b)
+    s = GraphSpec(1)
+    s.output(s.apply(op, s.input("f32", (False,)), s.input("f32", (False,))), "f32")
+    print(f"[case] binary {op}", flush=True)
+    _, (got,) = run_spec(G, s, [a, b])
+    want = oracle.evaluate(s, [a, b])[0]
+    G.h.compare(op, got, want, 2e-6, 1e-6)
+
+
+def test_compare_where_and_int_ops_are_exact(oracle, G):
+    rng = np.random.default_rng(9)
+    a = rng.integers(-3, 3, 1000).astype(np.float32); b = rng.integers(-3, 3, 1000).astype(np.float32)
+    ia = rng.integers(-2**31, 2**31 - 1, 1000).astype(np.int32); ib = rng.integers(-70000, 70000, 1000).astype(np.int32)
+    s = GraphSpec(1)
+    x = s.input("f32", (False,)); y = s.input("f32", (False,))
+    i = s.input("i32", (False,)); j = s.input("i32", (False,))
+    for op in ("gt", "ge", "lt", "le", "eq", "ne"):
+        s.output(s.apply(op, x, y), "i32")
+        s.output(s.apply("where", s.apply(op, i, j), x, y), "f32")
+    for op in ("add", "sub", "mul", "max", "min"):
+        s.output(s.apply(op, i, j), "i32")
+    s.output(s.apply("neg", i), "i32"); s.output(s.apply("abs", j), "i32"); s.output(s.apply("sqr", j), "i32")
+    s.output(s.add(s.mul(s.iota(0), s.const(3, "i32")), j), "i32")
+    s.output(s.cast(i, "f32"), "f32")
+    s.output(s.cast(s.mul(x, s.const(1.75)), "i32"), "i32")
+    s.output(s.cast(s.mul(x, s.const(0.3333)), "f16"), "f32")
+    _, got = run_spec(G, s, [a, b, ia, ib])
+    want = oracle.evaluate(s, [a, b, ia, ib])
+    for k, (g_, w_) in enumerate(zip(got, want)):
+        G.h.compare(f"out{k}", g_, w_, 0, 0)
+
+
+def test_nan_and_inf_conventions(oracle, G):
+    nan, inf = np.float32("nan"), np.float32("inf")
+    a = np.float32([1, nan, 3, nan, inf, -inf, 0.0, -0.0]); b = np.float32([2, 2, nan, nan, 1, 1, nan, 5])
+    s = GraphSpec(1)
+    x = s.input("f32", (False,)); y = s.input("f32", (False,))
+    s.output(s.apply("max", x, y), "f32"); s.output(s.apply("min", x, y), "f32")
+    s.output(s.apply("where", x, y, s.const(7.0)), "f32")
+    _, got = run_spec(G, s, [a, b])
+    want = oracle.evaluate(s, [a, b])
+    for g_, w_ in zip(got, want):
+        assert np.array_equal(g_, w_, equal_nan=True)
+
+
+def test_f16_storage_rounds_to_nearest_even(oracle, G):
+    rng = np.random.default_rng(10)
+    a = rng.uniform(-2, 2, 4096).astype(np.float16); b = rng.uniform(-2, 2, 4096).astype(np.float16)
+    s = GraphSpec(1)
+    s.output(s.mul(s.input("f16", (False,)), s.input("f16", (False,))), "f16")
+    _, (got,) = run_spec(G, s, [a, b])
+    # the product of two float16 values is exact in float32, so the stored result is the
+    # correctly rounded one: bit-exact against the oracle
+    assert np.array_equal(got, oracle.evaluate(s, [a, b])[0])
+
+
+def test_native_rate_math_meets_the_f16_bar(oracle, G):
+    rng = np.random.default_rng(11)
+    x = rng.uniform(-6, 6, 20000).astype(np.float16)
+    p = rng.uniform(0.1, 5, 20000).astype(np.float16)
+    s = GraphSpec(1)
+    a = s.input("f16", (False,)); b = s.input("f16", (False,))
+    for op in ("exp", "tanh", "sigmoid", "expm1"):
+        s.output(s.apply(op, a), "f16")
+    for op in ("log", "log1p", "sqrt", "recip"):
+        s.output(s.apply(op, b), "f16")
+    s.output(s.apply("pow", b, s.mul(a, s.const(0.25))), "f16")
+    s.output(s.div(a, b), "f16")
+    expr, got = run_spec(G, s, [x, p])
+    assert "ewf_fast::" in expr.source()
+    want = oracle.evaluate(s, [x, p])
+    for k, (g_, w_) in enumerate(zip(got, want)):
+        G.h.compare(f"fast{k}", g_, w_, 2e-3, 1e-3)
+
+
+# ------------------------------------------------------------------ layouts
+
+def test_transpose_and_slice_views(oracle, G):
+    rng = np.random.default_rng(12)
+    base = rng.standard_normal((70, 90)).astype(np.float32)
+    s = GraphSpec(2)
+    s.output(s.apply("tanh", s.add(s.input("f32", (False, False)), s.input("f32", (False, False)))), "f32")
+    for a, b in [(base[:64, :64], base[3:67, 5:69].T), (base[1:60:2, ::3], base[:30, :30]),
+                 (base.T[:33, :17], base[:33, 20:37])]:
+        _, (got,) = run_spec(G, s, [a, b])
+        want = oracle.evaluate(s, [a, b])[0]
+        G.h.compare("views", got, want, 2e-6, 1e-6)
+        # a strided view gives exactly what its contiguous copy gives
+        _, (got2,) = run_spec(G, s, [np.ascontiguousarray(a), np.ascontiguousarray(b)])
+        assert np.array_equal(got, got2)
+
+
+def test_broadcast_equals_materialised_operand(oracle, G):
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((9, 33, 20)).astype(np.float32)
+    b = rng.standard_normal((1, 33, 1)).astype(np.float32)
+    s = GraphSpec(3)
+    s.output(s.apply("exp", s.mul(s.input("f32", (False,) * 3), s.input("f32", (True, False, True)))), "f32")
+    s2 = GraphSpec(3)
+    s2.output(s2.apply("exp", s2.mul(s2.input("f32", (False,) * 3), s2.input("f32", (False,) * 3))), "f32")
+    _, (g1,) = run_spec(G, s, [X, b])
+    _, (g2,) = run_spec(G, s2, [X, np.ascontiguousarray(np.broadcast_to(b, X.shape))])
+    assert np.array_equal(g1, g2)
+
+
+def test_in_place_output(oracle, G):
+    torch = G.torch
+    rng = np.random.default_rng(14)
+    x = rng.standard_normal((300, 77)).astype(np.float32)
+    s = GraphSpec(2)
+    s.output(s.apply("sigmoid", s.input("f32", (False, False))), "f32")
+    want = oracle.evaluate(s, [x])[0]
+    t = torch.from_numpy(x.copy()).cuda()
+    expr = G.ewf.Expression(s)
+    expr.run([t], [t], (), None, torch.cuda.current_stream().cuda_stream)      # overwrites its input
+    torch.cuda.synchronize()
+    G.h.compare("inplace", t.cpu().numpy(), want, 2e-6, 1e-6)
+    u = torch.zeros(301, 77, device="cuda")
+    with pytest.raises(G.ewf.EwfError) as e:                                    # shifted overlap is refused
+        expr.run([u[:300]], [u[1:]], (), None, 0)
+    assert e.value.status == G.ewf.EALIAS
+
+
+def test_index64_kernels_give_the_same_result(oracle, G):
+    rng = np.random.default_rng(15)
+    x = rng.standard_normal((50, 70)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    s.output(s.apply("tanh", xi), "f32"); s.output(s.reduce("sum", xi, (1,)), "f32")
+    e32, g32 = run_spec(G, s, [x])
+    e64, g64 = run_spec(G, s, [x], force_index64=1)
+    assert e64.info()["index_bits"] == 64 and e32.info()["index_bits"] == 32
+    for a, b in zip(g32, g64):
+        assert np.array_equal(a, b)
+
+
+def test_canary_around_outputs(oracle, G):
+    # outputs live in the middle of a larger buffer; nothing outside the view may change
+    torch = G.torch
+    rng = np.random.default_rng(16)
+    x = rng.standard_normal((37, 53)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    s.output(s.apply("exp", xi), "f32"); s.output(s.reduce("max", xi, (1,)), "f32")
+    expr = G.ewf.Expression(s)
+    big = torch.full((45, 64), -777.0, device="cuda")
+    big2 = torch.full((64,), -777.0, device="cuda")
+    out = big[4:41, 5:58]; red = big2[9:46]
+    t = torch.from_numpy(x).cuda()
+    ws = G.h.make_workspace(expr, [t], [out, red])
+    expr.run([t], [out, red], (), ws, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = oracle.evaluate(s, [x])
+    G.h.compare("exp", out.cpu().numpy(), want[0], 2e-6, 1e-6)
+    G.h.compare("max", red.cpu().numpy(), want[1], 0, 0)
+    mask = torch.ones_like(big, dtype=torch.bool); mask[4:41, 5:58] = False
+    assert bool((big[mask] == -777.0).all())
+    mask2 = torch.ones_like(big2, dtype=torch.bool); mask2[9:46] = False
+    assert bool((big2[mask2] == -777.0).all())
+
+
+# ------------------------------------------------------------------ reductions
+
+def test_integer_valued_sums_are_bit_exact(oracle, G):
+    # |sum| < 2^24 and integer-valued data: every association order gives the same float32
+    rng = np.random.default_rng(17)
+    for shape, axes in [((64, 1000), (1,)), ((300, 40), (1,)), ((3, 7, 3000), (0, 2)), ((100000,), (0,)),
+                        ((5, 33, 21, 40), (0, 2, 3)), ((2, 70000), (1,))]:
+        X = rng.integers(-20, 20, shape).astype(np.float32)
+        s = GraphSpec(len(shape))
+        s.output(s.reduce("sum", s.input("f32", (False,) * len(shape)), axes), "f32")
+        print(f"[case] exact sum {shape} axes {axes}", flush=True)
+        expr, (got,) = run_spec(G, s, [X])
+        assert np.array_equal(got, X.astype(np.float64).sum(axis=axes).astype(np.float32)), (shape, expr.info())
+        assert np.array_equal(got, oracle.evaluate(s, [X])[0])
+
+
+def test_every_reduction_kind_row_and_split(oracle, G):
+    rng = np.random.default_rng(18)
+    for shape, axes in [((200, 333), (1,)), ((3, 40000), (1,)), ((6, 5, 2000), (0, 2))]:
+        nd = len(shape)
+        X = rng.uniform(0.9, 1.1, shape).astype(np.float32)
+        I = rng.integers(-1000, 1000, shape).astype(np.int32)
+        s = GraphSpec(nd)
+        x = s.input("f32", (False,) * nd); i = s.input("i32", (False,) * nd)
+        for red in ("sum", "max", "min"):
+            s.output(s.reduce(red, x, axes), "f32")
+            s.output(s.reduce(red, i, axes), "i32")
+        if shape[0] != 3:
+            s.output(s.reduce("prod", s.apply("sqrt", s.apply("sqrt", x)), axes), "f32")
+        if len(axes) == 1:
+            s.output(s.reduce("argmax", x, axes), "i32")
+            s.output(s.reduce("argmax", i, axes), "i32")
+        print(f"[case] reductions {shape} axes {axes}", flush=True)
+        expr, got = run_spec(G, s, [X, I])
+        want = oracle.evaluate(s, [X, I], nthreads=4)
+        for k, ((v, st), g_, w_) in enumerate(zip(s.outputs, got, want)):
+            if st == "i32":
+                G.h.compare(f"{shape}.out{k}", g_, w_, 0, 0)
+            else:
+                G.h.compare(f"{shape}.out{k}", g_, w_, 1e-5, 1e-6)
+
+
+def test_argmax_ties_take_the_first_index(oracle, G):
+    x = np.zeros((70, 5000), np.float32)
+    x[:, 4000] = 3.0; x[:, 123] = 3.0; x[5, 7] = 3.0
+    x[9, :] = -np.inf
+    s = GraphSpec(2)
+    s.output(s.reduce("argmax", s.input("f32", (False, False)), (1,)), "i32")
+    for opts in ({}, {"block_threads": 64}, {"block_threads": 1024}):
+        _, (got,) = run_spec(G, s, [x], **opts)
+        want = oracle.evaluate(s, [x])[0]
+        assert np.array_equal(got, want)
+        assert got[0] == 123 and got[5] == 7 and got[9] == 0
+
+
+def test_softmax_probabilities_row_class(oracle, G):
+    rng = np.random.default_rng(19)
+    for rows, cols in [(33, 1000), (5, 9000), (700, 24)]:
+        x = (rng.standard_normal((rows, cols)) * 3).astype(np.float32)
+        s = GraphSpec(2)
+        xi = s.input("f32", (False, False))
+        e = s.apply("exp", s.sub(xi, s.reduce("max", xi, (1,))))
+        p = s.div(e, s.reduce("sum", e, (1,)))
+        s.output(p, "f32")
+        s.output(s.reduce("sum", p, (1,)), "f32")          # third chained level: rows sum to one
+        print(f"[case] softmax {rows}x{cols}", flush=True)
+        expr, (gp, gs) = run_spec(G, s, [x])
+        assert expr.info()["kernel_class"] == "row"
+        wp, wsum = oracle.evaluate(s, [x], nthreads=4)
+        G.h.compare("p", gp, wp, 1e-5, 1e-7)
+        G.h.compare("rowsum", gs, wsum, 1e-5, 1e-6)
+        assert np.allclose(gs, 1.0, atol=1e-5)
+
+
+def test_streaming_rows_longer_than_registers(oracle, G):
+    # rows too long to stay in registers are re-read level by level
+    rng = np.random.default_rng(20)
+    x = (rng.standard_normal((4, 70000)) * 2).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    m = s.reduce("max", xi, (1,))
+    S = s.reduce("sum", s.apply("exp", s.sub(xi, m)), (1,))
+    s.output(s.add(m, s.apply("log", S)), "f32")
+    expr, (got,) = run_spec(G, s, [x])
+    assert expr.info()["kernel_class"] == "row"
+    G.h.compare("lse", got, oracle.evaluate(s, [x], nthreads=4)[0], 1e-5, 1e-6)
+
+
+# ------------------------------------------------------------------ random graphs
+
+SAFE_UN = ["neg", "abs", "exp", "log1p", "sqrt", "tanh", "sigmoid", "sqr", "recip", "expm1", "log"]
+
+
+def random_case(seed):
+    rng = np.random.default_rng(7000 + seed)
+    ndim = int(rng.integers(1, 5))
+    full = [int(rng.choice([1, 2, 3, 5, 8, 13, 32, 40])) for _ in range(ndim)]
+    if rng.integers(0, 2):
+        full[-1] = int(rng.choice([4, 16, 64, 100, 256]))
+    s = GraphSpec(ndim)
+    inputs, vals = [], []
+    for k in range(int(rng.integers(1, 4))):
+        bc = tuple(bool(rng.integers(0, 4) == 0) and k > 0 for _ in range(ndim))
+        shp = [1 if b else e for b, e in zip(bc, full)]
+        style = int(rng.integers(0, 3))
+        if style == 0:
+            view = rng.uniform(0.2, 2.0, shp).astype(np.float32)
+        elif style == 1:                                  # slice of a larger buffer
+            big = rng.uniform(0.2, 2.0, [e + 3 for e in shp]).astype(np.float32)
+            view = big[tuple(slice(1, 1 + e) for e in shp)]
+        else:                                             # permuted and strided
+            perm = rng.permutation(ndim)
+            big = rng.uniform(0.2, 2.0, [2 * shp[p] + 1 for p in perm]).astype(np.float32)
+            view = big.transpose(np.argsort(perm))[tuple(slice(1, 1 + 2 * e, 2) for e in shp)]
+        inputs.append(view)
+        vals.append(s.input("f32", bc))
+    vals.append(s.scalar("f32"))
+    reduce_axes = None
+    if rng.integers(0, 2):
+        # reductions the kernel classes cover: over the trailing axes of a contiguous operand
+        k = int(rng.integers(1, ndim + 1))
+        reduce_axes = tuple(range(ndim - k, ndim))
+        inputs[0] = np.ascontiguousarray(inputs[0])
+    for _ in range(int(rng.integers(2, 8))):
+        r = rng.integers(0, 10)
+        a = vals[int(rng.integers(len(vals)))]
+        if r < 4:
+            op = SAFE_UN[int(rng.integers(len(SAFE_UN)))]
+            if op in ("log", "recip"):
+                v = s.apply(op, s.add(s.apply("abs", a), s.const(0.5)))
+            elif op in ("sqrt", "log1p"):
+                v = s.apply(op, s.apply("abs", a))
+            else:
+                v = s.apply(op, a)
+        elif r < 8:
+            op = ["add", "mul", "max", "min", "sub"][int(rng.integers(5))]
+            v = s.apply(op, a, vals[int(rng.integers(len(vals)))])
+        else:
+            b, c = (vals[int(rng.integers(len(vals)))] for _ in range(2))
+            v = s.apply("where", s.apply("gt", a, b), c, a)
+        v = s.apply("tanh", v) if rng.integers(0, 3) == 0 else v
+        vals.append(v)
+    s.output(vals[-1], "f32")
+    if reduce_axes is not None:
+        x0 = vals[0]
+        red = ["sum", "max", "min"][int(rng.integers(3))]
+        s.output(s.reduce(red, s.apply("tanh", s.mul(x0, vals[-1])), reduce_axes), "f32")
+        s.outputs = s.outputs[int(rng.integers(0, 2)):]     # sometimes reduce-only
+    return s, inputs, [float(rng.uniform(0.5, 1.5))]
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_graphs_and_layouts(seed, oracle, G):
+    s, inputs, scal = random_case(seed)
+    print(f"[case] fuzz seed {seed} ndim {s.ndim} shapes {[a.shape for a in inputs]} strides "
+          f"{[tuple(x // 4 for x in a.strides) for a in inputs]} outputs {len(s.outputs)}", flush=True)
+    want = oracle.evaluate(s, inputs, scal)
+    try:
+        expr, got = run_spec(G, s, inputs, scal)
+    except G.ewf.EwfError as e:
+        if e.status == G.ewf.EUNSUPPORTED:
+            pytest.skip(f"layout not covered by a kernel class: {e.message}")
+        raise
+    for k, (g_, w_) in enumerate(zip(got, want)):
+        # structural test (indexing, broadcast, strides): looser than the per-op accuracy bar
+        # because random chains amplify float32 rounding
+        G.h.compare(f"seed{seed}.out{k}", g_, w_, 2e-4, 2e-5)

@@ -1,0 +1,401 @@
+"""Host-only tests of the library: the C ABI surface, graph validation, the stride /
+broadcast canonicaliser, kernel-class selection and run-time code generation (the run-time
+compiler cross-compiles for gfx950 without a GPU).  No kernel is launched here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1605_02688_amd import ewf
+from paper_1605_02688_amd.selfcheck import plan_layout
+from workloads import GraphSpec
+from workloads import configs as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BASE = 0x7F0000000000
+
+
+def contig(shape):
+    st, acc = [], 1
+    for e in reversed(shape):
+        st.append(acc)
+        acc *= e
+    return tuple(reversed(st))
+
+
+def ref(addr, shape, strides=None):
+    return ewf.TensorRef(addr, tuple(shape), tuple(strides) if strides is not None else contig(shape))
+
+
+def plan_workload(w, **opts):
+    expr = ewf.Expression(w.spec, **opts)
+    ws, info = plan_layout(expr, w.spec, w.views, [w.buffers[v.buffer].itemsize for v in w.views])
+    return expr, ws, info
+
+
+def strides_of(expr, info):
+    return [ewf.debug_operand_strides(expr.handle, k, info["rank"]) for k in range(info["noperands"])]
+
+
+# ------------------------------------------------------------------ ABI surface
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ewf.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ewf_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 20
+    import ctypes
+    lib = ctypes.CDLL(ewf.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in ewf.h but not exported"
+    assert declared == set(ewf.EXPORTED)
+
+
+def test_error_message_is_thread_local_text():
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.graph_create(99)
+    assert e.value.status == ewf.EINVAL and "rank" in e.value.message
+
+
+# ------------------------------------------------------------------ graph validation
+
+def test_type_rules():
+    g = ewf.graph_create(1)
+    f = ewf.input(g, ewf.F32, [0]); i = ewf.input(g, ewf.I32, [0]); h = ewf.input(g, ewf.F16, [0])
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.apply(g, ewf.OPS["add"], [f, i])
+    assert e.value.status == ewf.ETYPE
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.apply(g, ewf.OPS["exp"], [i])
+    assert e.value.status == ewf.ETYPE
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.apply(g, ewf.OPS["add"], [f])
+    assert e.value.status == ewf.EINVAL
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.apply(g, ewf.OPS["add"], [f, 77])
+    assert e.value.status == ewf.EINVAL
+    assert ewf.apply(g, ewf.OPS["add"], [f, h]) >= 0            # f16 storage is an f32 value
+    c = ewf.apply(g, ewf.OPS["gt"], [f, h])
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.output(g, c, ewf.F32)                                 # comparison results are int32
+    assert e.value.status == ewf.ETYPE
+    ewf.output(g, c, ewf.I32)
+    ewf.output(g, ewf.cast(g, c, ewf.F32), ewf.F16)
+    with pytest.raises(ewf.EwfError):
+        ewf.scalar(g, ewf.F16)
+    with pytest.raises(ewf.EwfError):
+        ewf.iota(g, 1)
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.reduce(g, ewf.REDOPS["sum"], f, [1], False)
+    assert e.value.status == ewf.EINVAL
+    with pytest.raises(ewf.EwfError):
+        ewf.reduce(g, ewf.REDOPS["sum"], f, [0, 0], False)
+    ewf.graph_destroy(g)
+    g = ewf.graph_create(2)
+    x = ewf.input(g, ewf.F32, [0, 0])
+    with pytest.raises(ewf.EwfError):
+        ewf.reduce(g, ewf.REDOPS["argmax"], x, [0, 1], False)      # argmax: one axis
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.compile(g)                                            # no output declared
+    assert e.value.status == ewf.EINVAL
+    ewf.graph_destroy(g)
+
+
+def test_output_shapes_follow_keep_flag():
+    w = wl.layout_only(wl.c3_softmax_xent, rows=12, vocab=30)
+    expr = ewf.Expression(w.spec)
+    ins = [ref(BASE, (12, 30)), ref(BASE + (1 << 20), (12, 1))]
+    assert expr.output_shapes(ins) == [(12,), (12,), (12,), (12,), (), (12,)]
+    s = GraphSpec(3)
+    x = s.input("f32", (False, False, False))
+    r = s.reduce("sum", x, (0, 2), keep=True)
+    s.output(r, "f32")
+    s.output(s.mul(r, s.reduce("max", x, (2,), keep=False)), "f32")
+    expr = ewf.Expression(s)
+    # an axis dropped by any operand stays dropped where the result is broadcastable
+    assert expr.output_shapes([ref(BASE, (4, 5, 6))]) == [(1, 5, 1), (4, 5)]
+
+
+# ------------------------------------------------------------------ canonical forms of the workloads
+
+def test_c1_canonical_form():
+    expr, ws, info = plan_workload(wl.layout_only(wl.c1_affine_tanh))
+    assert info["kernel_class"] == "tile" and ws == 0
+    assert info["rank"] == 2 and info["extent"] == (1024, 256)       # b [1,256] blocks the merge
+    assert info["vec"] == 4 and info["index_bits"] == 32
+    assert strides_of(expr, info) == [(256, 1), (0, 1), (256, 1)]
+
+
+def test_c2_canonical_form():
+    expr, ws, info = plan_workload(wl.layout_only(wl.c2_lstm_cell))
+    assert info["kernel_class"] == "tile" and info["extent"] == (64, 1024) and info["vec"] == 4
+    st = strides_of(expr, info)
+    assert st[:4] == [(4096, 1)] * 4 and st[4:8] == [(0, 1)] * 4 and st[8:] == [(1024, 1)] * 3
+
+
+def test_c3_canonical_form():
+    expr, ws, info = plan_workload(wl.layout_only(wl.c3_softmax_xent))
+    assert info["kernel_class"] == "row" and info["extent"] == (1280, 10000)
+    assert info["reduced"] == (False, True) and info["vec"] == 4
+    st = strides_of(expr, info)
+    assert st[0] == (10000, 1) and st[1] == (1, 0)
+    assert ws == 1280 * 4                                            # one loss value per row
+
+
+def test_c4_canonical_form():
+    expr, ws, info = plan_workload(wl.layout_only(wl.c4_bias_relu_chansum))
+    assert info["kernel_class"] == "tile_reduce"
+    assert info["extent"] == (128, 64, 12544) and info["reduced"] == (True, False, True)
+    st = strides_of(expr, info)
+    assert st[0] == (802816, 12544, 1) and st[1] == (0, 1, 0) and st[2] == (0, 1, 0)
+    assert st[3] == (802816, 12544, 1) and st[4] == (0, 1, 0)
+    assert info["tile"][0] == 1 and info["tile"][1] == 1              # a tile never leaves its channel
+
+
+@pytest.mark.parametrize("reading,x3", [("A", (802816, 1, 14336, 256)), ("B", (802816, 56, 1, 14336))])
+def test_c5_canonical_form(reading, x3):
+    expr, ws, info = plan_workload(wl.layout_only(wl.c5_stress, reading=reading), no_lds_staging=1)
+    assert info["kernel_class"] == "tile" and info["extent"] == (64, 256, 56, 56)   # nothing merges
+    assert info["vec"] == 8 and info["index_bits"] == 32
+    st = strides_of(expr, info)
+    assert st[0] == st[1] == st[2] == st[6] == (802816, 3136, 56, 1)
+    assert st[3] == x3 and st[4] == (0, 56, 0, 1) and st[5] == (0, 56, 1, 0)
+
+
+def test_contiguous_operands_collapse_to_one_dimension():
+    s = GraphSpec(4)
+    s.output(s.apply("exp", s.add(s.input("f32", (False,) * 4), s.input("f32", (False,) * 4))), "f32")
+    expr = ewf.Expression(s)
+    shape = (6, 5, 4, 8)
+    expr.plan([ref(BASE, shape), ref(BASE + (1 << 24), shape)], [ref(BASE + (2 << 24), shape)])
+    info = expr.info()
+    assert info["rank"] == 1 and info["extent"] == (960,) and info["vec"] == 4
+    # a transposed input keeps two dimensions; the output's memory order leads
+    expr.plan([ref(BASE, (6, 5, 4, 8)), ref(BASE + (1 << 24), shape, (160, 8, 40, 1))], [ref(BASE + (2 << 24), shape)])
+    info = expr.info()
+    assert info["extent"] == (6, 5, 4, 8)[0:1] + (5, 4, 8) or info["rank"] >= 3
+
+
+def test_extent_one_dimensions_disappear_and_single_element():
+    s = GraphSpec(3)
+    s.output(s.apply("tanh", s.input("f32", (False, False, False))), "f32")
+    expr = ewf.Expression(s)
+    expr.plan([ref(BASE, (1, 7, 1))], [ref(BASE + 4096, (1, 7, 1))])
+    assert expr.info()["extent"] == (7,)
+    expr.plan([ref(BASE, (1, 1, 1))], [ref(BASE + 4096, (1, 1, 1))])
+    assert expr.info()["extent"] == (1,) and expr.info()["grid_blocks"] == 1
+
+
+def test_vector_width_follows_alignment_and_extent():
+    s = GraphSpec(2)
+    s.output(s.apply("neg", s.input("f32", (False, False))), "f32")
+    expr = ewf.Expression(s)
+    expr.plan([ref(BASE, (8, 64))], [ref(BASE + (1 << 20), (8, 64))])
+    assert expr.info()["vec"] == 4
+    expr.plan([ref(BASE + 8, (8, 64))], [ref(BASE + (1 << 20), (8, 64))])       # 8-byte aligned input
+    assert expr.info()["vec"] == 2
+    expr.plan([ref(BASE + 4, (8, 64))], [ref(BASE + (1 << 20), (8, 64))])
+    assert expr.info()["vec"] == 1
+    expr.plan([ref(BASE, (8, 63), (64, 1))], [ref(BASE + (1 << 20), (8, 63), (64, 1))])  # odd row length
+    assert expr.info()["vec"] == 1
+    expr.plan([ref(BASE, (8, 62), (66, 1))], [ref(BASE + (1 << 20), (8, 62), (66, 1))])  # rows 8-byte aligned
+    assert expr.info()["vec"] == 2
+    e2 = ewf.Expression(s, force_scalar=1)
+    e2.plan([ref(BASE, (8, 64))], [ref(BASE + (1 << 20), (8, 64))])
+    assert e2.info()["vec"] == 1
+
+
+def test_index_width_selection():
+    s = GraphSpec(2)
+    s.output(s.apply("neg", s.input("f16", (False, False))), "f16")
+    expr = ewf.Expression(s)
+    expr.plan([ref(BASE, (1 << 15, 1 << 15))], [ref(BASE + (1 << 40), (1 << 15, 1 << 15))])
+    assert expr.info()["index_bits"] == 32                         # 2^30 elements
+    expr.plan([ref(BASE, (1 << 16, 1 << 15))], [ref(BASE + (1 << 40), (1 << 16, 1 << 15))])
+    assert expr.info()["index_bits"] == 64                         # 2^31 elements
+    # few elements but a huge stride also needs 64-bit offsets
+    expr.plan([ref(BASE, (4, 16), (1 << 31, 1))], [ref(BASE + (1 << 40), (4, 16))])
+    assert expr.info()["index_bits"] == 64
+    e2 = ewf.Expression(s, force_index64=1)
+    e2.plan([ref(BASE, (4, 16))], [ref(BASE + (1 << 40), (4, 16))])
+    assert e2.info()["index_bits"] == 64 and "long long idx_t" in e2.source()
+
+
+# ------------------------------------------------------------------ shape / alias / argument errors
+
+def _add2():
+    s = GraphSpec(2)
+    s.output(s.add(s.input("f32", (False, False)), s.input("f32", (True, False))), "f32")
+    return ewf.Expression(s)
+
+
+def test_broadcast_pattern_is_enforced():
+    expr = _add2()
+    out = ref(BASE + (2 << 20), (3, 4))
+    expr.plan([ref(BASE, (3, 4)), ref(BASE + (1 << 20), (1, 4))], [out])
+    with pytest.raises(ewf.EwfError) as e:                           # flagged dimension with extent 3
+        expr.plan([ref(BASE, (3, 4)), ref(BASE + (1 << 20), (3, 4))], [out])
+    assert e.value.status == ewf.ESHAPE
+    with pytest.raises(ewf.EwfError) as e:                           # unflagged extent 1 never broadcasts
+        expr.plan([ref(BASE, (1, 4)), ref(BASE + (1 << 20), (1, 4))], [out])
+    assert e.value.status == ewf.ESHAPE
+    with pytest.raises(ewf.EwfError) as e:
+        expr.plan([ref(BASE, (3, 4)), ref(BASE + (1 << 20), (1, 5))], [out])
+    assert e.value.status == ewf.ESHAPE
+    with pytest.raises(ewf.EwfError) as e:
+        expr.plan([ref(BASE, (3, 4)), ref(BASE + (1 << 20), (1, 4))], [ref(BASE + (2 << 20), (4, 3))])
+    assert e.value.status == ewf.ESHAPE
+    with pytest.raises(ewf.EwfError) as e:
+        expr.plan([ref(BASE, (3, 4))], [out])
+    assert e.value.status == ewf.EINVAL
+    with pytest.raises(ewf.EwfError) as e:
+        expr.plan([ref(BASE, (3, 4), (4, -1)), ref(BASE + (1 << 20), (1, 4))], [out])
+    assert e.value.status == ewf.EINVAL
+    with pytest.raises(ewf.EwfError) as e:
+        expr.plan([ref(0, (3, 4)), ref(BASE + (1 << 20), (1, 4))], [out])
+    assert e.value.status == ewf.EINVAL
+
+
+def test_aliasing_rules():
+    expr = _add2()
+    a = ref(BASE, (8, 16)); b = ref(BASE + (1 << 20), (1, 16))
+    expr.plan([a, b], [ref(BASE, (8, 16))])                            # exact alias: in place
+    with pytest.raises(ewf.EwfError) as e:                             # shifted by one row
+        expr.plan([a, b], [ref(BASE + 64, (8, 16))])
+    assert e.value.status == ewf.EALIAS
+    with pytest.raises(ewf.EwfError) as e:                             # same memory, transposed walk
+        expr.plan([ref(BASE, (16, 16)), ref(BASE + (1 << 20), (1, 16))], [ref(BASE, (16, 16), (1, 16))])
+    assert e.value.status == ewf.EALIAS
+    with pytest.raises(ewf.EwfError) as e:                             # output that writes an element twice
+        expr.plan([a, b], [ref(BASE + (2 << 20), (8, 16), (0, 1))])
+    assert e.value.status == ewf.EALIAS
+    # column blocks of one buffer interleave in address range but share no element
+    expr.plan([ref(BASE, (8, 16), (64, 1)), b], [ref(BASE + 16 * 4, (8, 16), (64, 1))])
+    with pytest.raises(ewf.EwfError) as e:
+        expr.plan([ref(BASE, (8, 16), (64, 1)), b], [ref(BASE + 8 * 4, (8, 16), (64, 1))])
+    assert e.value.status == ewf.EALIAS
+    # two outputs must not share elements either
+    s = GraphSpec(1)
+    x = s.input("f32", (False,))
+    s.output(s.apply("exp", x), "f32"); s.output(s.apply("neg", x), "f32")
+    e2 = ewf.Expression(s)
+    with pytest.raises(ewf.EwfError) as e:
+        e2.plan([ref(BASE, (64,))], [ref(BASE + 4096, (64,)), ref(BASE + 4096 + 128, (64,))])
+    assert e.value.status == ewf.EALIAS
+    e2.plan([ref(BASE, (64,))], [ref(BASE + 4096, (64,)), ref(BASE + 8192, (64,))])
+
+
+def test_zero_size_is_success_without_kernel():
+    expr = _add2()
+    ws = expr.plan([ref(0, (0, 4)), ref(BASE, (1, 4))], [ref(0, (0, 4))])
+    assert ws == 0 and expr.info()["kernel_class"] == "none"
+    s = GraphSpec(2)
+    s.output(s.reduce("max", s.input("f32", (False, False)), (1,)), "f32")
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.Expression(s).plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))])
+    assert e.value.status == ewf.ESHAPE
+
+
+# ------------------------------------------------------------------ kernel classes and code generation
+
+def test_kernel_class_selection():
+    def red(ndim, axes, shape, strides=None, extra=None):
+        s = GraphSpec(ndim)
+        x = s.input("f32", (False,) * ndim)
+        r = s.reduce("sum", x, axes)
+        s.output(r, "f32")
+        if extra:
+            extra(s, x, r)
+        expr = ewf.Expression(s)
+        ins = [ref(BASE, shape, strides)]
+        outs = [ref(BASE + (1 << 36) + k * (1 << 32), sh) for k, sh in enumerate(expr.output_shapes(ins))]
+        expr.plan(ins, outs)
+        return expr.info()
+    assert red(2, (1,), (4096, 512))["kernel_class"] == "row"            # many short rows
+    assert red(2, (1,), (4, 1 << 20))["kernel_class"] == "tile_reduce"    # few long rows: split them
+    assert red(1, (0,), (1 << 20,))["kernel_class"] == "tile_reduce"      # full reduction
+    assert red(3, (0, 2), (8, 16, 256))["kernel_class"] == "tile_reduce"
+    assert red(3, (1, 2), (64, 8, 32))["extent"] == (64, 256)            # reduced axes merge
+    # softmax: the output depends on a reduction and varies along the row -> row-resident class
+    info = red(2, (1,), (4, 1000), extra=lambda s, x, r: s.output(s.div(x, r), "f32"))
+    assert info["kernel_class"] == "row"
+    with pytest.raises(ewf.EwfError) as e:                                # column reduction: not yet covered
+        red(2, (0,), (512, 512))
+    assert e.value.status == ewf.EUNSUPPORTED
+    # reducing over extent-1 axes is the identity: plain element-wise kernel
+    assert red(2, (1,), (64, 1))["kernel_class"] == "tile"
+
+
+def test_generated_source_structure_and_cache():
+    w = wl.layout_only(wl.c1_affine_tanh)
+    w.spec.nodes.append(("const", "f32", 0.12345678))       # makes this source unique in the process-wide cache
+    expr, _, info = plan_workload(w)
+    src = expr.source()
+    assert "ewf_kernel" in src and "ewf_acc::tanh" in src and "ewf_ld<float, EWF_VEC>" in src
+    assert "p.s0" in src                                   # the run-time scalar is a kernel argument
+    n0 = ewf.debug_compile_count(expr.handle)
+    assert n0 <= 1
+    # another number of rows: same layout class, same source, nothing recompiled
+    w2 = wl.layout_only(wl.c1_affine_tanh, rows=4096)
+    ws, info2 = plan_layout(expr, w2.spec, w2.views, [4, 4])
+    assert expr.source() == src and ewf.debug_compile_count(expr.handle) == n0
+    # a literal is baked into the code
+    wc = wl.layout_only(wl.c1_affine_tanh, a_form="const")
+    exprc, _, _ = plan_workload(wc)
+    assert "0x3f000000" in exprc.source() and "p.s0" not in exprc.source()
+
+
+def test_math_mode_follows_storage():
+    w5 = wl.layout_only(wl.c5_stress, n=2)
+    e5, _, _ = plan_workload(w5)
+    assert "ewf_fast::exp" in e5.source() and "ewf_acc::" not in e5.source()
+    e5a, _, _ = plan_workload(w5, math_mode=1)
+    assert "ewf_acc::exp" in e5a.source()
+    w1 = wl.layout_only(wl.c1_affine_tanh)
+    e1, _, _ = plan_workload(w1, math_mode=2)
+    assert "ewf_fast::tanh" in e1.source()
+
+
+def test_streaming_hint_only_for_large_operands():
+    small, _, _ = plan_workload(wl.layout_only(wl.c4_bias_relu_chansum, n=2))
+    assert "ewf_ld_nt" not in small.source()
+    big, _, _ = plan_workload(wl.layout_only(wl.c4_bias_relu_chansum))
+    assert "ewf_ld_nt<float" in big.source() and "ewf_st_nt<float" in big.source()
+    assert "ewf_finish" in big.source()                    # partial sums are folded by a second kernel
+    off, _, _ = plan_workload(wl.layout_only(wl.c4_bias_relu_chansum), streaming=2)
+    assert "ewf_ld_nt" not in off.source()
+
+
+def test_unsupported_structures_are_reported():
+    # reductions over different axis sets in one expression
+    s = GraphSpec(2)
+    x = s.input("f32", (False, False))
+    s.output(s.reduce("sum", x, (1,)), "f32"); s.output(s.reduce("sum", x, (0,)), "f32")
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.Expression(s).plan([ref(BASE, (64, 64))], [ref(BASE + 65536, (64,)), ref(BASE + 131072, (64,))])
+    assert e.value.status == ewf.EUNSUPPORTED and "axis sets" in e.value.message
+    # a value that mixes a cross-row reduction with per-row values needs a grid-wide dependency
+    w = wl.layout_only(wl.c3_softmax_xent, rows=8, vocab=16)
+    s = w.spec
+    loss = s.outputs[3][0]; mean = s.outputs[4][0]
+    s.output(s.sub(loss, mean), "f32")
+    expr = ewf.Expression(s)
+    ins = [ref(BASE, (8, 16)), ref(BASE + 4096, (8, 1))]
+    outs = [ref(BASE + 8192 + 512 * k, sh) for k, sh in enumerate(expr.output_shapes(ins))]
+    with pytest.raises(ewf.EwfError) as e:
+        expr.plan(ins, outs)
+    assert e.value.status == ewf.EUNSUPPORTED
+
+
+def test_run_argument_checks_without_device():
+    expr = _add2()
+    ins = [ref(BASE, (3, 4)), ref(BASE + (1 << 20), (1, 4))]
+    out = [ref(BASE + (2 << 20), (3, 4))]
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.run(expr.handle, ins, [1.0], out)                  # the graph has no run-time scalar
+    assert e.value.status == ewf.EINVAL
+    # a reduce plan needs a workspace of the planned size
+    w = wl.layout_only(wl.c4_bias_relu_chansum, n=2)
+    e4, ws, _ = plan_workload(w)
+    assert ws > 0
