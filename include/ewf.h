@@ -87,8 +87,11 @@ typedef struct ewf_exec ewf_exec;
 
 /* Compile options; zero-initialise for defaults. */
 typedef struct {
-    int32_t math_mode;      /* 0 auto (native-rate transcendentals iff every output is stored
-                               as float16), 1 accurate float32 routines, 2 native-rate        */
+    int32_t math_mode;      /* 1 accurate float32 routines (about one unit in the last place);
+                               2 native-rate exp2/log2/rcp with fix-ups that keep log1p, expm1
+                               and tanh relatively accurate near zero; 3 native-rate without
+                               them (absolute error near zero about 6e-8); 0 auto: 3 iff every
+                               output is stored as float16, else 1                            */
     int32_t force_scalar;   /* 1: never use vector (multi-element) memory accesses           */
     int32_t force_index64;  /* 1: 64-bit offset arithmetic even when 32 bits suffice         */
     int32_t block_threads;  /* 0 = library default                                           */
@@ -98,7 +101,10 @@ typedef struct {
     int32_t streaming;      /* non-temporal accesses for operands touched once: 0 auto (operands
                                of 32 MiB or more), 1 always, 2 never                          */
     int32_t tile_elems;     /* elements per tile (per workgroup and loop trip); 0 = default  */
-    int32_t reserved[7];
+    int32_t waves_per_simd; /* register budget hint: resident wavefronts per SIMD to aim for
+                               (1..8); 0 = compiler default                                   */
+    int32_t no_prefetch;    /* 1: do not issue the next trip's loads ahead of the arithmetic */
+    int32_t reserved[5];
 } ewf_options;
 
 /* A strided n-d view of caller-owned device memory.  rank is implied by the graph (inputs:

@@ -185,7 +185,9 @@ ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **o
     if (st != EWF_OK) { delete x; return st; }
     bool all_f16 = true;
     for (const OutputDecl &o : x->e.g.outputs) if (o.storage != EWF_F16) all_f16 = false;
-    x->e.fast_math = x->e.opts.math_mode == 2 || (x->e.opts.math_mode == 0 && all_f16);
+    const int mm = x->e.opts.math_mode;
+    if (mm < 0 || mm > 3) { delete x; set_error("math_mode must be 0..3"); return EWF_EINVAL; }
+    x->e.math_flavour = mm == 0 ? (all_f16 ? 3 : 1) : mm;
     *out = x;
     return EWF_OK;
 }
@@ -284,7 +286,7 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
     size_t arg_size = p->args.size();
     void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
     hipError_t he = hipModuleLaunchKernel((hipFunction_t)p->function, (unsigned)p->grid, 1, 1, (unsigned)p->block, 1, 1,
-                                          (unsigned)p->lds_bytes, (hipStream_t)hip_stream, nullptr, config);
+                                          0 /* LDS is declared statically in the kernels */, (hipStream_t)hip_stream, nullptr, config);
     if (he != hipSuccess) { set_error("kernel launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
     if (p->finish_grid > 0) {
         // partial results are folded by a second kernel on the same stream

@@ -283,6 +283,7 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
         max_off = std::max(max_off, off);
     }
     c.idx64 = e.opts.force_index64 || max_off >= ((int64_t)1 << 31) - 65536;
+    c.byte32 = !c.idx64 && max_off < ((int64_t)1 << 30) - 65536;
 
     // ---- vector width and access class along the innermost dimension
     const int in_d = c.rank - 1;

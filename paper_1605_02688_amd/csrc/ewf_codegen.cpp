@@ -114,6 +114,51 @@ struct Gen {
     std::vector<char> is_level, is_cross;     // per node
     std::vector<char> after_cross;
     std::vector<char> live;
+    std::vector<char> nonneg, positive;       // sign facts provable from the graph alone
+
+    // A small sign analysis over the scalar graph, in the spirit of the specialisation stage
+    // of paper section 2.2.1: when the base of a power is provably positive (x*x + 1, exp(u),
+    // a positive literal ...) the cheap exp2(y*log2(x)) form needs no sign handling.
+    void analyse_signs()
+    {
+        const int N = (int)g.nodes.size();
+        nonneg.assign(N, 0); positive.assign(N, 0);
+        for (int n = 0; n < N; n++) {
+            const Node &nd = g.nodes[n];
+            if (nd.vtype != EWF_F32) continue;
+            auto P = [&](int a) { return positive[nd.args[a]] != 0; };
+            auto Z = [&](int a) { return nonneg[nd.args[a]] != 0; };
+            bool pos = false, nn = false;
+            switch (nd.kind) {
+            case NodeKind::Const: pos = nd.cval > 0 && (float)nd.cval > 0.0f; nn = nd.cval >= 0; break;
+            case NodeKind::Cast: if (g.nodes[nd.args[0]].vtype == EWF_F32 && nd.op != EWF_I32) { nn = Z(0); pos = nd.op == EWF_F32 && P(0); } break;
+            case NodeKind::Reduce:
+                if (nd.op == EWF_RSUM || nd.op == EWF_RMAX || nd.op == EWF_RMIN) nn = Z(0);
+                if (nd.op == EWF_RMAX || nd.op == EWF_RMIN) pos = P(0);
+                break;
+            case NodeKind::Apply:
+                switch (nd.op) {
+                case EWF_ABS: case EWF_SQR: case EWF_SQRT: nn = true; break;
+                case EWF_EXP: nn = true; break;            // may underflow to zero
+                case EWF_SIGMOID: nn = true; break;
+                case EWF_MUL: nn = (nd.args[0] == nd.args[1]) || (Z(0) && Z(1)); break;
+                case EWF_ADD: nn = Z(0) && Z(1); pos = nn && (P(0) || P(1)); break;
+                case EWF_DIV: nn = Z(0) && P(1); break;
+                case EWF_RECIP: nn = P(0); break;
+                case EWF_MAX: nn = Z(0) || Z(1); pos = P(0) || P(1); break;
+                case EWF_MIN: nn = Z(0) && Z(1); pos = P(0) && P(1); break;
+                case EWF_WHERE: nn = Z(1) && Z(2); pos = P(1) && P(2); break;
+                case EWF_LOG1P: nn = Z(0); break;
+                case EWF_EXPM1: nn = Z(0); break;
+                case EWF_TANH: nn = Z(0); break;
+                default: break;
+                }
+                break;
+            default: break;
+            }
+            positive[n] = pos; nonneg[n] = nn || pos;
+        }
+    }
 
     Gen(const Exec &e_, Plan &p_) : e(e_), p(p_), g(e_.g), c(p_.canon), red(p_.red)
     {
@@ -130,6 +175,7 @@ struct Gen {
             if (is_cross[n]) after_cross[n] = 1;
             for (int a = 0; a < g.nodes[n].nargs; a++) if (after_cross[g.nodes[n].args[a]]) after_cross[n] = 1;
         }
+        analyse_signs();
     }
 
     bool real_reduce(int n) const { return is_level[n] || is_cross[n]; }
@@ -170,7 +216,7 @@ struct Gen {
     // Emits `const T v<n> = ...;` for every needed node, in graph order.
     void emit_values(const std::vector<char> &need, const EmitCtx &cx, const std::string &ind)
     {
-        const char *M = e.fast_math ? "ewf_fast" : "ewf_acc";
+        const char *M = e.math_flavour == 3 ? "ewf_bare" : e.math_flavour == 2 ? "ewf_fast" : "ewf_acc";
         for (size_t n = 0; n < need.size(); n++) {
             if (!need[n]) continue;
             const Node &nd = g.nodes[n];
@@ -214,7 +260,7 @@ struct Gen {
                 case EWF_TANH: rhs = std::string(M) + "::tanh(" + a0 + ")"; break;
                 case EWF_SIGMOID: rhs = std::string(M) + "::sigmoid(" + a0 + ")"; break;
                 case EWF_RECIP: rhs = std::string(M) + "::recip(" + a0 + ")"; break;
-                case EWF_POW: rhs = std::string(M) + "::pow(" + a0 + ", " + a1 + ")"; break;
+                case EWF_POW: rhs = std::string(M) + (positive[nd.args[0]] ? "::pow_pos(" : "::pow(") + a0 + ", " + a1 + ")"; break;
                 case EWF_MAX: rhs = "ewf_max(" + a0 + ", " + a1 + ")"; break;
                 case EWF_MIN: rhs = "ewf_min(" + a0 + ", " + a1 + ")"; break;
                 case EWF_WHERE: rhs = "(ewf_truth(" + a0 + ") ? " + a1 + " : " + a2 + ")"; break;
@@ -347,6 +393,9 @@ struct Gen {
         o << "#define EWF_VEC " << VEC << "\n";
         o << "#define EWF_FIN_BLOCK 256\n";
         o << "typedef " << (c.idx64 ? "long long" : "int") << " idx_t;\n";
+        // offsets inside a tile are never negative; when every operand spans less than 4 GiB
+        // they are kept as 32-bit byte offsets from a uniform base
+        o << "typedef " << (c.byte32 ? "unsigned" : "long long") << " ioff_t;\n";
     }
 
     void build_layout()
@@ -386,6 +435,12 @@ struct Gen {
         o << ";\n";
     }
 
+    std::string occupancy_attr() const
+    {
+        if (e.opts.waves_per_simd < 1 || e.opts.waves_per_simd > 8) return "";
+        return "__attribute__((amdgpu_waves_per_eu(" + std::to_string(e.opts.waves_per_simd) + "))) ";
+    }
+
     ewf_status fail(const std::string &why)
     {
         set_error("%s", why.c_str());
@@ -403,9 +458,28 @@ static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 ewf_status Gen::gen_tile(bool with_reduce)
 {
-    const int block = e.opts.block_threads > 0 ? e.opts.block_threads : 256;
+    // vectors in flight per thread: two for streaming expressions; one when the expression is
+    // heavy in transcendental operations, where registers (occupancy) matter more
+    int heavy = 0;
+    for (size_t n = 0; n < g.nodes.size(); n++) {
+        if (!live[n] || g.nodes[n].kind != NodeKind::Apply) continue;
+        switch (g.nodes[n].op) {
+        case EWF_EXP: case EWF_LOG: case EWF_LOG1P: case EWF_TANH: case EWF_SIGMOID: case EWF_EXPM1: heavy += 1; break;
+        case EWF_POW: heavy += 2; break;
+        default: break;
+        }
+    }
+    // small problems are latency-bound: one vector per thread and small workgroups, so that
+    // every compute unit gets work and nobody loops
+    const int64_t items = c.total / VEC;
+    const bool small = items < (int64_t)256 * 512;
+    const int U = e.opts.unroll > 0 ? e.opts.unroll : ((heavy >= 4 || small) ? 1 : 2);
+    // arithmetic-heavy expressions run best with larger workgroups (measured on the 21-op
+    // float16 workload: 512 threads beat 256 by 4-8 %), streaming ones with 256
+    int block = heavy >= 4 ? 512 : 256;
+    if (small) { block = 64; while (block < 256 && items / block > 512) block *= 2; }
+    if (e.opts.block_threads > 0) block = e.opts.block_threads;
     if (block % 64 || block > 1024) return fail("block_threads must be a multiple of 64, at most 1024");
-    const int U = e.opts.unroll > 0 ? e.opts.unroll : 2;
     p.block = block;
 
     // ---- outputs by role
@@ -422,7 +496,10 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // ---- tile shape: innermost dimensions first, never across a group boundary
     int64_t T[kMaxDims];
     for (int d = 0; d < kMaxDims; d++) T[d] = 1;
-    int64_t target = (int64_t)block * VEC * U * (with_reduce ? 4 : 1);
+    // several trips per tile amortise the per-tile address set-up; small problems keep
+    // one trip per tile so that they still spread over the whole chip
+    const int64_t one_trip = (int64_t)block * VEC * U;
+    int64_t target = one_trip * ((with_reduce || c.total >= one_trip * 4 * 2048) ? 4 : 1);
     if (e.opts.tile_elems > 0) target = e.opts.tile_elems;
     {
         int64_t rem = target;
@@ -436,6 +513,120 @@ ewf_status Gen::gen_tile(bool with_reduce)
             break;
         }
     }
+    // ---- permuted operands: stage through LDS
+    // An operand whose own fastest dimension is not the output's would be read with one
+    // narrow access per element.  Instead the workgroup reads the operand's part of the tile
+    // along the operand's fastest dimension with wide accesses, scatters it into an LDS copy
+    // of the tile laid out in the output's order, and the compute phase reads it back with
+    // one wide LDS access per vector.  The tile is shaped so that both sides see long runs.
+    std::vector<int> staged;                           // operand numbers
+    std::vector<int> sdims;                            // dims ordered by the staged operand's stride
+    int VS = 1;
+    if (!with_reduce && !e.opts.no_lds_staging && c.total >= 65536 && R >= 2) {
+        std::vector<char> need0 = needed(std::vector<int>());
+        for (int k = 0; k < nin && staged.empty(); k++) {
+            const Operand &op = c.ops[k];
+            if (op.access != Access::Gather) continue;
+            bool full = true; int s0 = -1;
+            for (int d = 0; d < R; d++) { if (op.stride[d] == 0) full = false; if (op.stride[d] == 1) s0 = d; }
+            if (!full || s0 < 0 || c.extent[s0] < 16) continue;
+            staged.push_back(k);
+        }
+        (void)need0;
+    }
+    if (!staged.empty()) {
+        const Operand &S = c.ops[staged[0]];
+        const int szS = isz(S.storage);
+        for (int d = 0; d < R; d++) sdims.push_back(d);
+        std::sort(sdims.begin(), sdims.end(), [&](int a, int b) { return S.stride[a] < S.stride[b]; });
+        // other permuted operands that walk memory in the same order share the tile
+        for (int k = 0; k < nin; k++) {
+            if (k == staged[0] || c.ops[k].access != Access::Gather || isz(c.ops[k].storage) != szS) continue;
+            bool same = true;
+            for (int d = 0; d < R; d++) if (c.ops[k].stride[d] != S.stride[d]) same = false;
+            if (same) staged.push_back(k);
+        }
+        const int64_t budget = (e.opts.tile_elems > 0 ? e.opts.tile_elems : 32768 / szS);
+        for (int d = 0; d < kMaxDims; d++) T[d] = 1;
+        // runs of at least 128 bytes along the staged operand's memory order
+        int64_t need_run = 128 / szS;
+        for (size_t i = 0; i < sdims.size() && need_run > 1; i++) {
+            int d = sdims[i];
+            T[d] = std::min<int64_t>(c.extent[d], need_run);
+            if (T[d] < c.extent[d]) break;
+            if (i + 1 < sdims.size() && S.stride[sdims[i + 1]] != S.stride[d] * c.extent[d]) break;
+            need_run = ceil_div(need_run, T[d]);
+        }
+        // then the longest runs along the output's order that the LDS budget allows
+        for (int d = R - 1; d >= 0; d--) {
+            int64_t others = 1;
+            for (int d2 = 0; d2 < R; d2++) if (d2 != d) others *= T[d2];
+            int64_t cap = std::max<int64_t>(1, budget / others);
+            int64_t t = std::max<int64_t>(T[d], std::min<int64_t>(c.extent[d], cap));
+            if (t < c.extent[d]) {                        // prefer an even split of the dimension
+                for (int64_t q = t; q >= std::max<int64_t>(T[d], t / 2 + 1); q--)
+                    if (c.extent[d] % q == 0) { t = q; break; }
+            }
+            if (d == R - 1) t = std::max<int64_t>(VEC, t / VEC * VEC);
+            T[d] = t;
+            if (t < c.extent[d]) break;
+        }
+        // vector width on the staging side
+        const int s0 = sdims[0];
+        VS = 16 / szS;
+        auto vs_ok = [&](int v) {
+            if (T[s0] % v || c.extent[s0] % v) return false;
+            for (int k : staged) {
+                if (c.ops[k].addr % (uint64_t)(v * szS)) return false;
+                for (int d = 0; d < R; d++) if (d != s0 && c.ops[k].stride[d] % v) return false;
+            }
+            return true;
+        };
+        while (VS > 1 && !vs_ok(VS)) VS /= 2;
+    }
+    auto is_staged = [&](int k) { return std::find(staged.begin(), staged.end(), k) != staged.end(); };
+
+    // LDS copy of the tile: the output's order, with a few padding elements after every run
+    // of the staged operand's fastest dimension so that the scattering writes of one
+    // wavefront (lanes that differ along that dimension) spread over the LDS banks.
+    int64_t LS[kMaxDims], LSP[kMaxDims];
+    int64_t lds_pad = 0, lds_elems = 0;
+    { int64_t acc_ = 1; for (int d = R - 1; d >= 0; d--) { LS[d] = acc_; LSP[d] = acc_; acc_ *= T[d]; } lds_elems = acc_; }
+    if (!staged.empty()) {
+        const int s0 = sdims[0];
+        const int szS = isz(c.ops[staged[0]].storage);
+        std::vector<int> st;
+        for (int d : sdims) if (T[d] > 1) st.push_back(d);
+        auto conflicts = [&](int64_t pad) {
+            // worst number of distinct 4-byte words that one bank receives from the 64 lanes
+            // of a wavefront in one scattered write
+            std::map<int64_t, std::vector<int64_t>> bank;
+            for (int lane = 0; lane < 64; lane++) {
+                int64_t j = (int64_t)lane * VS, addr = 0;
+                for (size_t i = 0; i < st.size(); i++) {
+                    int d = st[i];
+                    int64_t cd = (i + 1 < st.size()) ? j % T[d] : j; j /= T[d];
+                    int64_t ls = LS[d];
+                    if (LS[d] >= LS[s0]) ls = LS[d] / LS[s0] * (LS[s0] + pad);
+                    addr += cd * ls;
+                }
+                int64_t word = addr * szS / 4;
+                auto &v = bank[word % 64];
+                if (std::find(v.begin(), v.end(), word) == v.end()) v.push_back(word);
+            }
+            size_t worst = 0;
+            for (auto &kv : bank) worst = std::max(worst, kv.second.size());
+            return (int)worst;
+        };
+        int best = conflicts(0);
+        for (int64_t pad = 4 / szS; pad * szS <= 32 && best > 1; pad += 4 / szS) {
+            int cf = conflicts(pad);
+            if (cf < best) { best = cf; lds_pad = pad; }
+        }
+        for (int d = 0; d < R; d++) if (LS[d] >= LS[s0]) LSP[d] = LS[d] / LS[s0] * (LS[s0] + lds_pad);
+        lds_elems = lds_elems / LS[s0] * (LS[s0] + lds_pad);
+    }
+
     int64_t TE = 1;
     for (int d = 0; d < R; d++) TE *= T[d];
     const int64_t step = (int64_t)block * VEC * U;
@@ -458,41 +649,69 @@ ewf_status Gen::gen_tile(bool with_reduce)
     emit_header(block);
     build_layout();
     if (with_reduce) emit_acc_struct("Acc", level);
-
-    o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) ewf_kernel(const Params p)\n{\n";
-    o << "    const int tid = threadIdx.x;\n";
     std::vector<int> all_dims;
     for (int d = 0; d < R; d++) all_dims.push_back(d);
     std::vector<int> load_ops;                         // operand numbers read per element
     for (int k : used_inputs) load_ops.push_back(k);
+
+    // what one trip of a thread holds in registers between its loads and its arithmetic
+    o << "struct Item {\n    bool ok[" << U << "];\n";
+    for (int d : tiled) o << "    int c" << d << "[" << U << "];\n";
+    for (int k : load_ops) {
+        const Operand &op = c.ops[k];
+        if (op.access == Access::Splat && !is_staged(k)) o << "    " << ctype(op.storage) << " x_" << opname(k) << "[" << U << "];\n";
+        else o << "    ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
+    }
+    o << "};\n";
+
+    o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) " << occupancy_attr() << "ewf_kernel(const Params p)\n{\n";
+    o << "    const int tid = threadIdx.x;\n";
     std::string ind = "        ";
     if (with_reduce) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
+    for (int k : staged)
+        o << "    __shared__ __attribute__((aligned(16))) " << ctype(c.ops[k].storage) << " lds_" << opname(k) << "[" << lds_elems << "];\n";
     // tiles are numbered in canonical (memory) order so that the workgroups resident at any
     // moment stream neighbouring addresses
     o << "    for (idx_t tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {\n";
     o << "        idx_t t_ = tile;\n";
     for (int d = R - 1; d >= 0; d--) {
-        if (d > 0) o << "        const idx_t ti" << d << " = t_ % p.ntile[" << d << "]; t_ /= p.ntile[" << d << "];\n";
-        else o << "        const idx_t ti0 = t_;\n";
+        if (d > 0) o << "        const idx_t ti" << d << " = ewf_uniform(t_ % p.ntile[" << d << "]); t_ /= p.ntile[" << d << "];\n";
+        else o << "        const idx_t ti0 = ewf_uniform(t_);\n";
         o << "        const idx_t o" << d << " = ti" << d << " * " << T[d] << ";\n";
     }
     if (with_reduce) o << "        Acc acc = Acc_identity();\n";
     for (int k : load_ops) emit_base(k, all_dims, ind);
     for (int k : ew_out_ops) emit_base(k, all_dims, ind);
 
+    if (!staged.empty()) {
+        const int s0 = sdims[0];
+        o << ind << "for (int J0 = 0; J0 < " << TE << "; J0 += " << (int64_t)block * VS << ") {\n";
+        o << ind << "    int j_ = J0 + tid * " << VS << ";\n";
+        o << ind << "    bool k_ = j_ < " << TE << ";\n";
+        o << ind << "    int lm_ = 0; ioff_t g_ = 0;\n";
+        std::vector<int> st;                           // staged-order dims with T > 1
+        for (int d : sdims) if (T[d] > 1) st.push_back(d);
+        for (size_t i = 0; i < st.size(); i++) {
+            int d = st[i];
+            o << ind << "    { const int c_ = " << (i + 1 < st.size() ? "j_ % " + std::to_string(T[d]) + "; j_ /= " + std::to_string(T[d]) : std::string("j_")) << ";\n";
+            if (c.extent[d] % T[d]) o << ind << "      k_ = k_ && (o" << d << " + c_ < p.ext[" << d << "]);\n";
+            o << ind << "      lm_ += c_ * " << LSP[d] << ";\n";
+            o << ind << "      g_ += (ioff_t)c_ * (ioff_t)" << (d == s0 ? std::string("1") : "p.st_" + opname(staged[0]) + "[" + std::to_string(d) + "]") << "; }\n";
+        }
+        o << ind << "    if (k_) {\n";
+        for (int k : staged) {
+            const Operand &op = c.ops[k];
+            o << ind << "        { const ewf_vec<" << ctype(op.storage) << ", " << VS << "> v_ = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<")
+              << ctype(op.storage) << ", " << VS << ">(ewf_at(q_" << opname(k) << ", g_));\n";
+            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < " << VS << "; ++e_) lds_" << opname(k) << "[lm_ + e_ * " << LSP[s0] << "] = v_.e[e_]; }\n";
+        }
+        o << ind << "    }\n";
+        o << ind << "}\n";
+        o << ind << "__syncthreads();\n";
+    }
     const bool looped = TE > step;
     const std::string ind0 = ind;
-    if (looped) { o << ind << "for (int L0 = 0; L0 < " << TE << "; L0 += " << step << ") {\n"; ind += "    "; }
-    else o << ind << "const int L0 = 0;\n";
 
-    // phase A: coordinates, masks, loads
-    o << ind << "bool ok[" << U << "];\n";
-    for (int d : tiled) o << ind << "int c" << d << "[" << U << "];\n";
-    for (int k : load_ops) {
-        const Operand &op = c.ops[k];
-        if (op.access == Access::Splat) o << ind << ctype(op.storage) << " x_" << opname(k) << "[" << U << "];\n";
-        else o << ind << "ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
-    }
     auto offset_expr = [&](int k, bool skip_inner) {
         const Operand &op = c.ops[k];
         std::string s;
@@ -500,11 +719,15 @@ ewf_status Gen::gen_tile(bool with_reduce)
             if (op.stride[d] == 0) continue;
             if (d == in_d && skip_inner) continue;
             if (!s.empty()) s += " + ";
-            if (d == in_d && op.stride[d] == 1) s += "c" + std::to_string(d) + "[u]";
-            else s += "(idx_t)c" + std::to_string(d) + "[u] * p.st_" + opname(k) + "[" + std::to_string(d) + "]";
+            if (d == in_d && op.stride[d] == 1) s += "(ioff_t)it.c" + std::to_string(d) + "[u]";
+            else s += "(ioff_t)it.c" + std::to_string(d) + "[u] * (ioff_t)p.st_" + opname(k) + "[" + std::to_string(d) + "]";
         }
-        return s.empty() ? std::string("0") : s;
+        return s.empty() ? std::string("(ioff_t)0") : s;
     };
+
+    // phase A as a local function: coordinates, masks and every load of one trip
+    o << ind << "auto load_item = [&](const int L0, Item &it) {\n";
+    ind += "    ";
     o << ind << "#pragma unroll\n" << ind << "for (int u = 0; u < " << U << "; ++u) {\n";
     o << ind << "    const int L = L0 + (u * EWF_BLOCK + tid) * EWF_VEC;\n";
     o << ind << "    bool k_ = L < " << TE << ";\n";
@@ -512,42 +735,61 @@ ewf_status Gen::gen_tile(bool with_reduce)
         o << ind << "    int l_ = L;\n";
         for (size_t i = 0; i < tiled.size(); i++) {
             int d = tiled[i];
-            if (i + 1 < tiled.size()) o << ind << "    c" << d << "[u] = l_ % " << T[d] << "; l_ /= " << T[d] << ";\n";
-            else o << ind << "    c" << d << "[u] = l_;\n";
-            o << ind << "    k_ = k_ && (o" << d << " + c" << d << "[u] < p.ext[" << d << "]);\n";
+            if (i + 1 < tiled.size()) o << ind << "    it.c" << d << "[u] = l_ % " << T[d] << "; l_ /= " << T[d] << ";\n";
+            else o << ind << "    it.c" << d << "[u] = l_;\n";
+            if (c.extent[d] % T[d]) o << ind << "    k_ = k_ && (o" << d << " + it.c" << d << "[u] < p.ext[" << d << "]);\n";
         }
     }
-    o << ind << "    ok[u] = k_;\n";
+    o << ind << "    it.ok[u] = k_;\n";
     o << ind << "    if (k_) {\n";
     for (int k : load_ops) {
         const Operand &op = c.ops[k];
         std::string nm = opname(k);
-        if (op.access == Access::Vector)
-            o << ind << "        x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + (" << offset_expr(k, false) << "));\n";
+        if (is_staged(k)) {
+            // padded position of the item in the LDS copy; wide pieces as far as the padding
+            // keeps them aligned
+            const int s0 = sdims[0];
+            const int szk = isz(op.storage);
+            int piece = VEC;                               // elements per LDS access
+            while (piece > 1 && ((lds_pad * szk) % (piece * szk) != 0 || piece * szk > 16)) piece /= 2;
+            std::string pos = lds_pad ? "(L + (L / " + std::to_string(LS[s0]) + ") * " + std::to_string(lds_pad) + ")" : std::string("L");
+            if (piece == VEC)
+                o << ind << "        it.x_" << nm << "[u] = ewf_ld<" << ctype(op.storage) << ", EWF_VEC>(&lds_" << nm << "[" << pos << "]);\n";
+            else
+                o << ind << "        _Pragma(\"unroll\") for (int i_ = 0; i_ < " << VEC / piece << "; ++i_) ((ewf_vec<" << ctype(op.storage) << ", " << piece
+                  << "> *)&it.x_" << nm << "[u])[i_] = ewf_ld<" << ctype(op.storage) << ", " << piece << ">(&lds_" << nm << "[" << pos << " + i_ * " << piece << "]);\n";
+        }
+        else if (op.access == Access::Vector)
+            o << ind << "        it.x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "));\n";
         else if (op.access == Access::Splat)
-            o << ind << "        x_" << nm << "[u] = q_" << nm << "[" << offset_expr(k, true) << "];\n";
+            o << ind << "        it.x_" << nm << "[u] = *ewf_at(q_" << nm << ", " << offset_expr(k, true) << ");\n";
         else {
-            o << ind << "        { const idx_t b_ = " << offset_expr(k, false) << ";\n";
-            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) x_" << nm << "[u].e[e_] = q_" << nm
-              << "[b_ + (idx_t)e_ * p.st_" << nm << "[" << in_d << "]]; }\n";
+            o << ind << "        { const ioff_t b_ = " << offset_expr(k, false) << ";\n";
+            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) it.x_" << nm << "[u].e[e_] = *ewf_at(q_" << nm
+              << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
         }
     }
     o << ind << "    }\n" << ind << "}\n";
+    ind = ind0;
+    o << ind << "};\n";
 
-    // phase B: evaluate, accumulate, store
+    // phase B as a local function: evaluate, accumulate, store
+    o << ind << "auto eval_item = [&](const Item &it) {\n";
+    ind += "    ";
     o << ind << "#pragma unroll\n" << ind << "for (int u = 0; u < " << U << "; ++u) {\n";
-    o << ind << "    if (!ok[u]) continue;\n";
+    o << ind << "    if (!it.ok[u]) continue;\n";
     for (int k : ew_out_ops) o << ind << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
     o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
     EmitCtx cx;
     cx.input = [&](int k) {
         const Operand &op = c.ops[k];
-        if (op.access == Access::Splat) return "ewf_in(x_" + opname(k) + "[u])";
-        return "ewf_in(x_" + opname(k) + "[u].e[e_])";
+        if (op.access == Access::Splat && !is_staged(k)) return "ewf_in(it.x_" + opname(k) + "[u])";
+        if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(it.x_" + opname(k) + "[u], e_)";
+        return "ewf_in(it.x_" + opname(k) + "[u].e[e_])";
     };
     cx.coord = [&](int d) {
         std::string s = "o" + std::to_string(d);
-        if (T[d] > 1) s += " + c" + std::to_string(d) + "[u]";
+        if (T[d] > 1) s += " + it.c" + std::to_string(d) + "[u]";
         if (d == in_d) s += " + e_";
         return s;
     };
@@ -565,15 +807,37 @@ ewf_status Gen::gen_tile(bool with_reduce)
         const Operand &op = c.ops[k];
         std::string nm = opname(k);
         if (op.access == Access::Vector)
-            o << ind << "    " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + (" << offset_expr(k, false) << "), y_" << nm << ");\n";
+            o << ind << "    " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "), y_" << nm << ");\n";
         else {
-            o << ind << "    { const idx_t b_ = " << offset_expr(k, op.access == Access::Splat) << ";\n";
-            o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) q_" << nm << "[b_ + (idx_t)e_ * p.st_" << nm
-              << "[" << in_d << "]] = y_" << nm << ".e[e_]; }\n";
+            o << ind << "    { const ioff_t b_ = " << offset_expr(k, op.access == Access::Splat) << ";\n";
+            o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) *ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
+              << "[" << in_d << "]) = y_" << nm << ".e[e_]; }\n";
         }
     }
     o << ind << "}\n";
-    if (looped) { ind = ind0; o << ind << "}\n"; }
+    ind = ind0;
+    o << ind << "};\n";
+
+    // the trips over the tile; with more than one trip the loads of the next trip are issued
+    // before the current one is evaluated, so that arithmetic and memory latency overlap
+    // inside a wavefront as well as between wavefronts
+    if (!looped) {
+        o << ind << "{ Item it; load_item(0, it); eval_item(it); }\n";
+    } else if (e.opts.no_prefetch || (heavy >= 4 && e.opts.no_prefetch == 0)) {
+        o << ind << "for (int L0 = 0; L0 < " << TE << "; L0 += " << step << ") { Item it; load_item(L0, it); eval_item(it); }\n";
+    } else {
+        o << ind << "{\n";
+        o << ind << "    Item cur, nxt;\n";
+        o << ind << "    load_item(0, cur);\n";
+        o << ind << "    for (int L0 = 0; L0 < " << TE << "; L0 += " << step << ") {\n";
+        o << ind << "        const bool more = L0 + " << step << " < " << TE << ";\n";
+        o << ind << "        if (more) load_item(L0 + " << step << ", nxt);\n";
+        o << ind << "        eval_item(cur);\n";
+        o << ind << "        if (more) cur = nxt;\n";
+        o << ind << "    }\n";
+        o << ind << "}\n";
+    }
+    if (!staged.empty()) o << ind << "__syncthreads();\n";
 
     if (with_reduce) {
         // Every wavefront folds its own lanes with cross-lane moves and stores one partial:
@@ -634,6 +898,8 @@ ewf_status Gen::gen_tile(bool with_reduce)
     int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)1 << 22;
     p.grid = std::max<int64_t>(1, std::min(ntiles, cap));
     p.lds_bytes = 0;
+    p.staged = (int)staged.size();
+    for (int k : staged) p.lds_bytes += (int)(lds_elems * isz(c.ops[k].storage));
     int64_t ngroups = 1, nslots = 1;
     for (int d = 0; d < R; d++) { if (c.reduced[d]) nslots *= ntile[d]; else ngroups *= c.extent[d]; }
     p.counter_bytes = 0;
@@ -718,7 +984,7 @@ ewf_status Gen::gen_row()
     const bool has_cross = !red.cross_nodes.empty();
     if (has_cross) emit_acc_struct("AccX", red.cross_nodes);
 
-    o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) ewf_kernel(const Params p)\n{\n";
+    o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) " << occupancy_attr() << "ewf_kernel(const Params p)\n{\n";
     o << "    const int tid = threadIdx.x;\n";
     o << "    const idx_t cols = p.ext[" << in_d << "];\n";
     for (int l = 1; l <= D; l++) o << "    __shared__ Acc" << l << " sm_acc" << l << "[EWF_NWAVES];\n";
@@ -727,8 +993,8 @@ ewf_status Gen::gen_row()
     o << "        idx_t t_ = row;\n";
     std::vector<int> outer;
     for (int d = R - 2; d >= 0; d--) {
-        if (d > 0) o << "        const idx_t o" << d << " = t_ % p.ext[" << d << "]; t_ /= p.ext[" << d << "];\n";
-        else o << "        const idx_t o0 = t_;\n";
+        if (d > 0) o << "        const idx_t o" << d << " = ewf_uniform(t_ % p.ext[" << d << "]); t_ /= p.ext[" << d << "];\n";
+        else o << "        const idx_t o0 = ewf_uniform(t_);\n";
     }
     for (int d = 0; d < R - 1; d++) outer.push_back(d);
     std::vector<int> based;

@@ -90,6 +90,7 @@ struct Canon {
     std::vector<Operand> ops;             // inputs then outputs
     int vec = 1;
     bool idx64 = false;
+    bool byte32 = false;                  // every operand's byte span fits 32 bits
     int64_t total = 0;                    // product of extents
 };
 
@@ -164,7 +165,7 @@ struct Plan {
 struct Exec {
     Graph g;
     ewf_options opts{};
-    bool fast_math = false;
+    int math_flavour = 1;                // 1 accurate, 2 native rate with fix-ups, 3 native rate
     std::map<std::string, std::unique_ptr<Plan>> plans;  // keyed by layout signature
     Plan *last = nullptr;
     int compile_count = 0;

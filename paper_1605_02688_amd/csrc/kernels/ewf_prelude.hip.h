@@ -25,6 +25,22 @@ struct alignas(ewf_align<N * (int)sizeof(T)>::value) ewf_vec {
     T e[N];
 };
 
+// float16 vectors of two or more elements are also visible as the 32-bit words that hold
+// pairs of halves, so that unpacking can work on whole registers
+#define EWF_HALF_VEC(N)                                        \
+    template <>                                                \
+    struct alignas(ewf_align<N * 2>::value) ewf_vec<ewf_half, N> { \
+        union {                                                \
+            ewf_half e[N];                                     \
+            unsigned w[N / 2];                                 \
+        };                                                     \
+    };
+EWF_HALF_VEC(2)
+EWF_HALF_VEC(4)
+EWF_HALF_VEC(8)
+EWF_HALF_VEC(16)
+#undef EWF_HALF_VEC
+
 // One aligned access of N elements (N * sizeof(T) bytes, in 16-byte pieces when larger).
 template <typename T, int N>
 EWF_DEV ewf_vec<T, N> ewf_ld(const T *p)
@@ -88,6 +104,25 @@ EWF_DEV float ewf_in(float x) { return x; }
 EWF_DEV float ewf_in(ewf_half x) { return (float)x; }
 EWF_DEV int ewf_in(int x) { return x; }
 
+// Element e of a float16 vector as float32.  Two halves share a register: the low one is
+// converted in place; the high one goes through a mixed-precision multiply-add that selects
+// the high half by itself (x * 1 + 0, exact), which saves the shift a plain conversion needs.
+template <int N>
+EWF_DEV float ewf_in_h(const ewf_vec<ewf_half, N> &v, int e)
+{
+    if constexpr (N >= 2) {
+        const unsigned w = v.w[e >> 1];
+        if (e & 1) {
+            float r;
+            asm("v_fma_mix_f32 %0, %1, 1.0, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w));
+            return r;
+        }
+        return (float)__builtin_bit_cast(ewf_half, (unsigned short)w);
+    } else {
+        return (float)v.e[e];
+    }
+}
+
 EWF_DEV float ewf_out_f32(float x) { return x; }
 EWF_DEV ewf_half ewf_out_f16(float x) { return (ewf_half)x; }   // round to nearest even
 EWF_DEV int ewf_out_i32(int x) { return x; }
@@ -132,6 +167,7 @@ struct ewf_acc {
     static EWF_DEV float tanh(float x) { return tanhf(x); }
     static EWF_DEV float sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
     static EWF_DEV float pow(float x, float y) { return powf(x, y); }
+    static EWF_DEV float pow_pos(float x, float y) { return powf(x, y); }
     static EWF_DEV float div(float x, float y) { return x / y; }
     static EWF_DEV float recip(float x) { return 1.0f / x; }
 };
@@ -166,14 +202,66 @@ struct ewf_fast {
         t = (a < 0.03125f) ? a * (1.0f - a * a * 0.33333334f) : t;
         return copysignf(t, x);
     }
+    // base known to be positive (the generator proves it from the graph, e.g. x*x + 1)
+    static EWF_DEV float pow_pos(float x, float y) { return __builtin_amdgcn_exp2f(y * __builtin_amdgcn_logf(x)); }
+    // any base: |x|^y, then the sign rules for negative bases (integer exponents only) and
+    // the convention pow(x, 0) = 1
     static EWF_DEV float pow(float x, float y)
     {
-        // positive bases only get the fast path; everything else the library routine
-        if (x > 0.0f) return __builtin_amdgcn_exp2f(y * __builtin_amdgcn_logf(x));
-        return powf(x, y);
+        float r = __builtin_amdgcn_exp2f(y * __builtin_amdgcn_logf(fabsf(x)));
+        float t = truncf(y);
+        float h = t * 0.5f;
+        bool isint = (t == y);
+        bool odd = isint && (truncf(h) != h);
+        float neg = isint ? (odd ? -r : r) : __uint_as_float(0x7fc00000u);
+        r = (x < 0.0f) ? neg : r;
+        return (y == 0.0f) ? 1.0f : r;
     }
     static EWF_DEV float div(float x, float y) { return x * recip(y); }
 };
+
+// native-rate flavour without the fix-ups: log1p(x) = log(1 + x), expm1(x) = exp(x) - 1.
+// Their absolute error near zero is about one float32 unit of 1.0 (6e-8): invisible once the
+// result is rounded to float16 under an absolute + relative bound, and a third of the
+// instructions.  Chosen automatically only when every output is stored as float16.
+struct ewf_bare : ewf_fast {
+    static EWF_DEV float log1p(float x) { return log(1.0f + x); }
+    static EWF_DEV float expm1(float x) { return exp(x) - 1.0f; }
+    static EWF_DEV float tanh(float x)
+    {
+        float e = exp(-2.0f * fabsf(x));
+        return copysignf((1.0f - e) * recip(1.0f + e), x);
+    }
+};
+
+// Tile coordinates come out of integer divisions, which run on the vector unit; telling the
+// compiler that the value is the same in every lane moves all address bases derived from it
+// to scalar registers.
+EWF_DEV int ewf_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+EWF_DEV long long ewf_uniform(long long v)
+{
+    unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)v);
+    unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)v >> 32));
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
+
+// Address of element `off` of a uniform base with 32-bit byte-offset arithmetic (the caller
+// guarantees that the byte offset fits): lets the load use a scalar base plus a 32-bit lane
+// offset instead of a 64-bit add per access.
+template <typename T>
+EWF_DEV T *ewf_at(T *base, unsigned off)
+{
+    return (T *)((char *)base + off * (unsigned)sizeof(T));
+}
+template <typename T>
+EWF_DEV const T *ewf_at(const T *base, unsigned off)
+{
+    return (const T *)((const char *)base + off * (unsigned)sizeof(T));
+}
+template <typename T>
+EWF_DEV T *ewf_at(T *base, long long off) { return base + off; }
+template <typename T>
+EWF_DEV const T *ewf_at(const T *base, long long off) { return base + off; }
 
 // ------------------------------------------------------------------ reductions
 

@@ -42,7 +42,8 @@ class ewf_options(ctypes.Structure):
                 ("force_index64", ctypes.c_int32), ("block_threads", ctypes.c_int32),
                 ("unroll", ctypes.c_int32), ("max_blocks", ctypes.c_int32),
                 ("no_lds_staging", ctypes.c_int32), ("streaming", ctypes.c_int32),
-                ("tile_elems", ctypes.c_int32), ("reserved", ctypes.c_int32 * 7)]
+                ("tile_elems", ctypes.c_int32), ("waves_per_simd", ctypes.c_int32),
+                ("no_prefetch", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
 
 
 class ewf_tensor(ctypes.Structure):

@@ -155,11 +155,12 @@ def test_native_rate_math_meets_the_f16_bar(oracle, G):
         s.output(s.apply(op, b), "f16")
     s.output(s.apply("pow", b, s.mul(a, s.const(0.25))), "f16")
     s.output(s.div(a, b), "f16")
-    expr, got = run_spec(G, s, [x, p])
-    assert "ewf_fast::" in expr.source()
     want = oracle.evaluate(s, [x, p])
-    for k, (g_, w_) in enumerate(zip(got, want)):
-        G.h.compare(f"fast{k}", g_, w_, 2e-3, 1e-3)
+    for mode, flavour in ((0, "ewf_bare::"), (2, "ewf_fast::"), (3, "ewf_bare::")):
+        expr, got = run_spec(G, s, [x, p], math_mode=mode)
+        assert flavour in expr.source()
+        for k, (g_, w_) in enumerate(zip(got, want)):
+            G.h.compare(f"mode{mode}.out{k}", g_, w_, 2e-3, 1e-3)
 
 
 # ------------------------------------------------------------------ layouts

@@ -244,6 +244,9 @@ def c5_stress(n: int = 64, c: int = 256, h: int = 56, w: int = 56, reading: str 
     if reading == "A":
         base3 = _uniform(g, (n, h, w, c), -2.0, 2.0, torch.float16)
         v3 = View(3, 0, shape, (h * w * c, 1, w * c, c))
+    elif reading == "contiguous":       # diagnostic only: no permuted operand
+        base3 = _uniform(g, shape, -2.0, 2.0, torch.float16)
+        v3 = View(3, 0, shape, _contig_strides(shape))
     else:
         base3 = _uniform(g, (n, w, c, h), -2.0, 2.0, torch.float16)
         v3 = View(3, 0, shape, (w * c * h, h, 1, c * h))
