@@ -328,7 +328,7 @@ def test_kernel_class_selection():
 
 
 def test_generated_source_structure_and_cache():
-    w = wl.layout_only(wl.c1_affine_tanh)
+    w = wl.layout_only(wl.c1_affine_tanh, rows=8192)
     w.spec.nodes.append(("const", "f32", 0.12345678))       # makes this source unique in the process-wide cache
     expr, _, info = plan_workload(w)
     src = expr.source()
@@ -337,7 +337,7 @@ def test_generated_source_structure_and_cache():
     n0 = ewf.debug_compile_count(expr.handle)
     assert n0 <= 1
     # another number of rows: same layout class, same source, nothing recompiled
-    w2 = wl.layout_only(wl.c1_affine_tanh, rows=4096)
+    w2 = wl.layout_only(wl.c1_affine_tanh, rows=16384)
     ws, info2 = plan_layout(expr, w2.spec, w2.views, [4, 4])
     assert expr.source() == src and ewf.debug_compile_count(expr.handle) == n0
     # a literal is baked into the code
