@@ -630,6 +630,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     int64_t TE = 1;
     for (int d = 0; d < R; d++) TE *= T[d];
     const int64_t step = (int64_t)block * VEC * U;
+    int fin_block_out = 64;
     int64_t ntile[kMaxDims], ntiles = 1;
     for (int d = 0; d < R; d++) { ntile[d] = ceil_div(c.extent[d], T[d]); ntiles *= ntile[d]; p.tile[d] = T[d]; }
     if (TE > ((int64_t)1 << 30) || ntiles >= ((int64_t)1 << 31) - 1) return fail("tile count out of range");
@@ -855,16 +856,22 @@ ewf_status Gen::gen_tile(bool with_reduce)
     o << "    }\n}\n";
 
     if (with_reduce) {
-        o << "\n// folds the partials of each reduction group, one wavefront per group\n";
-        o << "extern \"C\" __global__ void __launch_bounds__(64) ewf_finish(const Params p)\n{\n";
+        // one workgroup per group: a wavefront when a group has few partials, four otherwise
+        int64_t nparts_host = (int64_t)(block / 64);
+        for (int d = 0; d < R; d++) if (c.reduced[d]) nparts_host *= ntile[d];
+        const int fin_block = nparts_host > 256 ? 256 : 64;
+        fin_block_out = fin_block;
+        o << "\n// folds the partials of each reduction group in a fixed order\n";
+        o << "extern \"C\" __global__ void __launch_bounds__(" << fin_block << ") ewf_finish(const Params p)\n{\n";
         o << "    const int lane = threadIdx.x;\n";
+        o << "    __shared__ Acc sm_fin[" << fin_block / 64 << "];\n";
         o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
         o << "    const idx_t nparts = p.nslots * EWF_NWAVES;\n";
         o << "    for (idx_t group = blockIdx.x; group < p.nrows; group += gridDim.x) {\n";
         o << "        const Acc *const gpart = partials + (size_t)group * (size_t)nparts;\n";
         o << "        Acc tot = Acc_identity();\n";
-        o << "        for (idx_t i = lane; i < nparts; i += 64) tot = Acc_combine()(tot, gpart[i]);\n";
-        o << "        tot = ewf_wave_reduce(tot, Acc_combine());\n";
+        o << "        for (idx_t i = lane; i < nparts; i += " << fin_block << ") tot = Acc_combine()(tot, gpart[i]);\n";
+        o << "        tot = ewf_block_reduce<" << fin_block / 64 << ">(tot, Acc_combine(), sm_fin, lane);\n";
         o << "        if (lane != 0) continue;\n";
         o << "        idx_t g_ = group;\n";
         for (int d = R - 1; d >= 0; d--) {
@@ -911,7 +918,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         for (int n : level) acc_bytes += (g.nodes[n].op == EWF_RARGMAX) ? 8 : 4;
         p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(block / 64) * acc_bytes;
         p.finish_grid = std::min<int64_t>(ngroups, (int64_t)1 << 20);
-        p.finish_block = 64;
+        p.finish_block = fin_block_out;
     }
     p.args.assign(p.layout.size, 0);
     auto put_idx = [&](const std::string &name, int i, int64_t v) {
