@@ -280,12 +280,37 @@ struct Gen {
 
     // ---- accumulators -------------------------------------------------------------------
 
+    // A maximum over the same argument as an arg-max of the same list needs no slot of its
+    // own: the arg-max already carries the running maximum (with the same NaN rule).
+    // Returns the arg-max's slot, or -1.
+    int shared_slot(const std::vector<int> &nodes, size_t i) const
+    {
+        const Node &nd = g.nodes[nodes[i]];
+        if (nd.op != EWF_RMAX) return -1;
+        for (size_t j = 0; j < nodes.size(); j++) {
+            const Node &o2 = g.nodes[nodes[j]];
+            if (o2.op == EWF_RARGMAX && o2.args[0] == nd.args[0] && o2.axes == nd.axes) return (int)j;
+        }
+        return -1;
+    }
+
+    size_t acc_bytes(const std::vector<int> &nodes) const
+    {
+        size_t b = 0;
+        for (size_t i = 0; i < nodes.size(); i++) {
+            if (shared_slot(nodes, i) >= 0) continue;
+            b += (g.nodes[nodes[i]].op == EWF_RARGMAX) ? 8 : 4;
+        }
+        return b;
+    }
+
     // Declares `struct <name>` with one slot per reduction in `nodes`, its identity and its
     // combine function.
     void emit_acc_struct(const std::string &name, const std::vector<int> &nodes)
     {
         o << "struct " << name << " {\n";
         for (size_t i = 0; i < nodes.size(); i++) {
+            if (shared_slot(nodes, i) >= 0) continue;
             const Node &nd = g.nodes[nodes[i]];
             const Node &arg = g.nodes[nd.args[0]];
             if (nd.op == EWF_RARGMAX) o << "    " << vtype_c(arg.vtype) << " a" << i << "; int i" << i << ";\n";
@@ -294,6 +319,7 @@ struct Gen {
         o << "};\n";
         o << "EWF_DEV " << name << " " << name << "_identity()\n{\n    " << name << " a;\n";
         for (size_t i = 0; i < nodes.size(); i++) {
+            if (shared_slot(nodes, i) >= 0) continue;
             const Node &nd = g.nodes[nodes[i]];
             const bool isint = g.nodes[nd.args[0]].vtype == EWF_I32;
             std::string id;
@@ -310,6 +336,7 @@ struct Gen {
         o << "struct " << name << "_combine {\n    EWF_DEV " << name << " operator()(const " << name << " &x, const "
           << name << " &y) const\n    {\n        " << name << " r;\n";
         for (size_t i = 0; i < nodes.size(); i++) {
+            if (shared_slot(nodes, i) >= 0) continue;
             const Node &nd = g.nodes[nodes[i]];
             const bool isint = g.nodes[nd.args[0]].vtype == EWF_I32;
             std::string a = "x.a" + std::to_string(i), b = "y.a" + std::to_string(i);
@@ -341,16 +368,23 @@ struct Gen {
     {
         for (size_t i = 0; i < nodes.size(); i++) {
             const Node &nd = g.nodes[nodes[i]];
+            const int sh = shared_slot(nodes, i);
             if (nd.op == EWF_RARGMAX) o << ind << "const int r" << nodes[i] << " = " << acc << ".i" << i << ";\n";
-            else o << ind << "const " << vtype_c(nd.vtype) << " r" << nodes[i] << " = " << acc << ".a" << i << ";\n";
+            else o << ind << "const " << vtype_c(nd.vtype) << " r" << nodes[i] << " = " << acc << ".a" << (sh >= 0 ? sh : (int)i) << ";\n";
         }
     }
 
     // Folds one element into every slot of the accumulator `acc` (slot-wise, no temporaries).
+    // With `ascending` the caller guarantees that one thread meets the indices of an arg-max
+    // in increasing order: a later element then replaces the running maximum only when it is
+    // strictly greater (or the first NaN), and the index comparison falls away.  The
+    // identity index (no element taken yet) must then be resolved by emit_first_index.
     void emit_accumulate(const std::string &acc, const std::vector<int> &nodes,
-                         const std::function<std::string(int)> &argmax_index, const std::string &ind)
+                         const std::function<std::string(int)> &argmax_index, const std::string &ind,
+                         bool ascending = false)
     {
         for (size_t i = 0; i < nodes.size(); i++) {
+            if (shared_slot(nodes, i) >= 0) continue;
             const Node &nd = g.nodes[nodes[i]];
             const bool isint = g.nodes[nd.args[0]].vtype == EWF_I32;
             std::string a = acc + ".a" + std::to_string(i), v = "v" + std::to_string(nd.args[0]);
@@ -362,7 +396,12 @@ struct Gen {
             case EWF_RARGMAX: {
                 std::string ia = acc + ".i" + std::to_string(i);
                 std::string ib = "(int)(" + argmax_index(nodes[i]) + ")";
-                if (isint) {
+                if (ascending && isint) {
+                    o << ind << "{ const bool t = " << v << " > " << a << ";\n";
+                } else if (ascending) {
+                    // greater, or the first NaN; a NaN already held stays
+                    o << ind << "{ const bool t = !(" << v << " <= " << a << ") && (" << a << " == " << a << ");\n";
+                } else if (isint) {
                     o << ind << "{ const bool t = (" << v << " > " << a << ") || (" << v << " == " << a << " && " << ib << " < " << ia << ");\n";
                 } else {
                     o << ind << "{ const bool gt = (" << v << " > " << a << ") || (" << v << " != " << v << " && " << a << " == " << a << ");\n"
@@ -374,6 +413,18 @@ struct Gen {
             }
             }
         }
+    }
+
+    // After an `ascending` accumulation: a thread whose elements all equal the identity value
+    // (-inf, or the smallest integer) never replaced it, so its index is still the identity;
+    // the first element it met is then the first occurrence of that maximum.
+    void emit_first_index(const std::string &acc, const std::vector<int> &nodes, const std::string &has_first,
+                          const std::string &first_index, const std::string &ind)
+    {
+        for (size_t i = 0; i < nodes.size(); i++)
+            if (g.nodes[nodes[i]].op == EWF_RARGMAX)
+                o << ind << "if (" << acc << ".i" << i << " == 2147483647 && (" << has_first << ")) " << acc << ".i" << i
+                  << " = (int)(" << first_index << ");\n";
     }
 
     int argmax_canon_dim(int node) const
@@ -435,10 +486,13 @@ struct Gen {
         o << ";\n";
     }
 
+    int auto_waves_per_simd = 0;              // register budget the generator itself asks for
+
     std::string occupancy_attr() const
     {
-        if (e.opts.waves_per_simd < 1 || e.opts.waves_per_simd > 8) return "";
-        return "__attribute__((amdgpu_waves_per_eu(" + std::to_string(e.opts.waves_per_simd) + "))) ";
+        int w = (e.opts.waves_per_simd >= 1 && e.opts.waves_per_simd <= 8) ? e.opts.waves_per_simd : auto_waves_per_simd;
+        if (w < 1) return "";
+        return "__attribute__((amdgpu_waves_per_eu(" + std::to_string(w) + "))) ";
     }
 
     ewf_status fail(const std::string &why)
@@ -914,9 +968,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     p.finish_grid = 0;
     if (with_reduce) {
         if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31)) return fail("too many reduction groups");
-        size_t acc_bytes = 0;
-        for (int n : level) acc_bytes += (g.nodes[n].op == EWF_RARGMAX) ? 8 : 4;
-        p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(block / 64) * acc_bytes;
+        p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(block / 64) * acc_bytes(level);
         p.finish_grid = std::min<int64_t>(ngroups, (int64_t)1 << 20);
         p.finish_block = fin_block_out;
     }
@@ -984,6 +1036,17 @@ ewf_status Gen::gen_row()
     const bool resident = NV <= 32 && regs <= 96;
     const int U = resident ? (int)NV : (e.opts.unroll > 0 ? e.opts.unroll : 4);
     p.tile[in_d] = cols;
+    {
+        // When all rows can be resident on the chip at once there is no second round of
+        // workgroups (whose tail would idle most of the chip): ask the compiler for the
+        // register budget that lets that many wavefronts share a SIMD, if the row leaves
+        // room for the arithmetic under it.
+        int64_t nrows_ = 1;
+        for (int d = 0; d < R - 1; d++) nrows_ *= c.extent[d];
+        const int64_t wg_per_cu = ceil_div(nrows_, device_cu_count());
+        const int64_t waves = ceil_div(wg_per_cu * (block / 64), 4);
+        if (resident && waves >= 2 && waves <= 8 && regs + 40 <= 512 / waves / 8 * 8) auto_waves_per_simd = (int)waves;
+    }
 
     emit_header(block);
     build_layout();
@@ -1078,9 +1141,11 @@ ewf_status Gen::gen_row()
         stream_loads(need);
         o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
         emit_values(need, cx, "                ");
-        emit_accumulate(av, lvl[l], [&](int node) { return cx.coord(argmax_canon_dim(node)); }, "                ");
+        emit_accumulate(av, lvl[l], [&](int node) { return cx.coord(argmax_canon_dim(node)); }, "                ", true);
         o << "            }\n";
         close_pass();
+        // every thread walks its columns in increasing order, starting at tid * EWF_VEC
+        emit_first_index(av, lvl[l], "(idx_t)tid * EWF_VEC < cols", "tid * EWF_VEC", "        ");
         o << "        " << av << " = ewf_block_reduce<EWF_NWAVES>(" << av << ", " << an << "_combine(), sm_acc" << l << ", tid);\n";
         emit_results(av, lvl[l], "        ");
     }
@@ -1139,6 +1204,7 @@ ewf_status Gen::gen_row()
             if (has_cross) {
                 o << "            AccX ax = AccX_identity();\n";
                 for (size_t i = 0; i < red.cross_nodes.size(); i++) {
+                    if (shared_slot(red.cross_nodes, i) >= 0) continue;
                     const Node &nd = g.nodes[red.cross_nodes[i]];
                     o << "            ax.a" << i << " = v" << nd.args[0] << ";\n";
                     if (nd.op == EWF_RARGMAX) {
@@ -1192,9 +1258,7 @@ ewf_status Gen::gen_row()
     p.workspace_bytes = 0;
     p.finish_grid = 0;
     if (has_cross) {
-        size_t acc_bytes = 0;
-        for (int n : red.cross_nodes) acc_bytes += (g.nodes[n].op == EWF_RARGMAX) ? 8 : 4;
-        p.workspace_bytes = (size_t)nrows * acc_bytes;
+        p.workspace_bytes = (size_t)nrows * acc_bytes(red.cross_nodes);
         p.finish_grid = 1;
         p.finish_block = 256;
     }

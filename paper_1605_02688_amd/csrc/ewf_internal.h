@@ -199,5 +199,6 @@ ewf_status compile_source(const std::string &source, std::vector<char> &code, bo
 // Loads `entry` from a code object on the current device (cached per device and code object).
 ewf_status load_function(const std::vector<char> &code, const std::string &entry, void **function, int *device);
 const char *prelude_source();
+int device_cu_count();
 
 }  // namespace ewf

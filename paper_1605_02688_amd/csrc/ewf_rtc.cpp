@@ -92,4 +92,20 @@ ewf_status load_function(const std::vector<char> &code, const std::string &entry
     return EWF_OK;
 }
 
+// Compute units of the current device; the published MI355X figure when no device is
+// present (planning and compiling need none).
+int device_cu_count()
+{
+    static int cached = 0;
+    if (cached > 0) return cached;
+    int dev = -1, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+        cached = n;
+        return n;
+    }
+    (void)hipGetLastError();
+    return 256;
+}
+
 }  // namespace ewf

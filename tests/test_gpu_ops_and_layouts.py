@@ -67,6 +67,26 @@ def test_unary_op_accurate_mode(op, oracle, G):
     G.h.compare(op, got, want, rtol, atol)
 
 
+def test_exp_accurate_mode_whole_range(oracle, G):
+    # the accurate exp is the library's own (hardware exp2 plus a first-order correction):
+    # a few units in the last place from underflow to overflow, exact at the special values
+    rng = np.random.default_rng(77)
+    x = np.concatenate([rng.uniform(-87.3, 88.7, 200000), np.linspace(-87.3, 88.7, 50001),
+                        rng.uniform(-1e-3, 1e-3, 1000)]).astype(np.float32)
+    sp = np.float32([0.0, -0.0, np.inf, -np.inf, np.nan, 88.8, 100.0, 1e30, -104.0, -1e30, 1e-40, 88.72283])
+    x = np.concatenate([sp, x])
+    s = GraphSpec(1)
+    s.output(s.apply("exp", s.input("f32", (False,))), "f32")
+    expr, (got,) = run_spec(G, s, [x], math_mode=1)
+    assert "ewf_acc::exp" in expr.source()
+    want = oracle.evaluate(s, [x])[0]
+    k = len(sp)
+    with np.errstate(over="ignore", invalid="ignore"):
+        assert got[0] == 1.0 and got[1] == 1.0 and got[2] == np.inf and got[3] == 0.0 and np.isnan(got[4])
+        assert np.all(got[5:8] == np.inf) and np.all(got[8:10] == 0.0) and got[10] == 1.0
+    G.h.compare("exp", got[k:], want[k:], 4e-7, 0)          # about three units in the last place
+
+
 def test_log1p_keeps_small_arguments(oracle, G):
     x = np.float32([1e-7, -1e-7, 3e-10, 1e-5, -1e-5])
     s = GraphSpec(1)
@@ -302,6 +322,32 @@ def test_argmax_ties_take_the_first_index(oracle, G):
         want = oracle.evaluate(s, [x])[0]
         assert np.array_equal(got, want)
         assert got[0] == 123 and got[5] == 7 and got[9] == 0
+
+
+def test_max_shares_the_argmax_accumulator(oracle, G):
+    # max and arg-max of one argument share an accumulator; NaN wins both (first NaN), a row of
+    # -inf gives index 0, equal maxima the first index -- in the row class and the split class
+    rng = np.random.default_rng(181)
+    for shape in [(600, 700), (3, 50000)]:
+        x = rng.standard_normal(shape).astype(np.float32)
+        x[0, :] = -np.inf
+        x[1, 5] = np.nan; x[1, 400] = np.nan; x[1, 17] = 9.0
+        x[2, 3::64] = 7.0
+        if shape[0] > 3:
+            x[3, :] = -np.inf; x[3, 699] = -1e30
+            x[4, :] = 2.5
+        s = GraphSpec(2)
+        xi = s.input("f32", (False, False))
+        s.output(s.reduce("max", xi, (1,)), "f32")
+        s.output(s.reduce("argmax", xi, (1,)), "i32")
+        s.output(s.reduce("sum", s.apply("abs", s.apply("tanh", xi)), (1,)), "f32")
+        print(f"[case] shared max/argmax {shape}", flush=True)
+        expr, got = run_spec(G, s, [x])
+        want = oracle.evaluate(s, [x], nthreads=4)
+        assert np.array_equal(got[0], want[0], equal_nan=True), expr.info()
+        assert np.array_equal(got[1], want[1]), expr.info()
+        assert got[1][0] == 0 and got[1][1] == 5 and got[1][2] == 3
+        G.h.compare("sum", got[2], want[2], 1e-5, 1e-6)
 
 
 def test_softmax_probabilities_row_class(oracle, G):
