@@ -53,21 +53,32 @@ class Case:
         self.calls[self.k % len(self.calls)].launch()
         self.k += 1
 
+    def wall(self, steps, warmup):
+        """Wall-clock ms for `steps` back-to-back launches (synchronised on both sides)."""
+        import torch
+        for _ in range(warmup):
+            self.launch()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.launch()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
     def time(self, steps, warmup):
-        """Returns (wall ms for `steps` launches, per-launch event durations in ms)."""
+        """Per-launch durations in ms from HIP events recorded around every launch, on the
+        stream the kernels are launched on."""
         import torch
         for _ in range(warmup):
             self.launch()
         torch.cuda.synchronize()
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-        t0 = time.perf_counter()
         for a, b in ev:
             a.record()
             self.launch()
             b.record()
         torch.cuda.synchronize()
-        wall = (time.perf_counter() - t0) * 1e3
-        return wall, [a.elapsed_time(b) for a, b in ev]
+        return [a.elapsed_time(b) for a, b in ev]
 
 
 def copy_ceiling(nbytes, steps=20):
@@ -86,6 +97,25 @@ def copy_ceiling(nbytes, steps=20):
     b.record()
     torch.cuda.synchronize()
     return 2 * nbytes * steps / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
+def launch_floor(steps=200):
+    """Event-bracketed duration of a one-workgroup fill kernel: what the microsecond figures of
+    the small workloads sit on."""
+    import torch
+    from paper_1605_02688_amd import ewf
+    buf = torch.empty(64, dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(10):
+        ewf.workspace_init(buf.data_ptr(), 256, st)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        ewf.workspace_init(buf.data_ptr(), 256, st)
+        b.record()
+    torch.cuda.synchronize()
+    return _stats([a.elapsed_time(b) for a, b in ev])
 
 
 def cpu_baseline(budget_s=15.0):
@@ -131,8 +161,8 @@ def main():
 
     head_name = args.only or "c4"
     head = Case(wl.FULL_SIZE[head_name]())
-    wall_ms, per = head.time(args.steps, args.warmup)
-    st = _stats(per)
+    wall_ms = head.wall(args.steps, args.warmup)          # the timed region: exactly K steps
+    st = _stats(head.time(args.steps, 0))                   # the same K launches again, per-launch events
     w = head.w
     ms_per_step = wall_ms / args.steps
     gbps = w.algorithmic_bytes / (ms_per_step * 1e-3) / 1e9
@@ -161,6 +191,8 @@ def main():
                      "kernel_min_us": round(st["min_us"], 2)},
     }
     out["copy_ceiling_gbps"] = round(copy_ceiling(w.algorithmic_bytes // 2 // 16 * 16), 1)
+    fl = launch_floor()
+    out["launch_floor_us"] = {"avg": round(fl["avg_us"], 2), "min": round(fl["min_us"], 2)}
     del head
     torch.cuda.empty_cache()
 
@@ -173,9 +205,8 @@ def main():
             nsets = max(1, min(300, int(600e6 // max(1, wk.algorithmic_bytes)) + 1)) if wk.algorithmic_bytes < 300e6 else 1
             case = Case(wk, nsets=nsets)
             steps = 200 if wk.algorithmic_bytes < 300e6 else 50
-            _wall, per = case.time(steps, 20)
-            s = _stats(per)
-            wall2, _ = case.time(steps, 0)
+            s = _stats(case.time(steps, 20))
+            wall2 = case.wall(steps, 0)
             res = {"elements": wk.elements, "algorithmic_bytes": wk.algorithmic_bytes,
                    "kernel_class": case.info["kernel_class"], "buffer_sets": nsets,
                    "mode": "rotating" if nsets > 1 else "single set (exceeds on-chip cache)",
@@ -186,8 +217,7 @@ def main():
                    "gelem_per_s": round(wk.elements / (s["avg_us"] * 1e-6) / 1e9, 2)}
             if nsets > 1:
                 warm = Case(wk, nsets=1)
-                _w, perw = warm.time(steps, 20)
-                res["warm_kernel_avg_us"] = round(_stats(perw)["avg_us"], 2)
+                res["warm_kernel_avg_us"] = round(_stats(warm.time(steps, 20))["avg_us"], 2)
                 del warm
             per_config[name] = res
             del case

@@ -91,7 +91,10 @@ typedef struct {
                                2 native-rate exp2/log2/rcp with fix-ups that keep log1p, expm1
                                and tanh relatively accurate near zero; 3 native-rate without
                                them (absolute error near zero about 6e-8); 0 auto: 3 iff every
-                               output is stored as float16, else 1                            */
+                               output is stored as float16, else 1 -- except for values that
+                               reach the outputs only as terms of a float32 sum, which use 2
+                               (worst-case relative error of a term under 6e-6, inside the 1e-5
+                               bar of reduction outputs)                                      */
     int32_t force_scalar;   /* 1: never use vector (multi-element) memory accesses           */
     int32_t force_index64;  /* 1: 64-bit offset arithmetic even when 32 bits suffice         */
     int32_t block_threads;  /* 0 = library default                                           */

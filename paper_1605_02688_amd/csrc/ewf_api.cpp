@@ -188,6 +188,7 @@ ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **o
     const int mm = x->e.opts.math_mode;
     if (mm < 0 || mm > 3) { delete x; set_error("math_mode must be 0..3"); return EWF_EINVAL; }
     x->e.math_flavour = mm == 0 ? (all_f16 ? 3 : 1) : mm;
+    x->e.auto_math = mm == 0;
     *out = x;
     return EWF_OK;
 }

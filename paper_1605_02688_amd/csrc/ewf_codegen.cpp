@@ -115,6 +115,11 @@ struct Gen {
     std::vector<char> after_cross;
     std::vector<char> live;
     std::vector<char> nonneg, positive;       // sign facts provable from the graph alone
+    // Values that reach the outputs only as terms of a float32 sum.  The bar for such outputs
+    // is the reduction bar (1e-5 relative), which the native-rate routines with fix-ups meet in
+    // the worst case (exp: at most 6e-8 * (1 + |x| log2 e) relative, under 6e-6 wherever the
+    // result is finite), so under the automatic math mode these nodes use that flavour.
+    std::vector<char> sum_only;
 
     // A small sign analysis over the scalar graph, in the spirit of the specialisation stage
     // of paper section 2.2.1: when the base of a power is provably positive (x*x + 1, exp(u),
@@ -176,6 +181,16 @@ struct Gen {
             for (int a = 0; a < g.nodes[n].nargs; a++) if (after_cross[g.nodes[n].args[a]]) after_cross[n] = 1;
         }
         analyse_signs();
+        std::vector<char> direct(N, 0);
+        for (const OutputDecl &od : g.outputs) direct[od.value] = 1;
+        for (int n = N - 1; n >= 0; n--) {
+            if (!direct[n]) continue;
+            const Node &nd = g.nodes[n];
+            if (nd.kind == NodeKind::Reduce && nd.op == EWF_RSUM && nd.vtype == EWF_F32 && real_reduce(n)) continue;
+            for (int a = 0; a < nd.nargs; a++) direct[nd.args[a]] = 1;
+        }
+        sum_only.assign(N, 0);
+        for (int n = 0; n < N; n++) sum_only[n] = live[n] && !direct[n];
     }
 
     bool real_reduce(int n) const { return is_level[n] || is_cross[n]; }
@@ -216,10 +231,11 @@ struct Gen {
     // Emits `const T v<n> = ...;` for every needed node, in graph order.
     void emit_values(const std::vector<char> &need, const EmitCtx &cx, const std::string &ind)
     {
-        const char *M = e.math_flavour == 3 ? "ewf_bare" : e.math_flavour == 2 ? "ewf_fast" : "ewf_acc";
         for (size_t n = 0; n < need.size(); n++) {
             if (!need[n]) continue;
             const Node &nd = g.nodes[n];
+            const int fl = (e.auto_math && e.math_flavour == 1 && sum_only[n]) ? 2 : e.math_flavour;
+            const char *M = fl == 3 ? "ewf_bare" : fl == 2 ? "ewf_fast" : "ewf_acc";
             std::string a0 = nd.nargs > 0 ? "v" + std::to_string(nd.args[0]) : "";
             std::string a1 = nd.nargs > 1 ? "v" + std::to_string(nd.args[1]) : "";
             std::string a2 = nd.nargs > 2 ? "v" + std::to_string(nd.args[2]) : "";
@@ -425,6 +441,34 @@ struct Gen {
             if (g.nodes[nodes[i]].op == EWF_RARGMAX)
                 o << ind << "if (" << acc << ".i" << i << " == 2147483647 && (" << has_first << ")) " << acc << ".i" << i
                   << " = (int)(" << first_index << ");\n";
+    }
+
+    // "Sum over one axis of where(iota == T, X, 0)" with X a tensor input and T constant along
+    // that axis has exactly one non-zero term: it is X read at index T (zero when T is out
+    // of range).  The row class reads that element directly instead of comparing an index
+    // per element.  Adding +0 keeps the sign rule of the sum (a sum of zeros is +0).
+    struct Gather { int node, input, index_value, cdim; };
+    bool match_gather(int n, Gather &out) const
+    {
+        const Node &nd = g.nodes[n];
+        if (nd.kind != NodeKind::Reduce || nd.op != EWF_RSUM || nd.vtype != EWF_F32) return false;
+        if (nd.axes & (nd.axes - 1)) return false;
+        int axis = 0;
+        while (!(nd.axes & (1u << axis))) axis++;
+        const Node &w = g.nodes[nd.args[0]];
+        if (w.kind != NodeKind::Apply || w.op != EWF_WHERE) return false;
+        const Node &cnd = g.nodes[w.args[0]], &x = g.nodes[w.args[1]], &z = g.nodes[w.args[2]];
+        if (z.kind != NodeKind::Const || z.cval != 0.0 || std::signbit(z.cval)) return false;
+        if (x.kind != NodeKind::Input || (x.bcast & nd.axes)) return false;
+        if (cnd.kind != NodeKind::Apply || cnd.op != EWF_EQ) return false;
+        for (int side = 0; side < 2; side++) {
+            const Node &io = g.nodes[cnd.args[side]], &t = g.nodes[cnd.args[1 - side]];
+            if (io.kind == NodeKind::Iota && io.index == axis && t.vtype == EWF_I32 && (t.bcast & nd.axes)) {
+                out = {n, x.index, cnd.args[1 - side], c.orig_of_axis[axis]};
+                return out.cdim >= 0;
+            }
+        }
+        return false;
     }
 
     int argmax_canon_dim(int node) const
@@ -1018,11 +1062,16 @@ ewf_status Gen::gen_row()
     // ---- per-level targets
     const int D = red.max_depth;
     std::vector<std::vector<int>> lvl(D + 1);
-    for (int n : red.level_nodes) lvl[red.edepth[n]].push_back(n);
+    std::vector<std::vector<Gather>> gat(D + 1);
+    for (int n : red.level_nodes) {
+        Gather ga;
+        if (match_gather(n, ga) && ga.cdim == in_d) gat[red.edepth[n]].push_back(ga);
+        else lvl[red.edepth[n]].push_back(n);
+    }
 
     // which inputs vary along the row and are read by some per-element computation
     std::vector<int> elem_targets;
-    for (int n : red.level_nodes) elem_targets.push_back(g.nodes[n].args[0]);
+    for (int l = 1; l <= D; l++) for (int n : lvl[l]) elem_targets.push_back(g.nodes[n].args[0]);
     for (int k : full_out_ops) elem_targets.push_back(g.outputs[c.ops[k].index].value);
     std::vector<char> eneed = needed(elem_targets);
     std::vector<int> row_ops, splat_ops;
@@ -1050,14 +1099,14 @@ ewf_status Gen::gen_row()
 
     emit_header(block);
     build_layout();
-    for (int l = 1; l <= D; l++) emit_acc_struct("Acc" + std::to_string(l), lvl[l]);
+    for (int l = 1; l <= D; l++) if (!lvl[l].empty()) emit_acc_struct("Acc" + std::to_string(l), lvl[l]);
     const bool has_cross = !red.cross_nodes.empty();
     if (has_cross) emit_acc_struct("AccX", red.cross_nodes);
 
     o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) " << occupancy_attr() << "ewf_kernel(const Params p)\n{\n";
     o << "    const int tid = threadIdx.x;\n";
     o << "    const idx_t cols = p.ext[" << in_d << "];\n";
-    for (int l = 1; l <= D; l++) o << "    __shared__ Acc" << l << " sm_acc" << l << "[EWF_NWAVES];\n";
+    for (int l = 1; l <= D; l++) if (!lvl[l].empty()) o << "    __shared__ Acc" << l << " sm_acc" << l << "[EWF_NWAVES];\n";
     if (has_cross) o << "    AccX *const partials = (AccX *)p.ws_partials;\n";
     o << "    for (idx_t row = blockIdx.x; row < p.nrows; row += gridDim.x) {\n";
     o << "        idx_t t_ = row;\n";
@@ -1131,7 +1180,32 @@ ewf_status Gen::gen_row()
         }
     };
 
+    // values constant along the row, evaluated by every thread (uniform addresses)
+    std::vector<int> uniform_loaded = splat_ops;
+    EmitCtx ux;
+    ux.input = [&](int k) { return "ewf_in(g_" + opname(k) + ")"; };
+    ux.coord = [&](int d) { return d == in_d ? std::string("0") : "o" + std::to_string(d); };
+
     for (int l = 1; l <= D; l++) {
+        for (const Gather &ga : gat[l]) {
+            // issued ahead of the level's pass so that the element arrives under it
+            std::vector<char> need = needed(std::vector<int>{ga.index_value});
+            for (int k : inputs_of(need)) {
+                if (std::find(uniform_loaded.begin(), uniform_loaded.end(), k) != uniform_loaded.end()) continue;
+                uniform_loaded.push_back(k);
+                base_once(k, "        ");
+                o << "        const " << ctype(c.ops[k].storage) << " g_" << opname(k) << " = q_" << opname(k) << "[0];\n";
+            }
+            base_once(ga.input, "        ");
+            const std::string nm = opname(ga.input);
+            o << "        float r" << ga.node << ";\n        {\n";
+            emit_values(need, ux, "            ");
+            o << "            const int t_ = v" << ga.index_value << ";\n";
+            o << "            r" << ga.node << " = (t_ >= 0 && t_ < cols) ? ewf_in(q_" << nm << "[(idx_t)t_"
+              << (c.ops[ga.input].stride[in_d] == 1 ? std::string("") : " * p.st_" + nm + "[" + std::to_string(in_d) + "]")
+              << "]) + 0.0f : 0.0f;\n        }\n";
+        }
+        if (lvl[l].empty()) continue;
         std::string an = "Acc" + std::to_string(l), av = "acc" + std::to_string(l);
         std::vector<int> tg;
         for (int n : lvl[l]) tg.push_back(g.nodes[n].args[0]);
@@ -1187,7 +1261,7 @@ ewf_status Gen::gen_row()
             std::vector<char> need = needed(tg);
             o << "        if (tid == 0) {\n";
             for (int k : inputs_of(need)) {
-                if (std::find(splat_ops.begin(), splat_ops.end(), k) != splat_ops.end()) continue;
+                if (std::find(uniform_loaded.begin(), uniform_loaded.end(), k) != uniform_loaded.end()) continue;
                 base_once(k, "            ");
                 o << "            const " << ctype(c.ops[k].storage) << " g_" << opname(k) << " = q_" << opname(k) << "[0];\n";
             }

@@ -166,6 +166,7 @@ struct Exec {
     Graph g;
     ewf_options opts{};
     int math_flavour = 1;                // 1 accurate, 2 native rate with fix-ups, 3 native rate
+    bool auto_math = false;              // the flavour was chosen by the library (math_mode 0)
     std::map<std::string, std::unique_ptr<Plan>> plans;  // keyed by layout signature
     Plan *last = nullptr;
     int compile_count = 0;

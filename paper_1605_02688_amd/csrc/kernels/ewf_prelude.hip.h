@@ -211,7 +211,8 @@ struct ewf_fast {
     static EWF_DEV float sigmoid(float x) { return recip(1.0f + exp(-x)); }
     static EWF_DEV float tanh(float x)
     {
-        float a = fminf(fabsf(x), 15.0f);
+        float a = fabsf(x);
+        a = (a > 15.0f) ? 15.0f : a;                  // a NaN stays (a min() would drop it)
         float e = exp(-2.0f * a);
         float t = (1.0f - e) * recip(1.0f + e);
         t = (a < 0.03125f) ? a * (1.0f - a * a * 0.33333334f) : t;

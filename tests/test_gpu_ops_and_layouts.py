@@ -350,6 +350,32 @@ def test_max_shares_the_argmax_accumulator(oracle, G):
         G.h.compare("sum", got[2], want[2], 1e-5, 1e-6)
 
 
+def test_one_hot_sum_is_read_as_a_gather(oracle, G):
+    # sum_j where(iota_j == t, x_j, 0) is one element of x: the row class reads it directly.
+    # Out-of-range indices give 0, a NaN elsewhere in the row does not leak, -0 becomes +0.
+    rng = np.random.default_rng(182)
+    rows, cols = 700, 333
+    x = rng.standard_normal((rows, cols)).astype(np.float32)
+    t = rng.integers(0, cols, (rows, 1)).astype(np.int32)
+    t[0, 0] = -1; t[1, 0] = cols; t[2, 0] = 2**31 - 1; t[3, 0] = 0; t[4, 0] = cols - 1
+    x[5, :] = np.nan; x[5, 7] = 1.25; t[5, 0] = 7
+    x[6, 9] = -0.0; t[6, 0] = 9
+    for storage, tol in (("f32", 0.0), ("f16", 0.0)):
+        xs = x.astype(np.float16) if storage == "f16" else x
+        s = GraphSpec(2)
+        xi = s.input(storage, (False, False)); ti = s.input("i32", (False, True))
+        hit = s.apply("eq", ti, s.iota(1)) if storage == "f16" else s.apply("eq", s.iota(1), ti)
+        s.output(s.reduce("sum", s.apply("where", hit, xi, s.const(0.0)), (1,)), "f32")
+        s.output(s.reduce("sum", s.apply("abs", xi), (1,)), "f32")
+        print(f"[case] one-hot sum as gather, {storage}", flush=True)
+        expr, got = run_spec(G, s, [xs, t])
+        assert expr.info()["kernel_class"] == "row" and "(idx_t)t_" in expr.source()
+        want = oracle.evaluate(s, [xs, t], nthreads=4)
+        assert np.array_equal(got[0], want[0]) and not np.signbit(got[0][6])
+        assert got[0][0] == 0 and got[0][1] == 0 and got[0][2] == 0 and got[0][5] == 1.25
+        G.h.compare("abs-sum", got[1], want[1], 1e-5, 1e-6)
+
+
 def test_softmax_probabilities_row_class(oracle, G):
     rng = np.random.default_rng(19)
     for rows, cols in [(33, 1000), (5, 9000), (700, 24)]:
