@@ -1108,7 +1108,14 @@ ewf_status Gen::gen_row()
     o << "    const idx_t cols = p.ext[" << in_d << "];\n";
     for (int l = 1; l <= D; l++) if (!lvl[l].empty()) o << "    __shared__ Acc" << l << " sm_acc" << l << "[EWF_NWAVES];\n";
     if (has_cross) o << "    AccX *const partials = (AccX *)p.ws_partials;\n";
-    o << "    for (idx_t row = blockIdx.x; row < p.nrows; row += gridDim.x) {\n";
+    // one workgroup per row when the grid can hold them all: no loop, so nothing is hoisted
+    // out of it into registers that the row needs
+    int64_t nrows = 1;
+    for (int d = 0; d < R - 1; d++) nrows *= c.extent[d];
+    if (nrows >= ((int64_t)1 << 31) - 1) return fail("too many rows");
+    const int64_t grid_cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)256 * 32;
+    if (nrows <= grid_cap) o << "    if ((idx_t)blockIdx.x < p.nrows) {\n        const idx_t row = blockIdx.x;\n";
+    else o << "    for (idx_t row = blockIdx.x; row < p.nrows; row += gridDim.x) {\n";
     o << "        idx_t t_ = row;\n";
     std::vector<int> outer;
     for (int d = R - 2; d >= 0; d--) {
@@ -1127,11 +1134,16 @@ ewf_status Gen::gen_row()
     for (int k : full_out_ops) base_once(k, "        ");
 
     // the loop over the row: either over register-resident vectors or streaming chunks
+    // The first NFULL steps of a resident row are in range for every thread of the
+    // workgroup at this plan's row length: straight-line code there lets the compiler wait
+    // for the loads one by one instead of for all of them.  (The row length is part of the
+    // plan's key, and NFULL of the generated text, so the assumption travels with the code.)
+    const int64_t NFULL = resident ? cols / per_iter : 0;
     auto open_pass = [&](bool load) {
         if (resident) {
             o << "        #pragma unroll\n        for (int u = 0; u < " << U << "; ++u) {\n";
             o << "            const idx_t col = (idx_t)(u * EWF_BLOCK + tid) * EWF_VEC;\n";
-            o << "            if (col >= cols) continue;\n";
+            o << "            if (u >= " << NFULL << " && col >= cols) continue;\n";
         } else {
             o << "        for (idx_t c0 = 0; c0 < cols; c0 += " << (per_iter * U) << ") {\n";
             o << "        #pragma unroll\n        for (int u = 0; u < " << U << "; ++u) {\n";
@@ -1154,13 +1166,23 @@ ewf_status Gen::gen_row()
               << "[(col + e_) * p.st_" << nm << "[" << in_d << "]];\n";
     };
 
+    // values constant along the row come first: an index that a gather depends on is then
+    // the first load to return, and the dependent read queues right behind the row
+    std::vector<int> uniform_loaded = splat_ops;
+    for (int l = 1; l <= D; l++)
+        for (const Gather &ga : gat[l])
+            for (int k : inputs_of(needed(std::vector<int>{ga.index_value})))
+                if (std::find(uniform_loaded.begin(), uniform_loaded.end(), k) == uniform_loaded.end()) uniform_loaded.push_back(k);
+    for (int k : uniform_loaded) {
+        base_once(k, "        ");
+        o << "        const " << ctype(c.ops[k].storage) << " g_" << opname(k) << " = ewf_ld_uniform(q_" << opname(k) << ");\n";
+    }
     if (resident) {
         for (int k : row_ops) o << "        ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
         open_pass(true);
         for (int k : row_ops) emit_row_load(k, "            ", "x_" + opname(k) + "[u]");
         close_pass();
     }
-    for (int k : splat_ops) o << "        const " << ctype(c.ops[k].storage) << " g_" << opname(k) << " = q_" << opname(k) << "[0];\n";
 
     EmitCtx cx;
     cx.input = [&](int k) {
@@ -1181,7 +1203,6 @@ ewf_status Gen::gen_row()
     };
 
     // values constant along the row, evaluated by every thread (uniform addresses)
-    std::vector<int> uniform_loaded = splat_ops;
     EmitCtx ux;
     ux.input = [&](int k) { return "ewf_in(g_" + opname(k) + ")"; };
     ux.coord = [&](int d) { return d == in_d ? std::string("0") : "o" + std::to_string(d); };
@@ -1190,20 +1211,20 @@ ewf_status Gen::gen_row()
         for (const Gather &ga : gat[l]) {
             // issued ahead of the level's pass so that the element arrives under it
             std::vector<char> need = needed(std::vector<int>{ga.index_value});
-            for (int k : inputs_of(need)) {
-                if (std::find(uniform_loaded.begin(), uniform_loaded.end(), k) != uniform_loaded.end()) continue;
-                uniform_loaded.push_back(k);
-                base_once(k, "        ");
-                o << "        const " << ctype(c.ops[k].storage) << " g_" << opname(k) << " = q_" << opname(k) << "[0];\n";
-            }
             base_once(ga.input, "        ");
             const std::string nm = opname(ga.input);
+            // keep the wait for the index behind every load already issued
+            o << "        __builtin_amdgcn_sched_barrier(0);\n";
             o << "        float r" << ga.node << ";\n        {\n";
             emit_values(need, ux, "            ");
+            // the read itself is unconditional (index clamped into the row) so that it is one
+            // more load in flight, not a branch the wavefront has to wait behind
             o << "            const int t_ = v" << ga.index_value << ";\n";
-            o << "            r" << ga.node << " = (t_ >= 0 && t_ < cols) ? ewf_in(q_" << nm << "[(idx_t)t_"
+            o << "            const bool in_ = t_ >= 0 && t_ < cols;\n";
+            o << "            const float x_ = ewf_in(q_" << nm << "[(idx_t)(in_ ? t_ : 0)"
               << (c.ops[ga.input].stride[in_d] == 1 ? std::string("") : " * p.st_" + nm + "[" + std::to_string(in_d) + "]")
-              << "]) + 0.0f : 0.0f;\n        }\n";
+              << "]);\n";
+            o << "            r" << ga.node << " = in_ ? x_ + 0.0f : 0.0f;\n        }\n";
         }
         if (lvl[l].empty()) continue;
         std::string an = "Acc" + std::to_string(l), av = "acc" + std::to_string(l);
@@ -1322,11 +1343,7 @@ ewf_status Gen::gen_row()
     }
 
     // ---- launch geometry and argument block
-    int64_t nrows = 1;
-    for (int d = 0; d < R - 1; d++) nrows *= c.extent[d];
-    if (nrows >= ((int64_t)1 << 31) - 1) return fail("too many rows");
-    int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)256 * 32;
-    p.grid = std::max<int64_t>(1, std::min(nrows, cap));
+    p.grid = std::max<int64_t>(1, std::min(nrows, grid_cap));
     p.lds_bytes = 0;
     p.counter_bytes = 0;
     p.workspace_bytes = 0;

@@ -54,6 +54,15 @@ EWF_DEV void ewf_st(T *p, const ewf_vec<T, N> &v)
     *reinterpret_cast<ewf_vec<T, N> *>(p) = v;
 }
 
+// A value at an address that is the same in every lane and that no lane of this launch writes
+// before reading it: read through the scalar unit (one request per wavefront, its own wait
+// counter, the result in a scalar register).
+template <typename T>
+EWF_DEV T ewf_ld_uniform(const T *p)
+{
+    return *(const __attribute__((address_space(4))) T *)p;
+}
+
 // Streaming flavour of the same accesses for operands that are touched exactly once and
 // are much larger than the caches: the non-temporal hint keeps them from displacing the
 // broadcast operands and measurably raises sustained HBM throughput.

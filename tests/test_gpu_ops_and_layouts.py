@@ -369,7 +369,7 @@ def test_one_hot_sum_is_read_as_a_gather(oracle, G):
         s.output(s.reduce("sum", s.apply("abs", xi), (1,)), "f32")
         print(f"[case] one-hot sum as gather, {storage}", flush=True)
         expr, got = run_spec(G, s, [xs, t])
-        assert expr.info()["kernel_class"] == "row" and "(idx_t)t_" in expr.source()
+        assert expr.info()["kernel_class"] == "row" and "(idx_t)(in_ ? t_ : 0)" in expr.source()
         want = oracle.evaluate(s, [xs, t], nthreads=4)
         assert np.array_equal(got[0], want[0]) and not np.signbit(got[0][6])
         assert got[0][0] == 0 and got[0][1] == 0 and got[0][2] == 0 and got[0][5] == 1.25
