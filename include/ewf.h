@@ -106,8 +106,12 @@ typedef struct {
     int32_t tile_elems;     /* elements per tile (per workgroup and loop trip); 0 = default  */
     int32_t waves_per_simd; /* register budget hint: resident wavefronts per SIMD to aim for
                                (1..8); 0 = compiler default                                   */
-    int32_t no_prefetch;    /* 1: do not issue the next trip's loads ahead of the arithmetic */
-    int32_t reserved[5];
+    int32_t no_prefetch;    /* the next trip's loads ahead of the current trip's arithmetic:
+                               0 automatic, 1 never, 2 always                                 */
+    int32_t xcd_remap;      /* 1: neighbouring tiles go to the same accelerator die, whose L2
+                               they then share (default 0: workgroup w takes tile w, which
+                               measured faster on streaming workloads)                       */
+    int32_t reserved[4];
 } ewf_options;
 
 /* A strided n-d view of caller-owned device memory.  rank is implied by the graph (inputs:

@@ -288,6 +288,14 @@ EWF_DEV T *ewf_at(T *base, long long off) { return base + off; }
 template <typename T>
 EWF_DEV const T *ewf_at(const T *base, long long off) { return base + off; }
 
+// Product of two non-negative factors that the generator knows to be below 2^24: the masks
+// let the compiler pick the full-rate 24-bit multiply.
+EWF_DEV unsigned ewf_mul24(int a, int b)
+{
+    return ((unsigned)a & 0xffffffu) * ((unsigned)b & 0xffffffu);
+}
+EWF_DEV unsigned ewf_mul24(int a, long long b) { return ewf_mul24(a, (int)b); }
+
 // ------------------------------------------------------------------ reductions
 
 // Moves every 32-bit word of v through a DPP lane pattern.

@@ -43,7 +43,8 @@ class ewf_options(ctypes.Structure):
                 ("unroll", ctypes.c_int32), ("max_blocks", ctypes.c_int32),
                 ("no_lds_staging", ctypes.c_int32), ("streaming", ctypes.c_int32),
                 ("tile_elems", ctypes.c_int32), ("waves_per_simd", ctypes.c_int32),
-                ("no_prefetch", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
+                ("no_prefetch", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 4)]
 
 
 class ewf_tensor(ctypes.Structure):
