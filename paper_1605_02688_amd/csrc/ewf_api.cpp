@@ -132,10 +132,13 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
         for (const OutputDecl &od : e.g.outputs)
             if (plan->red.edepth[od.value] >= 1 && (e.g.nodes[od.value].bcast & plan->red.axes) != plan->red.axes) full_dep_out = true;
         if (!c.reduced[c.rank - 1]) {
-            set_error("unsupported layout: the reduced axes are not the fastest-varying ones in memory");
-            return EWF_EUNSUPPORTED;
-        }
-        if (needs_row || full_dep_out) {
+            // the reduced axes are not the fastest-varying ones in memory: column class
+            if (needs_row || full_dep_out) {
+                set_error("unsupported: chained or cross-group reductions need the reduced axes to form the innermost contiguous dimension");
+                return EWF_EUNSUPPORTED;
+            }
+            plan->kclass = KernelClass::Col;
+        } else if (needs_row || full_dep_out) {
             if (!inner_only) {
                 set_error("unsupported: chained or cross-group reductions need the reduced axes to form the innermost contiguous dimension");
                 return EWF_EUNSUPPORTED;

@@ -97,7 +97,7 @@ struct Canon {
 // ---------------------------------------------------------------------------------------
 // Reduce structure of a graph (which kernel class can run it)
 
-enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3 };
+enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3, Col = 4 };
 
 struct ReduceInfo {
     bool has_reduce = false;

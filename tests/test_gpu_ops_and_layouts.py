@@ -311,6 +311,76 @@ def test_every_reduction_kind_row_and_split(oracle, G):
                 G.h.compare(f"{shape}.out{k}", g_, w_, 1e-5, 1e-6)
 
 
+def test_column_reductions(oracle, G):
+    # reduced axes that are not the fastest-varying ones: the lanes run along the kept axis
+    rng = np.random.default_rng(183)
+    cases = [((1000, 64), (0,)), ((37, 5, 48), (0,)), ((37, 5, 48), (1,)), ((6, 50, 7, 32), (0, 2)), ((300, 3), (0,)),
+             ((5, 4096), (0,)), ((70000, 8), (0,)), ((3, 9, 1000), (0, 1)), ((129, 260), (0,))]
+    for shape, axes in cases:
+        nd = len(shape)
+        X = rng.uniform(0.9, 1.1, shape).astype(np.float32)
+        I = rng.integers(-1000, 1000, shape).astype(np.int32)
+        s = GraphSpec(nd)
+        x = s.input("f32", (False,) * nd); i = s.input("i32", (False,) * nd)
+        for red in ("sum", "max", "min"):
+            s.output(s.reduce(red, x, axes), "f32")
+            s.output(s.reduce(red, i, axes), "i32")
+        s.output(s.reduce("sum", s.apply("tanh", s.mul(x, x)), axes), "f32")
+        if len(axes) == 1:
+            s.output(s.reduce("argmax", x, axes), "i32")
+            s.output(s.reduce("argmax", i, axes), "i32")
+        s.output(s.apply("exp", x), "f32")                    # an element-wise output in the same pass
+        print(f"[case] column reductions {shape} axes {axes}", flush=True)
+        expr, got = run_spec(G, s, [X, I])
+        assert expr.info()["kernel_class"] == "col", expr.info()
+        want = oracle.evaluate(s, [X, I], nthreads=4)
+        for k, ((v, st), g_, w_) in enumerate(zip(s.outputs, got, want)):
+            if st == "i32":
+                G.h.compare(f"{shape}.out{k}", g_, w_, 0, 0)
+            elif k == len(s.outputs) - 1:
+                G.h.compare(f"{shape}.exp", g_, w_, 2e-6, 1e-6)
+            else:
+                G.h.compare(f"{shape}.out{k}", g_, w_, 1e-5, 1e-6)
+
+
+def test_column_reduction_special_cases(oracle, G):
+    rng = np.random.default_rng(184)
+    # integer-valued float sums are exact whatever the order; ties, NaN and -inf columns for arg-max
+    X = rng.integers(-20, 20, (5000, 40)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    s.output(s.reduce("sum", xi, (0,)), "f32")
+    s.output(s.reduce("argmax", xi, (0,)), "i32")
+    s.output(s.reduce("max", xi, (0,)), "f32")
+    X[:, 1] = -np.inf
+    X[7, 2] = np.nan; X[99, 2] = np.nan
+    X[:, 3] = 2.0
+    expr, got = run_spec(G, s, [X])
+    assert expr.info()["kernel_class"] == "col"
+    want = oracle.evaluate(s, [X], nthreads=4)
+    assert np.array_equal(got[0], want[0], equal_nan=True)
+    assert np.array_equal(got[1], want[1]) and got[1][1] == 0 and got[1][2] == 7 and got[1][3] == 0
+    assert np.array_equal(got[2], want[2], equal_nan=True)
+    # float16 storage, a broadcast operand and a transposed view whose reduced axis is the slow one
+    A = rng.uniform(-1, 1, (64, 300)).astype(np.float16)
+    Bv = rng.uniform(0.5, 1.5, (1, 300)).astype(np.float16)
+    s = GraphSpec(2)
+    a = s.input("f16", (False, False)); b = s.input("f16", (True, False))
+    s.output(s.reduce("sum", s.mul(a, b), (0,)), "f32")
+    s.output(s.mul(a, b), "f16")
+    expr, got = run_spec(G, s, [A, Bv])
+    assert expr.info()["kernel_class"] == "col"
+    want = oracle.evaluate(s, [A, Bv])
+    G.h.compare("f16 colsum", got[0], want[0], 1e-5, 1e-6)
+    assert np.array_equal(got[1], want[1])
+    T = rng.standard_normal((96, 200)).astype(np.float32).T           # logical [200, 96], strides (1, 200)
+    s = GraphSpec(2)
+    s.output(s.reduce("sum", s.apply("abs", s.input("f32", (False, False))), (1,)), "f32")
+    expr, got = run_spec(G, s, [T])
+    assert expr.info()["kernel_class"] == "col", expr.info()
+    G.h.compare("transposed", got[0], oracle.evaluate(s, [T])[0], 1e-5, 1e-6)
+
+
 def test_argmax_ties_take_the_first_index(oracle, G):
     x = np.zeros((70, 5000), np.float32)
     x[:, 4000] = 3.0; x[:, 123] = 3.0; x[5, 7] = 3.0
@@ -440,9 +510,11 @@ def random_case(seed):
     vals.append(s.scalar("f32"))
     reduce_axes = None
     if rng.integers(0, 2):
-        # reductions the kernel classes cover: over the trailing axes of a contiguous operand
+        # trailing axes of a contiguous operand, or (every other case) any subset of the axes
         k = int(rng.integers(1, ndim + 1))
         reduce_axes = tuple(range(ndim - k, ndim))
+        if seed % 2:
+            reduce_axes = tuple(sorted(rng.choice(ndim, size=int(rng.integers(1, ndim + 1)), replace=False).tolist()))
         inputs[0] = np.ascontiguousarray(inputs[0])
     for _ in range(int(rng.integers(2, 8))):
         r = rng.integers(0, 10)

@@ -320,8 +320,13 @@ def test_kernel_class_selection():
     # softmax: the output depends on a reduction and varies along the row -> row-resident class
     info = red(2, (1,), (4, 1000), extra=lambda s, x, r: s.output(s.div(x, r), "f32"))
     assert info["kernel_class"] == "row"
-    with pytest.raises(ewf.EwfError) as e:                                # column reduction: not yet covered
-        red(2, (0,), (512, 512))
+    # the kept axis is the fastest-varying one: column class, lanes along the columns
+    info = red(2, (0,), (512, 512))
+    assert info["kernel_class"] == "col" and info["reduced"] == (True, False)
+    assert red(4, (0, 2), (6, 50, 7, 32))["kernel_class"] == "col"
+    assert red(2, (1,), (200, 96), strides=(1, 200))["kernel_class"] == "col"   # a transposed view, reduced along its rows
+    with pytest.raises(ewf.EwfError) as e:        # normalising by a column sum needs a second pass: not covered
+        red(2, (0,), (512, 512), extra=lambda s, x, r: s.output(s.div(x, r), "f32"))
     assert e.value.status == ewf.EUNSUPPORTED
     # reducing over extent-1 axes is the identity: plain element-wise kernel
     assert red(2, (1,), (64, 1))["kernel_class"] == "tile"
