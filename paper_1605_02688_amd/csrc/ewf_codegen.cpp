@@ -545,6 +545,54 @@ struct Gen {
         return EWF_EUNSUPPORTED;
     }
 
+    // Second kernel of the split reductions: one workgroup per reduction group; its lanes walk
+    // the group's partials (contiguous in the workspace), a wavefront butterfly and an LDS
+    // step in wavefront order fold them -- the same order on every run.
+    void emit_finish_lanes(const std::vector<int> &level, const std::vector<int> &group_out_ops,
+                           const std::string &nparts_expr, int fin_block)
+    {
+        std::vector<int> all_dims;
+        for (int d = 0; d < R; d++) all_dims.push_back(d);
+        o << "\n// folds the partials of each reduction group in a fixed order\n";
+        o << "extern \"C\" __global__ void __launch_bounds__(" << fin_block << ") ewf_finish(const Params p)\n{\n";
+        o << "    const int lane = threadIdx.x;\n";
+        o << "    __shared__ Acc sm_fin[" << fin_block / 64 << "];\n";
+        o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
+        o << "    const idx_t nparts = " << nparts_expr << ";\n";
+        o << "    for (idx_t group = blockIdx.x; group < p.nrows; group += gridDim.x) {\n";
+        o << "        const Acc *const gpart = partials + (size_t)group * (size_t)nparts;\n";
+        o << "        Acc tot = Acc_identity();\n";
+        o << "        for (idx_t i = lane; i < nparts; i += " << fin_block << ") tot = Acc_combine()(tot, gpart[i]);\n";
+        o << "        tot = ewf_block_reduce<" << fin_block / 64 << ">(tot, Acc_combine(), sm_fin, lane);\n";
+        o << "        if (lane != 0) continue;\n";
+        o << "        idx_t g_ = group;\n";
+        for (int d = R - 1; d >= 0; d--) {
+            if (c.reduced[d]) { o << "        const idx_t o" << d << " = 0;\n"; continue; }
+            bool last_kept = true;
+            for (int d2 = d - 1; d2 >= 0; d2--) if (!c.reduced[d2]) last_kept = false;
+            if (!last_kept) o << "        const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
+            else o << "        const idx_t o" << d << " = g_;\n";
+        }
+        for (int d = 0; d < R; d++) o << "        (void)o" << d << ";\n";
+        emit_results("tot", level, "        ");
+        std::vector<int> gt;
+        for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
+        std::vector<char> gneed = needed(gt);
+        for (int k : inputs_of(gneed)) emit_base(k, all_dims, "        ");
+        EmitCtx gx;
+        gx.input = [&](int k) { return "ewf_in(q_" + opname(k) + "[0])"; };
+        gx.coord = [&](int d) { return "o" + std::to_string(d); };
+        emit_values(gneed, gx, "        ");
+        for (int k : group_out_ops) {
+            const Operand &op = c.ops[k];
+            int v = g.outputs[op.index].value;
+            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
+            emit_base(k, all_dims, "        ");
+            o << "        q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
+        }
+        o << "    }\n}\n";
+    }
+
     ewf_status gen_tile(bool with_reduce);
     ewf_status gen_row();
     ewf_status gen_col();
@@ -1007,44 +1055,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         for (int d = 0; d < R; d++) if (c.reduced[d]) nparts_host *= ntile[d];
         const int fin_block = nparts_host > 256 ? 256 : 64;
         fin_block_out = fin_block;
-        o << "\n// folds the partials of each reduction group in a fixed order\n";
-        o << "extern \"C\" __global__ void __launch_bounds__(" << fin_block << ") ewf_finish(const Params p)\n{\n";
-        o << "    const int lane = threadIdx.x;\n";
-        o << "    __shared__ Acc sm_fin[" << fin_block / 64 << "];\n";
-        o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
-        o << "    const idx_t nparts = p.nslots * EWF_NWAVES;\n";
-        o << "    for (idx_t group = blockIdx.x; group < p.nrows; group += gridDim.x) {\n";
-        o << "        const Acc *const gpart = partials + (size_t)group * (size_t)nparts;\n";
-        o << "        Acc tot = Acc_identity();\n";
-        o << "        for (idx_t i = lane; i < nparts; i += " << fin_block << ") tot = Acc_combine()(tot, gpart[i]);\n";
-        o << "        tot = ewf_block_reduce<" << fin_block / 64 << ">(tot, Acc_combine(), sm_fin, lane);\n";
-        o << "        if (lane != 0) continue;\n";
-        o << "        idx_t g_ = group;\n";
-        for (int d = R - 1; d >= 0; d--) {
-            if (c.reduced[d]) { o << "        const idx_t o" << d << " = 0;\n"; continue; }
-            bool last_kept = true;
-            for (int d2 = d - 1; d2 >= 0; d2--) if (!c.reduced[d2]) last_kept = false;
-            if (!last_kept) o << "        const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
-            else o << "        const idx_t o" << d << " = g_;\n";
-        }
-        for (int d = 0; d < R; d++) o << "        (void)o" << d << ";\n";
-        emit_results("tot", level, "        ");
-        std::vector<int> gt;
-        for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
-        std::vector<char> gneed = needed(gt);
-        for (int k : inputs_of(gneed)) emit_base(k, all_dims, "        ");
-        EmitCtx gx;
-        gx.input = [&](int k) { return "ewf_in(q_" + opname(k) + "[0])"; };
-        gx.coord = [&](int d) { return "o" + std::to_string(d); };
-        emit_values(gneed, gx, "        ");
-        for (int k : group_out_ops) {
-            const Operand &op = c.ops[k];
-            int v = g.outputs[op.index].value;
-            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
-            emit_base(k, all_dims, "        ");
-            o << "        q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
-        }
-        o << "    }\n}\n";
+        emit_finish_lanes(level, group_out_ops, "p.nslots * EWF_NWAVES", fin_block);
     }
 
     // ---- launch geometry and argument block
@@ -1479,6 +1490,9 @@ ewf_status Gen::gen_col()
     if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31) || ngroups * nslots >= ((int64_t)1 << 40))
         return fail("too many reduction groups");
 
+    const bool fin_lanes = nslots > 16;
+    const int fin_block = nslots > 256 ? 256 : 64;
+
     // ---- what to evaluate per element
     std::vector<int> targets;
     for (int k : ew_out_ops) targets.push_back(g.outputs[c.ops[k].index].value);
@@ -1605,12 +1619,16 @@ ewf_status Gen::gen_col()
         else if (d == in_d) o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + cc_);\n";
         else o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)o" << d << ";\n";
     }
-    o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[slot * (size_t)p.nrows + group + e_] = acc[e_];\n";
+    if (fin_lanes) o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[(group + e_) * (size_t)p.nslots + slot] = acc[e_];\n";
+    else o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[slot * (size_t)p.nrows + group + e_] = acc[e_];\n";
     o << ind << "}\n";
     if (TY > 1) o << ind << "__syncthreads();\n";
     o << "    }\n}\n";
 
-    // ---- second kernel: one thread per column folds its slots in slot order
+    // ---- second kernel.  Many slots per column: the partials of a column are contiguous and a
+    // workgroup's lanes walk them.  Few: one thread per column folds its slots in slot order.
+    if (fin_lanes) emit_finish_lanes(level, group_out_ops, "p.nslots", fin_block);
+    else {
     o << "\nextern \"C\" __global__ void __launch_bounds__(256) ewf_finish(const Params p)\n{\n";
     o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
     o << "    for (idx_t group = blockIdx.x * 256 + threadIdx.x; group < p.nrows; group += gridDim.x * 256) {\n";
@@ -1643,6 +1661,7 @@ ewf_status Gen::gen_col()
         }
     }
     o << "    }\n}\n";
+    }
 
     // ---- launch geometry and argument block
     int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)1 << 22;
@@ -1652,8 +1671,9 @@ ewf_status Gen::gen_col()
     p.staged = 0;
     p.counter_bytes = 0;
     p.workspace_bytes = (size_t)ngroups * (size_t)nslots * acc_bytes(level);
-    p.finish_grid = std::max<int64_t>(1, std::min<int64_t>(ceil_div(ngroups, 256), (int64_t)1 << 16));
-    p.finish_block = 256;
+    p.finish_grid = fin_lanes ? std::min<int64_t>(ngroups, (int64_t)1 << 20)
+                              : std::max<int64_t>(1, std::min<int64_t>(ceil_div(ngroups, 256), (int64_t)1 << 16));
+    p.finish_block = fin_lanes ? fin_block : 256;
     p.args.assign(p.layout.size, 0);
     auto put_idx = [&](const std::string &name, int i, int64_t v) {
         int f = p.layout.find(name);
