@@ -111,7 +111,10 @@ typedef struct {
     int32_t xcd_remap;      /* 1: neighbouring tiles go to the same accelerator die, whose L2
                                they then share (default 0: workgroup w takes tile w, which
                                measured faster on streaming workloads)                       */
-    int32_t reserved[4];
+    int32_t no_rewrite;     /* 1: compile the scalar graph as described (default: duplicates
+                               merged, constants folded, log(1+x) -> log1p(x), exp(x)-1 ->
+                               expm1(x), x*x and pow(x,2) -> a square, identities removed)   */
+    int32_t reserved[3];
 } ewf_options;
 
 /* A strided n-d view of caller-owned device memory.  rank is implied by the graph (inputs:
@@ -212,6 +215,10 @@ ewf_status ewf_debug_operand_strides(ewf_exec *e, int32_t k, int64_t *strides_ou
 const char *ewf_debug_source(ewf_exec *e);
 /* Number of kernels compiled so far by this executable (cache misses). */
 int32_t ewf_debug_compile_count(ewf_exec *e);
+/* Nodes of the scalar graph as described, and after the rewrites of ewf_compile (section
+ * 2.2.1 of the paper: canonicalisation merges duplicates and folds constants, stabilisation
+ * replaces log(1 + x) by log1p(x)). */
+ewf_status ewf_debug_graph_size(ewf_exec *e, int32_t *nodes_described, int32_t *nodes_compiled);
 
 /* ---- measurement aid ---- */
 

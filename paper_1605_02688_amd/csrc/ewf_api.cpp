@@ -186,6 +186,13 @@ ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **o
     if (opts) x->e.opts = *opts;
     ewf_status st = finalize_graph(x->e.g);
     if (st != EWF_OK) { delete x; return st; }
+    x->e.nodes_before = (int)x->e.g.nodes.size();
+    if (!x->e.opts.no_rewrite) {
+        rewrite_graph(x->e.g);
+        st = finalize_graph(x->e.g);
+        if (st != EWF_OK) { delete x; return st; }
+    }
+    x->e.nodes_after = (int)x->e.g.nodes.size();
     bool all_f16 = true;
     for (const OutputDecl &o : x->e.g.outputs) if (o.storage != EWF_F16) all_f16 = false;
     const int mm = x->e.opts.math_mode;
@@ -340,6 +347,14 @@ const char *ewf_debug_source(ewf_exec *e)
 }
 
 int32_t ewf_debug_compile_count(ewf_exec *e) { return e ? e->e.compile_count : 0; }
+
+ewf_status ewf_debug_graph_size(ewf_exec *e, int32_t *nodes_described, int32_t *nodes_compiled)
+{
+    if (!e || !nodes_described || !nodes_compiled) { set_error("null argument"); return EWF_EINVAL; }
+    *nodes_described = e->e.nodes_before;
+    *nodes_compiled = e->e.nodes_after;
+    return EWF_OK;
+}
 
 ewf_status ewf_copy_bytes(void *dst, const void *src, size_t nbytes, void *hip_stream)
 {

@@ -170,6 +170,7 @@ struct Exec {
     std::map<std::string, std::unique_ptr<Plan>> plans;  // keyed by layout signature
     Plan *last = nullptr;
     int compile_count = 0;
+    int nodes_before = 0, nodes_after = 0;   // size of the scalar graph before / after the rewrites
 };
 
 // ---- ewf_ir.cpp
@@ -180,6 +181,10 @@ ewf_status finalize_graph(Graph &g);     // recompute derived fields, validate o
 ReduceInfo analyse_reductions(const Graph &g, uint32_t unit_mask);
 void set_error_str(const std::string &s);
 uint32_t all_mask(int ndim);
+
+// ---- ewf_rewrite.cpp
+// Merges duplicate nodes, folds constants, applies the stabilising rewrites; in place.
+int rewrite_graph(Graph &g);
 
 // ---- ewf_canon.cpp
 // Builds the canonical layout.  `in`/`out` give shapes and strides in the original rank

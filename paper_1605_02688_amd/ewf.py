@@ -44,7 +44,7 @@ class ewf_options(ctypes.Structure):
                 ("no_lds_staging", ctypes.c_int32), ("streaming", ctypes.c_int32),
                 ("tile_elems", ctypes.c_int32), ("waves_per_simd", ctypes.c_int32),
                 ("no_prefetch", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 4)]
+                ("no_rewrite", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 class ewf_tensor(ctypes.Structure):
@@ -88,6 +88,7 @@ _sigs = {
     "ewf_debug_operand_strides": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_int64)]),
     "ewf_debug_source": (ctypes.c_char_p, [_vp]),
     "ewf_debug_compile_count": (_i32, [_vp]),
+    "ewf_debug_graph_size": (_i32, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "ewf_copy_bytes": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
 }
 for _name, (_res, _args) in _sigs.items():
@@ -250,6 +251,12 @@ def debug_compile_count(e: int) -> int:
     return _lib.ewf_debug_compile_count(e)
 
 
+def debug_graph_size(e: int) -> Tuple[int, int]:
+    a, b = _i32(), _i32()
+    _check(_lib.ewf_debug_graph_size(e, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
 def copy_bytes(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
     _check(_lib.ewf_copy_bytes(dst_ptr, src_ptr, nbytes, stream or None))
 
@@ -333,6 +340,10 @@ class Expression:
 
     def source(self) -> str:
         return debug_source(self.handle)
+
+    def graph_size(self) -> Tuple[int, int]:
+        """(nodes described, nodes compiled after the rewrites)."""
+        return debug_graph_size(self.handle)
 
 
 class BoundCall:

@@ -183,6 +183,38 @@ def test_native_rate_math_meets_the_f16_bar(oracle, G):
             G.h.compare(f"mode{mode}.out{k}", g_, w_, 2e-3, 1e-3)
 
 
+def test_rewritten_graph_matches_the_graph_as_described(oracle, G):
+    # the oracle evaluates the description node by node; the library first merges duplicates,
+    # folds constants and applies the stabilising rewrites
+    rng = np.random.default_rng(185)
+    x = rng.uniform(-3, 3, 6000).astype(np.float32)
+    x[:6] = np.float32([1e-7, -1e-7, 3e-10, 0.0, 20.0, -20.0])
+    y = rng.uniform(0.1, 2, 6000).astype(np.float32)
+    s = GraphSpec(1)
+    xi = s.input("f32", (False,)); yi = s.input("f32", (False,))
+    softplus = s.apply("log", s.add(s.const(1.0), s.apply("exp", xi)))                 # -> log1p(exp(x))
+    em1 = s.sub(s.apply("exp", xi), s.const(1.0))                                     # -> expm1(x)
+    sq = s.apply("pow", s.add(s.mul(yi, s.const(1.0)), s.const(0.0)), s.const(2.0))   # -> y * y
+    k = s.apply("exp", s.mul(s.const(0.5), s.const(-2.0)))                            # -> literal e^-1
+    dup = s.apply("tanh", s.mul(xi, yi)); dup2 = s.apply("tanh", s.mul(yi, xi))       # one node
+    s.output(softplus, "f32"); s.output(em1, "f32"); s.output(sq, "f32")
+    s.output(s.mul(s.add(dup, dup2), k), "f32")
+    want = oracle.evaluate(s, [x, y])
+    for opts in ({}, {"no_rewrite": 1}):
+        expr, got = run_spec(G, s, [x, y], **opts)
+        before, after = expr.graph_size()
+        assert (after < before) == (not opts)
+        for k_, (g_, w_) in enumerate(zip(got, want)):
+            if opts and k_ == 1:
+                # exp(x) - 1 as described loses the small arguments in float32; only the rewritten form meets the bar there
+                G.h.compare(f"described.out{k_}", g_[6:], w_[6:], 2e-6, 1e-6)
+                continue
+            G.h.compare(f"{'described' if opts else 'rewritten'}.out{k_}", g_, w_, 2e-6, 1e-6)
+    # the stable forms keep the tiny arguments that the described forms would lose
+    expr, got = run_spec(G, s, [x, y])
+    assert np.allclose(got[1][:3], x[:3].astype(np.float64), rtol=1e-5)
+
+
 # ------------------------------------------------------------------ layouts
 
 def test_transpose_and_slice_views(oracle, G):

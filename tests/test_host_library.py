@@ -351,6 +351,69 @@ def test_generated_source_structure_and_cache():
     assert "0x3f000000" in exprc.source() and "p.s0" not in exprc.source()
 
 
+def _values(expr):
+    return [l.split("=", 1)[1].strip() for l in expr.source().split("\n")
+            if l.strip().startswith(("const float v", "const int v"))]
+
+
+def test_scalar_graph_rewrites():
+    """Canonicalisation and stabilisation of the scalar graph (paper section 2.2.1): merged
+    duplicates, folded constants, log(1+x) -> log1p(x), exp(x)-1 -> expm1(x), x*x and
+    pow(x,2) -> a square, identities removed."""
+    def planned(s, n=1024, **opts):
+        expr = ewf.Expression(s, **opts)
+        ins = [ref(BASE + k * (1 << 24), (n,)) for k in range(sum(1 for nd in s.nodes if nd[0] == "input"))]
+        outs = [ref(BASE + (1 << 36) + k * (1 << 24), sh) for k, sh in enumerate(expr.output_shapes(ins))]
+        expr.plan(ins, outs)
+        return expr
+    s = GraphSpec(1); x = s.input("f32", (False,))
+    a = s.apply("log", s.add(s.const(1.0), s.apply("exp", x)))
+    b = s.apply("log", s.add(s.apply("exp", x), s.const(1.0)))       # the same value, written the other way round
+    c = s.sub(s.apply("exp", x), s.const(1.0))
+    d = s.apply("pow", s.mul(x, s.const(1.0)), s.const(2.0))
+    k = s.mul(s.const(2.0), s.const(3.0))
+    s.output(s.add(s.add(a, b), s.mul(s.add(c, d), k)), "f32")
+    expr = planned(s)
+    before, after = expr.graph_size()
+    assert before == 23 and after == 10
+    vals = " ".join(_values(expr))
+    assert vals.count("::exp(") == 1 and vals.count("::log1p(") == 1 and vals.count("::expm1(") == 1
+    assert "::log(" not in vals and "::pow" not in vals and "0x40c00000u" in vals       # 2 * 3 folded to 6.0f
+    raw = planned(s, no_rewrite=1)
+    assert raw.graph_size() == (23, 23) and " ".join(_values(raw)).count("::exp(") == 3
+
+    # integer folding wraps around; casts fold; comparisons fold to 0/1
+    s = GraphSpec(1); i = s.input("i32", (False,))
+    big = s.mul(s.const(65536, "i32"), s.const(65536, "i32"))                           # 2^32 wraps to 0
+    one = s.apply("gt", s.const(2.5), s.const(1.0))
+    s.output(s.add(s.add(i, big), s.add(one, s.cast(s.const(-3.9), "i32"))), "i32")   # i + 0 + (1 + -3)
+    expr = planned(s)
+    assert "0xfffffffeu" in " ".join(_values(expr)) and expr.graph_size()[1] == 3     # input, literal -2, add
+
+    # a rewrite never changes an output's shape: where(true, row_vector, full) keeps the full extent
+    s = GraphSpec(2)
+    rowv = s.input("f32", (True, False)); fullv = s.input("f32", (False, False))
+    s.output(s.apply("where", s.const(1, "i32"), rowv, fullv), "f32")
+    expr = ewf.Expression(s)
+    ins = [ref(BASE, (1, 64)), ref(BASE + (1 << 24), (8, 64))]
+    assert expr.output_shapes(ins) == [(8, 64)]
+    # ... while where(true, a, b) with equal patterns is just a
+    s = GraphSpec(1); p_ = s.input("f32", (False,)); q_ = s.input("f32", (False,))
+    s.output(s.apply("where", s.const(1, "i32"), s.apply("tanh", p_), s.apply("exp", q_)), "f32")
+    expr = planned(s)
+    assert "::exp(" not in " ".join(_values(expr)) and "::tanh(" in " ".join(_values(expr))
+
+    # reductions merge too: two sums of the same argument over the same axes are one accumulator
+    s = GraphSpec(2); x = s.input("f32", (False, False))
+    e1 = s.apply("exp", x); e2 = s.apply("exp", x)
+    s.output(s.reduce("sum", e1, (1,)), "f32"); s.output(s.reduce("sum", e2, (1,)), "f32")
+    expr = ewf.Expression(s)
+    ins = [ref(BASE, (600, 128))]
+    outs = [ref(BASE + (1 << 36) + k * (1 << 24), sh) for k, sh in enumerate(expr.output_shapes(ins))]
+    expr.plan(ins, outs)
+    assert expr.graph_size() == (5, 3) and "float a1;" not in expr.source()
+
+
 def test_math_mode_follows_storage():
     w5 = wl.layout_only(wl.c5_stress, n=2)
     e5, _, _ = plan_workload(w5)
