@@ -153,6 +153,20 @@ ewf_value ewf_cast(ewf_graph *g, ewf_value v, ewf_dtype to);
  * reduced axes are removed from the shape of any output computed from the result alone. */
 ewf_value ewf_reduce(ewf_graph *g, ewf_redop op, ewf_value v, const int32_t *axes, int32_t naxes,
                      int32_t keep_as_bcast);
+/* Reverse-mode differentiation (section 2.1.3 of the paper: gradients are built symbolically
+ * by traversing the graph from the outputs back to the inputs).  y[k] are float32 values of
+ * the graph and ybar[k] their cotangents (float32 values of the same graph, usually further
+ * inputs; a cotangent may be broadcastable where its value is not).  For every wrt[j] (a
+ * float32 value, usually an input) the call appends the nodes of
+ *     grads[j] = sum_k sum_elements ybar[k] * d y[k] / d wrt[j]
+ * to the graph and returns their ids; declare them as outputs like any other value.  Where
+ * wrt[j] is broadcastable and the cotangent is not, the result is summed over those axes (kept
+ * as broadcastable, so it has the shape of wrt[j]).  Conventions: max/min give the cotangent to
+ * the first operand on ties, reduce-max/min to every element equal to the result, abs has
+ * derivative 0 at 0, comparisons and int32 values stop the cotangent, float16 rounding passes
+ * it through.  EWF_EUNSUPPORTED for a product reduction on the path. */
+ewf_status ewf_grad(ewf_graph *g, const ewf_value *y, const ewf_value *ybar, int32_t ny,
+                    const ewf_value *wrt, int32_t nwrt, ewf_value *grads);
 /* Declares output number k (k counts ewf_output calls) stored as `storage`. */
 ewf_status ewf_output(ewf_graph *g, ewf_value v, ewf_dtype storage);
 
@@ -206,6 +220,24 @@ typedef struct {
     int32_t staged_operands;  /* number of operands staged through LDS                       */
     int64_t tile[EWF_MAX_DIMS];
 } ewf_plan_info;
+
+/* One node of a graph under construction, as the library holds it (lets a test read back what
+ * ewf_grad appended). kind: 0 input, 1 scalar, 2 literal, 3 iota, 4 apply, 5 cast, 6 reduce. */
+typedef struct {
+    int32_t kind;
+    int32_t op;               /* apply: ewf_op; reduce: ewf_redop; cast: target ewf_dtype      */
+    int32_t nargs;
+    int32_t args[3];
+    int32_t index;            /* input / scalar ordinal; iota axis                            */
+    uint32_t axes;            /* reduce: bit d set = axis d reduced                           */
+    int32_t keep;             /* reduce: reduced axes stay in output shapes                   */
+    int32_t vtype;            /* value type (EWF_F32 or EWF_I32)                              */
+    int32_t storage;          /* input: storage type                                          */
+    uint32_t bcast;           /* bit d set = constant along axis d                            */
+    double cval;              /* literal                                                      */
+} ewf_node_info;
+int32_t ewf_debug_graph_count(const ewf_graph *g);
+ewf_status ewf_debug_graph_node(const ewf_graph *g, int32_t i, ewf_node_info *info);
 
 /* Describes the most recent plan made (or looked up) on this executable. */
 ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info);

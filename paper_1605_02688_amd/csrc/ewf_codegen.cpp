@@ -1467,7 +1467,19 @@ ewf_status Gen::gen_col()
     if (colvecs < 64) { TX = 1; while (TX < colvecs) TX *= 2; }
     const int TY = block / TX;
     const int64_t TK = std::min<int64_t>(c.extent[in_d], (int64_t)TX * VEC);   // columns per tile
-    const int U = e.opts.unroll > 0 ? e.opts.unroll : 4;                      // rows in flight per thread
+    // rows in flight per thread: four for streaming expressions, fewer when the expression is
+    // heavy in transcendental operations (registers) or the problem is small (spread it out)
+    int heavy = 0;
+    for (size_t n = 0; n < g.nodes.size(); n++) {
+        if (!live[n] || g.nodes[n].kind != NodeKind::Apply) continue;
+        switch (g.nodes[n].op) {
+        case EWF_EXP: case EWF_LOG: case EWF_LOG1P: case EWF_TANH: case EWF_SIGMOID: case EWF_EXPM1: heavy += 1; break;
+        case EWF_POW: case EWF_DIV: heavy += 2; break;
+        default: break;
+        }
+    }
+    const bool small = c.total / VEC < (int64_t)256 * 512;
+    const int U = e.opts.unroll > 0 ? e.opts.unroll : small ? 1 : heavy >= 4 ? 2 : 4;
     int64_t T[kMaxDims];
     for (int d = 0; d < kMaxDims; d++) T[d] = 1;
     T[in_d] = TK;

@@ -367,8 +367,30 @@ ewf_status ewf_output(ewf_graph *g, ewf_value v, ewf_dtype storage)
 
 const char *ewf_last_error(void) { return get_error(); }
 
+int32_t ewf_debug_graph_count(const ewf_graph *g) { return g ? (int32_t)g->g.nodes.size() : 0; }
+
+ewf_status ewf_debug_graph_node(const ewf_graph *g, int32_t i, ewf_node_info *info)
+{
+    if (!g || !info || i < 0 || i >= (int32_t)g->g.nodes.size()) { set_error("no such node"); return EWF_EINVAL; }
+    const Node &nd = g->g.nodes[i];
+    info->kind = (int32_t)nd.kind;
+    info->op = nd.op;
+    info->nargs = nd.nargs;
+    for (int a = 0; a < 3; a++) info->args[a] = nd.args[a];
+    info->index = nd.index;
+    info->axes = nd.axes;
+    info->keep = nd.keep ? 1 : 0;
+    info->vtype = (int32_t)nd.vtype;
+    info->storage = (int32_t)nd.storage;
+    info->bcast = nd.bcast;
+    info->cval = nd.cval;
+    return EWF_OK;
+}
+
 }  // extern "C"
 
 namespace ewf {
 const Graph &graph_of(const ewf_graph *g) { return g->g; }
+Graph &graph_of_mut(ewf_graph *g) { return g->g; }
+ewf_value graph_push(Graph *g, Node nd) { return push_node(g, nd); }
 }

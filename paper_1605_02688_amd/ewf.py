@@ -61,6 +61,13 @@ class ewf_plan_info(ctypes.Structure):
                 ("tile", ctypes.c_int64 * MAX_DIMS)]
 
 
+class ewf_node_info(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("op", ctypes.c_int32), ("nargs", ctypes.c_int32),
+                ("args", ctypes.c_int32 * 3), ("index", ctypes.c_int32), ("axes", ctypes.c_uint32),
+                ("keep", ctypes.c_int32), ("vtype", ctypes.c_int32), ("storage", ctypes.c_int32),
+                ("bcast", ctypes.c_uint32), ("cval", ctypes.c_double)]
+
+
 _vp = ctypes.c_void_p
 _i32 = ctypes.c_int32
 _sigs = {
@@ -74,6 +81,8 @@ _sigs = {
     "ewf_cast": (_i32, [_vp, _i32, _i32]),
     "ewf_reduce": (_i32, [_vp, _i32, _i32, ctypes.POINTER(_i32), _i32, _i32]),
     "ewf_output": (_i32, [_vp, _i32, _i32]),
+    "ewf_grad": (_i32, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32), _i32, ctypes.POINTER(_i32), _i32,
+                        ctypes.POINTER(_i32)]),
     "ewf_compile": (_i32, [_vp, ctypes.POINTER(ewf_options), ctypes.POINTER(_vp)]),
     "ewf_exec_destroy": (None, [_vp]),
     "ewf_output_shape": (_i32, [_vp, ctypes.POINTER(ewf_tensor), _i32, _i32, ctypes.POINTER(_i32),
@@ -84,6 +93,8 @@ _sigs = {
     "ewf_run": (_i32, [_vp, ctypes.POINTER(ewf_tensor), _i32, ctypes.POINTER(ctypes.c_double), _i32,
                        ctypes.POINTER(ewf_tensor), _i32, _vp, ctypes.c_size_t, _vp]),
     "ewf_last_error": (ctypes.c_char_p, []),
+    "ewf_debug_graph_count": (_i32, [_vp]),
+    "ewf_debug_graph_node": (_i32, [_vp, _i32, ctypes.POINTER(ewf_node_info)]),
     "ewf_debug_plan_info": (_i32, [_vp, ctypes.POINTER(ewf_plan_info)]),
     "ewf_debug_operand_strides": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_int64)]),
     "ewf_debug_source": (ctypes.c_char_p, [_vp]),
@@ -150,6 +161,15 @@ def cast(g: int, v: int, to: int) -> int:
 def reduce(g: int, redop: int, v: int, axes: Sequence[int], keep_as_bcast: bool) -> int:
     a = (_i32 * max(1, len(axes)))(*axes)
     return _check(_lib.ewf_reduce(g, redop, v, a, len(axes), 1 if keep_as_bcast else 0))
+
+
+def grad(g: int, ys: Sequence[int], ybars: Sequence[int], wrt: Sequence[int]) -> List[int]:
+    ya = (_i32 * len(ys))(*ys)
+    yb = (_i32 * len(ybars))(*ybars)
+    wa = (_i32 * len(wrt))(*wrt)
+    out = (_i32 * len(wrt))()
+    _check(_lib.ewf_grad(g, ya, yb, len(ys), wa, len(wrt), out))
+    return list(out)
 
 
 def output(g: int, v: int, storage: int) -> None:
@@ -270,12 +290,13 @@ def options(**kw) -> ewf_options:
     return o
 
 
-def build_graph(spec) -> int:
+def build_graph(spec, return_ids: bool = False):
     """Replays a data-only graph description (``ndim``, ``nodes``, ``outputs``; node tuples as
     produced by ``workloads.GraphSpec``) through the graph-building calls."""
     g = graph_create(spec.ndim)
     try:
         ids: List[int] = []
+        grad_results = {}
         for node in spec.nodes:
             kind = node[0]
             if kind == "input":
@@ -292,6 +313,12 @@ def build_graph(spec) -> int:
                 ids.append(cast(g, ids[node[1]], DTYPES[node[2]]))
             elif kind == "reduce":
                 ids.append(reduce(g, REDOPS[node[1]], ids[node[2]], node[3], node[4]))
+            elif kind == "grad":
+                # one differentiation call; its results are picked up by "gradof" nodes
+                grad_results[len(ids)] = grad(g, [ids[v] for v in node[1]], [ids[v] for v in node[2]], [ids[v] for v in node[3]])
+                ids.append(-1)
+            elif kind == "gradof":
+                ids.append(grad_results[node[1]][node[2]])
             else:
                 raise ValueError(kind)
         for v, storage in spec.outputs:
@@ -299,7 +326,44 @@ def build_graph(spec) -> int:
     except Exception:
         graph_destroy(g)
         raise
-    return g
+    return (g, ids) if return_ids else g
+
+
+def export_spec(spec):
+    """Replays ``spec`` through the graph-building calls (differentiation requests included) and
+    reads the resulting node list back as a plain description without such requests: what the
+    library will compile, in a form any evaluator of descriptions can take."""
+    from workloads import GraphSpec
+    names = {v: k for k, v in OPS.items()}
+    rnames = {v: k for k, v in REDOPS.items()}
+    dnames = {v: k for k, v in DTYPES.items()}
+    g, ids = build_graph(spec, return_ids=True)
+    try:
+        out = GraphSpec(spec.ndim)
+        info = ewf_node_info()
+        for i in range(_lib.ewf_debug_graph_count(g)):
+            _check(_lib.ewf_debug_graph_node(g, i, ctypes.byref(info)))
+            a = [info.args[k] for k in range(info.nargs)]
+            bc = tuple(bool(info.bcast >> d & 1) for d in range(spec.ndim))
+            if info.kind == 0:
+                out.input(dnames[info.storage], bc)
+            elif info.kind == 1:
+                out.scalar(dnames[info.vtype])
+            elif info.kind == 2:
+                out.const(info.cval, dnames[info.vtype])
+            elif info.kind == 3:
+                out.iota(info.index)
+            elif info.kind == 4:
+                out.apply(names[info.op], *a)
+            elif info.kind == 5:
+                out.cast(a[0], dnames[info.op])
+            else:
+                out.reduce(rnames[info.op], a[0], [d for d in range(spec.ndim) if info.axes >> d & 1], bool(info.keep))
+        for v, storage in spec.outputs:
+            out.output(ids[v], storage)
+        return out
+    finally:
+        graph_destroy(g)
 
 
 class Expression:

@@ -73,7 +73,7 @@ def compare(name, got, want, rtol, atol):
 
 def check_workload(w, oracle, nthreads=8, **opts):
     expr, got = run_gpu(w, **opts)
-    want = oracle.evaluate(w.spec, wl.host_inputs(w), w.scalars, nthreads=nthreads)
+    want = oracle.evaluate(w.oracle_spec or w.spec, wl.host_inputs(w), w.scalars, nthreads=nthreads)
     stats = {}
     for name, g, o, (rtol, atol) in zip(w.out_names, got, want, w.tol):
         stats[name] = compare(f"{w.name}.{name}", g, o, rtol, atol)

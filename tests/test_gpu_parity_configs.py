@@ -29,6 +29,14 @@ CASES = {
     "c5b_small": lambda: wl.c5_stress(n=2, c=256, h=56, w=56, reading="B"),
     "c5a_ragged": lambda: wl.c5_stress(n=2, c=10, h=7, w=9, reading="A"),
     "c5b_ragged_c": lambda: wl.c5_stress(n=3, c=6, h=5, w=12, reading="B", bcast="c"),
+    # backward passes: the library differentiates the forward description, the oracle evaluates
+    # the gradient written out by hand
+    "c2b_full": lambda: wl.c2_lstm_cell_backward(),
+    "c2b_ragged": lambda: wl.c2_lstm_cell_backward(batch=7, hidden=250),
+    "c3b_rows64": lambda: wl.c3_softmax_xent_backward(rows=64, vocab=10000),
+    "c3b_ragged": lambda: wl.c3_softmax_xent_backward(rows=37, vocab=1003),
+    "c4b_small": lambda: wl.c4_bias_relu_chansum_backward(n=4, c=64, h=112, w=112),
+    "c4b_ragged": lambda: wl.c4_bias_relu_chansum_backward(n=3, c=5, h=13, w=17),
 }
 
 

@@ -49,6 +49,9 @@ class Workload:
     elements: int                 # unit of work: output coordinates of the element-wise part
     algorithmic_bytes: int        # every operand read once at its own size + every output once
     notes: Dict[str, object] = field(default_factory=dict)
+    # Backward workloads: ``spec`` asks the evaluator's own differentiation for the gradient,
+    # which the oracle does not have; it evaluates this hand-derived description instead.
+    oracle_spec: object = None
 
 
 def host_inputs(w: Workload) -> List[np.ndarray]:
@@ -276,6 +279,131 @@ def c5_stress(n: int = 64, c: int = 256, h: int = 56, w: int = 56, reading: str 
     return Workload(f"c5_stress_{reading}", s, buffers, views, [], ["out"], [TOL_F16], ne,
                     _nbytes(buffers) + ne * 2, {"reading": reading, "bcast": bcast})
 
+
+# --------------------------------------------------------------------------- backward passes
+#
+# The paper's benchmarks time forward and backward passes (section 4.2), and its gradients are
+# built symbolically (section 2.1.3).  Each workload below gives two descriptions of the same
+# backward computation: one that asks the evaluator to differentiate the forward expression,
+# and one written out by hand from the chain rule for the oracle.
+
+def c2_lstm_cell_backward(batch: int = 64, hidden: int = 1024) -> Workload:
+    """Gradients of the LSTM cell's point-wise part: given dh, dc (cotangents of h and c),
+    the cotangents of the four gate pre-activations, of the bias (summed over the batch) and
+    of c_prev."""
+    g = _gen(SEED0 + 12)
+    P = _normal(g, (batch, 4 * hidden))
+    bias = _normal(g, (1, 4 * hidden))
+    c_prev = _normal(g, (batch, hidden))
+    dh = _normal(g, (batch, hidden))
+    dc = _normal(g, (batch, hidden))
+
+    def forward(s):
+        p_ = [s.input("f32", (False, False)) for _ in range(4)]
+        b_ = [s.input("f32", (True, False)) for _ in range(4)]
+        cp = s.input("f32", (False, False))
+        dh_ = s.input("f32", (False, False)); dc_ = s.input("f32", (False, False))
+        z = [s.add(p_[k], b_[k]) for k in range(4)]
+        i_ = s.apply("sigmoid", z[0]); f_ = s.apply("sigmoid", z[1]); o_ = s.apply("sigmoid", z[2])
+        g_ = s.apply("tanh", z[3])
+        c = s.add(s.mul(f_, cp), s.mul(i_, g_))
+        tc = s.apply("tanh", c)
+        h = s.mul(o_, tc)
+        return p_, b_, cp, dh_, dc_, (i_, f_, o_, g_, tc), h, c
+
+    s = GraphSpec(2)
+    p_, b_, cp, dh_, dc_, _gates, h, c = forward(s)
+    grads = s.grad([h, c], [dh_, dc_], p_ + b_ + [cp])
+    for v in grads:
+        s.output(v, "f32")
+
+    r = GraphSpec(2)
+    p_, b_, cp, dh_, dc_, (i_, f_, o_, g_, tc), h, c = forward(r)
+    one = r.const(1.0)
+    dct = r.add(dc_, r.mul(r.mul(dh_, o_), r.sub(one, r.mul(tc, tc))))
+    dzo = r.mul(r.mul(dh_, tc), r.mul(o_, r.sub(one, o_)))
+    dzi = r.mul(r.mul(dct, g_), r.mul(i_, r.sub(one, i_)))
+    dzf = r.mul(r.mul(dct, cp), r.mul(f_, r.sub(one, f_)))
+    dzg = r.mul(r.mul(dct, i_), r.sub(one, r.mul(g_, g_)))
+    dz = [dzi, dzf, dzo, dzg]
+    for v in dz:
+        r.output(v, "f32")
+    for v in dz:
+        r.output(r.reduce("sum", v, (0,), keep=True), "f32")
+    r.output(r.mul(dct, f_), "f32")
+
+    views = [View(0, k * hidden, (batch, hidden), (4 * hidden, 1)) for k in range(4)]
+    views += [View(1, k * hidden, (1, hidden), (4 * hidden, 1)) for k in range(4)]
+    views += [_full_view(2, c_prev.shape), _full_view(3, dh.shape), _full_view(4, dc.shape)]
+    n = batch * hidden
+    names = [f"dz_{k}" for k in "ifog"] + [f"dbias_{k}" for k in "ifog"] + ["dc_prev"]
+    tol = [(2e-5, 2e-6)] * 4 + [TOL_F32_REDUCE] * 4 + [(2e-5, 2e-6)]
+    return Workload("c2_lstm_cell_backward", s, [P, bias, c_prev, dh, dc], views, [], names, tol, n,
+                    _nbytes([P, bias, c_prev, dh, dc]) + 5 * n * 4 + 4 * hidden * 4, oracle_spec=r)
+
+
+def c3_softmax_xent_backward(rows: int = 1280, vocab: int = 10000, std: float = 2.0) -> Workload:
+    """Gradient of the mean cross-entropy loss with respect to the logits: (softmax - onehot) / rows."""
+    g = _gen(SEED0 + 13)
+    logits = _normal(g, (rows, vocab), std)
+    targets = (torch.randint(0, vocab, (rows, 1), generator=g, dtype=torch.int32).numpy()
+               if _DATA else Placeholder((rows, 1), np.int32))
+    s = GraphSpec(2)
+    x = s.input("f32", (False, False)); t = s.input("i32", (False, True))
+    m = s.reduce("max", x, (1,), keep=True)
+    S = s.reduce("sum", s.apply("exp", s.sub(x, m)), (1,), keep=True)
+    xt = s.reduce("sum", s.apply("where", s.apply("eq", s.iota(1), t), x, s.const(0.0)), (1,), keep=True)
+    loss = s.apply("neg", s.sub(s.sub(xt, m), s.apply("log", S)))
+    mean = s.div(s.reduce("sum", loss, (0,), keep=True), s.const(float(rows)))
+    (dx,) = s.grad([mean], [s.const(1.0)], [x])
+    s.output(dx, "f32")
+
+    r = GraphSpec(2)
+    x = r.input("f32", (False, False)); t = r.input("i32", (False, True))
+    m = r.reduce("max", x, (1,), keep=True)
+    e = r.apply("exp", r.sub(x, m))
+    p = r.div(e, r.reduce("sum", e, (1,), keep=True))
+    onehot = r.apply("where", r.apply("eq", r.iota(1), t), r.const(1.0), r.const(0.0))
+    r.output(r.div(r.sub(p, onehot), r.const(float(rows))), "f32")
+    return Workload("c3_softmax_xent_backward", s, [logits, targets],
+                    [_full_view(0, logits.shape), _full_view(1, targets.shape)], [], ["dlogits"],
+                    [(1e-5, 1e-9)], rows * vocab, 2 * logits.nbytes + targets.nbytes, oracle_spec=r)
+
+
+def c4_bias_relu_chansum_backward(n: int = 128, c: int = 64, h: int = 112, w: int = 112) -> Workload:
+    """Gradients of Y = max(0, X*s + t) and its per-channel sum: given dY and the cotangent of
+    the channel sums, the cotangent of X and the per-channel cotangents of s and t."""
+    g = _gen(SEED0 + 14)
+    X = _normal(g, (n, c, h, w))
+    sc = _uniform(g, (1, c, 1, 1), 0.5, 1.5)
+    sh = _uniform(g, (1, c, 1, 1), -0.5, 0.5)
+    dY = _normal(g, (n, c, h, w))
+    dsum = _normal(g, (1, c, 1, 1))
+    chan = (True, False, True, True)
+    s = GraphSpec(4)
+    x_ = s.input("f32", (False,) * 4); s_ = s.input("f32", chan); t_ = s.input("f32", chan)
+    dy_ = s.input("f32", (False,) * 4); ds_ = s.input("f32", chan)
+    y = s.apply("max", s.const(0.0), s.add(s.mul(x_, s_), t_))
+    tot = s.reduce("sum", y, (0, 2, 3), keep=True)
+    gx, gs, gt = s.grad([y, tot], [dy_, ds_], [x_, s_, t_])
+    s.output(gx, "f32"); s.output(gs, "f32"); s.output(gt, "f32")
+
+    r = GraphSpec(4)
+    x_ = r.input("f32", (False,) * 4); s_ = r.input("f32", chan); t_ = r.input("f32", chan)
+    dy_ = r.input("f32", (False,) * 4); ds_ = r.input("f32", chan)
+    z = r.add(r.mul(x_, s_), t_)
+    gz = r.apply("where", r.apply("gt", z, r.const(0.0)), r.add(dy_, ds_), r.const(0.0))
+    r.output(r.mul(gz, s_), "f32")
+    r.output(r.reduce("sum", r.mul(gz, x_), (0, 2, 3), keep=True), "f32")
+    r.output(r.reduce("sum", gz, (0, 2, 3), keep=True), "f32")
+    ne = n * c * h * w
+    bufs = [X, sc, sh, dY, dsum]
+    return Workload("c4_bias_relu_chansum_backward", s, bufs, [_full_view(k, b.shape) for k, b in enumerate(bufs)], [],
+                    ["dX", "ds", "dt"], [TOL_F32_ELEMWISE, (2e-5, 1e-3), (2e-5, 1e-3)], ne,
+                    _nbytes(bufs) + ne * 4 + 2 * c * 4, oracle_spec=r)
+
+
+BACKWARD = {"c2b": c2_lstm_cell_backward, "c3b": c3_softmax_xent_backward, "c4b": c4_bias_relu_chansum_backward}
 
 FULL_SIZE = {
     "c1": c1_affine_tanh, "c2": c2_lstm_cell, "c3": c3_softmax_xent,

@@ -71,6 +71,13 @@ class GraphSpec:
         assert redop in REDUCTIONS
         return self._push(("reduce", redop, int(arg), tuple(int(a) for a in axes), bool(keep)))
 
+    def grad(self, ys: Sequence[int], ybars: Sequence[int], wrt: Sequence[int]) -> List[int]:
+        """Asks the evaluator's own differentiation for d(sum_k <ybar_k, y_k>)/d wrt_j; returns one
+        value per wrt.  (Only the GPU library implements it; the oracle is given hand-derived
+        gradient expressions or finite differences instead.)"""
+        call = self._push(("grad", tuple(int(v) for v in ys), tuple(int(v) for v in ybars), tuple(int(v) for v in wrt)))
+        return [self._push(("gradof", call, j)) for j in range(len(wrt))]
+
     def output(self, value: int, storage: str) -> None:
         assert storage in STORAGE
         self.outputs.append((int(value), storage))
