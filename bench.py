@@ -146,7 +146,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="time one workload (c1,c2,c3,c4,c5a,c5b) as the headline")
+    ap.add_argument("--only", default="", help="time one workload (c1,c2,c3,c4,c5a,c5b,c2b,c3b,c4b) as the headline")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -160,7 +160,12 @@ def main():
     torch.cuda.set_device(0)
 
     head_name = args.only or "c4"
-    head = Case(wl.FULL_SIZE[head_name]())
+    makers = dict(wl.FULL_SIZE)
+    makers.update(wl.BACKWARD)
+    hw = makers[head_name]()
+    # small workloads rotate through enough buffer sets to exceed the on-chip cache
+    head_sets = max(1, min(300, int(600e6 // max(1, hw.algorithmic_bytes)) + 1)) if hw.algorithmic_bytes < 300e6 else 1
+    head = Case(hw, nsets=head_sets)
     wall_ms = head.wall(args.steps, args.warmup)          # the timed region: exactly K steps
     st = _stats(head.time(args.steps, 0))                   # the same K launches again, per-launch events
     w = head.w
@@ -182,7 +187,7 @@ def main():
         "config": {"workload": f"{head_name}: {w.name}", "elements": w.elements,
                    "algorithmic_bytes": w.algorithmic_bytes, "kernel_class": head.info["kernel_class"],
                    "block_threads": head.info["block_threads"], "grid_blocks": head.info["grid_blocks"],
-                   "vec": head.info["vec"]},
+                   "vec": head.info["vec"], "buffer_sets": head_sets},
         "gelem_per_s": round(w.elements / (ms_per_step * 1e-3) / 1e9, 2),
         "pct_of_peak": round(100 * gbps / PEAK_HBM_GBPS, 1),
         "roofline": {"bound": "hbm", "achieved": round(kern_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
@@ -227,6 +232,23 @@ def main():
             del case
             torch.cuda.empty_cache()
         out["per_config"] = per_config
+        # backward passes (kernels generated from the library's own differentiation of the forward
+        # descriptions): supplementary, not among the five headline workloads
+        backward = {}
+        for name, make in wl.BACKWARD.items():
+            wk = make()
+            nsets = max(1, min(300, int(600e6 // max(1, wk.algorithmic_bytes)) + 1)) if wk.algorithmic_bytes < 300e6 else 1
+            case = Case(wk, nsets=nsets)
+            steps = 200 if wk.algorithmic_bytes < 300e6 else 50
+            us_step = 1e3 * min(case.wall(steps, 20), case.wall(steps, 0)) / steps
+            backward[name] = {"workload": wk.name, "elements": wk.elements, "algorithmic_bytes": wk.algorithmic_bytes,
+                              "kernel_class": case.info["kernel_class"], "buffer_sets": nsets,
+                              "us_per_step": round(us_step, 2),
+                              "gbps": round(wk.algorithmic_bytes / (us_step * 1e-6) / 1e9, 1),
+                              "pct_of_peak": round(100 * wk.algorithmic_bytes / (us_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 1)}
+            del case
+            torch.cuda.empty_cache()
+        out["backward"] = backward
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()

@@ -167,6 +167,18 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
     st = compile_source(plan->source, plan->code, &cached);
     if (st != EWF_OK) return st;
     if (!cached) e.compile_count++;
+    if (plan->used_auto_occupancy && code_scratch_bytes(plan->code) > 0) {
+        // the register budget the generator asked for made the compiler spill: a second round
+        // of workgroups costs less than scratch traffic, so generate again without it
+        plan->no_auto_occupancy = true;
+        plan->used_auto_occupancy = false;
+        plan->layout = ParamLayout();
+        st = generate(e, *plan);
+        if (st != EWF_OK) return st;
+        st = compile_source(plan->source, plan->code, &cached);
+        if (st != EWF_OK) return st;
+        if (!cached) e.compile_count++;
+    }
     e.last = plan.get();
     *result = e.last;
     e.plans.emplace(sig, std::move(plan));

@@ -1153,7 +1153,10 @@ ewf_status Gen::gen_row()
         for (int d = 0; d < R - 1; d++) nrows_ *= c.extent[d];
         const int64_t wg_per_cu = ceil_div(nrows_, device_cu_count());
         const int64_t waves = ceil_div(wg_per_cu * (block / 64), 4);
-        if (resident && waves >= 2 && waves <= 8 && regs + 40 <= 512 / waves / 8 * 8) auto_waves_per_simd = (int)waves;
+        if (resident && !p.no_auto_occupancy && waves >= 2 && waves <= 8 && regs + 40 <= 512 / waves / 8 * 8) {
+            auto_waves_per_simd = (int)waves;
+            p.used_auto_occupancy = !(e.opts.waves_per_simd >= 1 && e.opts.waves_per_simd <= 8);
+        }
     }
 
     emit_header(block);

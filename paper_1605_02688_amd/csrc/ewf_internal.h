@@ -160,6 +160,8 @@ struct Plan {
     // fill kernels for empty reductions etc. are not needed: handled on the host by memset-free
     // identity stores through a tiny generated kernel
     bool empty = false;                  // zero-size iteration space: nothing to launch
+    bool used_auto_occupancy = false;    // the generator asked for a register budget on its own
+    bool no_auto_occupancy = false;      // ... and must not (it made the compiler spill)
 };
 
 struct Exec {
@@ -206,5 +208,6 @@ ewf_status compile_source(const std::string &source, std::vector<char> &code, bo
 ewf_status load_function(const std::vector<char> &code, const std::string &entry, void **function, int *device);
 const char *prelude_source();
 int device_cu_count();
+int64_t code_scratch_bytes(const std::vector<char> &code);
 
 }  // namespace ewf

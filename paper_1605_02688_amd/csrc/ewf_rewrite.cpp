@@ -5,6 +5,7 @@
 // broadcast pattern and dropped axes, so output shapes never change.
 #include <cmath>
 #include <cstring>
+#include <functional>
 #include <map>
 #include <tuple>
 
@@ -166,6 +167,41 @@ int rewrite_graph(Graph &g)
         return push(nd);
     };
 
+    // sum over axes A of (a * k), (a / k) or (-a) with k constant along A: the factor leaves the
+    // sum (fewer operations per element, and the remaining sum is often one that exists already)
+    std::function<int(int, uint32_t, bool)> make_sum = [&](int a, uint32_t axes, bool keep) -> int {
+        const Node arg = out.nodes[a];
+        auto constant_along = [&](int v) { return (out.nodes[v].bcast & axes) == axes; };
+        if (arg.kind == NodeKind::Apply && arg.vtype == EWF_F32) {
+            int inner = -1, factor = -1;
+            if (arg.op == EWF_MUL) {
+                if (constant_along(arg.args[1]) && !constant_along(arg.args[0])) { inner = arg.args[0]; factor = arg.args[1]; }
+                else if (constant_along(arg.args[0]) && !constant_along(arg.args[1])) { inner = arg.args[1]; factor = arg.args[0]; }
+            } else if (arg.op == EWF_DIV && constant_along(arg.args[1]) && !constant_along(arg.args[0])) {
+                inner = arg.args[0]; factor = arg.args[1];
+            } else if (arg.op == EWF_NEG) {
+                inner = arg.args[0];
+            }
+            if (inner >= 0) {
+                const int r = make_sum(inner, axes, keep);
+                Node like = out.nodes[r];
+                Node ap;
+                ap.kind = NodeKind::Apply; ap.op = arg.op; ap.vtype = EWF_F32;
+                ap.nargs = factor >= 0 ? 2 : 1; ap.args[0] = r; ap.args[1] = factor;
+                ap.bcast = like.bcast & (factor >= 0 ? out.nodes[factor].bcast : all_mask(g.ndim));
+                ap.dropped = (like.dropped | (factor >= 0 ? out.nodes[factor].dropped : 0u)) & ap.bcast;
+                return push(ap);
+            }
+        }
+        Node rd;
+        rd.kind = NodeKind::Reduce; rd.op = EWF_RSUM; rd.nargs = 1; rd.args[0] = a; rd.axes = axes; rd.keep = keep;
+        rd.vtype = EWF_F32;
+        rd.bcast = arg.bcast | axes;
+        rd.dropped = (arg.dropped | (keep ? 0u : axes)) & rd.bcast;
+        rd.depth = arg.depth + 1;
+        return push(rd);
+    };
+
     for (int n = 0; n < N; n++) {
         Node nd = g.nodes[n];
         const Node orig = nd;
@@ -235,6 +271,16 @@ int rewrite_graph(Graph &g)
             default: break;
             }
             if (r >= 0) { repl[n] = r; changed++; continue; }
+        }
+        if (nd.kind == NodeKind::Reduce && nd.op == EWF_RSUM && nd.vtype == EWF_F32) {
+            const size_t mark = out.nodes.size();
+            const int r = make_sum(nd.args[0], nd.axes, nd.keep);
+            if (same_shape(out.nodes[r], orig)) {
+                if (out.nodes[r].kind != NodeKind::Reduce) changed++;
+                repl[n] = r;
+                continue;
+            }
+            (void)mark;                                  // (what was pushed stays as dead nodes, removed below)
         }
         repl[n] = push(nd);
     }

@@ -92,6 +92,28 @@ ewf_status load_function(const std::vector<char> &code, const std::string &entry
     return EWF_OK;
 }
 
+// Largest per-lane scratch (register spill) size, in bytes, that the metadata of a code object
+// records for any of its kernels.  The metadata is a MessagePack map; the value follows the
+// key ".private_segment_fixed_size" as an unsigned integer.
+int64_t code_scratch_bytes(const std::vector<char> &code)
+{
+    static const char key[] = ".private_segment_fixed_size";
+    const size_t klen = sizeof key - 1;
+    int64_t worst = 0;
+    for (size_t i = 0; i + klen + 1 <= code.size(); i++) {
+        if (memcmp(code.data() + i, key, klen) != 0) continue;
+        const unsigned char *q = (const unsigned char *)code.data() + i + klen;
+        const size_t left = code.size() - (i + klen);
+        int64_t v = -1;
+        if (left >= 1 && q[0] <= 0x7f) v = q[0];
+        else if (left >= 2 && q[0] == 0xcc) v = q[1];
+        else if (left >= 3 && q[0] == 0xcd) v = ((int64_t)q[1] << 8) | q[2];
+        else if (left >= 5 && q[0] == 0xce) v = ((int64_t)q[1] << 24) | ((int64_t)q[2] << 16) | ((int64_t)q[3] << 8) | q[4];
+        if (v > worst) worst = v;
+    }
+    return worst;
+}
+
 // Compute units of the current device; the published MI355X figure when no device is
 // present (planning and compiling need none).
 int device_cu_count()
