@@ -130,12 +130,15 @@ def cpu_baseline(budget_s=15.0):
     n = max(1, min(128, int(budget_s / max(per_n, 1e-3))))
     w = wl.c4_bias_relu_chansum(n=n)
     ins = wl.host_inputs(w)
-    t0 = time.perf_counter()
-    orc.evaluate(w.spec, ins, nthreads=cores)
-    dt = time.perf_counter() - t0
+    # whole passes until about `budget_s` seconds of processor time are spent (at least two)
+    passes, t0 = 0, time.perf_counter()
+    while passes < 2 or (time.perf_counter() - t0) * cores < budget_s:
+        orc.evaluate(w.spec, ins, nthreads=cores)
+        passes += 1
+    dt = (time.perf_counter() - t0) / passes
     return {"value": w.algorithmic_bytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "sample": f"same workload at batch {n} of 128 ([{n},64,112,112], {w.elements} elements), "
-                      f"{dt:.2f} s wall on {cores} threads",
+                      f"{passes} passes, {dt:.2f} s wall each on {cores} threads",
             "gelem_per_s": w.elements / dt / 1e9}
 
 
