@@ -46,3 +46,28 @@ def test_config_parity(case, oracle, H):
     print(f"[case] {case} {w.name} elements={w.elements}", flush=True)
     expr, stats = H.check_workload(w, oracle)
     print(f"[ok] {case} {expr.info()['kernel_class']} {stats}", flush=True)
+
+
+# The sizes and launch configurations bench.py times.  The oracle (C, one thread per core) still
+# finishes each of these in seconds, so every element is compared, not a sample.
+FULL = {
+    "c3_full": lambda: wl.c3_softmax_xent(),
+    "c4_full": lambda: wl.c4_bias_relu_chansum(),
+    "c5a_full": lambda: wl.c5_stress(reading="A"),
+    "c5b_full": lambda: wl.c5_stress(reading="B"),
+    "c3b_full": lambda: wl.c3_softmax_xent_backward(),
+    "c4b_full": lambda: wl.c4_bias_relu_chansum_backward(),
+}
+
+
+@pytest.mark.parametrize("case", sorted(FULL))
+def test_full_size_parity(case, oracle, H):
+    import gc
+    import torch
+    w = FULL[case]()
+    print(f"[case] {case} {w.name} elements={w.elements}", flush=True)
+    expr, stats = H.check_workload(w, oracle, nthreads=16)
+    print(f"[ok] {case} {expr.info()} {stats}", flush=True)
+    del w, expr
+    gc.collect()
+    torch.cuda.empty_cache()
