@@ -118,6 +118,43 @@ def launch_floor(steps=200):
     return _stats([a.elapsed_time(b) for a, b in ev])
 
 
+def lstm_graph_step_us(T=64, replays=20):
+    """C2 applied T times in a row (the cell state ping-pongs between two buffers), captured
+    once into a HIP graph and replayed: microseconds per step inside the replay."""
+    import torch
+    import tests.harness as h
+    from paper_1605_02688_amd import ewf
+    from workloads import configs as wl
+    w = wl.c2_lstm_cell()
+    expr = ewf.Expression(w.spec)
+    bufs, ins = h.device_inputs(w)
+    hs = torch.empty((T,) + tuple(ins[8].shape), dtype=torch.float32, device="cuda")
+    cb = [ins[8], torch.empty_like(ins[8])]
+    calls = [expr.bind(ins[:8] + [cb[t % 2]], [hs[t], cb[(t + 1) % 2]], (), None, 0) for t in range(T)]
+    side = torch.cuda.Stream()
+
+    def run_all(stream):
+        for c in calls:
+            c._stream = ctypes.c_void_p(stream)
+            c.launch()
+    import ctypes
+    run_all(torch.cuda.current_stream().cuda_stream)          # plans, compiles, loads before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run_all(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e6 / (replays * T)
+
+
 def cpu_baseline(budget_s=15.0):
     """The oracle, as it stands, on a bounded sample of the headline workload."""
     from oracle import oracle as orc
@@ -231,6 +268,8 @@ def main():
                 warm = Case(wk, nsets=1)
                 res["warm_us_per_step"] = round(1e3 * min(warm.wall(steps, 20), warm.wall(steps, 0)) / steps, 2)
                 del warm
+            if name == "c2":
+                res["graph_replay_us_per_step"] = round(lstm_graph_step_us(), 2)
             per_config[name] = res
             del case
             torch.cuda.empty_cache()
