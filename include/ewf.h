@@ -172,6 +172,15 @@ ewf_status ewf_output(ewf_graph *g, ewf_value v, ewf_dtype storage);
 
 /* ---- compile / plan / run (section 2.2: compile once into a callable) ---- */
 
+/* Directory for compiled kernels kept across processes (section 2.2.3 of the paper: generated
+ * code is cached on disk so that it is compiled once).  One file per kernel source, named by a
+ * hash of the device helpers, the generated text, the compiler options and the run-time
+ * compiler's version; written through a temporary file and a rename, so concurrent processes may
+ * share a directory.  NULL or "" turns the disk cache off (the default; the in-process cache is
+ * always on).  Also read from the environment variable EWF_CACHE_DIR when the library loads.
+ * A directory that cannot be written is not an error: kernels are then compiled every time. */
+ewf_status ewf_set_cache_dir(const char *path);
+
 /* Type-level compilation.  opts may be NULL.  The graph may be destroyed afterwards. */
 ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **out);
 void ewf_exec_destroy(ewf_exec *e);
@@ -251,6 +260,9 @@ int32_t ewf_debug_compile_count(ewf_exec *e);
  * 2.2.1 of the paper: canonicalisation merges duplicates and folds constants, stabilisation
  * replaces log(1 + x) by log1p(x)). */
 ewf_status ewf_debug_graph_size(ewf_exec *e, int32_t *nodes_described, int32_t *nodes_compiled);
+
+/* Process-wide counts of kernel sources served from memory, from the disk cache, and compiled. */
+ewf_status ewf_debug_cache_stats(int32_t *memory_hits, int32_t *disk_hits, int32_t *compiles);
 
 /* ---- measurement aid ---- */
 

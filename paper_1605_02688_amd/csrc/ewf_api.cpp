@@ -368,6 +368,21 @@ ewf_status ewf_debug_graph_size(ewf_exec *e, int32_t *nodes_described, int32_t *
     return EWF_OK;
 }
 
+ewf_status ewf_set_cache_dir(const char *path)
+{
+    set_cache_dir(path);
+    return EWF_OK;
+}
+
+ewf_status ewf_debug_cache_stats(int32_t *memory_hits, int32_t *disk_hits, int32_t *compiles)
+{
+    if (!memory_hits || !disk_hits || !compiles) { set_error("null argument"); return EWF_EINVAL; }
+    int a, b, c;
+    cache_stats(&a, &b, &c);
+    *memory_hits = a; *disk_hits = b; *compiles = c;
+    return EWF_OK;
+}
+
 ewf_status ewf_copy_bytes(void *dst, const void *src, size_t nbytes, void *hip_stream)
 {
     if (nbytes == 0) return EWF_OK;

@@ -208,6 +208,8 @@ ewf_status compile_source(const std::string &source, std::vector<char> &code, bo
 ewf_status load_function(const std::vector<char> &code, const std::string &entry, void **function, int *device);
 const char *prelude_source();
 int device_cu_count();
+void set_cache_dir(const char *path);
+void cache_stats(int *mem_hits, int *disk_hits, int *compiles);
 int64_t code_scratch_bytes(const std::vector<char> &code);
 
 }  // namespace ewf

@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <hip/hiprtc.h>
 
+#include <unistd.h>
+
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -21,6 +24,59 @@ const char *prelude_source() { return kPrelude; }
 
 namespace {
 std::mutex g_mutex;
+std::string g_cache_dir;                                                    // empty: no disk cache
+int g_stat_mem_hits = 0, g_stat_disk_hits = 0, g_stat_compiles = 0;
+
+// FNV-1a with two different offsets: a 128-bit name for a source text
+void hash128(const std::string &text, uint64_t out[2])
+{
+    uint64_t a = 0xcbf29ce484222325ull, b = 0x84222325cbf29ce4ull;
+    for (unsigned char ch : text) {
+        a = (a ^ ch) * 0x100000001b3ull;
+        b = (b ^ (ch + 0x9e)) * 0x100000001b3ull;
+    }
+    out[0] = a; out[1] = b;
+}
+
+std::string disk_name(const std::string &keyed)
+{
+    uint64_t h[2];
+    hash128(keyed, h);
+    char buf[64];
+    snprintf(buf, sizeof buf, "/ewf_%016llx%016llx.co", (unsigned long long)h[0], (unsigned long long)h[1]);
+    return g_cache_dir + buf;
+}
+
+// File layout: "EWFC1\n", the length of the keyed source text (8 bytes), the code object.
+bool disk_load(const std::string &keyed, std::vector<char> &code)
+{
+    FILE *f = fopen(disk_name(keyed).c_str(), "rb");
+    if (!f) return false;
+    char magic[6];
+    uint64_t len = 0;
+    bool ok = fread(magic, 1, 6, f) == 6 && memcmp(magic, "EWFC1\n", 6) == 0 && fread(&len, 8, 1, f) == 1 && len == keyed.size();
+    if (ok) {
+        fseek(f, 0, SEEK_END);
+        long sz = ftell(f) - 14;
+        fseek(f, 14, SEEK_SET);
+        ok = sz > 0;
+        if (ok) { code.resize((size_t)sz); ok = fread(code.data(), 1, (size_t)sz, f) == (size_t)sz; }
+    }
+    fclose(f);
+    return ok;
+}
+
+void disk_store(const std::string &keyed, const std::vector<char> &code)
+{
+    const std::string name = disk_name(keyed);
+    const std::string tmp = name + ".tmp" + std::to_string((long long)getpid());
+    FILE *f = fopen(tmp.c_str(), "wb");
+    if (!f) return;                                     // an unwritable cache is not an error
+    uint64_t len = keyed.size();
+    bool ok = fwrite("EWFC1\n", 1, 6, f) == 6 && fwrite(&len, 8, 1, f) == 1 && fwrite(code.data(), 1, code.size(), f) == code.size();
+    ok = (fclose(f) == 0) && ok;
+    if (!ok || rename(tmp.c_str(), name.c_str()) != 0) remove(tmp.c_str());
+}
 std::unordered_map<std::string, std::vector<char>> g_code;                 // source -> code object
 struct Loaded { hipModule_t module; std::unordered_map<std::string, hipFunction_t> fn; };
 std::unordered_map<std::string, Loaded> g_loaded;                          // device:hash -> module
@@ -33,9 +89,24 @@ ewf_status compile_source(const std::string &source, std::vector<char> &code, bo
     if (it != g_code.end()) {
         code = it->second;
         if (was_cached) *was_cached = true;
+        g_stat_mem_hits++;
         return EWF_OK;
     }
     if (was_cached) *was_cached = false;
+    // second level: code objects kept on disk across processes, named by a hash of everything
+    // that determines them (device helpers, generated text, compiler options and version)
+    std::string keyed;
+    if (!g_cache_dir.empty()) {
+        int major = 0, minor = 0;
+        hiprtcVersion(&major, &minor);
+        keyed = "gfx950 -O3 no-packed-fp32 hiprtc " + std::to_string(major) + "." + std::to_string(minor) + "\n" + kPrelude + "\n" + source;
+        if (disk_load(keyed, code)) {
+            g_code.emplace(source, code);
+            g_stat_disk_hits++;
+            return EWF_OK;
+        }
+    }
+    g_stat_compiles++;
     hiprtcProgram prog;
     const char *hdr_src[] = {kPrelude};
     const char *hdr_name[] = {"ewf_prelude.hip.h"};
@@ -62,7 +133,27 @@ ewf_status compile_source(const std::string &source, std::vector<char> &code, bo
     hiprtcGetCode(prog, code.data());
     hiprtcDestroyProgram(&prog);
     g_code.emplace(source, code);
+    if (!g_cache_dir.empty()) disk_store(keyed, code);
     return EWF_OK;
+}
+
+namespace {
+// the environment can name the cache directory before any call is made
+struct CacheDirFromEnv {
+    CacheDirFromEnv() { const char *d = getenv("EWF_CACHE_DIR"); if (d && *d) g_cache_dir = d; }
+} g_cache_dir_from_env;
+}  // namespace
+
+void set_cache_dir(const char *path)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_cache_dir = path ? path : "";
+}
+
+void cache_stats(int *mem_hits, int *disk_hits, int *compiles)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    *mem_hits = g_stat_mem_hits; *disk_hits = g_stat_disk_hits; *compiles = g_stat_compiles;
 }
 
 ewf_status load_function(const std::vector<char> &code, const std::string &entry, void **function, int *device)

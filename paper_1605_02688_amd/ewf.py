@@ -101,6 +101,8 @@ _sigs = {
     "ewf_debug_compile_count": (_i32, [_vp]),
     "ewf_debug_graph_size": (_i32, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "ewf_copy_bytes": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
+    "ewf_set_cache_dir": (_i32, [ctypes.c_char_p]),
+    "ewf_debug_cache_stats": (_i32, [ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
 }
 for _name, (_res, _args) in _sigs.items():
     _f = getattr(_lib, _name)
@@ -275,6 +277,16 @@ def debug_graph_size(e: int) -> Tuple[int, int]:
     a, b = _i32(), _i32()
     _check(_lib.ewf_debug_graph_size(e, ctypes.byref(a), ctypes.byref(b)))
     return a.value, b.value
+
+
+def set_cache_dir(path: Optional[str]) -> None:
+    _check(_lib.ewf_set_cache_dir(path.encode() if path else None))
+
+
+def debug_cache_stats() -> dict:
+    a, b, c = _i32(), _i32(), _i32()
+    _check(_lib.ewf_debug_cache_stats(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return {"memory_hits": a.value, "disk_hits": b.value, "compiles": c.value}
 
 
 def copy_bytes(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:

@@ -414,6 +414,34 @@ def test_scalar_graph_rewrites():
     assert expr.graph_size() == (5, 3) and "float a1;" not in expr.source()
 
 
+def test_disk_cache_of_compiled_kernels(tmp_path):
+    """A second process finds the code object of the first on disk and compiles nothing (paper
+    section 2.2.3: compiled modules are cached persistently)."""
+    import json, subprocess, sys, os
+    script = (
+        "import sys, json; sys.path.insert(0, %r)\n"
+        "from paper_1605_02688_amd import ewf\n"
+        "from workloads import GraphSpec\n"
+        "s = GraphSpec(1); x = s.input('f32', (False,))\n"
+        "s.output(s.apply('tanh', s.mul(x, s.const(0.4242))), 'f32')\n"
+        "e = ewf.Expression(s)\n"
+        "B = 0x7F0000000000\n"
+        "e.plan([ewf.TensorRef(B, (4096,), (1,))], [ewf.TensorRef(B + (1 << 20), (4096,), (1,))])\n"
+        "print(json.dumps(ewf.debug_cache_stats()))\n" % ROOT)
+    env = dict(os.environ, EWF_CACHE_DIR=str(tmp_path))
+    runs = [json.loads(subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, check=True).stdout.strip().split("\n")[-1])
+            for _ in range(2)]
+    assert runs[0] == {"memory_hits": 0, "disk_hits": 0, "compiles": 1}
+    assert runs[1] == {"memory_hits": 0, "disk_hits": 1, "compiles": 0}
+    files = [f for f in os.listdir(tmp_path) if f.endswith(".co")]
+    assert len(files) == 1
+    # a damaged file is ignored, not trusted
+    with open(os.path.join(tmp_path, files[0]), "r+b") as f:
+        f.seek(6); f.write(b"\x01\x02")
+    again = json.loads(subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, check=True).stdout.strip().split("\n")[-1])
+    assert again["compiles"] == 1 and again["disk_hits"] == 0
+
+
 def test_math_mode_follows_storage():
     w5 = wl.layout_only(wl.c5_stress, n=2)
     e5, _, _ = plan_workload(w5)
