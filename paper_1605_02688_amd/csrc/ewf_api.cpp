@@ -57,6 +57,12 @@ bool args_present(const Graph &g, const ewf_tensor *in, int nin, const ewf_tenso
     return true;
 }
 
+}  // namespace
+
+namespace ewf {
+
+static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full);
+
 ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result)
 {
     if (!args_present(e.g, in, nin, out, nout)) {
@@ -117,6 +123,24 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
         return EWF_OK;
     }
 
+    st = single_kernel_plan(e, plan.get(), full);
+    if (st == EWF_EUNSUPPORTED && !e.is_stage) {
+        // no single kernel covers the expression: several passes, reductions materialised
+        const std::string why = get_error();
+        st = plan_multi(e, in, nin, out, nout, *plan);
+        if (st == EWF_EUNSUPPORTED) set_error_str(why + "; and a plan in several passes failed: " + get_error());
+        if (st == EWF_OK) plan->kclass = KernelClass::Multi;
+    }
+    if (st != EWF_OK) return st;
+    e.last = plan.get();
+    *result = e.last;
+    e.plans.emplace(sig, std::move(plan));
+    return EWF_OK;
+}
+
+static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
+{
+    ewf_status st;
     const Canon &c = plan->canon;
     if (!plan->red.has_reduce) {
         plan->kclass = KernelClass::Tile;
@@ -179,13 +203,10 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
         if (st != EWF_OK) return st;
         if (!cached) e.compile_count++;
     }
-    e.last = plan.get();
-    *result = e.last;
-    e.plans.emplace(sig, std::move(plan));
     return EWF_OK;
 }
 
-}  // namespace
+}  // namespace ewf
 
 extern "C" {
 
@@ -261,7 +282,16 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!e) { set_error("null executable"); return EWF_EINVAL; }
-    Exec &x = e->e;
+    return run_exec(e->e, in, nin, scalars, nscalars, out, nout, workspace, workspace_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+namespace ewf {
+
+ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
+                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
     if (nscalars != x.g.nscalars || (nscalars > 0 && !scalars)) {
         set_error("expected %d run-time scalar(s), got %d", x.g.nscalars, nscalars);
         return EWF_EINVAL;
@@ -277,6 +307,8 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
         }
         if ((uintptr_t)workspace & 15) { set_error("workspace must be 16-byte aligned"); return EWF_EINVAL; }
     }
+    if (p->kclass == KernelClass::Multi)
+        return run_multi(x, *p, in, nin, scalars, nscalars, out, nout, workspace, workspace_bytes, hip_stream);
     int dev = -1;
     if (!p->function || hipGetDevice(&dev) != hipSuccess || dev != p->function_device) {
         st = load_function(p->code, "ewf_kernel", &p->function, &p->function_device);
@@ -319,6 +351,10 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
     }
     return EWF_OK;
 }
+
+}  // namespace ewf
+
+extern "C" {
 
 ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info)
 {

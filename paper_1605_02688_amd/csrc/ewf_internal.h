@@ -33,6 +33,7 @@ struct Node {
     ewf_dtype storage = EWF_F32;// Input: storage type
     uint32_t bcast = 0;         // bit d: value does not vary along d
     uint32_t dropped = 0;       // bit d: d is removed from the shape of an output of this value
+    uint32_t in_dropped = 0;    // Input standing for a materialised reduction: the axes that reduction dropped
     int depth = 0;              // number of reduce nodes on the longest path from the inputs
 };
 
@@ -97,7 +98,7 @@ struct Canon {
 // ---------------------------------------------------------------------------------------
 // Reduce structure of a graph (which kernel class can run it)
 
-enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3, Col = 4 };
+enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3, Col = 4, Multi = 5 };
 
 struct ReduceInfo {
     bool has_reduce = false;
@@ -135,8 +136,27 @@ struct ParamLayout {
     std::string declare(const std::string &struct_name, bool idx64) const;
 };
 
+// One kernel of a plan that needs several passes over memory: a sub-expression with its own
+// executable, reading the caller's inputs and/or temporaries, writing temporaries and/or the
+// caller's outputs.
+struct Stage {
+    std::unique_ptr<Exec> exec;
+    std::vector<int> in_src;             // per stage input: >= 0 caller's input; < 0 temporary -(t+1)
+    std::vector<int> out_dst;            // per stage output: >= 0 caller's output; < 0 temporary -(t+1)
+    size_t ws_offset = 0, ws_bytes = 0;  // the stage's own workspace inside the caller's
+};
+
+struct Temp {
+    ewf_dtype dtype = EWF_F32;
+    int64_t shape[kMaxDims] = {0};
+    int64_t strides[kMaxDims] = {0};
+    size_t offset = 0, bytes = 0;        // place inside the caller's workspace
+};
+
 struct Plan {
     KernelClass kclass = KernelClass::None;
+    std::vector<Stage> stages;           // KernelClass::Multi only
+    std::vector<Temp> temps;
     Canon canon;
     ReduceInfo red;
     ParamLayout layout;
@@ -165,6 +185,7 @@ struct Plan {
 };
 
 struct Exec {
+    bool is_stage = false;               // a stage of a multi-pass plan: must fit one kernel
     Graph g;
     ewf_options opts{};
     int math_flavour = 1;                // 1 accurate, 2 native rate with fix-ups, 3 native rate
@@ -200,6 +221,18 @@ ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int
 
 // ---- ewf_codegen.cpp
 ewf_status generate(const Exec &e, Plan &p);
+
+// ---- ewf_api.cpp
+ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result);
+ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
+                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+// ---- ewf_multi.cpp
+// Splits an expression that no single kernel class covers into stages: first-level reductions
+// are materialised into temporaries, the rest of the graph reads them as broadcast operands.
+ewf_status plan_multi(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan);
+ewf_status run_multi(Exec &e, Plan &p, const ewf_tensor *in, int nin, const double *scalars, int nscalars,
+                     const ewf_tensor *out, int nout, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 // ---- ewf_rtc.cpp
 // Compiles HIP source for gfx950 (no device needed); identical sources share one code object.

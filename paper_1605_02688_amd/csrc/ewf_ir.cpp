@@ -46,7 +46,7 @@ static ewf_status infer_node(Graph &g, int n)
     case NodeKind::Input:
         nd.vtype = (nd.storage == EWF_I32) ? EWF_I32 : EWF_F32;
         nd.bcast &= all;
-        nd.dropped = 0;
+        nd.dropped = nd.in_dropped & nd.bcast;
         return EWF_OK;
     case NodeKind::Scalar:
     case NodeKind::Const:

@@ -1,0 +1,229 @@
+// Plans in several passes.
+//
+// The single-kernel classes cover one set of reduced axes, chained reductions only along the
+// innermost dimension, and outputs that use a reduction only per group.  Anything else (a value
+// normalised by a column sum, reductions over unrelated axis sets in one description, a chain
+// of reductions over an outer axis) is split the way the paper's fusion stage groups a graph
+// into kernels (section 2.2.1): the reductions that depend on no other reduction are
+// materialised by kernels of their own into temporaries inside the caller's workspace, the rest
+// of the graph then reads them as broadcastable inputs, and so on until what remains fits one
+// kernel.  Every stage is an ordinary sub-expression with its own executable and plan cache.
+#include <algorithm>
+#include <cstring>
+#include <map>
+
+#include "ewf_internal.h"
+
+namespace ewf {
+
+namespace {
+
+constexpr uint64_t kFakeBase = (uint64_t)0x0F00 << 44;     // stands in for workspace addresses while planning
+
+struct Cut { int temp; };
+
+// Builds the sub-expression that computes `targets` (node id, storage, forced keep) from the
+// caller's inputs and the temporaries of already materialised nodes.
+void build_stage(const Graph &g, const std::vector<std::pair<int, ewf_dtype>> &targets, bool force_keep,
+                 const std::map<int, int> &cuts, Exec &sub, std::vector<int> &in_src)
+{
+    const int N = (int)g.nodes.size();
+    std::vector<char> need(N, 0);
+    for (auto &t : targets) need[t.first] = 1;
+    for (int n = N - 1; n >= 0; n--) {
+        if (!need[n] || cuts.count(n)) continue;
+        for (int a = 0; a < g.nodes[n].nargs; a++) need[g.nodes[n].args[a]] = 1;
+    }
+    Graph &h = sub.g;
+    h = Graph();
+    h.ndim = g.ndim;
+    std::vector<int> pos(N, -1);
+    // every run-time scalar keeps its ordinal
+    for (int k = 0; k < g.nscalars; k++) {
+        Node nd = g.nodes[g.scalar_node[k]];
+        pos[g.scalar_node[k]] = (int)h.nodes.size();
+        h.scalar_node.push_back((int)h.nodes.size());
+        h.nodes.push_back(nd);
+    }
+    h.nscalars = g.nscalars;
+    in_src.clear();
+    for (int n = 0; n < N; n++) {
+        if (!need[n] || pos[n] >= 0) continue;
+        Node nd = g.nodes[n];
+        auto cut = cuts.find(n);
+        if (cut != cuts.end()) {
+            Node in;
+            in.kind = NodeKind::Input;
+            in.storage = nd.vtype == EWF_I32 ? EWF_I32 : EWF_F32;
+            in.bcast = nd.bcast;
+            in.in_dropped = nd.dropped;
+            in.index = h.ninputs++;
+            in_src.push_back(-(cut->second + 1));
+            pos[n] = (int)h.nodes.size();
+            h.input_node.push_back(pos[n]);
+            h.nodes.push_back(in);
+            continue;
+        }
+        if (nd.kind == NodeKind::Input) {
+            in_src.push_back(nd.index);
+            nd.index = h.ninputs++;
+            pos[n] = (int)h.nodes.size();
+            h.input_node.push_back(pos[n]);
+            h.nodes.push_back(nd);
+            continue;
+        }
+        for (int a = 0; a < nd.nargs; a++) nd.args[a] = pos[nd.args[a]];
+        if (force_keep && nd.kind == NodeKind::Reduce)
+            for (auto &t : targets) if (t.first == n) nd.keep = true;
+        pos[n] = (int)h.nodes.size();
+        h.nodes.push_back(nd);
+    }
+    for (auto &t : targets) h.outputs.push_back({pos[t.first], t.second});
+}
+
+}  // namespace
+
+ewf_status plan_multi(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan)
+{
+    const Graph &g = e.g;
+    const int N = (int)g.nodes.size();
+    int64_t full[kMaxDims];
+    ewf_status st = infer_full_extents(g, in, nin, full);
+    if (st != EWF_OK) return st;
+    uint32_t unit = 0;
+    for (int d = 0; d < g.ndim; d++) if (full[d] == 1) unit |= 1u << d;
+
+    std::vector<char> live(N, 0);
+    for (const OutputDecl &o : g.outputs) live[o.value] = 1;
+    for (int n = N - 1; n >= 0; n--)
+        if (live[n]) for (int a = 0; a < g.nodes[n].nargs; a++) live[g.nodes[n].args[a]] = 1;
+
+    plan.stages.clear();
+    plan.temps.clear();
+    std::map<int, int> cuts;                            // node -> temporary
+    size_t ws = 0;
+    auto align_up = [](size_t v) { return (v + 255) / 256 * 256; };
+
+    // tensors of a stage while planning: the caller's, or a temporary at a stand-in address
+    auto stage_tensors = [&](const Stage &sg, std::vector<ewf_tensor> &tin, std::vector<ewf_tensor> &tout) {
+        tin.clear(); tout.clear();
+        for (int s : sg.in_src) {
+            if (s >= 0) tin.push_back(in[s]);
+            else { const Temp &t = plan.temps[-s - 1]; tin.push_back({(void *)(uintptr_t)(kFakeBase + t.offset), t.shape, t.strides}); }
+        }
+        for (int d : sg.out_dst) {
+            if (d >= 0) tout.push_back(out[d]);
+            else { const Temp &t = plan.temps[-d - 1]; tout.push_back({(void *)(uintptr_t)(kFakeBase + t.offset), t.shape, t.strides}); }
+        }
+    };
+    auto try_stage = [&](Stage &sg) -> ewf_status {
+        sg.exec->opts = e.opts;
+        sg.exec->math_flavour = e.math_flavour;
+        sg.exec->auto_math = e.auto_math;
+        sg.exec->is_stage = true;
+        ewf_status s2 = finalize_graph(sg.exec->g);
+        if (s2 != EWF_OK) return s2;
+        std::vector<ewf_tensor> tin, tout;
+        stage_tensors(sg, tin, tout);
+        Plan *sp = nullptr;
+        s2 = make_plan(*sg.exec, tin.data(), (int)tin.size(), tout.data(), (int)tout.size(), &sp);
+        if (s2 != EWF_OK) return s2;
+        sg.ws_bytes = sp->workspace_bytes;
+        return EWF_OK;
+    };
+
+    for (int round = 0; round < 16; round++) {
+        // does what remains fit one kernel?
+        {
+            Stage fin;
+            fin.exec.reset(new Exec());
+            std::vector<std::pair<int, ewf_dtype>> targets;
+            for (const OutputDecl &o : g.outputs) targets.push_back({o.value, o.storage});
+            build_stage(g, targets, false, cuts, *fin.exec, fin.in_src);
+            for (int k = 0; k < nout; k++) fin.out_dst.push_back(k);
+            st = try_stage(fin);
+            if (st == EWF_OK) {
+                plan.stages.push_back(std::move(fin));
+                break;
+            }
+            if (st != EWF_EUNSUPPORTED) return st;
+        }
+        // materialise the reductions that depend on no other (unmaterialised) reduction,
+        // one stage per set of reduced axes
+        std::vector<int> depth(N, 0);
+        for (int n = 0; n < N; n++) {
+            if (cuts.count(n)) { depth[n] = 0; continue; }
+            const Node &nd = g.nodes[n];
+            for (int a = 0; a < nd.nargs; a++) depth[n] = std::max(depth[n], depth[nd.args[a]]);
+            if (nd.kind == NodeKind::Reduce && (nd.axes & ~g.nodes[nd.args[0]].bcast & ~unit)) depth[n]++;
+        }
+        std::map<uint32_t, std::vector<int>> groups;
+        for (int n = 0; n < N; n++) {
+            const Node &nd = g.nodes[n];
+            if (!live[n] || cuts.count(n) || nd.kind != NodeKind::Reduce || depth[n] != 1) continue;
+            const uint32_t eff = nd.axes & ~g.nodes[nd.args[0]].bcast & ~unit;
+            if (eff) groups[eff].push_back(n);
+        }
+        if (groups.empty()) { set_error("no reduction left to split off"); return EWF_EUNSUPPORTED; }
+        for (auto &gr : groups) {
+            Stage sg;
+            sg.exec.reset(new Exec());
+            std::vector<std::pair<int, ewf_dtype>> targets;
+            for (int n : gr.second) targets.push_back({n, g.nodes[n].vtype == EWF_I32 ? EWF_I32 : EWF_F32});
+            build_stage(g, targets, true, cuts, *sg.exec, sg.in_src);
+            for (int n : gr.second) {
+                Temp t;
+                t.dtype = g.nodes[n].vtype == EWF_I32 ? EWF_I32 : EWF_F32;
+                int64_t count = 1;
+                for (int d = g.ndim - 1; d >= 0; d--) {
+                    t.shape[d] = (g.nodes[n].bcast & (1u << d)) ? 1 : full[d];
+                    t.strides[d] = count;
+                    count *= t.shape[d];
+                }
+                t.bytes = (size_t)count * 4;
+                t.offset = ws;
+                ws = align_up(ws + t.bytes);
+                plan.temps.push_back(t);
+                sg.out_dst.push_back(-(int)plan.temps.size());
+            }
+            st = try_stage(sg);
+            if (st != EWF_OK) return st;
+            for (size_t i = 0; i < gr.second.size(); i++) cuts[gr.second[i]] = (int)plan.temps.size() - (int)gr.second.size() + (int)i;
+            plan.stages.push_back(std::move(sg));
+        }
+        if (round == 15) { set_error("too many reduction levels"); return EWF_EUNSUPPORTED; }
+    }
+    for (Stage &sg : plan.stages) {
+        sg.ws_offset = ws;
+        ws = align_up(ws + sg.ws_bytes);
+    }
+    plan.workspace_bytes = ws;
+    plan.counter_bytes = 0;
+    plan.finish_grid = 0;
+    plan.grid = (int64_t)plan.stages.size();
+    return EWF_OK;
+}
+
+ewf_status run_multi(Exec &, Plan &p, const ewf_tensor *in, int, const double *scalars, int nscalars,
+                     const ewf_tensor *out, int, void *workspace, size_t, void *hip_stream)
+{
+    char *base = (char *)workspace;
+    std::vector<ewf_tensor> tin, tout;
+    for (Stage &sg : p.stages) {
+        tin.clear(); tout.clear();
+        for (int s : sg.in_src) {
+            if (s >= 0) tin.push_back(in[s]);
+            else { const Temp &t = p.temps[-s - 1]; tin.push_back({base + t.offset, t.shape, t.strides}); }
+        }
+        for (int d : sg.out_dst) {
+            if (d >= 0) tout.push_back(out[d]);
+            else { const Temp &t = p.temps[-d - 1]; tout.push_back({base + t.offset, t.shape, t.strides}); }
+        }
+        ewf_status st = run_exec(*sg.exec, tin.data(), (int)tin.size(), scalars, nscalars, tout.data(), (int)tout.size(),
+                                 sg.ws_bytes ? base + sg.ws_offset : nullptr, sg.ws_bytes, hip_stream);
+        if (st != EWF_OK) return st;
+    }
+    return EWF_OK;
+}
+
+}  // namespace ewf

@@ -413,6 +413,57 @@ def test_column_reduction_special_cases(oracle, G):
     G.h.compare("transposed", got[0], oracle.evaluate(s, [T])[0], 1e-5, 1e-6)
 
 
+def test_plans_in_several_passes(oracle, G):
+    # structures no single kernel class covers: reductions are materialised stage by stage
+    rng = np.random.default_rng(186)
+    # batch normalisation over axis 0: mean, then variance of the centred values, then the normalised tensor
+    x = rng.standard_normal((300, 70)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    inv_n = s.const(1.0 / 300)
+    mean = s.mul(s.reduce("sum", xi, (0,), keep=True), inv_n)
+    cen = s.sub(xi, mean)
+    var = s.mul(s.reduce("sum", s.apply("sqr", cen), (0,), keep=True), inv_n)
+    s.output(s.div(cen, s.apply("sqrt", s.add(var, s.const(1e-5)))), "f32")
+    s.output(mean, "f32"); s.output(var, "f32")
+    print("[case] batch normalisation in stages", flush=True)
+    expr, got = run_spec(G, s, [x])
+    assert expr.info()["kernel_class"] == "multi" and expr.info()["grid_blocks"] == 3
+    want = oracle.evaluate(s, [x])
+    G.h.compare("normalised", got[0], want[0], 2e-5, 2e-6)
+    G.h.compare("mean", got[1], want[1], 1e-5, 1e-6); G.h.compare("var", got[2], want[2], 1e-5, 1e-6)
+    # reductions over unrelated axis sets, an arg-max among them, dropped axes in the outputs
+    y = rng.standard_normal((40, 50, 12)).astype(np.float32)
+    s = GraphSpec(3)
+    yi = s.input("f32", (False,) * 3)
+    s.output(s.reduce("sum", yi, (0,)), "f32")
+    s.output(s.reduce("max", yi, (1, 2)), "f32")
+    s.output(s.reduce("argmax", yi, (1,)), "i32")
+    s.output(s.apply("tanh", yi), "f32")
+    print("[case] three axis sets", flush=True)
+    expr, got = run_spec(G, s, [y])
+    assert expr.info()["kernel_class"] == "multi"
+    want = oracle.evaluate(s, [y])
+    assert [g_.shape for g_ in got] == [(50, 12), (40,), (40, 12), (40, 50, 12)]
+    G.h.compare("sum0", got[0], want[0], 1e-5, 1e-6); G.h.compare("max12", got[1], want[1], 0, 0)
+    G.h.compare("argmax1", got[2], want[2], 0, 0); G.h.compare("tanh", got[3], want[3], 2e-6, 1e-6)
+    # a per-row value combined with a reduction over the rows (loss minus mean loss), and a softmax along an outer axis
+    z = (rng.standard_normal((64, 33)) * 2).astype(np.float32)
+    s = GraphSpec(2)
+    zi = s.input("f32", (False, False))
+    m = s.reduce("max", zi, (0,), keep=True)
+    e = s.apply("exp", s.sub(zi, m))
+    p = s.div(e, s.reduce("sum", e, (0,), keep=True))                    # softmax down the columns
+    rowsum = s.reduce("sum", p, (1,), keep=True)
+    s.output(p, "f32")
+    s.output(s.sub(rowsum, s.mul(s.reduce("sum", rowsum, (0,), keep=True), s.const(1.0 / 64))), "f32")
+    print("[case] column softmax and centred row sums", flush=True)
+    expr, got = run_spec(G, s, [z])
+    assert expr.info()["kernel_class"] == "multi"
+    want = oracle.evaluate(s, [z])
+    G.h.compare("p", got[0], want[0], 1e-5, 1e-7); G.h.compare("centred", got[1], want[1], 2e-5, 2e-6)
+
+
 def test_argmax_ties_take_the_first_index(oracle, G):
     x = np.zeros((70, 5000), np.float32)
     x[:, 4000] = 3.0; x[:, 123] = 3.0; x[5, 7] = 3.0
@@ -571,7 +622,10 @@ def random_case(seed):
     if reduce_axes is not None:
         x0 = vals[0]
         red = ["sum", "max", "min"][int(rng.integers(3))]
-        s.output(s.reduce(red, s.apply("tanh", s.mul(x0, vals[-1])), reduce_axes), "f32")
+        r_ = s.reduce(red, s.apply("tanh", s.mul(x0, vals[-1])), reduce_axes, keep=bool(seed % 3 == 2))
+        s.output(r_, "f32")
+        if seed % 3 == 2:                                   # a value normalised by the reduction (may need several passes)
+            s.output(s.sub(vals[-1], r_), "f32")
         s.outputs = s.outputs[int(rng.integers(0, 2)):]     # sometimes reduce-only
     return s, inputs, [float(rng.uniform(0.5, 1.5))]
 

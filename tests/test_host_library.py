@@ -325,9 +325,9 @@ def test_kernel_class_selection():
     assert info["kernel_class"] == "col" and info["reduced"] == (True, False)
     assert red(4, (0, 2), (6, 50, 7, 32))["kernel_class"] == "col"
     assert red(2, (1,), (200, 96), strides=(1, 200))["kernel_class"] == "col"   # a transposed view, reduced along its rows
-    with pytest.raises(ewf.EwfError) as e:        # normalising by a column sum needs a second pass: not covered
-        red(2, (0,), (512, 512), extra=lambda s, x, r: s.output(s.div(x, r), "f32"))
-    assert e.value.status == ewf.EUNSUPPORTED
+    # normalising by a column sum needs a second pass over memory: two stages
+    info = red(2, (0,), (512, 512), extra=lambda s, x, r: s.output(s.div(x, r), "f32"))
+    assert info["kernel_class"] == "multi" and info["grid_blocks"] == 2
     # reducing over extent-1 axes is the identity: plain element-wise kernel
     assert red(2, (1,), (64, 1))["kernel_class"] == "tile"
 
@@ -463,14 +463,17 @@ def test_streaming_hint_only_for_large_operands():
     assert "ewf_ld_nt" not in off.source()
 
 
-def test_unsupported_structures_are_reported():
-    # reductions over different axis sets in one expression
+def test_structures_beyond_one_kernel_are_planned_in_stages():
+    """What no single kernel class covers is split: the reductions that depend on no other are
+    materialised by kernels of their own, the rest reads them as broadcastable operands."""
+    # reductions over different axis sets in one expression: one stage per set, then nothing is left but copies
     s = GraphSpec(2)
     x = s.input("f32", (False, False))
     s.output(s.reduce("sum", x, (1,)), "f32"); s.output(s.reduce("sum", x, (0,)), "f32")
-    with pytest.raises(ewf.EwfError) as e:
-        ewf.Expression(s).plan([ref(BASE, (64, 64))], [ref(BASE + 65536, (64,)), ref(BASE + 131072, (64,))])
-    assert e.value.status == ewf.EUNSUPPORTED and "axis sets" in e.value.message
+    expr = ewf.Expression(s)
+    ws = expr.plan([ref(BASE, (64, 64))], [ref(BASE + 65536, (64,)), ref(BASE + 131072, (64,))])
+    info = expr.info()
+    assert info["kernel_class"] == "multi" and info["grid_blocks"] == 3 and ws >= 2 * 64 * 4
     # a value that mixes a cross-row reduction with per-row values needs a grid-wide dependency
     w = wl.layout_only(wl.c3_softmax_xent, rows=8, vocab=16)
     s = w.spec
@@ -479,8 +482,14 @@ def test_unsupported_structures_are_reported():
     expr = ewf.Expression(s)
     ins = [ref(BASE, (8, 16)), ref(BASE + 4096, (8, 1))]
     outs = [ref(BASE + 8192 + 512 * k, sh) for k, sh in enumerate(expr.output_shapes(ins))]
+    expr.plan(ins, outs)
+    assert expr.info()["kernel_class"] == "multi"
+    # options that force one kernel per stage cannot help a stage that does not exist: product gradients stay an error
+    s = GraphSpec(1)
+    xx = s.input("f32", (False,))
+    s.grad([s.reduce("prod", xx, (0,), keep=True)], [s.const(1.0)], [xx])
     with pytest.raises(ewf.EwfError) as e:
-        expr.plan(ins, outs)
+        ewf.Expression(s)
     assert e.value.status == ewf.EUNSUPPORTED
 
 
