@@ -627,7 +627,6 @@ ewf_status Gen::gen_tile(bool with_reduce)
     if (small) { block = 64; while (block < 256 && items / block > 512) block *= 2; }
     if (e.opts.block_threads > 0) block = e.opts.block_threads;
     if (block % 64 || block > 1024) return fail("block_threads must be a multiple of 64, at most 1024");
-    p.block = block;
 
     // ---- outputs by role
     std::vector<int> ew_out_ops, group_out_ops;        // operand numbers
@@ -700,7 +699,9 @@ ewf_status Gen::gen_tile(bool with_reduce)
             for (int d = 0; d < R; d++) if (c.ops[k].stride[d] != S.stride[d]) same = false;
             if (same) staged.push_back(k);
         }
-        const int64_t budget = (e.opts.tile_elems > 0 ? e.opts.tile_elems : 32768 / szS);
+        // 64 KiB of LDS per staged operand (two workgroups per compute unit): room for runs along
+        // the output's order that are whole cache lines
+        const int64_t budget = (e.opts.tile_elems > 0 ? e.opts.tile_elems : 65536 / szS);
         for (int d = 0; d < kMaxDims; d++) T[d] = 1;
         // runs of at least 128 bytes along the staged operand's memory order
         int64_t need_run = 128 / szS;
@@ -717,9 +718,18 @@ ewf_status Gen::gen_tile(bool with_reduce)
             for (int d2 = 0; d2 < R; d2++) if (d2 != d) others *= T[d2];
             int64_t cap = std::max<int64_t>(1, budget / others);
             int64_t t = std::max<int64_t>(T[d], std::min<int64_t>(c.extent[d], cap));
-            if (t < c.extent[d]) {                        // prefer an even split of the dimension
-                for (int64_t q = t; q >= std::max<int64_t>(T[d], t / 2 + 1); q--)
-                    if (c.extent[d] % q == 0) { t = q; break; }
+            if (t < c.extent[d]) {
+                // prefer a split whose runs in the contiguous operands are whole 128-byte lines
+                // (a line shared by two tiles is fetched twice: the tiles run on different dies),
+                // then an even split of the dimension, then the larger tile
+                int64_t run = 1;                          // elements of a run below this dimension
+                for (int d2 = d + 1; d2 < R; d2++) run *= T[d2];
+                int64_t best_q = t; int best_score = -1;
+                for (int64_t q = t; q >= std::max<int64_t>(T[d], t / 2 + 1); q--) {
+                    int score = ((q * run * szS) % 128 == 0 ? 2 : 0) + (c.extent[d] % q == 0 ? 1 : 0);
+                    if (score > best_score) { best_score = score; best_q = q; }
+                }
+                t = best_q;
             }
             if (d == R - 1) t = std::max<int64_t>(VEC, t / VEC * VEC);
             T[d] = t;
@@ -739,6 +749,15 @@ ewf_status Gen::gen_tile(bool with_reduce)
         while (VS > 1 && !vs_ok(VS)) VS /= 2;
     }
     auto is_staged = [&](int k) { return std::find(staged.begin(), staged.end(), k) != staged.end(); };
+    if (!staged.empty() && e.opts.block_threads <= 0) {
+        // two workgroups of twelve wavefronts share a compute unit when the staged tile takes about
+        // half its LDS (measured on both readings of the float16 stress workload: 768 threads 89-90 us,
+        // 512 threads 93-94 us, 1024 threads 101-108 us)
+        int64_t te = 1;
+        for (int d = 0; d < R; d++) te *= T[d];
+        if (te * isz(c.ops[staged[0]].storage) > 40 * 1024) block = 768;
+    }
+    p.block = block;
 
     // LDS copy of the tile: the output's order, with a few padding elements after every run
     // of the staged operand's fastest dimension so that the scattering writes of one
@@ -883,7 +902,12 @@ ewf_status Gen::gen_tile(bool with_reduce)
         o << ind << "    if (k_) {\n";
         for (int k : staged) {
             const Operand &op = c.ops[k];
-            o << ind << "        { const ewf_vec<" << ctype(op.storage) << ", " << VS << "> v_ = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<")
+            // a staged operand is read exactly once through these wide loads: stream it past the
+            // caches under the same rule as the unit-stride operands
+            int64_t fp_ = isz(op.storage);
+            for (int d = 0; d < R; d++) if (op.stride[d] != 0) fp_ *= c.extent[d];
+            const bool nt_ = e.opts.streaming == 1 || (e.opts.streaming == 0 && fp_ >= ((int64_t)32 << 20));
+            o << ind << "        { const ewf_vec<" << ctype(op.storage) << ", " << VS << "> v_ = " << (nt_ ? "ewf_ld_nt<" : "ewf_ld<")
               << ctype(op.storage) << ", " << VS << ">(ewf_at(q_" << opname(k) << ", g_));\n";
             o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < " << VS << "; ++e_) lds_" << opname(k) << "[lm_ + e_ * " << LSP[s0] << "] = v_.e[e_]; }\n";
         }
