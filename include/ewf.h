@@ -33,8 +33,9 @@
  *   - An output may alias an input only exactly (same pointer, shape and strides; section
  *     2.2.1: element-wise operations may overwrite an input); any other overlap between an
  *     output and an input or another output is EWF_EALIAS.
- *   - A tensor with a zero extent is legal: success, nothing launched (sum / prod outputs
- *     of an empty reduction are filled with the identity; max / min / argmax are EWF_ESHAPE).
+ *   - A tensor with a zero extent is legal: success, nothing traversed.  An output that is a
+ *     sum or a product over an empty axis is filled with 0 or 1; any other value computed from
+ *     a reduction over an empty axis (max, min, arg-max, expressions of them) is EWF_ESHAPE.
  *   - Thread safety: different ewf_exec handles may be used concurrently; one handle must be
  *     externally synchronised.
  */

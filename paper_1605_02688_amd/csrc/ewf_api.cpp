@@ -15,6 +15,8 @@ namespace ewf {
 const Graph &graph_of(const ewf_graph *g);
 void aux_fill_zero(void *ptr, size_t nbytes, hipStream_t stream);
 void aux_copy(void *dst, const void *src, size_t nbytes, hipStream_t stream);
+void aux_fill_view(void *ptr, int rank, const int64_t *shape, const int64_t *strides, int elem_bytes, uint32_t bits,
+                   hipStream_t stream);
 }  // namespace ewf
 
 using namespace ewf;
@@ -111,8 +113,20 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
             for (int d = 0; d < e.g.ndim; d++)
                 if (!(v.bcast & (1u << d)) && full[d] == 0) out_empty = true;
             if (!out_empty) {
-                set_error("output %d is a reduction over an empty axis; not supported", (int)k);
-                return EWF_ESHAPE;
+                // a reduction over an empty axis: sum and product have an identity, the others do not
+                const int orank = e.g.ndim - __builtin_popcount(v.dropped);
+                uint32_t bits = 0;
+                bool ok = v.kind == NodeKind::Reduce && (v.op == EWF_RSUM || v.op == EWF_RPROD);
+                if (ok && v.op == EWF_RPROD) {
+                    if (e.g.outputs[k].storage == EWF_I32) bits = 1;
+                    else if (e.g.outputs[k].storage == EWF_F16) bits = 0x3c00u;
+                    else bits = 0x3f800000u;
+                }
+                if (!ok) {
+                    set_error("output %d reduces over an empty axis: only a plain sum (0) or product (1) is defined there", (int)k);
+                    return EWF_ESHAPE;
+                }
+                plan->fills.push_back({(int)k, orank, e.g.outputs[k].storage == EWF_F16 ? 2 : 4, bits});
             }
         }
         plan->empty = true;
@@ -299,7 +313,15 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
     Plan *p = nullptr;
     ewf_status st = make_plan(x, in, nin, out, nout, &p);
     if (st != EWF_OK) return st;
-    if (p->empty) return EWF_OK;
+    if (p->empty) {
+        for (const Plan::Fill &f : p->fills) {
+            aux_fill_view(out[f.output].ptr, f.rank, out[f.output].shape, out[f.output].strides, f.elem_bytes, f.bits,
+                          (hipStream_t)hip_stream);
+            hipError_t he = hipGetLastError();
+            if (he != hipSuccess) { set_error("fill launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
+        }
+        return EWF_OK;
+    }
     if (p->workspace_bytes > 0) {
         if (!workspace || workspace_bytes < p->workspace_bytes) {
             set_error("workspace of %zu bytes needed, %zu given", p->workspace_bytes, workspace ? workspace_bytes : (size_t)0);

@@ -35,6 +35,36 @@ __global__ void __launch_bounds__(256) k_copy(uint4 *__restrict__ dst, const uin
     }
 }
 
+// Fills a strided n-d view with one 2- or 4-byte pattern (the identity of a reduction over an
+// empty axis).
+struct FillView { long long shape[8]; long long strides[8]; int rank; };
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_fill_view(T *p, FillView v, long long total, T value)
+{
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        long long r = i, off = 0;
+        for (int d = v.rank - 1; d >= 0; d--) { off += (r % v.shape[d]) * v.strides[d]; r /= v.shape[d]; }
+        p[off] = value;
+    }
+}
+
+void aux_fill_view(void *ptr, int rank, const int64_t *shape, const int64_t *strides, int elem_bytes, uint32_t bits,
+                   hipStream_t stream)
+{
+    FillView v;
+    long long total = 1;
+    v.rank = rank;
+    for (int d = 0; d < rank; d++) { v.shape[d] = shape[d]; v.strides[d] = strides[d]; total *= shape[d]; }
+    if (total <= 0) return;
+    unsigned blocks = (unsigned)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(k_fill_view<unsigned short>, dim3(blocks), dim3(256), 0, stream, (unsigned short *)ptr, v, total, (unsigned short)bits);
+    else
+        hipLaunchKernelGGL(k_fill_view<unsigned int>, dim3(blocks), dim3(256), 0, stream, (unsigned int *)ptr, v, total, bits);
+}
+
 void aux_fill_zero(void *ptr, size_t nbytes, hipStream_t stream)
 {
     size_t n16 = nbytes / 16, ntail = nbytes % 16;

@@ -83,6 +83,9 @@ static bool lattice_hit(const std::vector<std::pair<int64_t, int64_t>> &ds, size
 
 static bool views_overlap(const RawView &a, const RawView &b)
 {
+    // a view without elements overlaps nothing, whatever its pointer
+    for (int d = 0; d < a.rank; d++) if (a.ext[d] == 0) return false;
+    for (int d = 0; d < b.rank; d++) if (b.ext[d] == 0) return false;
     uint64_t alo, ahi, blo, bhi;
     byte_range(a, alo, ahi);
     byte_range(b, blo, bhi);

@@ -179,7 +179,9 @@ struct Plan {
     size_t counter_bytes = 0;
     // fill kernels for empty reductions etc. are not needed: handled on the host by memset-free
     // identity stores through a tiny generated kernel
-    bool empty = false;                  // zero-size iteration space: nothing to launch
+    bool empty = false;                  // zero-size iteration space: nothing to traverse
+    struct Fill { int output; int rank; int elem_bytes; uint32_t bits; };
+    std::vector<Fill> fills;             // empty space: outputs that are reductions over an empty axis
     bool used_auto_occupancy = false;    // the generator asked for a register budget on its own
     bool no_auto_occupancy = false;      // ... and must not (it made the compiler spill)
 };

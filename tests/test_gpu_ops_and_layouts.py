@@ -317,6 +317,27 @@ def test_integer_valued_sums_are_bit_exact(oracle, G):
         assert np.array_equal(got, oracle.evaluate(s, [X])[0])
 
 
+def test_reductions_over_an_empty_axis_give_the_identity(oracle, G):
+    import torch
+    x = np.zeros((5, 0, 3), np.float32)
+    s = GraphSpec(3)
+    xi = s.input("f32", (False,) * 3)
+    s.output(s.reduce("sum", xi, (1,)), "f32")
+    s.output(s.reduce("prod", xi, (1,), keep=True), "f16")
+    s.output(s.apply("exp", xi), "f32")                       # an empty element-wise output next to them
+    expr = G.ewf.Expression(s)
+    dev = [torch.from_numpy(x).cuda()]
+    big = torch.full((5, 6), 7.0, device="cuda")
+    outs = [big[:, ::2], torch.full((5, 1, 3), 7.0, dtype=torch.float16, device="cuda"), torch.empty((5, 0, 3), device="cuda")]
+    assert expr.output_shapes(dev) == [(5, 3), (5, 1, 3), (5, 0, 3)]
+    expr.run(dev, outs, (), None, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = oracle.evaluate(s, [x])
+    assert np.array_equal(outs[0].cpu().numpy(), want[0]) and np.all(want[0] == 0)
+    assert np.array_equal(outs[1].cpu().numpy(), want[1]) and np.all(want[1] == 1)
+    assert torch.all(big[:, 1::2] == 7.0)                     # the strided fill stayed inside its view
+
+
 def test_every_reduction_kind_row_and_split(oracle, G):
     rng = np.random.default_rng(18)
     for shape, axes in [((200, 333), (1,)), ((3, 40000), (1,)), ((6, 5, 2000), (0, 2))]:

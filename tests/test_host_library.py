@@ -295,6 +295,18 @@ def test_zero_size_is_success_without_kernel():
     with pytest.raises(ewf.EwfError) as e:
         ewf.Expression(s).plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))])
     assert e.value.status == ewf.ESHAPE
+    # a sum or a product over an empty axis has an identity: planned (a fill at run time); an
+    # expression of it has no such shortcut
+    for red_ in ("sum", "prod"):
+        s = GraphSpec(2)
+        s.output(s.reduce(red_, s.input("f32", (False, False)), (1,)), "f32")
+        e3 = ewf.Expression(s)
+        assert e3.plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))]) == 0 and e3.info()["kernel_class"] == "none"
+    s = GraphSpec(2)
+    s.output(s.apply("exp", s.reduce("sum", s.input("f32", (False, False)), (1,))), "f32")
+    with pytest.raises(ewf.EwfError) as e:
+        ewf.Expression(s).plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))])
+    assert e.value.status == ewf.ESHAPE
 
 
 # ------------------------------------------------------------------ kernel classes and code generation
