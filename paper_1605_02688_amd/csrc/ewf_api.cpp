@@ -351,9 +351,7 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
     size_t f = 0;
     for (int k = 0; k < nin; k++, f++) memcpy(args + L.offsets[f], &in[k].ptr, 8);
     for (int k = 0; k < nout; k++, f++) memcpy(args + L.offsets[f], &out[k].ptr, 8);
-    void *counters = workspace;
-    void *partials = workspace ? (char *)workspace + p->counter_bytes : nullptr;
-    memcpy(args + L.offsets[f++], &counters, 8);
+    void *partials = workspace;
     memcpy(args + L.offsets[f++], &partials, 8);
     for (int k = 0; k < nscalars; k++) {
         size_t fi = L.fields.size() - (size_t)nscalars + (size_t)k;

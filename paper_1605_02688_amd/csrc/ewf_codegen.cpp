@@ -211,8 +211,6 @@ struct Gen {
             if (!need[n]) continue;
             const Node &nd = g.nodes[n];
             if (nd.kind == NodeKind::Reduce && real_reduce(n)) {
-                bool is_target = std::find(targets.begin(), targets.end(), n) != targets.end();
-                (void)is_target;
                 continue;                       // read from its result variable
             }
             for (int a = 0; a < nd.nargs; a++) need[nd.args[a]] = 1;
@@ -499,7 +497,6 @@ struct Gen {
         L.fields.clear();
         const ParamField::Type IDX = c.idx64 ? ParamField::I64 : ParamField::I32;
         for (size_t k = 0; k < c.ops.size(); k++) L.add(ParamField::Ptr, opname((int)k), 0);
-        L.add(ParamField::Ptr, "ws_counters", 0);
         L.add(ParamField::Ptr, "ws_partials", 0);
         L.add(IDX, "ext", std::max(1, R));
         L.add(IDX, "ntile", std::max(1, R));
@@ -676,7 +673,6 @@ ewf_status Gen::gen_tile(bool with_reduce)
     std::vector<int> sdims;                            // dims ordered by the staged operand's stride
     int VS = 1;
     if (!with_reduce && !e.opts.no_lds_staging && c.total >= 65536 && R >= 2) {
-        std::vector<char> need0 = needed(std::vector<int>());
         for (int k = 0; k < nin && staged.empty(); k++) {
             const Operand &op = c.ops[k];
             if (op.access != Access::Gather) continue;
@@ -685,7 +681,6 @@ ewf_status Gen::gen_tile(bool with_reduce)
             if (!full || s0 < 0 || c.extent[s0] < 16) continue;
             staged.push_back(k);
         }
-        (void)need0;
     }
     if (!staged.empty()) {
         const Operand &S = c.ops[staged[0]];
@@ -1090,7 +1085,6 @@ ewf_status Gen::gen_tile(bool with_reduce)
     for (int k : staged) p.lds_bytes += (int)(lds_elems * isz(c.ops[k].storage));
     int64_t ngroups = 1, nslots = 1;
     for (int d = 0; d < R; d++) { if (c.reduced[d]) nslots *= ntile[d]; else ngroups *= c.extent[d]; }
-    p.counter_bytes = 0;
     p.workspace_bytes = 0;
     p.finish_grid = 0;
     if (with_reduce) {
@@ -1225,7 +1219,7 @@ ewf_status Gen::gen_row()
     // for the loads one by one instead of for all of them.  (The row length is part of the
     // plan's key, and NFULL of the generated text, so the assumption travels with the code.)
     const int64_t NFULL = resident ? cols / per_iter : 0;
-    auto open_pass = [&](bool load) {
+    auto open_pass = [&]() {
         if (resident) {
             o << "        #pragma unroll\n        for (int u = 0; u < " << U << "; ++u) {\n";
             o << "            const idx_t col = (idx_t)(u * EWF_BLOCK + tid) * EWF_VEC;\n";
@@ -1236,7 +1230,6 @@ ewf_status Gen::gen_row()
             o << "            const idx_t col = c0 + (idx_t)(u * EWF_BLOCK + tid) * EWF_VEC;\n";
             o << "            if (col >= cols) continue;\n";
         }
-        (void)load;
     };
     auto close_pass = [&]() {
         o << "        }\n";
@@ -1265,7 +1258,7 @@ ewf_status Gen::gen_row()
     }
     if (resident) {
         for (int k : row_ops) o << "        ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
-        open_pass(true);
+        open_pass();
         for (int k : row_ops) emit_row_load(k, "            ", "x_" + opname(k) + "[u]");
         close_pass();
     }
@@ -1318,7 +1311,7 @@ ewf_status Gen::gen_row()
         for (int n : lvl[l]) tg.push_back(g.nodes[n].args[0]);
         std::vector<char> need = needed(tg);
         o << "        " << an << " " << av << " = " << an << "_identity();\n";
-        open_pass(false);
+        open_pass();
         stream_loads(need);
         o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
         emit_values(need, cx, "                ");
@@ -1335,7 +1328,7 @@ ewf_status Gen::gen_row()
         std::vector<int> tg;
         for (int k : full_out_ops) tg.push_back(g.outputs[c.ops[k].index].value);
         std::vector<char> need = needed(tg);
-        open_pass(false);
+        open_pass();
         stream_loads(need);
         for (int k : full_out_ops) o << "            ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
         o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
@@ -1431,7 +1424,6 @@ ewf_status Gen::gen_row()
     // ---- launch geometry and argument block
     p.grid = std::max<int64_t>(1, std::min(nrows, grid_cap));
     p.lds_bytes = 0;
-    p.counter_bytes = 0;
     p.workspace_bytes = 0;
     p.finish_grid = 0;
     if (has_cross) {
@@ -1708,7 +1700,6 @@ ewf_status Gen::gen_col()
     p.lds_bytes = TY > 1 ? (int)((TY - 1) * TX * VEC * acc_bytes(level)) : 0;
     if (p.lds_bytes > 60 * 1024) return fail("too many reductions for one column kernel (LDS)");
     p.staged = 0;
-    p.counter_bytes = 0;
     p.workspace_bytes = (size_t)ngroups * (size_t)nslots * acc_bytes(level);
     p.finish_grid = fin_lanes ? std::min<int64_t>(ngroups, (int64_t)1 << 20)
                               : std::max<int64_t>(1, std::min<int64_t>(ceil_div(ngroups, 256), (int64_t)1 << 16));

@@ -176,9 +176,6 @@ struct Plan {
     int staged = 0;
     int64_t tile[kMaxDims] = {0};
     size_t workspace_bytes = 0;
-    size_t counter_bytes = 0;
-    // fill kernels for empty reductions etc. are not needed: handled on the host by memset-free
-    // identity stores through a tiny generated kernel
     bool empty = false;                  // zero-size iteration space: nothing to traverse
     struct Fill { int output; int rank; int elem_bytes; uint32_t bits; };
     std::vector<Fill> fills;             // empty space: outputs that are reductions over an empty axis

@@ -198,7 +198,6 @@ ewf_status plan_multi(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *
         ws = align_up(ws + sg.ws_bytes);
     }
     plan.workspace_bytes = ws;
-    plan.counter_bytes = 0;
     plan.finish_grid = 0;
     plan.grid = (int64_t)plan.stages.size();
     return EWF_OK;

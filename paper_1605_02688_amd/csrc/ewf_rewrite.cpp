@@ -64,12 +64,7 @@ bool fold(const Graph &g, const Node &nd, double &out)
         case EWF_LE: out = x <= y; return true;
         case EWF_EQ: out = x == y; return true;
         case EWF_NE: out = x != y; return true;
-        case EWF_WHERE: {
-            const Node &t = g.nodes[nd.args[1]];
-            out = x != 0 ? a[1] : a[2];
-            (void)t;
-            return true;
-        }
+        case EWF_WHERE: out = x != 0 ? a[1] : a[2]; return true;
         default: return false;
         }
     }
@@ -273,14 +268,13 @@ int rewrite_graph(Graph &g)
             if (r >= 0) { repl[n] = r; changed++; continue; }
         }
         if (nd.kind == NodeKind::Reduce && nd.op == EWF_RSUM && nd.vtype == EWF_F32) {
-            const size_t mark = out.nodes.size();
-            const int r = make_sum(nd.args[0], nd.axes, nd.keep);
-            if (same_shape(out.nodes[r], orig)) {
-                if (out.nodes[r].kind != NodeKind::Reduce) changed++;
-                repl[n] = r;
+            const int rs = make_sum(nd.args[0], nd.axes, nd.keep);
+            if (same_shape(out.nodes[rs], orig)) {
+                if (out.nodes[rs].kind != NodeKind::Reduce) changed++;
+                repl[n] = rs;
                 continue;
             }
-            (void)mark;                                  // (what was pushed stays as dead nodes, removed below)
+            // (what was pushed stays as dead nodes and is removed below)
         }
         repl[n] = push(nd);
     }
