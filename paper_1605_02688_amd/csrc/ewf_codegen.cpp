@@ -766,30 +766,38 @@ ewf_status Gen::gen_tile(bool with_reduce)
         std::vector<int> st;
         for (int d : sdims) if (T[d] > 1) st.push_back(d);
         auto conflicts = [&](int64_t pad) {
-            // worst number of distinct 4-byte words that one bank receives from the 64 lanes
-            // of a wavefront in one scattered write
-            std::map<int64_t, std::vector<int64_t>> bank;
-            for (int lane = 0; lane < 64; lane++) {
-                int64_t j = (int64_t)lane * VS, addr = 0;
-                for (size_t i = 0; i < st.size(); i++) {
-                    int d = st[i];
-                    int64_t cd = (i + 1 < st.size()) ? j % T[d] : j; j /= T[d];
-                    int64_t ls = LS[d];
-                    if (LS[d] >= LS[s0]) ls = LS[d] / LS[s0] * (LS[s0] + pad);
-                    addr += cd * ls;
+            // passes one scattered write of a wavefront needs: the LDS has 32 banks of 4 bytes
+            // and takes the 64 lanes as two halves; a half needs as many passes as the largest
+            // number of distinct words that fall into one bank
+            int total = 0;
+            for (int half = 0; half < 2; half++) {
+                std::map<int64_t, std::vector<int64_t>> bank;
+                for (int lane = half * 32; lane < half * 32 + 32; lane++) {
+                    int64_t j = (int64_t)lane * VS, addr = 0;
+                    for (size_t i = 0; i < st.size(); i++) {
+                        int d = st[i];
+                        int64_t cd = (i + 1 < st.size()) ? j % T[d] : j; j /= T[d];
+                        int64_t ls = LS[d];
+                        if (LS[d] >= LS[s0]) ls = LS[d] / LS[s0] * (LS[s0] + pad);
+                        addr += cd * ls;
+                    }
+                    int64_t word = addr * szS / 4;
+                    auto &v = bank[word % 32];
+                    if (std::find(v.begin(), v.end(), word) == v.end()) v.push_back(word);
                 }
-                int64_t word = addr * szS / 4;
-                auto &v = bank[word % 64];
-                if (std::find(v.begin(), v.end(), word) == v.end()) v.push_back(word);
+                size_t worst = 0;
+                for (auto &kv : bank) worst = std::max(worst, kv.second.size());
+                total += (int)worst;
             }
-            size_t worst = 0;
-            for (auto &kv : bank) worst = std::max(worst, kv.second.size());
-            return (int)worst;
+            return total;
         };
+        // fewest passes first; among equals the padding that keeps the widest aligned reads on
+        // the consuming side (16 bytes, then 8), then the smallest
+        auto read_bytes = [&](int64_t pad) { int64_t b = pad * szS; return b % 16 == 0 ? 16 : b % 8 == 0 ? 8 : 4; };
         int best = conflicts(0);
-        for (int64_t pad = 4 / szS; pad * szS <= 32 && best > 1; pad += 4 / szS) {
+        for (int64_t pad = 4 / szS; pad * szS <= 64; pad += 4 / szS) {
             int cf = conflicts(pad);
-            if (cf < best) { best = cf; lds_pad = pad; }
+            if (cf < best || (cf == best && read_bytes(pad) > read_bytes(lds_pad))) { best = cf; lds_pad = pad; }
         }
         for (int d = 0; d < R; d++) if (LS[d] >= LS[s0]) LSP[d] = LS[d] / LS[s0] * (LS[s0] + lds_pad);
         lds_elems = lds_elems / LS[s0] * (LS[s0] + lds_pad);

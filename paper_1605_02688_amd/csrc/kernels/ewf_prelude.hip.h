@@ -166,7 +166,7 @@ EWF_DEV int ewf_negi(int a) { return (int)(0u - (ewf_u32)a); }
 EWF_DEV bool ewf_truth(float c) { return c != 0.0f; }
 EWF_DEV bool ewf_truth(int c) { return c != 0; }
 
-// accurate float32 flavour (about one to two units in the last place)
+// accurate float32 flavour (one to two units in the last place; tanh up to about six near |x| = 0.25)
 struct ewf_acc {
     // exp(x) = 2^(x * log2 e).  The product is formed in two pieces: its float32 rounding t,
     // and r = the rounding error of t plus x times the part of log2 e that float32 drops.
@@ -188,8 +188,37 @@ struct ewf_acc {
     static EWF_DEV float log1p(float x) { return log1pf(x); }
     static EWF_DEV float expm1(float x) { return expm1f(x); }
     static EWF_DEV float sqrt(float x) { return sqrtf(x); }
-    static EWF_DEV float tanh(float x) { return tanhf(x); }
-    static EWF_DEV float sigmoid(float x) { return 1.0f / (1.0f + exp(-x)); }
+    // 1 / y for y >= 1 (finite): the hardware reciprocal refined by one Newton step
+    static EWF_DEV float recip_ge1(float y)
+    {
+        const float r = __builtin_amdgcn_rcpf(y);
+        return __builtin_fmaf(__builtin_fmaf(-y, r, 1.0f), r, r);
+    }
+    // tanh: below 0.25 the odd series up to x^11 (relative error under one unit in the last
+    // place); above, 1 - 2 / (exp(2|x|) + 1), whose subtraction amplifies the quotient's error at
+    // most threefold there (about six units in the last place at the seam, one far from it).
+    // The argument of exp is capped so that it stays finite (a NaN passes the comparison).
+    static EWF_DEV float tanh(float x)
+    {
+        float a = fabsf(x);
+        const float x2 = x * x;
+        float p = __builtin_fmaf(x2, -0.00886323552990219656f, 0.02186948853615520282f);    // -1382/155925, 62/2835
+        p = __builtin_fmaf(x2, p, -0.05396825396825396825f);                                // -17/315
+        p = __builtin_fmaf(x2, p, 0.13333333333333333333f);                                 // 2/15
+        p = __builtin_fmaf(x2, p, -0.33333333333333333333f);
+        p = __builtin_fmaf(x2 * a, p, a);
+        const float c = (a > 44.0f) ? 44.0f : a;
+        const float e = exp(c + c);
+        const float t = __builtin_fmaf(-2.0f, recip_ge1(e + 1.0f), 1.0f);
+        return copysignf((a < 0.25f) ? p : t, x);
+    }
+    // sigmoid: 1 / (1 + exp(-x)) with the argument of exp capped at 88 (the result is then below
+    // the smallest normal number and comes out as 0 or a subnormal)
+    static EWF_DEV float sigmoid(float x)
+    {
+        const float m = -x;
+        return recip_ge1(1.0f + exp((m > 88.0f) ? 88.0f : m));
+    }
     static EWF_DEV float pow(float x, float y) { return powf(x, y); }
     static EWF_DEV float pow_pos(float x, float y) { return powf(x, y); }
     static EWF_DEV float div(float x, float y) { return x / y; }

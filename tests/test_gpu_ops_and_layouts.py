@@ -87,6 +87,30 @@ def test_exp_accurate_mode_whole_range(oracle, G):
     G.h.compare("exp", got[k:], want[k:], 4e-7, 0)          # about three units in the last place
 
 
+def test_tanh_and_sigmoid_accurate_mode_whole_range(oracle, G):
+    # the library's own routines (hardware exp2 and reciprocal, a series near 0): a few units
+    # in the last place everywhere, exact at the special values
+    rng = np.random.default_rng(78)
+    x = np.concatenate([rng.uniform(-1, 1, 200000), rng.uniform(-20, 20, 100000), np.linspace(-0.3, 0.3, 60001),
+                        rng.uniform(-100, 100, 20000), rng.uniform(-1e-4, 1e-4, 2000)]).astype(np.float32)
+    sp = np.float32([0.0, -0.0, np.inf, -np.inf, np.nan, 1e30, -1e30, 44.0, 88.0, -88.0, 89.0, -104.0, 1e-30, -1e-38])
+    x = np.concatenate([sp, x])
+    s = GraphSpec(1)
+    xi = s.input("f32", (False,))
+    s.output(s.apply("tanh", xi), "f32"); s.output(s.apply("sigmoid", xi), "f32")
+    expr, (gt, gs) = run_spec(G, s, [x], math_mode=1)
+    assert "ewf_acc::tanh" in expr.source() and "ewf_acc::sigmoid" in expr.source()
+    wt, ws = oracle.evaluate(s, [x])
+    k = len(sp)
+    assert gt[0] == 0 and not np.signbit(gt[0]) and gt[1] == 0 and np.signbit(gt[1])
+    assert gt[2] == 1 and gt[3] == -1 and np.isnan(gt[4]) and gt[5] == 1 and gt[6] == -1
+    assert gs[0] == 0.5 and gs[2] == 1 and gs[3] == 0 and np.isnan(gs[4]) and gs[5] == 1 and gs[6] == 0
+    G.h.compare("tanh", gt[k:], wt[k:], 6e-7, 0)            # ten units in the last place at most
+    G.h.compare("tanh specials", gt[:k], wt[:k], 6e-7, 0)
+    G.h.compare("sigmoid", gs[k:], ws[k:], 4e-7, 1.2e-38)   # results below the smallest normal may flush
+    G.h.compare("sigmoid specials", gs[:k], ws[:k], 4e-7, 1.2e-38)
+
+
 def test_log1p_keeps_small_arguments(oracle, G):
     x = np.float32([1e-7, -1e-7, 3e-10, 1e-5, -1e-5])
     s = GraphSpec(1)
