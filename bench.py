@@ -254,8 +254,8 @@ def main():
             wall2 = case.wall(steps, 0)
             # throughput figures come from the wall clock over back-to-back steps; the
             # event-bracketed durations carry the launch floor (see launch_floor_us) on top
-            wall2 = min(wall2, case.wall(steps, 0))
-            us_step = 1e3 * wall2 / steps
+            blocks = sorted([wall2] + [case.wall(steps, 0) for _ in range(4)])
+            us_step = 1e3 * blocks[len(blocks) // 2] / steps        # median of five timed blocks
             res = {"elements": wk.elements, "algorithmic_bytes": wk.algorithmic_bytes,
                    "kernel_class": case.info["kernel_class"], "buffer_sets": nsets,
                    "mode": "rotating" if nsets > 1 else "single set (exceeds on-chip cache)",
@@ -297,7 +297,8 @@ def main():
             nsets = max(1, min(300, int(600e6 // max(1, wk.algorithmic_bytes)) + 1)) if wk.algorithmic_bytes < 300e6 else 1
             case = Case(wk, nsets=nsets)
             steps = 200 if wk.algorithmic_bytes < 300e6 else 50
-            us_step = 1e3 * min(case.wall(steps, 20), case.wall(steps, 0)) / steps
+            blocks = sorted([case.wall(steps, 20)] + [case.wall(steps, 0) for _ in range(4)])
+            us_step = 1e3 * blocks[len(blocks) // 2] / steps
             backward[name] = {"workload": wk.name, "elements": wk.elements, "algorithmic_bytes": wk.algorithmic_bytes,
                               "kernel_class": case.info["kernel_class"], "buffer_sets": nsets,
                               "us_per_step": round(us_step, 2),

@@ -946,108 +946,122 @@ ewf_status Gen::gen_tile(bool with_reduce)
         return s.empty() ? std::string("(ioff_t)0") : s;
     };
 
-    // phase A as a local function: coordinates, masks and every load of one trip
-    o << ind << "auto load_item = [&](const int L0, Item &it) {\n";
-    ind += "    ";
-    o << ind << "#pragma unroll\n" << ind << "for (int u = 0; u < " << U << "; ++u) {\n";
-    o << ind << "    const int L = L0 + (u * EWF_BLOCK + tid) * EWF_VEC;\n";
-    o << ind << "    it.L[u] = L;\n";
-    o << ind << "    bool k_ = L < " << TE << ";\n";
-    if (!tiled.empty()) {
-        o << ind << "    int l_ = L;\n";
-        for (size_t i = 0; i < tiled.size(); i++) {
-            int d = tiled[i];
-            if (i + 1 < tiled.size()) o << ind << "    it.c" << d << "[u] = l_ % " << T[d] << "; l_ /= " << T[d] << ";\n";
-            else o << ind << "    it.c" << d << "[u] = l_;\n";
-            if (c.extent[d] % T[d]) o << ind << "    k_ = k_ && (o" << d << " + it.c" << d << "[u] < p.ext[" << d << "]);\n";
-        }
-    }
-    o << ind << "    it.ok[u] = k_;\n";
-    o << ind << "    if (k_) {\n";
-    for (int k : load_ops) {
-        const Operand &op = c.ops[k];
-        std::string nm = opname(k);
-        if (is_staged(k)) {
-            // padded position of the item in the LDS copy; wide pieces as far as the padding
-            // keeps them aligned
-            const int s0 = sdims[0];
-            const int szk = isz(op.storage);
-            int piece = VEC;                               // elements per LDS access
-            while (piece > 1 && ((lds_pad * szk) % (piece * szk) != 0 || piece * szk > 16)) piece /= 2;
-            std::string pos = lds_pad ? "(L + (L / " + std::to_string(LS[s0]) + ") * " + std::to_string(lds_pad) + ")" : std::string("L");
-            if (piece == VEC)
-                o << ind << "        it.x_" << nm << "[u] = ewf_ld<" << ctype(op.storage) << ", EWF_VEC>(&lds_" << nm << "[" << pos << "]);\n";
-            else
-                o << ind << "        _Pragma(\"unroll\") for (int i_ = 0; i_ < " << VEC / piece << "; ++i_) ((ewf_vec<" << ctype(op.storage) << ", " << piece
-                  << "> *)&it.x_" << nm << "[u])[i_] = ewf_ld<" << ctype(op.storage) << ", " << piece << ">(&lds_" << nm << "[" << pos << " + i_ * " << piece << "]);\n";
-        }
-        else if (op.access == Access::Vector)
-            o << ind << "        it.x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "));\n";
-        else if (op.access == Access::Splat)
-            o << ind << "        it.x_" << nm << "[u] = *ewf_at(q_" << nm << ", " << offset_expr(k, true) << ");\n";
-        else {
-            o << ind << "        { const ioff_t b_ = " << offset_expr(k, false) << ";\n";
-            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) it.x_" << nm << "[u].e[e_] = *ewf_at(q_" << nm
-              << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
-        }
-    }
-    o << ind << "    }\n" << ind << "}\n";
-    ind = ind0;
-    o << ind << "};\n";
-
-    // phase B as a local function: evaluate, accumulate, store
-    o << ind << "auto eval_item = [&](const Item &it) {\n";
-    ind += "    ";
-    o << ind << "#pragma unroll\n" << ind << "for (int u = 0; u < " << U << "; ++u) {\n";
-    o << ind << "    if (!it.ok[u]) continue;\n";
-    for (int k : ew_out_ops) o << ind << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
-    o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
-    EmitCtx cx;
-    cx.input = [&](int k) {
-        const Operand &op = c.ops[k];
-        if (op.access == Access::Splat && !is_staged(k)) return "ewf_in(it.x_" + opname(k) + "[u])";
-        if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(it.x_" + opname(k) + "[u], e_)";
-        return "ewf_in(it.x_" + opname(k) + "[u].e[e_])";
+    // The text of one trip in three pieces: coordinates and mask of the thread's items (A), its
+    // loads (B), and the arithmetic with accumulation and stores (C).  They are assembled
+    // either as two local functions (so that the next trip's loads can be issued ahead of the
+    // current trip's arithmetic) or, when there is no such prefetch, as one function that keeps
+    // loads and arithmetic under a single mask: the values then never cross a branch, which
+    // otherwise costs a register copy per loaded word.
+    auto capture = [&](const std::function<void()> &emit) {
+        const std::string before = o.str();
+        o.str("");
+        emit();
+        const std::string text = o.str();
+        o.str("");
+        o << before;
+        return text;
     };
-    cx.coord = [&](int d) {
-        std::string s = "o" + std::to_string(d);
-        if (T[d] > 1) s += " + it.c" + std::to_string(d) + "[u]";
-        if (d == in_d) s += " + e_";
-        return s;
-    };
-    emit_values(need, cx, ind + "        ");
-    if (with_reduce)
-        emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ");
-    for (int k : ew_out_ops) {
-        const Operand &op = c.ops[k];
-        int v = g.outputs[op.index].value;
-        const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
-        o << ind << "        y_" << opname(k) << ".e[e_] = " << cv << "(v" << v << ");\n";
-    }
-    o << ind << "    }\n";
-    for (int k : ew_out_ops) {
-        const Operand &op = c.ops[k];
-        std::string nm = opname(k);
-        if (op.access == Access::Vector)
-            o << ind << "    " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "), y_" << nm << ");\n";
-        else {
-            o << ind << "    { const ioff_t b_ = " << offset_expr(k, op.access == Access::Splat) << ";\n";
-            o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) *ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
-              << "[" << in_d << "]) = y_" << nm << ".e[e_]; }\n";
+    const std::string ind2 = ind + "    ";
+    const std::string text_a = capture([&]() {
+        o << ind2 << "    const int L = L0 + (u * EWF_BLOCK + tid) * EWF_VEC;\n";
+        o << ind2 << "    it.L[u] = L;\n";
+        o << ind2 << "    bool k_ = L < " << TE << ";\n";
+        if (!tiled.empty()) {
+            o << ind2 << "    int l_ = L;\n";
+            for (size_t i = 0; i < tiled.size(); i++) {
+                int d = tiled[i];
+                if (i + 1 < tiled.size()) o << ind2 << "    it.c" << d << "[u] = l_ % " << T[d] << "; l_ /= " << T[d] << ";\n";
+                else o << ind2 << "    it.c" << d << "[u] = l_;\n";
+                if (c.extent[d] % T[d]) o << ind2 << "    k_ = k_ && (o" << d << " + it.c" << d << "[u] < p.ext[" << d << "]);\n";
+            }
         }
-    }
-    o << ind << "}\n";
-    ind = ind0;
-    o << ind << "};\n";
+    });
+    const std::string text_b = capture([&]() {
+        const std::string &ind = ind2;
+        for (int k : load_ops) {
+            const Operand &op = c.ops[k];
+            std::string nm = opname(k);
+            if (is_staged(k)) {
+                // padded position of the item in the LDS copy; wide pieces as far as the padding
+                // keeps them aligned
+                const int s0 = sdims[0];
+                const int szk = isz(op.storage);
+                int piece = VEC;                               // elements per LDS access
+                while (piece > 1 && ((lds_pad * szk) % (piece * szk) != 0 || piece * szk > 16)) piece /= 2;
+                std::string pos = lds_pad ? "(L + (L / " + std::to_string(LS[s0]) + ") * " + std::to_string(lds_pad) + ")" : std::string("L");
+                if (piece == VEC)
+                    o << ind << "        it.x_" << nm << "[u] = ewf_ld<" << ctype(op.storage) << ", EWF_VEC>(&lds_" << nm << "[" << pos << "]);\n";
+                else
+                    o << ind << "        _Pragma(\"unroll\") for (int i_ = 0; i_ < " << VEC / piece << "; ++i_) ((ewf_vec<" << ctype(op.storage) << ", " << piece
+                      << "> *)&it.x_" << nm << "[u])[i_] = ewf_ld<" << ctype(op.storage) << ", " << piece << ">(&lds_" << nm << "[" << pos << " + i_ * " << piece << "]);\n";
+            }
+            else if (op.access == Access::Vector)
+                o << ind << "        it.x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "));\n";
+            else if (op.access == Access::Splat)
+                o << ind << "        it.x_" << nm << "[u] = *ewf_at(q_" << nm << ", " << offset_expr(k, true) << ");\n";
+            else {
+                o << ind << "        { const ioff_t b_ = " << offset_expr(k, false) << ";\n";
+                o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) it.x_" << nm << "[u].e[e_] = *ewf_at(q_" << nm
+                  << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
+            }
+        }
+    });
+    const std::string text_c = capture([&]() {
+        const std::string &ind = ind2;
+        for (int k : ew_out_ops) o << ind << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
+        o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+        EmitCtx cx;
+        cx.input = [&](int k) {
+            const Operand &op = c.ops[k];
+            if (op.access == Access::Splat && !is_staged(k)) return "ewf_in(it.x_" + opname(k) + "[u])";
+            if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(it.x_" + opname(k) + "[u], e_)";
+            return "ewf_in(it.x_" + opname(k) + "[u].e[e_])";
+        };
+        cx.coord = [&](int d) {
+            std::string s = "o" + std::to_string(d);
+            if (T[d] > 1) s += " + it.c" + std::to_string(d) + "[u]";
+            if (d == in_d) s += " + e_";
+            return s;
+        };
+        emit_values(need, cx, ind + "        ");
+        if (with_reduce)
+            emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ");
+        for (int k : ew_out_ops) {
+            const Operand &op = c.ops[k];
+            int v = g.outputs[op.index].value;
+            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
+            o << ind << "        y_" << opname(k) << ".e[e_] = " << cv << "(v" << v << ");\n";
+        }
+        o << ind << "    }\n";
+        for (int k : ew_out_ops) {
+            const Operand &op = c.ops[k];
+            std::string nm = opname(k);
+            if (op.access == Access::Vector)
+                o << ind << "    " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "), y_" << nm << ");\n";
+            else {
+                o << ind << "    { const ioff_t b_ = " << offset_expr(k, op.access == Access::Splat) << ";\n";
+                o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) *ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
+                  << "[" << in_d << "]) = y_" << nm << ".e[e_]; }\n";
+            }
+        }
+    });
 
-    // the trips over the tile; with more than one trip the loads of the next trip are issued
-    // before the current one is evaluated, so that arithmetic and memory latency overlap
-    // inside a wavefront as well as between wavefronts
-    if (!looped) {
-        o << ind << "{ Item it; load_item(0, it); eval_item(it); }\n";
-    } else if (e.opts.no_prefetch == 1 || (heavy >= 4 && e.opts.no_prefetch == 0)) {
-        o << ind << "for (int L0 = 0; L0 < " << TE << "; L0 += " << step << ") { Item it; load_item(L0, it); eval_item(it); }\n";
-    } else {
+    const bool prefetch = looped && !(e.opts.no_prefetch == 1 || (heavy >= 4 && e.opts.no_prefetch == 0));
+    if (prefetch) {
+        o << ind << "auto load_item = [&](const int L0, Item &it) {\n";
+        o << ind2 << "#pragma unroll\n" << ind2 << "for (int u = 0; u < " << U << "; ++u) {\n";
+        o << text_a;
+        o << ind2 << "    it.ok[u] = k_;\n";
+        o << ind2 << "    if (k_) {\n" << text_b << ind2 << "    }\n" << ind2 << "}\n";
+        o << ind << "};\n";
+        o << ind << "auto eval_item = [&](const Item &it) {\n";
+        o << ind2 << "#pragma unroll\n" << ind2 << "for (int u = 0; u < " << U << "; ++u) {\n";
+        o << ind2 << "    if (!it.ok[u]) continue;\n";
+        o << text_c;
+        o << ind2 << "}\n";
+        o << ind << "};\n";
+        // the next trip's loads are issued before the current trip is evaluated, so that
+        // arithmetic and memory latency overlap inside a wavefront as well as between wavefronts
         o << ind << "{\n";
         o << ind << "    Item cur, nxt;\n";
         o << ind << "    load_item(0, cur);\n";
@@ -1058,6 +1072,17 @@ ewf_status Gen::gen_tile(bool with_reduce)
         o << ind << "        if (more) cur = nxt;\n";
         o << ind << "    }\n";
         o << ind << "}\n";
+    } else {
+        o << ind << "auto run_item = [&](const int L0) {\n";
+        o << ind2 << "Item it;\n";
+        o << ind2 << "#pragma unroll\n" << ind2 << "for (int u = 0; u < " << U << "; ++u) {\n";
+        o << text_a;
+        o << ind2 << "    if (!k_) continue;\n";
+        o << text_b << text_c;
+        o << ind2 << "}\n";
+        o << ind << "};\n";
+        if (!looped) o << ind << "run_item(0);\n";
+        else o << ind << "for (int L0 = 0; L0 < " << TE << "; L0 += " << step << ") run_item(L0);\n";
     }
     if (!staged.empty()) o << ind << "__syncthreads();\n";
 
