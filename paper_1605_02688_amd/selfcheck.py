@@ -1,5 +1,5 @@
 """Build-time check: generate and compile, for gfx950, the kernels of the five benchmark
-workloads at their full shapes.  Needs no GPU: planning inspects pointers only for alignment
+workloads and of the three backward workloads at their full shapes.  Needs no GPU: planning inspects pointers only for alignment
 and aliasing, so synthetic addresses stand in for device memory."""
 from __future__ import annotations
 
@@ -35,7 +35,7 @@ def plan_layout(expr, spec, views, itemsizes):
 def compile_all_workload_kernels(verbose: bool = False) -> int:
     from workloads import configs as wl     # data-only descriptions of the workloads
     count = 0
-    for name, make in wl.FULL_SIZE.items():
+    for name, make in list(wl.FULL_SIZE.items()) + list(wl.BACKWARD.items()):
         w = wl.layout_only(make)
         expr = ewf.Expression(w.spec)
         ws, info = plan_layout(expr, w.spec, w.views, [w.buffers[v.buffer].itemsize for v in w.views])
