@@ -16,6 +16,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libewf.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1605_02688_amd.build`")
+# PyTorch ships a HIP runtime of its own.  The dynamic loader keeps one runtime per process, the
+# first one loaded; device memory handed over by PyTorch is only valid in PyTorch's.  So when
+# PyTorch is installed it is imported before the library (a process that never uses PyTorch
+# simply gets the system runtime).
+try:
+    import torch  # noqa: F401
+except ImportError:
+    pass
 _lib = ctypes.CDLL(LIB_PATH)
 
 MAX_DIMS = 8
