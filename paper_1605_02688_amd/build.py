@@ -63,6 +63,15 @@ def build(verbose: bool = False) -> str:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    # the plain C program that drives the library through its C ABI (used by a GPU test)
+    csrc = os.path.join(ROOT, "tests", "c_abi", "c1_from_c.c")
+    if os.path.exists(csrc):
+        cmd = ["gcc", csrc, "-o", os.path.join(ROOT, "tests", "c_abi", "c1_from_c"), "-O2", "-std=c11", "-Wall",
+               "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"), "-I", "/opt/rocm/include",
+               "-L", HERE, "-lewf", "-L", "/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath," + HERE, "-Wl,-rpath,/opt/rocm/lib"]
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.check_call(cmd)
     return LIB
 
 
