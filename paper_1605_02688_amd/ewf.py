@@ -398,7 +398,9 @@ class Expression:
         self.n_outputs = len(spec.outputs)
 
     def close(self) -> None:
-        if getattr(self, "handle", None):
+        # at interpreter shutdown the module's globals may already be gone: then the process
+        # is ending and the handle goes with it
+        if getattr(self, "handle", None) and exec_destroy is not None:
             exec_destroy(self.handle)
             self.handle = None
 
