@@ -165,7 +165,8 @@ ewf_value ewf_reduce(ewf_graph *g, ewf_redop op, ewf_value v, const int32_t *axe
  * as broadcastable, so it has the shape of wrt[j]).  Conventions: max/min give the cotangent to
  * the first operand on ties, reduce-max/min to every element equal to the result, abs has
  * derivative 0 at 0, comparisons and int32 values stop the cotangent, float16 rounding passes
- * it through.  EWF_EUNSUPPORTED for a product reduction on the path. */
+ * it through; the derivative of a product reduction is the product of the other elements
+ * (exact also where elements are zero). */
 ewf_status ewf_grad(ewf_graph *g, const ewf_value *y, const ewf_value *ybar, int32_t ny,
                     const ewf_value *wrt, int32_t nwrt, ewf_value *grads);
 /* Declares output number k (k counts ewf_output calls) stored as `storage`. */

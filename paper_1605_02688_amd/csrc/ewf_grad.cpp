@@ -107,7 +107,21 @@ extern "C" ewf_status ewf_grad(ewf_graph *graph, const ewf_value *y, const ewf_v
             if (nd.op == EWF_RSUM) accumulate(a0, G);
             else if (nd.op == EWF_RMAX || nd.op == EWF_RMIN)    // every element equal to the extreme value receives it
                 accumulate(a0, b.ap(EWF_WHERE, b.ap(EWF_EQ, a0, n), G, b.lit(0.0)));
-            else if (nd.op == EWF_RPROD) { set_error("the gradient of a product reduction is not provided"); return EWF_EUNSUPPORTED; }
+            else if (nd.op == EWF_RPROD) {
+                // d(prod)/dx_i is the product of the other elements.  With no zero among the reduced
+                // elements that is prod / x_i; with exactly one zero only that element has a non-zero
+                // derivative (the product of the non-zero ones); with more, every derivative is zero.
+                const int z = b.lit(0.0), one = b.lit(1.0);
+                const int is_zero = b.ap(EWF_EQ, a0, z);
+                Node r; r.kind = NodeKind::Reduce; r.nargs = 1; r.axes = nd.axes; r.keep = true;
+                r.op = EWF_RSUM; r.args[0] = b.ap(EWF_WHERE, is_zero, one, z);
+                const int zeros = b.push(r);
+                r.op = EWF_RPROD; r.args[0] = b.ap(EWF_WHERE, is_zero, one, a0);
+                const int others = b.push(r);
+                const int at_zero = b.ap(EWF_WHERE, b.ap(EWF_EQ, zeros, one), others, z);
+                const int elsewhere = b.ap(EWF_WHERE, b.ap(EWF_EQ, zeros, z), b.ap(EWF_DIV, others, a0), z);
+                accumulate(a0, b.ap(EWF_MUL, G, b.ap(EWF_WHERE, is_zero, at_zero, elsewhere)));
+            }
             break;
         case NodeKind::Apply:
             switch (nd.op) {

@@ -509,6 +509,23 @@ def test_plans_in_several_passes(oracle, G):
     G.h.compare("p", got[0], want[0], 1e-5, 1e-7); G.h.compare("centred", got[1], want[1], 2e-5, 2e-6)
 
 
+def test_gradient_of_a_product_reduction(oracle, G):
+    # the library differentiates prod over an axis (zeros handled: one zero in a row, several in another)
+    rng = np.random.default_rng(187)
+    x = (rng.uniform(0.9, 1.1, (37, 130)) * np.where(rng.random((37, 130)) < 0.3, -1, 1)).astype(np.float32)
+    x[5, 17] = 0.0; x[9, 3] = 0.0; x[9, 129] = 0.0
+    c = rng.standard_normal((37, 1)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False)); ci = s.input("f32", (False, True))
+    (gx,) = s.grad([s.reduce("prod", xi, (1,), keep=True)], [ci], [xi])
+    s.output(gx, "f32")
+    print("[case] gradient of a row product", flush=True)
+    expr, got = run_spec(G, s, [x, c])
+    want = oracle.evaluate(G.ewf.export_spec(s), [x, c])
+    assert np.count_nonzero(want[0][9]) == 0 and np.count_nonzero(want[0][5]) == 1
+    G.h.compare("dprod", got[0], want[0], 3e-5, 1e-7)
+
+
 def test_argmax_ties_take_the_first_index(oracle, G):
     x = np.zeros((70, 5000), np.float32)
     x[:, 4000] = 3.0; x[:, 123] = 3.0; x[5, 7] = 3.0

@@ -121,6 +121,28 @@ def test_reductions_on_the_path(oracle):
     check(oracle, lambda s, xs: [s.reduce("sum", s.apply("sqr", xs[0]), (0,), keep=True), s.reduce("min", xs[0], (1,), keep=True)], [x], [0])
 
 
+def test_product_reduction_gradient_with_and_without_zeros(oracle):
+    rng = np.random.default_rng(10)
+    x = grid(rng, (4, 5), 0.5, 1.5) * np.where(rng.random((4, 5)) < 0.5, -1, 1).astype(np.float32)
+    x[1, 3] = 0.0                                   # one zero in row 1: only that element has a derivative
+    x[2, 0] = 0.0; x[2, 4] = 0.0                    # two zeros in row 2: every derivative is zero
+    check(oracle, lambda s, xs: [s.reduce("prod", xs[0], (1,), keep=True)], [x], [0])
+    check(oracle, lambda s, xs: [s.reduce("prod", xs[0], (0,), keep=True)], [x], [0])
+    check(oracle, lambda s, xs: [s.apply("tanh", s.reduce("prod", s.mul(xs[0], xs[0]), (0, 1), keep=True))], [x[:1] + np.float32(2.0)], [0])
+    # and the closed form, exactly: row 0 has no zero
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    (g_,) = s.grad([s.reduce("prod", xi, (1,), keep=True)], [s.const(1.0)], [xi])
+    s.output(g_, "f32")
+    got, = oracle.evaluate(ewf.export_spec(s), [x])
+    x64 = x.astype(np.float64)
+    want = np.zeros_like(x64)
+    for r in range(4):
+        for c in range(5):
+            want[r, c] = np.prod(np.delete(x64[r], c))
+    assert np.allclose(got, want, rtol=1e-5, atol=0)
+
+
 def test_softmax_cross_entropy_gradient_is_softmax_minus_one_hot(oracle):
     rng = np.random.default_rng(10)
     rows, V = 6, 9
@@ -164,13 +186,6 @@ def test_conventions_and_errors():
     s.output(g_unrelated, "f32"); s.output(unused, "f32")
     plain = ewf.export_spec(s)
     assert plain.nodes[plain.outputs[0][0]][0] == "apply"                       # y * 0: a zero with y's pattern
-    s = GraphSpec(1)
-    x = s.input("f32", (False,))
-    p_ = s.reduce("prod", x, (0,), keep=True)
-    s.grad([p_], [s.const(1.0)], [x])
-    with pytest.raises(ewf.EwfError) as e:
-        ewf.export_spec(s)
-    assert e.value.status == ewf.EUNSUPPORTED
     s = GraphSpec(1)
     i = s.input("i32", (False,))
     s.grad([s.cast(i, "f32")], [s.const(1.0)], [i])
