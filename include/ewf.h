@@ -115,7 +115,13 @@ typedef struct {
     int32_t no_rewrite;     /* 1: compile the scalar graph as described (default: duplicates
                                merged, constants folded, log(1+x) -> log1p(x), exp(x)-1 ->
                                expm1(x), x*x and pow(x,2) -> a square, identities removed)   */
-    int32_t reserved[3];
+    int32_t split_rows;     /* chained reductions along rows (softmax, log-sum-exp): one workgroup
+                               per row holding the row in registers, or several passes with the
+                               rows split over workgroups (max -> sum of exp fused into one
+                               level that is rescaled as the maximum grows).  0 automatic: split
+                               when a row does not fit the registers or the rows are too few to
+                               occupy the chip; 1 always split; 2 never                       */
+    int32_t reserved[2];
 } ewf_options;
 
 /* A strided n-d view of caller-owned device memory.  rank is implied by the graph (inputs:
@@ -258,6 +264,11 @@ ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info);
 ewf_status ewf_debug_operand_strides(ewf_exec *e, int32_t k, int64_t *strides_out);
 /* Generated HIP source of the last plan (library-owned, valid until the next plan). */
 const char *ewf_debug_source(ewf_exec *e);
+/* A plan in several passes (kernel_class 5, grid_blocks = number of stages): the plan and the
+ * generated source of stage `stage`, in execution order.  EWF_EINVAL when the last plan has no
+ * such stage. */
+ewf_status ewf_debug_stage_plan_info(ewf_exec *e, int32_t stage, ewf_plan_info *info);
+const char *ewf_debug_stage_source(ewf_exec *e, int32_t stage);
 /* Number of kernels compiled so far by this executable (cache misses). */
 int32_t ewf_debug_compile_count(ewf_exec *e);
 /* Nodes of the scalar graph as described, and after the rewrites of ewf_compile (section

@@ -137,13 +137,33 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
         return EWF_OK;
     }
 
+    plan->avoid_poor_rows = !e.is_stage || e.strict_rows;
     st = single_kernel_plan(e, plan.get(), full);
     if (st == EWF_EUNSUPPORTED && !e.is_stage) {
-        // no single kernel covers the expression: several passes, reductions materialised
+        // no single kernel covers the expression (or only a poorly fitting one does): several
+        // passes, reductions materialised; a softmax-style chain max -> sum of exp first
+        // becomes one level
         const std::string why = get_error();
-        st = plan_multi(e, in, nin, out, nout, *plan);
-        if (st == EWF_EUNSUPPORTED) set_error_str(why + "; and a plan in several passes failed: " + get_error());
-        if (st == EWF_OK) plan->kclass = KernelClass::Multi;
+        const bool refused = plan->row_refused;
+        Graph split = e.g;
+        fuse_shifted_exp_sums(split);
+        st = plan_multi(e, split, true, in, nin, out, nout, *plan);
+        if (st == EWF_EUNSUPPORTED) {
+            plan->stages.clear();
+            plan->temps.clear();
+            if (refused) {
+                // the single kernel after all
+                plan->avoid_poor_rows = false;
+                plan->row_refused = false;
+                st = single_kernel_plan(e, plan.get(), full);
+            } else {
+                st = plan_multi(e, split, false, in, nin, out, nout, *plan);
+                if (st == EWF_EUNSUPPORTED) set_error_str(why + "; and a plan in several passes failed: " + get_error());
+                if (st == EWF_OK) plan->kclass = KernelClass::Multi;
+            }
+        } else if (st == EWF_OK) {
+            plan->kclass = KernelClass::Multi;
+        }
     }
     if (st != EWF_OK) return st;
     e.last = plan.get();
@@ -156,6 +176,7 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
 {
     ewf_status st;
     const Canon &c = plan->canon;
+    bool row_only = false;                     // only the row class covers the expression
     if (!plan->red.has_reduce) {
         plan->kclass = KernelClass::Tile;
     } else {
@@ -192,6 +213,7 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
                 }
             }
             plan->kclass = KernelClass::Row;
+            row_only = true;
         } else if (inner_only && rows >= 512 && c.extent[c.rank - 1] <= 65536) {
             plan->kclass = KernelClass::Row;
         } else {
@@ -200,6 +222,12 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
     }
 
     st = generate(e, *plan);
+    if (st == EWF_EUNSUPPORTED && plan->row_refused && plan->kclass == KernelClass::Row && !row_only) {
+        // plain row reductions do not need the row class
+        plan->row_refused = false;
+        plan->kclass = KernelClass::TileReduce;
+        st = generate(e, *plan);
+    }
     if (st != EWF_OK) return st;
     bool cached = false;
     st = compile_source(plan->source, plan->code, &cached);
@@ -376,11 +404,39 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
 
 extern "C" {
 
+static void fill_plan_info(const Plan *p, ewf_plan_info *info);
+
 ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info)
 {
     if (!e || !info) { set_error("null argument"); return EWF_EINVAL; }
     const Plan *p = e->e.last;
     if (!p) { set_error("no plan yet"); return EWF_EINVAL; }
+    fill_plan_info(p, info);
+    return EWF_OK;
+}
+
+static const Plan *stage_plan(ewf_exec *e, int32_t stage)
+{
+    if (!e || !e->e.last || stage < 0 || stage >= (int32_t)e->e.last->stages.size()) return nullptr;
+    return e->e.last->stages[stage].exec->last;
+}
+
+ewf_status ewf_debug_stage_plan_info(ewf_exec *e, int32_t stage, ewf_plan_info *info)
+{
+    const Plan *p = stage_plan(e, stage);
+    if (!p || !info) { set_error("no such stage"); return EWF_EINVAL; }
+    fill_plan_info(p, info);
+    return EWF_OK;
+}
+
+const char *ewf_debug_stage_source(ewf_exec *e, int32_t stage)
+{
+    const Plan *p = stage_plan(e, stage);
+    return p ? p->source.c_str() : "";
+}
+
+static void fill_plan_info(const Plan *p, ewf_plan_info *info)
+{
     memset(info, 0, sizeof *info);
     info->kernel_class = (int)p->kclass;
     info->rank = p->canon.rank;
@@ -396,7 +452,6 @@ ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info)
     info->grid_blocks = (int)p->grid;
     info->lds_bytes = p->lds_bytes;
     info->staged_operands = p->staged;
-    return EWF_OK;
 }
 
 ewf_status ewf_debug_operand_strides(ewf_exec *e, int32_t k, int64_t *strides_out)

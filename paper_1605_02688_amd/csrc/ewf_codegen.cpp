@@ -313,9 +313,18 @@ struct Gen {
         size_t b = 0;
         for (size_t i = 0; i < nodes.size(); i++) {
             if (shared_slot(nodes, i) >= 0) continue;
-            b += (g.nodes[nodes[i]].op == EWF_RARGMAX) ? 8 : 4;
+            const int op = g.nodes[nodes[i]].op;
+            b += (op == EWF_RARGMAX || op == kRSumExpShifted) ? 8 : 4;
         }
         return b;
+    }
+
+    // the exponential inside a sum: under the automatic math mode the native-rate flavour with
+    // fix-ups (see sum_only)
+    const char *sum_math() const
+    {
+        const int fl = (e.auto_math && e.math_flavour == 1) ? 2 : e.math_flavour;
+        return fl == 3 ? "ewf_bare" : fl == 2 ? "ewf_fast" : "ewf_acc";
     }
 
     // Declares `struct <name>` with one slot per reduction in `nodes`, its identity and its
@@ -328,6 +337,7 @@ struct Gen {
             const Node &nd = g.nodes[nodes[i]];
             const Node &arg = g.nodes[nd.args[0]];
             if (nd.op == EWF_RARGMAX) o << "    " << vtype_c(arg.vtype) << " a" << i << "; int i" << i << ";\n";
+            else if (nd.op == kRSumExpShifted) o << "    float a" << i << ", b" << i << ";      // running maximum, sum of exp(x - maximum)\n";
             else o << "    " << vtype_c(nd.vtype) << " a" << i << ";\n";
         }
         o << "};\n";
@@ -342,6 +352,9 @@ struct Gen {
             case EWF_RPROD: id = isint ? "1" : "1.0f"; break;
             case EWF_RMAX: case EWF_RARGMAX: id = isint ? "(-2147483647 - 1)" : "ewf_bits_f32(0xff800000u)"; break;
             case EWF_RMIN: id = isint ? "2147483647" : "ewf_bits_f32(0x7f800000u)"; break;
+            // the most negative finite number, not -inf: x - maximum then never is inf - inf
+            // for an element that is -inf, and exp(x - maximum) is 0 for it as it should be
+            case kRSumExpShifted: id = "ewf_bits_f32(0xff7fffffu)"; o << "    a.b" << i << " = 0.0f;\n"; break;
             }
             o << "    a.a" << i << " = " << id << ";\n";
             if (nd.op == EWF_RARGMAX) o << "    a.i" << i << " = 2147483647;\n";
@@ -359,6 +372,12 @@ struct Gen {
             case EWF_RPROD: o << "        r.a" << i << " = " << (isint ? "ewf_muli(" + a + ", " + b + ")" : a + " * " + b) << ";\n"; break;
             case EWF_RMAX: o << "        r.a" << i << " = ewf_max(" << a << ", " << b << ");\n"; break;
             case EWF_RMIN: o << "        r.a" << i << " = ewf_min(" << a << ", " << b << ");\n"; break;
+            case kRSumExpShifted:
+                // both sums are rescaled to the common maximum
+                o << "        r.a" << i << " = ewf_max(" << a << ", " << b << ");\n"
+                  << "        r.b" << i << " = x.b" << i << " * " << sum_math() << "::exp(" << a << " - r.a" << i << ") + y.b" << i << " * "
+                  << sum_math() << "::exp(" << b << " - r.a" << i << ");\n";
+                break;
             case EWF_RARGMAX: {
                 std::string ia = "x.i" + std::to_string(i), ib = "y.i" + std::to_string(i);
                 if (isint) {
@@ -384,6 +403,11 @@ struct Gen {
             const Node &nd = g.nodes[nodes[i]];
             const int sh = shared_slot(nodes, i);
             if (nd.op == EWF_RARGMAX) o << ind << "const int r" << nodes[i] << " = " << acc << ".i" << i << ";\n";
+            else if (nd.op == kRSumExpShifted)
+                // no term at all (every element -inf) or a maximum of +inf: x - max(x) is
+                // inf - inf for some element, so the sum as described is NaN
+                o << ind << "const float r" << nodes[i] << " = (" << acc << ".b" << i << " == 0.0f || " << acc << ".a" << i
+                  << " == ewf_bits_f32(0x7f800000u)) ? ewf_bits_f32(0x7fc00000u) : " << acc << ".b" << i << ";\n";
             else o << ind << "const " << vtype_c(nd.vtype) << " r" << nodes[i] << " = " << acc << ".a" << (sh >= 0 ? sh : (int)i) << ";\n";
         }
     }
@@ -407,6 +431,16 @@ struct Gen {
             case EWF_RPROD: o << ind << a << " = " << (isint ? "ewf_muli(" + a + ", " + v + ")" : a + " * " + v) << ";\n"; break;
             case EWF_RMAX: o << ind << a << " = ewf_max(" << a << ", " << v << ");\n"; break;
             case EWF_RMIN: o << ind << a << " = ewf_min(" << a << ", " << v << ");\n"; break;
+            case kRSumExpShifted: {
+                // exp(-|x - maximum|) serves both cases: it rescales the sum when x is the new
+                // maximum and is the new term otherwise
+                const std::string b = acc + ".b" + std::to_string(i);
+                o << ind << "{ const float d_ = " << v << " - " << a << ";\n"
+                  << ind << "  const float w_ = " << sum_math() << "::exp(-__builtin_fabsf(d_));\n"
+                  << ind << "  " << b << " = d_ > 0.0f ? " << b << " * w_ + 1.0f : " << b << " + w_;\n"
+                  << ind << "  " << a << " = ewf_max(" << a << ", " << v << "); }\n";
+                break;
+            }
             case EWF_RARGMAX: {
                 std::string ia = acc + ".i" + std::to_string(i);
                 std::string ib = "(int)(" + argmax_index(nodes[i]) + ")";
@@ -545,8 +579,13 @@ struct Gen {
     // Second kernel of the split reductions: one workgroup per reduction group; its lanes walk
     // the group's partials (contiguous in the workspace), a wavefront butterfly and an LDS
     // step in wavefront order fold them -- the same order on every run.
+    // `inflight`: partials a thread loads before it folds them (more than one when a group has
+    // many partials per thread, so that the loads overlap instead of each waiting for the last).
+    // `gathers`: sums with a single non-zero term (see match_gather) that the streaming kernel
+    // left out: the finishing thread reads that one element itself.
     void emit_finish_lanes(const std::vector<int> &level, const std::vector<int> &group_out_ops,
-                           const std::string &nparts_expr, int fin_block)
+                           const std::string &nparts_expr, int fin_block, int inflight = 1,
+                           const std::vector<Gather> &gathers = std::vector<Gather>())
     {
         std::vector<int> all_dims;
         for (int d = 0; d < R; d++) all_dims.push_back(d);
@@ -559,7 +598,19 @@ struct Gen {
         o << "    for (idx_t group = blockIdx.x; group < p.nrows; group += gridDim.x) {\n";
         o << "        const Acc *const gpart = partials + (size_t)group * (size_t)nparts;\n";
         o << "        Acc tot = Acc_identity();\n";
-        o << "        for (idx_t i = lane; i < nparts; i += " << fin_block << ") tot = Acc_combine()(tot, gpart[i]);\n";
+        if (inflight <= 1) {
+            o << "        for (idx_t i = lane; i < nparts; i += " << fin_block << ") tot = Acc_combine()(tot, gpart[i]);\n";
+        } else {
+            o << "        for (idx_t i0 = lane; i0 < nparts; i0 += " << fin_block * inflight << ") {\n";
+            o << "            Acc part_[" << inflight << "];\n";
+            o << "            #pragma unroll\n            for (int u = 0; u < " << inflight << "; ++u) {\n";
+            o << "                const idx_t i = i0 + (idx_t)u * " << fin_block << ";\n";
+            o << "                part_[u] = Acc_identity();\n";
+            o << "                if (i < nparts) part_[u] = gpart[i];\n";
+            o << "            }\n";
+            o << "            #pragma unroll\n            for (int u = 0; u < " << inflight << "; ++u) tot = Acc_combine()(tot, part_[u]);\n";
+            o << "        }\n";
+        }
         o << "        tot = ewf_block_reduce<" << fin_block / 64 << ">(tot, Acc_combine(), sm_fin, lane);\n";
         o << "        if (lane != 0) continue;\n";
         o << "        idx_t g_ = group;\n";
@@ -575,16 +626,39 @@ struct Gen {
         std::vector<int> gt;
         for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
         std::vector<char> gneed = needed(gt);
-        for (int k : inputs_of(gneed)) emit_base(k, all_dims, "        ");
         EmitCtx gx;
         gx.input = [&](int k) { return "ewf_in(q_" + opname(k) + "[0])"; };
         gx.coord = [&](int d) { return "o" + std::to_string(d); };
+        std::vector<char> based(c.ops.size(), 0);
+        auto base_once = [&](int k) {
+            if (based[k]) return;
+            based[k] = 1;
+            emit_base(k, all_dims, "        ");
+        };
+        if (!gathers.empty()) {
+            std::vector<int> it;
+            for (const Gather &ga : gathers) it.push_back(ga.index_value);
+            std::vector<char> ineed = needed(it);
+            for (int k : inputs_of(ineed)) base_once(k);
+            emit_values(ineed, gx, "        ");
+            for (size_t n = 0; n < ineed.size(); n++) if (ineed[n]) gneed[n] = 0;
+            for (const Gather &ga : gathers) {
+                base_once(ga.input);
+                const std::string nm = opname(ga.input);
+                o << "        float r" << ga.node << ";\n        {\n";
+                o << "            const int t_ = v" << ga.index_value << ";\n";
+                o << "            const bool in_ = t_ >= 0 && t_ < p.ext[" << ga.cdim << "];\n";
+                o << "            const float x_ = ewf_in(q_" << nm << "[(idx_t)(in_ ? t_ : 0) * p.st_" << nm << "[" << ga.cdim << "]]);\n";
+                o << "            r" << ga.node << " = in_ ? x_ + 0.0f : 0.0f;\n        }\n";
+            }
+        }
+        for (int k : inputs_of(gneed)) base_once(k);
         emit_values(gneed, gx, "        ");
         for (int k : group_out_ops) {
             const Operand &op = c.ops[k];
             int v = g.outputs[op.index].value;
             const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
-            emit_base(k, all_dims, "        ");
+            base_once(k);
             o << "        q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
         }
         o << "    }\n}\n";
@@ -606,6 +680,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // heavy in transcendental operations, where registers (occupancy) matter more
     int heavy = 0;
     for (size_t n = 0; n < g.nodes.size(); n++) {
+        if (live[n] && g.nodes[n].kind == NodeKind::Reduce && g.nodes[n].op == kRSumExpShifted) heavy += 1;
         if (!live[n] || g.nodes[n].kind != NodeKind::Apply) continue;
         switch (g.nodes[n].op) {
         case EWF_EXP: case EWF_LOG: case EWF_LOG1P: case EWF_TANH: case EWF_SIGMOID: case EWF_EXPM1: heavy += 1; break;
@@ -818,8 +893,24 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // ---- what to evaluate per element
     std::vector<int> targets;
     for (int k : ew_out_ops) targets.push_back(g.outputs[c.ops[k].index].value);
-    std::vector<int> level = with_reduce ? red.level_nodes : std::vector<int>();
+    // Sums with one non-zero term are left to the second kernel, which reads that element
+    // itself (as long as something else remains to be accumulated here).
+    std::vector<int> level;
+    std::vector<Gather> gathers;
+    if (with_reduce) {
+        for (int n : red.level_nodes) {
+            Gather ga;
+            if (match_gather(n, ga) && g.nodes[n].axes == red.axes && c.reduced[ga.cdim]) gathers.push_back(ga);
+            else level.push_back(n);
+        }
+        if (level.empty()) { level = red.level_nodes; gathers.clear(); }
+    }
     for (int n : level) targets.push_back(g.nodes[n].args[0]);
+    // One thread meets the elements of a tile in increasing order of the linear index; when the
+    // tile extends along the arg-max axis only, that is increasing order of the arg-max index.
+    bool ascending = with_reduce && tiled.size() <= 1;
+    for (int n : level)
+        if (g.nodes[n].op == EWF_RARGMAX && !tiled.empty() && argmax_canon_dim(n) != tiled[0]) ascending = false;
     std::vector<char> need = needed(targets);
     std::vector<int> used_inputs = inputs_of(need);
 
@@ -1025,7 +1116,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         };
         emit_values(need, cx, ind + "        ");
         if (with_reduce)
-            emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ");
+            emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ", ascending);
         for (int k : ew_out_ops) {
             const Operand &op = c.ops[k];
             int v = g.outputs[op.index].value;
@@ -1091,6 +1182,18 @@ ewf_status Gen::gen_tile(bool with_reduce)
         // no LDS, no barrier, no atomic -- the waves of a workgroup never wait for each other
         // and the kernel streams like a copy.  A second, tiny kernel folds the partials of a
         // group in a fixed order (deterministic, and ordered by the kernel boundary alone).
+        if (ascending) {
+            // a thread's first element of the tile is item tid of the first trip
+            std::string first = "(idx_t)0", has = "tid * EWF_VEC < " + std::to_string(TE);
+            if (!tiled.empty()) {
+                const std::string d = std::to_string(tiled[0]);
+                first = "o" + d + " + tid * EWF_VEC";
+                has += " && o" + d + " + tid * EWF_VEC < p.ext[" + d + "]";
+            } else {
+                for (int n : level) if (g.nodes[n].op == EWF_RARGMAX) first = "o" + std::to_string(argmax_canon_dim(n));
+            }
+            emit_first_index("acc", level, has, first, ind);
+        }
         o << ind << "idx_t group = 0, slot = 0;\n";
         for (int d = 0; d < R; d++) {
             if (c.reduced[d]) o << ind << "slot = slot * p.ntile[" << d << "] + ti" << d << ";\n";
@@ -1105,9 +1208,12 @@ ewf_status Gen::gen_tile(bool with_reduce)
         // one workgroup per group: a wavefront when a group has few partials, four otherwise
         int64_t nparts_host = (int64_t)(block / 64);
         for (int d = 0; d < R; d++) if (c.reduced[d]) nparts_host *= ntile[d];
-        const int fin_block = nparts_host > 256 ? 256 : 64;
+        // (1024 threads and eight partials in flight per thread when there are thousands: a total
+        // over a large tensor is one group, and its finish is otherwise a chain of dependent loads)
+        const int fin_block = nparts_host > 4096 ? 1024 : nparts_host > 256 ? 256 : 64;
         fin_block_out = fin_block;
-        emit_finish_lanes(level, group_out_ops, "p.nslots * EWF_NWAVES", fin_block);
+        const int inflight = (int)std::min<int64_t>(8, std::max<int64_t>(1, ceil_div(nparts_host, fin_block)));
+        emit_finish_lanes(level, group_out_ops, "p.nslots * EWF_NWAVES", fin_block, inflight, gathers);
     }
 
     // ---- launch geometry and argument block
@@ -1193,6 +1299,20 @@ ewf_status Gen::gen_row()
     int regs = 0;
     for (int k : row_ops) regs += (int)NV * VEC * isz(c.ops[k].storage) / 4;
     const bool resident = NV <= 32 && regs <= 96;
+    if (p.avoid_poor_rows && e.opts.split_rows != 2) {
+        int64_t nr = 1;
+        for (int d = 0; d < R - 1; d++) nr *= c.extent[d];
+        // measured on [rows, cols] float32 softmax cross-entropy of 268 MB: rows held in registers
+        // run at 5.3-5.5 TB/s up to 32768 columns but 4.1 TB/s at 65536 (64 registers per thread,
+        // 1024 threads: one workgroup per compute unit), rows streamed once per level 2.7-3.4 TB/s;
+        // split over workgroups 5.0-5.2 TB/s at any row length
+        const bool too_long = !resident || regs > 48;
+        if (too_long || (nr * 2 < device_cu_count() && cols >= 16384) || e.opts.split_rows == 1) {
+            p.row_refused = true;
+            return fail(too_long ? "a row does not fit the registers of a workgroup well: the row class would read it once per reduction level or run one workgroup per compute unit"
+                                 : "too few rows for one workgroup per row to occupy the chip");
+        }
+    }
     const int U = resident ? (int)NV : (e.opts.unroll > 0 ? e.opts.unroll : 4);
     p.tile[in_d] = cols;
     {
@@ -1414,6 +1534,7 @@ ewf_status Gen::gen_row()
                     if (shared_slot(red.cross_nodes, i) >= 0) continue;
                     const Node &nd = g.nodes[red.cross_nodes[i]];
                     o << "            ax.a" << i << " = v" << nd.args[0] << ";\n";
+                    if (nd.op == kRSumExpShifted) o << "            ax.b" << i << " = 1.0f;\n";
                     if (nd.op == EWF_RARGMAX) {
                         int cd = argmax_canon_dim(red.cross_nodes[i]);
                         o << "            ax.i" << i << " = (int)(" << (cd < 0 ? std::string("0") : "o" + std::to_string(cd)) << ");\n";

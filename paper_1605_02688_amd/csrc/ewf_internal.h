@@ -100,6 +100,13 @@ struct Canon {
 
 enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3, Col = 4, Multi = 5 };
 
+// A reduction the library introduces itself (never part of a caller's description):
+// sum over the axes of exp(x - max over the same axes of x), accumulated in one pass as a
+// (running maximum, sum relative to it) pair that is rescaled whenever the maximum grows.
+// It turns the two chained reductions of a softmax or log-sum-exp into one level, so rows of
+// any length can be split over workgroups.
+constexpr int kRSumExpShifted = 64;
+
 struct ReduceInfo {
     bool has_reduce = false;
     uint32_t axes = 0;                   // axes of the fused (first-level) reductions
@@ -154,6 +161,10 @@ struct Temp {
 };
 
 struct Plan {
+    // Planning hints for the row class: refuse (EWF_EUNSUPPORTED, row_refused set) when a row
+    // does not fit the registers of a workgroup or the rows are too few to occupy the chip, so
+    // that the caller can try a plan in several passes first.
+    bool avoid_poor_rows = false, row_refused = false;
     KernelClass kclass = KernelClass::None;
     std::vector<Stage> stages;           // KernelClass::Multi only
     std::vector<Temp> temps;
@@ -185,6 +196,7 @@ struct Plan {
 
 struct Exec {
     bool is_stage = false;               // a stage of a multi-pass plan: must fit one kernel
+    bool strict_rows = false;            // a stage that must not fall back on a poorly fitting row kernel
     Graph g;
     ewf_options opts{};
     int math_flavour = 1;                // 1 accurate, 2 native rate with fix-ups, 3 native rate
@@ -207,6 +219,9 @@ uint32_t all_mask(int ndim);
 // ---- ewf_rewrite.cpp
 // Merges duplicate nodes, folds constants, applies the stabilising rewrites; in place.
 int rewrite_graph(Graph &g);
+// Replaces every sum(exp(x - max(x))) over matching axes by one kRSumExpShifted node; in place.
+// Returns the number of replacements.
+int fuse_shifted_exp_sums(Graph &g);
 
 // ---- ewf_canon.cpp
 // Builds the canonical layout.  `in`/`out` give shapes and strides in the original rank
@@ -229,7 +244,9 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
 // ---- ewf_multi.cpp
 // Splits an expression that no single kernel class covers into stages: first-level reductions
 // are materialised into temporaries, the rest of the graph reads them as broadcast operands.
-ewf_status plan_multi(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan);
+// `g` is e.g or a rewritten copy of it with the same inputs, scalars and outputs.
+// With `strict_rows` no stage may use the row class where it fits poorly (see Plan::avoid_poor_rows).
+ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan);
 ewf_status run_multi(Exec &e, Plan &p, const ewf_tensor *in, int nin, const double *scalars, int nscalars,
                      const ewf_tensor *out, int nout, void *workspace, size_t workspace_bytes, void *hip_stream);
 

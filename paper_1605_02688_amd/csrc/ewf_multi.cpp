@@ -83,9 +83,8 @@ void build_stage(const Graph &g, const std::vector<std::pair<int, ewf_dtype>> &t
 
 }  // namespace
 
-ewf_status plan_multi(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan)
+ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan)
 {
-    const Graph &g = e.g;
     const int N = (int)g.nodes.size();
     int64_t full[kMaxDims];
     ewf_status st = infer_full_extents(g, in, nin, full);
@@ -121,6 +120,7 @@ ewf_status plan_multi(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *
         sg.exec->math_flavour = e.math_flavour;
         sg.exec->auto_math = e.auto_math;
         sg.exec->is_stage = true;
+        sg.exec->strict_rows = strict_rows;
         ewf_status s2 = finalize_graph(sg.exec->g);
         if (s2 != EWF_OK) return s2;
         std::vector<ewf_tensor> tin, tout;

@@ -111,6 +111,26 @@ bool commutative(int op)
 }  // namespace
 
 // Rewrites `g` in place.  Returns the number of nodes removed or replaced (for tests).
+int fuse_shifted_exp_sums(Graph &g)
+{
+    int count = 0;
+    for (Node &s : g.nodes) {
+        if (s.kind != NodeKind::Reduce || s.op != EWF_RSUM || s.vtype != EWF_F32) continue;
+        const Node &ex = g.nodes[s.args[0]];
+        if (ex.kind != NodeKind::Apply || ex.op != EWF_EXP) continue;
+        const Node &sub = g.nodes[ex.args[0]];
+        if (sub.kind != NodeKind::Apply || sub.op != EWF_SUB) continue;
+        const int x = sub.args[0];
+        const Node &m = g.nodes[sub.args[1]];
+        if (m.kind != NodeKind::Reduce || m.op != EWF_RMAX || m.args[0] != x || m.axes != s.axes) continue;
+        if (g.nodes[x].vtype != EWF_F32 || g.nodes[x].bcast != ex.bcast) continue;
+        s.op = kRSumExpShifted;
+        s.args[0] = x;
+        count++;
+    }
+    return count;
+}
+
 int rewrite_graph(Graph &g)
 {
     const int N = (int)g.nodes.size();

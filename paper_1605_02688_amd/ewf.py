@@ -52,7 +52,8 @@ class ewf_options(ctypes.Structure):
                 ("no_lds_staging", ctypes.c_int32), ("streaming", ctypes.c_int32),
                 ("tile_elems", ctypes.c_int32), ("waves_per_simd", ctypes.c_int32),
                 ("no_prefetch", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
-                ("no_rewrite", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("no_rewrite", ctypes.c_int32), ("split_rows", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
 
 class ewf_tensor(ctypes.Structure):
@@ -106,6 +107,8 @@ _sigs = {
     "ewf_debug_plan_info": (_i32, [_vp, ctypes.POINTER(ewf_plan_info)]),
     "ewf_debug_operand_strides": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_int64)]),
     "ewf_debug_source": (ctypes.c_char_p, [_vp]),
+    "ewf_debug_stage_plan_info": (_i32, [_vp, _i32, ctypes.POINTER(ewf_plan_info)]),
+    "ewf_debug_stage_source": (ctypes.c_char_p, [_vp, _i32]),
     "ewf_debug_compile_count": (_i32, [_vp]),
     "ewf_debug_graph_size": (_i32, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "ewf_copy_bytes": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
@@ -254,9 +257,13 @@ def run(e: int, inputs: Sequence, scalars: Sequence[float], outputs: Sequence, w
                         workspace_bytes, stream or None))
 
 
-def debug_plan_info(e: int) -> dict:
+def debug_plan_info(e: int, stage: int = -1) -> dict:
+    """The last plan; with ``stage`` >= 0, that stage of a plan in several passes."""
     info = ewf_plan_info()
-    _check(_lib.ewf_debug_plan_info(e, ctypes.byref(info)))
+    if stage >= 0:
+        _check(_lib.ewf_debug_stage_plan_info(e, stage, ctypes.byref(info)))
+    else:
+        _check(_lib.ewf_debug_plan_info(e, ctypes.byref(info)))
     r = info.rank
     return {"kernel_class": KERNEL_CLASSES.get(info.kernel_class, "?"), "rank": r,
             "extent": tuple(info.extent[d] for d in range(r)),
@@ -273,7 +280,9 @@ def debug_operand_strides(e: int, k: int, rank: int) -> Tuple[int, ...]:
     return tuple(st[d] for d in range(rank))
 
 
-def debug_source(e: int) -> str:
+def debug_source(e: int, stage: int = -1) -> str:
+    if stage >= 0:
+        return _lib.ewf_debug_stage_source(e, stage).decode()
     return _lib.ewf_debug_source(e).decode()
 
 
@@ -421,11 +430,11 @@ class Expression:
         """Marshals the arguments once; ``BoundCall.launch()`` is then a single ewf_run call."""
         return BoundCall(self, inputs, outputs, scalars, workspace, stream)
 
-    def info(self) -> dict:
-        return debug_plan_info(self.handle)
+    def info(self, stage: int = -1) -> dict:
+        return debug_plan_info(self.handle, stage)
 
-    def source(self) -> str:
-        return debug_source(self.handle)
+    def source(self, stage: int = -1) -> str:
+        return debug_source(self.handle, stage)
 
     def graph_size(self) -> Tuple[int, int]:
         """(nodes described, nodes compiled after the rewrites)."""

@@ -619,9 +619,14 @@ def test_streaming_rows_longer_than_registers(oracle, G):
     m = s.reduce("max", xi, (1,))
     S = s.reduce("sum", s.apply("exp", s.sub(xi, m)), (1,))
     s.output(s.add(m, s.apply("log", S)), "f32")
-    expr, (got,) = run_spec(G, s, [x])
+    want = oracle.evaluate(s, [x], nthreads=4)[0]
+    expr, (got,) = run_spec(G, s, [x], split_rows=2)
     assert expr.info()["kernel_class"] == "row"
-    G.h.compare("lse", got, oracle.evaluate(s, [x], nthreads=4)[0], 1e-5, 1e-6)
+    G.h.compare("lse", got, want, 1e-5, 1e-6)
+    # left to itself the library splits such rows over workgroups instead
+    expr, (got,) = run_spec(G, s, [x])
+    assert expr.info()["kernel_class"] == "multi"
+    G.h.compare("lse_split", got, want, 1e-5, 1e-6)
 
 
 # ------------------------------------------------------------------ random graphs
@@ -708,3 +713,76 @@ def test_random_graphs_and_layouts(seed, oracle, G):
         # structural test (indexing, broadcast, strides): looser than the per-op accuracy bar
         # because random chains amplify float32 rounding
         G.h.compare(f"seed{seed}.out{k}", g_, w_, 2e-4, 2e-5)
+
+
+# ------------------------------------------------------------------ softmax chains split over workgroups
+
+def _lse_spec(storage="f32", axis=1):
+    """max, sum of exp(x - max), log-sum-exp and the softmax probabilities along `axis`."""
+    s = GraphSpec(2)
+    x = s.input(storage, (False, False))
+    m = s.reduce("max", x, (axis,), keep=True)
+    ex = s.apply("exp", s.sub(x, m))
+    S = s.reduce("sum", ex, (axis,), keep=True)
+    s.output(m, "f32"); s.output(S, "f32")
+    s.output(s.add(m, s.apply("log", S)), "f32")
+    s.output(s.div(ex, S), storage)
+    return s
+
+
+def test_long_rows_are_split_and_the_exp_sum_is_rescaled_online(oracle, G):
+    from workloads import configs as wl
+    # rows too long for the registers of a workgroup: the chain max -> sum of exp becomes one level
+    w = wl.c3_softmax_xent(rows=37, vocab=150001)
+    print(f"[case] {w.name} 37 x 150001", flush=True)
+    expr, stats = G.h.check_workload(w, oracle)
+    info = expr.info()
+    assert info["kernel_class"] == "multi", info
+    assert expr.info(0)["kernel_class"] == "tile_reduce" and "b2 * w_" in expr.source(0).replace("acc.", "")
+    w = wl.c3_softmax_xent_backward(rows=5, vocab=70001)
+    print(f"[case] {w.name} 5 x 70001", flush=True)
+    expr, stats = G.h.check_workload(w, oracle)
+    assert expr.info()["kernel_class"] == "multi" and expr.info()["grid_blocks"] == 2
+    # few rows that would fit: one workgroup per row would leave the chip idle
+    rng = np.random.default_rng(188)
+    x = (rng.standard_normal((3, 40000)) * 3).astype(np.float32)
+    s = _lse_spec()
+    print("[case] 3 x 40000 softmax", flush=True)
+    expr, got = run_spec(G, s, [x])
+    assert expr.info()["kernel_class"] == "multi"
+    want = oracle.evaluate(s, [x])
+    for name, g_, w_ in zip(("max", "expsum", "lse", "p"), got, want):
+        G.h.compare(name, g_, w_, 1e-5, 1e-9 if name == "p" else 1e-6)
+
+
+@pytest.mark.parametrize("storage,axis", [("f32", 1), ("f16", 1), ("f32", 0)])
+def test_split_softmax_at_small_sizes_and_special_values(storage, axis, oracle, G):
+    rng = np.random.default_rng(189)
+    dt = np.float32 if storage == "f32" else np.float16
+    x = (rng.standard_normal((41, 1003)) * 4).astype(dt)
+    inf = dt(np.inf)
+    x[1, 5] = -inf; x[1, 900] = -inf                       # terms that vanish
+    x[2, :] = -inf                                          # nothing but -inf: NaN as described
+    x[3, 0] = -inf; x[3, 1] = 2.0                           # the first elements a thread meets are -inf
+    x[4, 77] = inf                                          # inf - inf
+    x[5, 500] = np.nan
+    x[6, :] = 1.5                                           # every element the maximum
+    x[7, :] = -3.0e38 if storage == "f32" else -60000.0     # the most negative numbers
+    x[8, 1002] = 80.0 if storage == "f32" else 30.0         # the maximum arrives last: everything before is rescaled
+    if axis == 0:
+        x = np.ascontiguousarray(x.T)
+    s = _lse_spec(storage, axis)
+    print(f"[case] split softmax {storage} axis {axis}", flush=True)
+    expr, got = run_spec(G, s, [x], split_rows=1)
+    assert expr.info()["kernel_class"] == "multi", expr.info()
+    want = oracle.evaluate(s, [x])
+    tol_p = (1e-5, 1e-9) if storage == "f32" else (2e-3, 1e-3)
+    assert np.array_equal(got[0], want[0], equal_nan=True)
+    G.h.compare("expsum", got[1], want[1], 1e-5, 1e-6)
+    G.h.compare("lse", got[2], want[2], 1e-5, 1e-6)
+    G.h.compare("p", got[3], want[3], *tol_p)
+    # and the same description with one workgroup per row agrees
+    if axis == 1:
+        expr2, got2 = run_spec(G, s, [x], split_rows=2)
+        assert expr2.info()["kernel_class"] == "row"
+        G.h.compare("expsum_row", got2[1], want[1], 1e-5, 1e-6)

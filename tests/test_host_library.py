@@ -222,6 +222,39 @@ def test_index_width_selection():
     assert e2.info()["index_bits"] == 64 and "long long idx_t" in e2.source()
 
 
+def test_long_or_few_rows_are_split_over_workgroups():
+    # softmax cross-entropy: one workgroup per row while a row sits well in registers ...
+    def plan(rows, vocab, maker=wl.c3_softmax_xent, **opts):
+        w = wl.layout_only(maker, rows=rows, vocab=vocab)
+        return plan_workload(w, **opts)[0]
+    assert plan(1280, 10000).info()["kernel_class"] == "row"
+    assert plan(2048, 32768).info()["kernel_class"] == "row"
+    # ... otherwise the chain max -> sum of exp(x - max) becomes one reduction level whose
+    # (maximum, sum) pair is rescaled as the maximum grows, and rows are split over workgroups
+    for rows, vocab in ((1024, 65536), (640, 100000), (64, 1 << 20), (100, 20000)):
+        e = plan(rows, vocab)
+        info = e.info()
+        assert info["kernel_class"] == "multi" and info["grid_blocks"] == 2, (rows, vocab, info)
+        first = e.info(0)
+        assert first["kernel_class"] == "tile_reduce" and first["extent"] == (rows, vocab)
+        src = e.source(0)
+        assert "* w_ + 1.0f" in src and "ewf_fast::exp(-__builtin_fabsf(d_))" in src
+        assert len(re.findall(r"ewf_ld(?:_nt)?<float, EWF_VEC>", src)) == 1      # the logits are read once
+        assert e.info(1)["extent"] == (rows,)                            # the mean over the per-row losses
+    # the caller can insist either way
+    assert plan(640, 100000, split_rows=2).info()["kernel_class"] == "row"
+    assert plan(1280, 10000, split_rows=1).info()["kernel_class"] == "multi"
+    # backward: the statistics in one pass, the gradient in a second
+    e = plan(512, 131072, maker=wl.c3_softmax_xent_backward)
+    assert e.info()["kernel_class"] == "multi" and [e.info(k)["kernel_class"] for k in range(2)] == ["tile_reduce", "tile"]
+    # plain row reductions never needed the row class
+    s = GraphSpec(2)
+    s.output(s.reduce("sum", s.input("f32", (False, False)), (1,)), "f32")
+    e = ewf.Expression(s, split_rows=1)
+    e.plan([ref(BASE, (1000, 4096))], [ref(BASE + (1 << 30), (1000,))])
+    assert e.info()["kernel_class"] == "tile_reduce"
+
+
 # ------------------------------------------------------------------ shape / alias / argument errors
 
 def _add2():
@@ -496,13 +529,14 @@ def test_structures_beyond_one_kernel_are_planned_in_stages():
     outs = [ref(BASE + 8192 + 512 * k, sh) for k, sh in enumerate(expr.output_shapes(ins))]
     expr.plan(ins, outs)
     assert expr.info()["kernel_class"] == "multi"
-    # options that force one kernel per stage cannot help a stage that does not exist: product gradients stay an error
+    # the gradient of a product over a whole vector: count of zeros and product of the others, then the element-wise part
     s = GraphSpec(1)
     xx = s.input("f32", (False,))
-    s.grad([s.reduce("prod", xx, (0,), keep=True)], [s.const(1.0)], [xx])
-    with pytest.raises(ewf.EwfError) as e:
-        ewf.Expression(s)
-    assert e.value.status == ewf.EUNSUPPORTED
+    (gx,) = s.grad([s.reduce("prod", xx, (0,), keep=True)], [s.const(1.0)], [xx])
+    s.output(gx, "f32")
+    expr = ewf.Expression(s)
+    expr.plan([ref(BASE, (1 << 20,))], [ref(BASE + (1 << 30), (1 << 20,))])
+    assert expr.info()["kernel_class"] == "multi" and expr.info()["grid_blocks"] == 2
 
 
 def test_run_argument_checks_without_device():
