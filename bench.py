@@ -274,15 +274,18 @@ def main():
             del case
             torch.cuda.empty_cache()
         out["per_config"] = per_config
-        # the same C1 / C2 kernels on 64 times the rows: supplementary bandwidth points, not
-        # among the five workloads (whose C1 / C2 sizes are launch-bound)
+        # the same C1 / C2 kernels on 64 times the rows, and the C3 expression on rows of 131072
+        # logits (rows split over workgroups): supplementary bandwidth points, not among the five
+        # workloads (whose C1 / C2 sizes are launch-bound)
         scaled = {}
-        for name, make in (("c1_x64", lambda: wl.c1_affine_tanh(rows=65536)), ("c2_x64", lambda: wl.c2_lstm_cell(batch=4096))):
+        for name, make in (("c1_x64", lambda: wl.c1_affine_tanh(rows=65536)), ("c2_x64", lambda: wl.c2_lstm_cell(batch=4096)),
+                           ("c3_512x131072", lambda: wl.c3_softmax_xent(rows=512, vocab=131072))):
             wk = make()
             nsets = max(1, int(600e6 // wk.algorithmic_bytes) + 1)
             case = Case(wk, nsets=nsets)
             us_step = 1e3 * min(case.wall(100, 10), case.wall(100, 0)) / 100
             scaled[name] = {"elements": wk.elements, "algorithmic_bytes": wk.algorithmic_bytes, "buffer_sets": nsets,
+                            "kernel_class": case.info["kernel_class"],
                             "us_per_step": round(us_step, 2),
                             "gbps": round(wk.algorithmic_bytes / (us_step * 1e-6) / 1e9, 1),
                             "pct_of_peak": round(100 * wk.algorithmic_bytes / (us_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 1)}
