@@ -1812,7 +1812,8 @@ ewf_status Gen::gen_col()
 
     // ---- second kernel.  Many slots per column: the partials of a column are contiguous and a
     // workgroup's lanes walk them.  Few: one thread per column folds its slots in slot order.
-    if (fin_lanes) emit_finish_lanes(level, group_out_ops, "p.nslots", fin_block);
+    if (fin_lanes) emit_finish_lanes(level, group_out_ops, "p.nslots", fin_block,
+                                     (int)std::min<int64_t>(8, std::max<int64_t>(1, ceil_div(nslots, fin_block))));
     else {
     o << "\nextern \"C\" __global__ void __launch_bounds__(256) ewf_finish(const Params p)\n{\n";
     o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";

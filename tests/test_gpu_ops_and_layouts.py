@@ -786,3 +786,49 @@ def test_split_softmax_at_small_sizes_and_special_values(storage, axis, oracle, 
         expr2, got2 = run_spec(G, s, [x], split_rows=2)
         assert expr2.info()["kernel_class"] == "row"
         G.h.compare("expsum_row", got2[1], want[1], 1e-5, 1e-6)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_softmax_chains(seed, oracle, G):
+    """max -> sum of exp(. - max) chains along a random axis of random shapes, with one workgroup
+    per row, split over workgroups, and whatever the library picks."""
+    rng = np.random.default_rng(9000 + seed)
+    ndim = int(rng.integers(2, 4))
+    shape = [int(rng.choice([1, 3, 7, 33, 130, 257])) for _ in range(ndim)]
+    axis = int(rng.integers(0, ndim))
+    shape[axis] = int(rng.choice([5, 64, 1000, 4099]))
+    storage = "f16" if seed % 4 == 3 else "f32"
+    dt = np.float16 if storage == "f16" else np.float32
+    x = (rng.standard_normal(shape) * 3).astype(dt)
+    bshape = [1 if d == axis or rng.integers(0, 2) else e for d, e in enumerate(shape)]
+    b = rng.standard_normal(bshape).astype(np.float32)
+    s = GraphSpec(ndim)
+    xi = s.input(storage, tuple(False for _ in shape))
+    bi = s.input("f32", tuple(e == 1 and shape[d] > 1 for d, e in enumerate(bshape)))
+    pre = int(rng.integers(0, 3))
+    f = xi if pre == 0 else s.add(s.mul(xi, s.const(0.5)), bi) if pre == 1 else s.mul(s.apply("tanh", xi), s.const(4.0))
+    keep = bool(rng.integers(0, 2))
+    m = s.reduce("max", f, (axis,), keep=True)
+    ex = s.apply("exp", s.sub(f, m))
+    S = s.reduce("sum", ex, (axis,), keep=True)
+    names = []
+    if rng.integers(0, 2) or True:
+        s.output(s.add(m, s.apply("log", S)), "f32"); names.append("lse")
+    if rng.integers(0, 2):
+        # of the input itself: a computed value would let rounding decide the index
+        s.output(s.reduce("argmax", xi, (axis,), keep=keep), "i32"); names.append("argmax")
+    if rng.integers(0, 2):
+        s.output(s.div(ex, S), storage); names.append("p")
+    if rng.integers(0, 2):
+        s.output(s.div(s.reduce("sum", s.mul(ex, f), (axis,), keep=keep), s.reduce("sum", ex, (axis,), keep=keep)), "f32"); names.append("mean_f")
+    mode = seed % 3
+    print(f"[case] chain seed={seed} shape={shape} axis={axis} {storage} pre={pre} outputs={names} split_rows={mode}", flush=True)
+    expr, got = run_spec(G, s, [x, b], split_rows=mode)
+    want = oracle.evaluate(s, [x, b], nthreads=4)
+    for name, g_, w_ in zip(names, got, want):
+        if name == "argmax":
+            G.h.compare(name, g_, w_, 0, 0)
+        elif name == "p":
+            G.h.compare(name, g_, w_, *((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3)))
+        else:
+            G.h.compare(name, g_, w_, 1e-5, 2e-6)
