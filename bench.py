@@ -65,6 +65,35 @@ class Case:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3
 
+    def graph_replay_us(self, replays=20):
+        """One launch per buffer set captured into a HIP graph (everything planned, compiled and
+        loaded beforehand); microseconds per step inside the replays."""
+        import ctypes
+        import torch
+        side = torch.cuda.Stream()
+
+        def run_all(stream):
+            for c in self.calls:
+                c._stream = ctypes.c_void_p(stream)
+                c.launch()
+        run_all(self.stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                run_all(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.current_stream().wait_stream(side)
+        for c in self.calls:
+            c._stream = ctypes.c_void_p(self.stream or None)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / (replays * len(self.calls))
+
     def time(self, steps, warmup):
         """Per-launch durations in ms from HIP events recorded around every launch, on the
         stream the kernels are launched on."""
@@ -270,6 +299,9 @@ def main():
                 del warm
             if name == "c2":
                 res["graph_replay_us_per_step"] = round(lstm_graph_step_us(), 2)
+            if name in ("c1", "c3"):
+                # the same launches (one per buffer set) replayed from a captured HIP graph
+                res["graph_replay_us_per_step"] = round(case.graph_replay_us(), 2)
             per_config[name] = res
             del case
             torch.cuda.empty_cache()
