@@ -587,8 +587,6 @@ struct Gen {
                            const std::string &nparts_expr, int fin_block, int inflight = 1,
                            const std::vector<Gather> &gathers = std::vector<Gather>())
     {
-        std::vector<int> all_dims;
-        for (int d = 0; d < R; d++) all_dims.push_back(d);
         o << "\n// folds the partials of each reduction group in a fixed order\n";
         o << "extern \"C\" __global__ void __launch_bounds__(" << fin_block << ") ewf_finish(const Params p)\n{\n";
         o << "    const int lane = threadIdx.x;\n";
@@ -613,16 +611,29 @@ struct Gen {
         }
         o << "        tot = ewf_block_reduce<" << fin_block / 64 << ">(tot, Acc_combine(), sm_fin, lane);\n";
         o << "        if (lane != 0) continue;\n";
-        o << "        idx_t g_ = group;\n";
+        emit_group_epilogue(level, group_out_ops, gathers, "        ");
+        o << "    }\n}\n";
+    }
+
+    // What one thread does with the folded accumulator `tot` of reduction group `group`: the
+    // results of the reductions, the single-term sums it reads itself, the values computed from
+    // them, and the stores of the per-group outputs.
+    void emit_group_epilogue(const std::vector<int> &level, const std::vector<int> &group_out_ops,
+                             const std::vector<Gather> &gathers, const std::string &ind)
+    {
+        std::vector<int> all_dims;
+        for (int d = 0; d < R; d++) all_dims.push_back(d);
+        o << ind << "idx_t g_ = group;\n";
         for (int d = R - 1; d >= 0; d--) {
-            if (c.reduced[d]) { o << "        const idx_t o" << d << " = 0;\n"; continue; }
+            if (c.reduced[d]) { o << ind << "const idx_t o" << d << " = 0;\n"; continue; }
             bool last_kept = true;
             for (int d2 = d - 1; d2 >= 0; d2--) if (!c.reduced[d2]) last_kept = false;
-            if (!last_kept) o << "        const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
-            else o << "        const idx_t o" << d << " = g_;\n";
+            if (!last_kept) o << ind << "const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
+            else o << ind << "const idx_t o" << d << " = g_;\n";
         }
-        for (int d = 0; d < R; d++) o << "        (void)o" << d << ";\n";
-        emit_results("tot", level, "        ");
+        for (int d = 0; d < R; d++) o << ind << "(void)o" << d << ";\n";
+        o << ind << "(void)g_;\n";
+        emit_results("tot", level, ind);
         std::vector<int> gt;
         for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
         std::vector<char> gneed = needed(gt);
@@ -633,35 +644,34 @@ struct Gen {
         auto base_once = [&](int k) {
             if (based[k]) return;
             based[k] = 1;
-            emit_base(k, all_dims, "        ");
+            emit_base(k, all_dims, ind);
         };
         if (!gathers.empty()) {
             std::vector<int> it;
             for (const Gather &ga : gathers) it.push_back(ga.index_value);
             std::vector<char> ineed = needed(it);
             for (int k : inputs_of(ineed)) base_once(k);
-            emit_values(ineed, gx, "        ");
+            emit_values(ineed, gx, ind);
             for (size_t n = 0; n < ineed.size(); n++) if (ineed[n]) gneed[n] = 0;
             for (const Gather &ga : gathers) {
                 base_once(ga.input);
                 const std::string nm = opname(ga.input);
-                o << "        float r" << ga.node << ";\n        {\n";
-                o << "            const int t_ = v" << ga.index_value << ";\n";
-                o << "            const bool in_ = t_ >= 0 && t_ < p.ext[" << ga.cdim << "];\n";
-                o << "            const float x_ = ewf_in(q_" << nm << "[(idx_t)(in_ ? t_ : 0) * p.st_" << nm << "[" << ga.cdim << "]]);\n";
-                o << "            r" << ga.node << " = in_ ? x_ + 0.0f : 0.0f;\n        }\n";
+                o << ind << "float r" << ga.node << ";\n" << ind << "{\n";
+                o << ind << "    const int t_ = v" << ga.index_value << ";\n";
+                o << ind << "    const bool in_ = t_ >= 0 && t_ < p.ext[" << ga.cdim << "];\n";
+                o << ind << "    const float x_ = ewf_in(q_" << nm << "[(idx_t)(in_ ? t_ : 0) * p.st_" << nm << "[" << ga.cdim << "]]);\n";
+                o << ind << "    r" << ga.node << " = in_ ? x_ + 0.0f : 0.0f;\n" << ind << "}\n";
             }
         }
         for (int k : inputs_of(gneed)) base_once(k);
-        emit_values(gneed, gx, "        ");
+        emit_values(gneed, gx, ind);
         for (int k : group_out_ops) {
             const Operand &op = c.ops[k];
             int v = g.outputs[op.index].value;
             const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
             base_once(k);
-            o << "        q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
+            o << ind << "q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
         }
-        o << "    }\n}\n";
     }
 
     ewf_status gen_tile(bool with_reduce);
@@ -935,7 +945,12 @@ ewf_status Gen::gen_tile(bool with_reduce)
     o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) " << occupancy_attr() << "ewf_kernel(const Params p)\n{\n";
     o << "    const int tid = threadIdx.x;\n";
     std::string ind = "        ";
-    if (with_reduce) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
+    // When every reduction group is a single tile the workgroup holds the whole group: it folds
+    // its wavefronts through LDS and writes the results itself -- one launch, no workspace.
+    bool one_tile = with_reduce;
+    for (int d = 0; d < R; d++) if (c.reduced[d] && ntile[d] != 1) one_tile = false;
+    if (with_reduce && !one_tile) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
+    if (one_tile) o << "    __shared__ Acc sm_one[EWF_NWAVES];\n";
     for (int k : staged)
         o << "    __shared__ __attribute__((aligned(16))) " << ctype(c.ops[k].storage) << " lds_" << opname(k) << "[" << lds_elems << "];\n";
     // tiles are numbered in canonical (memory) order so that the workgroups resident at any
@@ -1199,12 +1214,21 @@ ewf_status Gen::gen_tile(bool with_reduce)
             if (c.reduced[d]) o << ind << "slot = slot * p.ntile[" << d << "] + ti" << d << ";\n";
             else o << ind << "group = group * p.ext[" << d << "] + o" << d << ";\n";
         }
-        o << ind << "acc = ewf_wave_reduce(acc, Acc_combine());\n";
-        o << ind << "if ((tid & 63) == 0) partials[((size_t)group * (size_t)p.nslots + (size_t)slot) * EWF_NWAVES + (tid >> 6)] = acc;\n";
+        if (one_tile) {
+            o << ind << "(void)slot;\n";
+            o << ind << "acc = ewf_block_reduce<EWF_NWAVES>(acc, Acc_combine(), sm_one, tid);\n";
+            o << ind << "if (tid == 0) {\n";
+            o << ind << "    const Acc tot = acc;\n";
+            emit_group_epilogue(level, group_out_ops, gathers, ind + "    ");
+            o << ind << "}\n";
+        } else {
+            o << ind << "acc = ewf_wave_reduce(acc, Acc_combine());\n";
+            o << ind << "if ((tid & 63) == 0) partials[((size_t)group * (size_t)p.nslots + (size_t)slot) * EWF_NWAVES + (tid >> 6)] = acc;\n";
+        }
     }
     o << "    }\n}\n";
 
-    if (with_reduce) {
+    if (with_reduce && !one_tile) {
         // one workgroup per group: a wavefront when a group has few partials, four otherwise
         int64_t nparts_host = (int64_t)(block / 64);
         for (int d = 0; d < R; d++) if (c.reduced[d]) nparts_host *= ntile[d];
@@ -1226,7 +1250,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     for (int d = 0; d < R; d++) { if (c.reduced[d]) nslots *= ntile[d]; else ngroups *= c.extent[d]; }
     p.workspace_bytes = 0;
     p.finish_grid = 0;
-    if (with_reduce) {
+    if (with_reduce && !one_tile) {
         if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31)) return fail("too many reduction groups");
         p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(block / 64) * acc_bytes(level);
         p.finish_grid = std::min<int64_t>(ngroups, (int64_t)1 << 20);
