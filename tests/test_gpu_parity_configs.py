@@ -71,3 +71,36 @@ def test_full_size_parity(case, oracle, H):
     del w, expr
     gc.collect()
     torch.cuda.empty_cache()
+
+
+# Tuning options change how a kernel is generated and launched, never what it computes: every
+# workload under every option still has to match the oracle.
+OPTION_SETS = [
+    {"force_scalar": 1}, {"force_index64": 1}, {"no_lds_staging": 1}, {"no_prefetch": 1}, {"no_prefetch": 2},
+    {"xcd_remap": 1}, {"streaming": 1}, {"streaming": 2}, {"unroll": 1}, {"unroll": 4}, {"block_threads": 64},
+    {"block_threads": 1024}, {"tile_elems": 1024}, {"waves_per_simd": 2}, {"max_blocks": 3}, {"no_rewrite": 1},
+    {"split_rows": 1}, {"split_rows": 2},
+]
+OPTION_CASES = ["c1_ragged", "c2_ragged", "c3_ragged", "c4_ragged", "c4_small", "c5a_small", "c5b_ragged_c", "c2b_ragged",
+                "c3b_ragged", "c4b_ragged"]
+
+
+@pytest.mark.parametrize("case", OPTION_CASES)
+def test_options_do_not_change_results(case, oracle, H):
+    from paper_1605_02688_amd import ewf
+    w = CASES[case]()
+    want = oracle.evaluate(w.oracle_spec or w.spec, wl.host_inputs(w), w.scalars, nthreads=8)
+    ran = 0
+    for opts in OPTION_SETS:
+        print(f"[case] {case} {opts}", flush=True)
+        try:
+            expr, got = H.run_gpu(w, **opts)
+        except ewf.EwfError as e:
+            # an option that does not fit the workload is refused cleanly, never run wrongly
+            assert e.status in (ewf.EUNSUPPORTED, ewf.EINVAL), (opts, e)
+            print(f"[refused] {opts}: {e.message[:100]}", flush=True)
+            continue
+        for name, g, o, (rtol, atol) in zip(w.out_names, got, want, w.tol):
+            H.compare(f"{w.name}.{name} {opts}", g, o, rtol, atol)
+        ran += 1
+    assert ran >= len(OPTION_SETS) - 3
