@@ -550,3 +550,39 @@ def test_run_argument_checks_without_device():
     w = wl.layout_only(wl.c4_bias_relu_chansum, n=2)
     e4, ws, _ = plan_workload(w)
     assert ws > 0
+
+
+def test_distinct_executables_plan_concurrently():
+    # the library promises thread safety across distinct executables: the run-time compiler and
+    # the code caches are shared, error text is per thread
+    import threading
+    ops = ["tanh", "exp", "sigmoid", "sqrt", "abs", "neg", "log1p", "sqr"]
+    results, errors = {}, []
+
+    def work(i):
+        try:
+            s = GraphSpec(2)
+            x = s.input("f32", (False, False)); b = s.input("f32", (True, False))
+            s.output(s.add(s.apply(ops[i % len(ops)], x), b), "f32")
+            s.output(s.reduce("sum", x, (1,)), "f32")
+            e = ewf.Expression(s)
+            ws = e.plan([ref(BASE, (1000 + i % 2, 64)), ref(BASE + (1 << 30), (1, 64))],
+                        [ref(BASE + (2 << 30), (1000 + i % 2, 64)), ref(BASE + (3 << 30), (1000 + i % 2,))])
+            results[i] = (e.info()["kernel_class"], ws, e.source())
+            if i % 4 == 0:                      # and an error on this thread only
+                with pytest.raises(ewf.EwfError) as err:
+                    e.plan([ref(BASE, (10, 64)), ref(BASE + (1 << 30), (1, 63))], [ref(BASE + (2 << 30), (10, 64)), ref(BASE + (3 << 30), (10,))])
+                assert err.value.status == ewf.ESHAPE
+        except Exception as ex:                 # noqa: BLE001 - reported below
+            errors.append((i, repr(ex)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(16)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert len(results) == 16
+    for i in range(16):
+        assert results[i][0] == "row" and (ops[i % len(ops)] in results[i][2] or ops[i % len(ops)] in ("neg", "abs", "sqr", "sqrt"))
+        assert results[i][2] == results[(i + 8) % 16][2] or i % 2 != (i + 8) % 2     # same description and layout: same source
