@@ -1,0 +1,280 @@
+#include "ewf_gen.h"
+
+namespace ewf {
+
+// =========================================================================================
+// Col: reductions whose reduced axes are not the fastest-varying ones in memory
+//
+// The lanes of a wavefront lie along the innermost (kept) dimension, so loads stay wide and
+// coalesced and every lane owns its own columns: no cross-lane step at all.  The rows of the
+// innermost reduced dimension are spread over the wavefronts of the workgroup (and over
+// several workgroups, "slots", when there are few columns); the per-wavefront results meet in
+// LDS in a fixed order, one partial per column and slot goes to the workspace, and a second
+// kernel folds the slots of each column in slot order.
+
+ewf_status Gen::gen_col()
+{
+    const int in_d = R - 1;
+    int dR = -1;                                       // innermost reduced dimension
+    for (int d = R - 1; d >= 0; d--) if (c.reduced[d]) { dR = d; break; }
+    if (dR < 0 || c.reduced[in_d]) return fail("column class needs a kept innermost dimension");
+    const int nin = g.ninputs;
+    int block = e.opts.block_threads > 0 ? e.opts.block_threads : 256;
+    if (block % 64 || block > 1024) return fail("block_threads must be a multiple of 64, at most 1024");
+    p.block = block;
+
+    // ---- outputs by role
+    std::vector<int> ew_out_ops, group_out_ops;
+    for (size_t k = nin; k < c.ops.size(); k++) {
+        const int vn = g.outputs[c.ops[k].index].value;
+        const Node &v = g.nodes[vn];
+        bool group = (v.bcast & red.axes) == red.axes;
+        if (red.edepth[vn] >= 1 && !group) return fail("an output depends on a reduction and varies along the reduced axes");
+        (group ? group_out_ops : ew_out_ops).push_back((int)k);
+    }
+    const std::vector<int> &level = red.level_nodes;
+
+    // ---- thread layout: TX lanes along the columns, TY groups of lanes along the rows
+    const int64_t colvecs = c.extent[in_d] / VEC;
+    int TX = 64;
+    if (colvecs < 64) { TX = 1; while (TX < colvecs) TX *= 2; }
+    const int TY = block / TX;
+    const int64_t TK = std::min<int64_t>(c.extent[in_d], (int64_t)TX * VEC);   // columns per tile
+    // rows in flight per thread: four for streaming expressions, fewer when the expression is
+    // heavy in transcendental operations (registers) or the problem is small (spread it out)
+    int heavy = 0;
+    for (size_t n = 0; n < g.nodes.size(); n++) {
+        if (!live[n] || g.nodes[n].kind != NodeKind::Apply) continue;
+        switch (g.nodes[n].op) {
+        case EWF_EXP: case EWF_LOG: case EWF_LOG1P: case EWF_TANH: case EWF_SIGMOID: case EWF_EXPM1: heavy += 1; break;
+        case EWF_POW: case EWF_DIV: heavy += 2; break;
+        default: break;
+        }
+    }
+    const bool small = c.total / VEC < (int64_t)256 * 512;
+    const int U = e.opts.unroll > 0 ? e.opts.unroll : small ? 1 : heavy >= 4 ? 2 : 4;
+    int64_t T[kMaxDims];
+    for (int d = 0; d < kMaxDims; d++) T[d] = 1;
+    T[in_d] = TK;
+    {
+        // rows per tile: enough tiles to fill the chip, but whole trips of the workgroup
+        int64_t other = ceil_div(c.extent[in_d], TK);
+        for (int d = 0; d < R - 1; d++) if (d != dR) other *= c.extent[d];
+        const int64_t want = (int64_t)16 * device_cu_count();
+        int64_t slices = std::max<int64_t>(1, std::min(ceil_div(want, other), ceil_div(c.extent[dR], (int64_t)TY * U)));
+        int64_t tr = ceil_div(c.extent[dR], slices);
+        if (e.opts.tile_elems > 0) tr = std::max<int64_t>(1, e.opts.tile_elems / TK);
+        T[dR] = std::min(c.extent[dR], tr);
+    }
+    const int64_t TR = T[dR];
+    int64_t ntile[kMaxDims], ntiles = 1;
+    for (int d = 0; d < R; d++) { ntile[d] = ceil_div(c.extent[d], T[d]); ntiles *= ntile[d]; p.tile[d] = T[d]; }
+    if (ntiles >= ((int64_t)1 << 31) - 1 || TR >= ((int64_t)1 << 30)) return fail("tile count out of range");
+    int64_t ngroups = 1, nslots = 1;
+    for (int d = 0; d < R; d++) { if (c.reduced[d]) nslots *= ntile[d]; else ngroups *= c.extent[d]; }
+    if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31) || ngroups * nslots >= ((int64_t)1 << 40))
+        return fail("too many reduction groups");
+
+    const bool fin_lanes = nslots > 16;
+    const int fin_block = nslots > 256 ? 256 : 64;
+
+    // ---- what to evaluate per element
+    std::vector<int> targets;
+    for (int k : ew_out_ops) targets.push_back(g.outputs[c.ops[k].index].value);
+    for (int n : level) targets.push_back(g.nodes[n].args[0]);
+    std::vector<char> need = needed(targets);
+    std::vector<int> load_ops = inputs_of(need);
+
+    emit_header(block);
+    o << "#define EWF_TX " << TX << "\n#define EWF_TY " << TY << "\n";
+    build_layout();
+    emit_acc_struct("Acc", level);
+    std::vector<int> all_dims;
+    for (int d = 0; d < R; d++) all_dims.push_back(d);
+
+    auto off_expr = [&](int k) {
+        // offset of (row r_, column cc_) from the tile's origin
+        const Operand &op = c.ops[k];
+        const std::string nm = opname(k);
+        std::string s;
+        if (op.stride[dR] != 0) s = "(ioff_t)r_ * (ioff_t)p.st_" + nm + "[" + std::to_string(dR) + "]";
+        if (op.stride[in_d] != 0) {
+            if (!s.empty()) s += " + ";
+            s += op.stride[in_d] == 1 ? std::string("(ioff_t)cc_") : "(ioff_t)cc_ * (ioff_t)p.st_" + nm + "[" + std::to_string(in_d) + "]";
+        }
+        return s.empty() ? std::string("(ioff_t)0") : s;
+    };
+
+    o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) " << occupancy_attr() << "ewf_kernel(const Params p)\n{\n";
+    o << "    const int tid = threadIdx.x;\n";
+    o << "    const int tx = tid & (EWF_TX - 1), ty = tid / EWF_TX;\n";
+    o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
+    if (TY > 1) o << "    __shared__ Acc sm_col[(EWF_TY - 1) * EWF_TX * EWF_VEC];\n";
+    o << "    for (idx_t tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {\n";
+    o << "        idx_t t_ = tile;\n";
+    for (int d = R - 1; d >= 0; d--) {
+        if (d > 0) o << "        const idx_t ti" << d << " = ewf_uniform(t_ % p.ntile[" << d << "]); t_ /= p.ntile[" << d << "];\n";
+        else o << "        const idx_t ti0 = ewf_uniform(t_);\n";
+        o << "        const idx_t o" << d << " = ti" << d << " * " << T[d] << ";\n";
+    }
+    std::string ind = "        ";
+    for (int k : load_ops) emit_base(k, all_dims, ind);
+    for (int k : ew_out_ops) emit_base(k, all_dims, ind);
+    o << ind << "const int cc_ = tx * EWF_VEC;\n";
+    o << ind << "const bool colok_ = cc_ < " << TK << " && o" << in_d << " + cc_ < p.ext[" << in_d << "];\n";
+    o << ind << "const int rows_ = (int)((p.ext[" << dR << "] - o" << dR << ") < " << TR << " ? (p.ext[" << dR << "] - o" << dR << ") : " << TR << ");\n";
+    o << ind << "Acc acc[EWF_VEC];\n";
+    o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_identity();\n";
+    o << ind << "for (int r0_ = ty; r0_ < rows_; r0_ += EWF_TY * " << U << ") {\n";
+    // loads of U rows, then their arithmetic
+    for (int k : load_ops) {
+        const Operand &op = c.ops[k];
+        if (op.stride[in_d] == 0) o << ind << "    " << ctype(op.storage) << " x_" << opname(k) << "[" << U << "];\n";
+        else o << ind << "    ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
+    }
+    o << ind << "    #pragma unroll\n" << ind << "    for (int u = 0; u < " << U << "; ++u) {\n";
+    o << ind << "        const int r_ = r0_ + u * EWF_TY;\n";
+    o << ind << "        if (!colok_ || r_ >= rows_) continue;\n";
+    for (int k : load_ops) {
+        const Operand &op = c.ops[k];
+        const std::string nm = opname(k);
+        if (op.stride[in_d] == 0)
+            o << ind << "        x_" << nm << "[u] = *ewf_at(q_" << nm << ", " << off_expr(k) << ");\n";
+        else if (op.access == Access::Vector)
+            o << ind << "        x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "));\n";
+        else {
+            o << ind << "        { const ioff_t b_ = " << off_expr(k) << ";\n";
+            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) x_" << nm << "[u].e[e_] = *ewf_at(q_" << nm
+              << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
+        }
+    }
+    o << ind << "    }\n";
+    o << ind << "    #pragma unroll\n" << ind << "    for (int u = 0; u < " << U << "; ++u) {\n";
+    o << ind << "        const int r_ = r0_ + u * EWF_TY;\n";
+    o << ind << "        if (!colok_ || r_ >= rows_) continue;\n";
+    for (int k : ew_out_ops) o << ind << "        ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
+    o << ind << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+    EmitCtx cx;
+    cx.input = [&](int k) {
+        const Operand &op = c.ops[k];
+        if (op.stride[in_d] == 0) return "ewf_in(x_" + opname(k) + "[u])";
+        if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(x_" + opname(k) + "[u], e_)";
+        return "ewf_in(x_" + opname(k) + "[u].e[e_])";
+    };
+    cx.coord = [&](int d) {
+        std::string s = "o" + std::to_string(d);
+        if (d == dR) s += " + r_";
+        if (d == in_d) s += " + cc_ + e_";
+        return s;
+    };
+    emit_values(need, cx, ind + "            ");
+    emit_accumulate("acc[e_]", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "            ");
+    for (int k : ew_out_ops) {
+        const Operand &op = c.ops[k];
+        const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
+        o << ind << "            y_" << opname(k) << ".e[e_] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
+    }
+    o << ind << "        }\n";
+    for (int k : ew_out_ops) {
+        const Operand &op = c.ops[k];
+        const std::string nm = opname(k);
+        if (op.access == Access::Vector)
+            o << ind << "        " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "), y_" << nm << ");\n";
+        else {
+            o << ind << "        { const ioff_t b_ = " << off_expr(k) << ";\n";
+            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) *ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
+              << "[" << in_d << "]) = y_" << nm << ".e[e_]; }\n";
+        }
+    }
+    o << ind << "    }\n";
+    o << ind << "}\n";
+    // the row groups of the workgroup meet in LDS; group 0 folds them in order
+    if (TY > 1) {
+        o << ind << "if (ty > 0) { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) sm_col[((ty - 1) * EWF_TX + tx) * EWF_VEC + e_] = acc[e_]; }\n";
+        o << ind << "__syncthreads();\n";
+        o << ind << "if (ty == 0) {\n";
+        o << ind << "    for (int w_ = 0; w_ < EWF_TY - 1; ++w_)\n";
+        o << ind << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], sm_col[(w_ * EWF_TX + tx) * EWF_VEC + e_]);\n";
+        o << ind << "}\n";
+    }
+    o << ind << "if (ty == 0 && colok_) {\n";
+    o << ind << "    size_t group = 0, slot = 0;\n";
+    for (int d = 0; d < R; d++) {
+        if (c.reduced[d]) o << ind << "    slot = slot * (size_t)p.ntile[" << d << "] + (size_t)ti" << d << ";\n";
+        else if (d == in_d) o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + cc_);\n";
+        else o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)o" << d << ";\n";
+    }
+    if (fin_lanes) o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[(group + e_) * (size_t)p.nslots + slot] = acc[e_];\n";
+    else o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[slot * (size_t)p.nrows + group + e_] = acc[e_];\n";
+    o << ind << "}\n";
+    if (TY > 1) o << ind << "__syncthreads();\n";
+    o << "    }\n}\n";
+
+    // ---- second kernel.  Many slots per column: the partials of a column are contiguous and a
+    // workgroup's lanes walk them.  Few: one thread per column folds its slots in slot order.
+    if (fin_lanes) emit_finish_lanes(level, group_out_ops, "p.nslots", fin_block,
+                                     (int)std::min<int64_t>(8, std::max<int64_t>(1, ceil_div(nslots, fin_block))));
+    else {
+    o << "\nextern \"C\" __global__ void __launch_bounds__(256) ewf_finish(const Params p)\n{\n";
+    o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
+    o << "    for (idx_t group = blockIdx.x * 256 + threadIdx.x; group < p.nrows; group += gridDim.x * 256) {\n";
+    o << "        Acc tot = partials[group];\n";
+    o << "        for (idx_t s_ = 1; s_ < p.nslots; ++s_) tot = Acc_combine()(tot, partials[(size_t)s_ * (size_t)p.nrows + (size_t)group]);\n";
+    o << "        idx_t g_ = group;\n";
+    for (int d = R - 1; d >= 0; d--) {
+        if (c.reduced[d]) { o << "        const idx_t o" << d << " = 0;\n"; continue; }
+        bool last_kept = true;
+        for (int d2 = d - 1; d2 >= 0; d2--) if (!c.reduced[d2]) last_kept = false;
+        if (!last_kept) o << "        const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
+        else o << "        const idx_t o" << d << " = g_;\n";
+    }
+    for (int d = 0; d < R; d++) o << "        (void)o" << d << ";\n";
+    emit_results("tot", level, "        ");
+    {
+        std::vector<int> gt;
+        for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
+        std::vector<char> gneed = needed(gt);
+        for (int k : inputs_of(gneed)) emit_base(k, all_dims, "        ");
+        EmitCtx gx;
+        gx.input = [&](int k) { return "ewf_in(q_" + opname(k) + "[0])"; };
+        gx.coord = [&](int d) { return "o" + std::to_string(d); };
+        emit_values(gneed, gx, "        ");
+        for (int k : group_out_ops) {
+            const Operand &op = c.ops[k];
+            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
+            emit_base(k, all_dims, "        ");
+            o << "        q_" << opname(k) << "[0] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
+        }
+    }
+    o << "    }\n}\n";
+    }
+
+    // ---- launch geometry and argument block
+    int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)1 << 22;
+    p.grid = std::max<int64_t>(1, std::min(ntiles, cap));
+    p.lds_bytes = TY > 1 ? (int)((TY - 1) * TX * VEC * acc_bytes(level)) : 0;
+    if (p.lds_bytes > 60 * 1024) return fail("too many reductions for one column kernel (LDS)");
+    p.staged = 0;
+    p.workspace_bytes = (size_t)ngroups * (size_t)nslots * acc_bytes(level);
+    p.finish_grid = fin_lanes ? std::min<int64_t>(ngroups, (int64_t)1 << 20)
+                              : std::max<int64_t>(1, std::min<int64_t>(ceil_div(ngroups, 256), (int64_t)1 << 16));
+    p.finish_block = fin_lanes ? fin_block : 256;
+    p.args.assign(p.layout.size, 0);
+    auto put_idx = [&](const std::string &name, int i, int64_t v) {
+        int f = p.layout.find(name);
+        size_t off = p.layout.offsets[f];
+        if (c.idx64) memcpy(&p.args[off + 8 * (size_t)i], &v, 8);
+        else { int32_t w = (int32_t)v; memcpy(&p.args[off + 4 * (size_t)i], &w, 4); }
+    };
+    for (int d = 0; d < R; d++) { put_idx("ext", d, c.extent[d]); put_idx("ntile", d, ntile[d]); }
+    put_idx("ntiles", 0, ntiles);
+    put_idx("nrows", 0, ngroups);
+    put_idx("nslots", 0, nslots);
+    for (size_t k = 0; k < c.ops.size(); k++)
+        for (int d = 0; d < R; d++) put_idx("st_" + opname((int)k), d, c.ops[k].stride[d]);
+    p.source = o.str();
+    return EWF_OK;
+}
+
+
+}  // namespace ewf
