@@ -38,6 +38,20 @@ ewf_status Gen::gen_col()
     const int64_t colvecs = c.extent[in_d] / VEC;
     int TX = 64;
     if (colvecs < 64) { TX = 1; while (TX < colvecs) TX *= 2; }
+    const bool small = c.total / VEC < (int64_t)256 * 512;
+    // A small problem is bound by launches, not bandwidth: when one workgroup can take whole
+    // columns (a single reduced dimension of modest extent) the column strips are narrowed until
+    // there are enough workgroups, each folds its columns completely and writes the results
+    // itself -- one launch, no workspace.
+    int nreduced = 0;
+    for (int d = 0; d < R; d++) nreduced += c.reduced[d];
+    const bool whole_columns = small && nreduced == 1 && c.extent[dR] <= 1024 && e.opts.tile_elems <= 0;
+    if (whole_columns) {
+        int64_t other = 1;
+        for (int d = 0; d < R - 1; d++) if (d != dR) other *= c.extent[d];
+        const int min_tx = std::max(1, 16 / VEC);
+        while (TX > min_tx && ceil_div(c.extent[in_d], (int64_t)TX * VEC) * other < 64) TX /= 2;
+    }
     const int TY = block / TX;
     const int64_t TK = std::min<int64_t>(c.extent[in_d], (int64_t)TX * VEC);   // columns per tile
     // rows in flight per thread: four for streaming expressions, fewer when the expression is
@@ -51,7 +65,6 @@ ewf_status Gen::gen_col()
         default: break;
         }
     }
-    const bool small = c.total / VEC < (int64_t)256 * 512;
     const int U = e.opts.unroll > 0 ? e.opts.unroll : small ? 1 : heavy >= 4 ? 2 : 4;
     int64_t T[kMaxDims];
     for (int d = 0; d < kMaxDims; d++) T[d] = 1;
@@ -62,6 +75,7 @@ ewf_status Gen::gen_col()
         for (int d = 0; d < R - 1; d++) if (d != dR) other *= c.extent[d];
         const int64_t want = (int64_t)16 * device_cu_count();
         int64_t slices = std::max<int64_t>(1, std::min(ceil_div(want, other), ceil_div(c.extent[dR], (int64_t)TY * U)));
+        if (whole_columns) slices = 1;
         int64_t tr = ceil_div(c.extent[dR], slices);
         if (e.opts.tile_elems > 0) tr = std::max<int64_t>(1, e.opts.tile_elems / TK);
         T[dR] = std::min(c.extent[dR], tr);
@@ -75,6 +89,8 @@ ewf_status Gen::gen_col()
     if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31) || ngroups * nslots >= ((int64_t)1 << 40))
         return fail("too many reduction groups");
 
+    const bool one_tile = nslots == 1;
+    const int NW = block / 64;
     const bool fin_lanes = nslots > 16;
     const int fin_block = nslots > 256 ? 256 : 64;
 
@@ -108,8 +124,8 @@ ewf_status Gen::gen_col()
     o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) " << occupancy_attr() << "ewf_kernel(const Params p)\n{\n";
     o << "    const int tid = threadIdx.x;\n";
     o << "    const int tx = tid & (EWF_TX - 1), ty = tid / EWF_TX;\n";
-    o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
-    if (TY > 1) o << "    __shared__ Acc sm_col[(EWF_TY - 1) * EWF_TX * EWF_VEC];\n";
+    if (!one_tile) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
+    if (NW > 1) o << "    __shared__ Acc sm_col[(EWF_NWAVES - 1) * EWF_TX * EWF_VEC];\n";
     o << "    for (idx_t tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {\n";
     o << "        idx_t t_ = tile;\n";
     for (int d = R - 1; d >= 0; d--) {
@@ -188,31 +204,46 @@ ewf_status Gen::gen_col()
     }
     o << ind << "    }\n";
     o << ind << "}\n";
-    // the row groups of the workgroup meet in LDS; group 0 folds them in order
-    if (TY > 1) {
-        o << ind << "if (ty > 0) { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) sm_col[((ty - 1) * EWF_TX + tx) * EWF_VEC + e_] = acc[e_]; }\n";
+    // the row groups inside a wavefront (lanes that differ by a multiple of TX) fold with lane
+    // exchanges in a fixed butterfly; the wavefronts then meet in LDS and the first folds them
+    // in order
+    for (int m = TX; m < 64; m *= 2)
+        o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], ewf_lane_xor(acc[e_], " << m << "));\n";
+    if (NW > 1) {
+        o << ind << "if (tid >= 64 && (tid & 63) < EWF_TX) { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) sm_col[(((tid >> 6) - 1) * EWF_TX + tx) * EWF_VEC + e_] = acc[e_]; }\n";
         o << ind << "__syncthreads();\n";
-        o << ind << "if (ty == 0) {\n";
-        o << ind << "    for (int w_ = 0; w_ < EWF_TY - 1; ++w_)\n";
+        o << ind << "if (tid < EWF_TX) {\n";
+        o << ind << "    for (int w_ = 0; w_ < EWF_NWAVES - 1; ++w_)\n";
         o << ind << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], sm_col[(w_ * EWF_TX + tx) * EWF_VEC + e_]);\n";
         o << ind << "}\n";
     }
-    o << ind << "if (ty == 0 && colok_) {\n";
+    o << ind << "if (tid < EWF_TX && colok_) {\n";
     o << ind << "    size_t group = 0, slot = 0;\n";
     for (int d = 0; d < R; d++) {
         if (c.reduced[d]) o << ind << "    slot = slot * (size_t)p.ntile[" << d << "] + (size_t)ti" << d << ";\n";
         else if (d == in_d) o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + cc_);\n";
         else o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)o" << d << ";\n";
     }
-    if (fin_lanes) o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[(group + e_) * (size_t)p.nslots + slot] = acc[e_];\n";
+    if (one_tile) {
+        // every column is complete here: its results are written straight away
+        o << ind << "    (void)slot;\n";
+        o << ind << "    const size_t group0_ = group;\n";
+        o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+        o << ind << "        const Acc tot = acc[e_];\n";
+        o << ind << "        const idx_t group = (idx_t)(group0_ + e_);\n";
+        emit_group_epilogue(level, group_out_ops, std::vector<Gather>(), ind + "        ");
+        o << ind << "    }\n";
+    }
+    else if (fin_lanes) o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[(group + e_) * (size_t)p.nslots + slot] = acc[e_];\n";
     else o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[slot * (size_t)p.nrows + group + e_] = acc[e_];\n";
     o << ind << "}\n";
-    if (TY > 1) o << ind << "__syncthreads();\n";
+    if (NW > 1) o << ind << "__syncthreads();\n";
     o << "    }\n}\n";
 
     // ---- second kernel.  Many slots per column: the partials of a column are contiguous and a
     // workgroup's lanes walk them.  Few: one thread per column folds its slots in slot order.
-    if (fin_lanes) emit_finish_lanes(level, group_out_ops, "p.nslots", fin_block,
+    if (one_tile) { /* no second kernel */ }
+    else if (fin_lanes) emit_finish_lanes(level, group_out_ops, "p.nslots", fin_block,
                                      (int)std::min<int64_t>(8, std::max<int64_t>(1, ceil_div(nslots, fin_block))));
     else {
     o << "\nextern \"C\" __global__ void __launch_bounds__(256) ewf_finish(const Params p)\n{\n";
@@ -252,11 +283,11 @@ ewf_status Gen::gen_col()
     // ---- launch geometry and argument block
     int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)1 << 22;
     p.grid = std::max<int64_t>(1, std::min(ntiles, cap));
-    p.lds_bytes = TY > 1 ? (int)((TY - 1) * TX * VEC * acc_bytes(level)) : 0;
+    p.lds_bytes = NW > 1 ? (int)((NW - 1) * TX * VEC * acc_bytes(level)) : 0;
     if (p.lds_bytes > 60 * 1024) return fail("too many reductions for one column kernel (LDS)");
     p.staged = 0;
-    p.workspace_bytes = (size_t)ngroups * (size_t)nslots * acc_bytes(level);
-    p.finish_grid = fin_lanes ? std::min<int64_t>(ngroups, (int64_t)1 << 20)
+    p.workspace_bytes = one_tile ? 0 : (size_t)ngroups * (size_t)nslots * acc_bytes(level);
+    p.finish_grid = one_tile ? 0 : fin_lanes ? std::min<int64_t>(ngroups, (int64_t)1 << 20)
                               : std::max<int64_t>(1, std::min<int64_t>(ceil_div(ngroups, 256), (int64_t)1 << 16));
     p.finish_block = fin_lanes ? fin_block : 256;
     p.args.assign(p.layout.size, 0);
