@@ -202,10 +202,24 @@ def cpu_baseline(budget_s=15.0):
         orc.evaluate(w.spec, ins, nthreads=cores)
         passes += 1
     dt = (time.perf_counter() - t0) / passes
-    return {"value": w.algorithmic_bytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"same workload at batch {n} of 128 ([{n},64,112,112], {w.elements} elements), "
-                      f"{passes} passes, {dt:.2f} s wall each on {cores} threads",
-            "gelem_per_s": w.elements / dt / 1e9}
+    res = {"value": w.algorithmic_bytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+           "sample": f"same workload at batch {n} of 128 ([{n},64,112,112], {w.elements} elements), "
+                     f"{passes} passes, {dt:.2f} s wall each on {cores} threads",
+           "gelem_per_s": w.elements / dt / 1e9}
+    # the other workloads once each, for context (C5 on an eighth of its batch)
+    others = {}
+    for name, make, threads in (("c1", wl.c1_affine_tanh, (1, cores)), ("c2", wl.c2_lstm_cell, (1, cores)),
+                                ("c3", wl.c3_softmax_xent, (1, cores)),
+                                ("c5a_batch8", lambda: wl.c5_stress(n=8, reading="A"), (cores,))):
+        wk = make()
+        ins = wl.host_inputs(wk)
+        for nt in threads:
+            t0 = time.perf_counter()
+            orc.evaluate(wk.spec, ins, wk.scalars, nthreads=nt)
+            dt = time.perf_counter() - t0
+            others[f"{name}_{nt}t"] = {"ms": round(dt * 1e3, 2), "gbps": round(wk.algorithmic_bytes / dt / 1e9, 3)}
+    res["other_workloads"] = others
+    return res
 
 
 def main():
