@@ -128,6 +128,22 @@ def copy_ceiling(nbytes, steps=20):
     return 2 * nbytes * steps / (a.elapsed_time(b) * 1e-3) / 1e9
 
 
+def torch_elementwise_rate(nbytes, steps=20):
+    """PyTorch's own element-wise kernel (y = x + 1, float32) on tensors of `nbytes` each: what
+    another streaming kernel with the same read/write mix reaches on this chip."""
+    import torch
+    src = torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        torch.add(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+    return 2 * nbytes * steps / (time.perf_counter() - t0) / 1e9
+
+
 def launch_floor(steps=200):
     """Event-bracketed duration of a one-workgroup fill kernel: what the microsecond figures of
     the small workloads sit on."""
@@ -280,6 +296,8 @@ def main():
                      "kernel_min_us": round(st["min_us"], 2)},
     }
     out["copy_ceiling_gbps"] = round(copy_ceiling(w.algorithmic_bytes // 2 // 16 * 16), 1)
+    # context only: PyTorch's element-wise y = x + 1 on tensors of the same size (same read/write mix)
+    out["torch_elementwise_gbps"] = round(torch_elementwise_rate(w.algorithmic_bytes // 2 // 16 * 16), 1)
     fl = launch_floor()
     out["launch_floor_us"] = {"avg": round(fl["avg_us"], 2), "min": round(fl["min_us"], 2)}
     del head
