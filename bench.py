@@ -48,21 +48,29 @@ class Case:
         self.info = self.expr.info()
         self.calls = [self.expr.bind(ins, outs, w.scalars, self.ws, self.stream) for _b, ins, outs in self.sets]
         self.k = 0
+        self._sequences = {}
 
     def launch(self):
         self.calls[self.k % len(self.calls)].launch()
         self.k += 1
 
     def wall(self, steps, warmup):
-        """Wall-clock ms for `steps` back-to-back launches (synchronised on both sides)."""
+        """Wall-clock ms for `steps` back-to-back launches (synchronised on both sides).  The
+        steps are prepared calls (cycling through the buffer sets) issued by one
+        ewf_run_sequence call: the launch loop runs in the library, not in the interpreter."""
         import torch
+        from paper_1605_02688_amd import ewf
         for _ in range(warmup):
             self.launch()
+        seq = self._sequences.get(steps)
+        if seq is None:
+            seq = ewf.CallSequence([self.calls[(self.k + i) % len(self.calls)] for i in range(steps)])
+            self._sequences = {steps: seq}
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            self.launch()
+        seq.launch()
         torch.cuda.synchronize()
+        self.k += steps
         return (time.perf_counter() - t0) * 1e3
 
     def graph_replay_us(self, replays=20):

@@ -404,6 +404,28 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
 
 extern "C" {
 
+ewf_status ewf_run_call(const ewf_call *c)
+{
+    if (!c) { set_error("null argument"); return EWF_EINVAL; }
+    return ewf_run(c->exec, c->in, c->nin, c->scalars, c->nscalars, c->out, c->nout, c->workspace, c->workspace_bytes,
+                   c->hip_stream);
+}
+
+ewf_status ewf_run_sequence(const ewf_call *calls, int32_t ncalls, int32_t *failed)
+{
+    if (ncalls < 0 || (ncalls > 0 && !calls)) { set_error("null or negative argument"); return EWF_EINVAL; }
+    for (int32_t i = 0; i < ncalls; i++) {
+        const ewf_call &c = calls[i];
+        ewf_status st = ewf_run(c.exec, c.in, c.nin, c.scalars, c.nscalars, c.out, c.nout, c.workspace, c.workspace_bytes,
+                                c.hip_stream);
+        if (st != EWF_OK) {
+            if (failed) *failed = i;
+            return st;
+        }
+    }
+    return EWF_OK;
+}
+
 static void fill_plan_info(const Plan *p, ewf_plan_info *info);
 
 ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info)

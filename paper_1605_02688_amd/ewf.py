@@ -61,6 +61,13 @@ class ewf_tensor(ctypes.Structure):
                 ("strides", ctypes.POINTER(ctypes.c_int64))]
 
 
+class ewf_call(ctypes.Structure):
+    _fields_ = [("exec", ctypes.c_void_p), ("tin", ctypes.POINTER(ewf_tensor)), ("tout", ctypes.POINTER(ewf_tensor)),
+                ("scalars", ctypes.POINTER(ctypes.c_double)), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("hip_stream", ctypes.c_void_p),
+                ("nin", ctypes.c_int32), ("nout", ctypes.c_int32), ("nscalars", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
 class ewf_plan_info(ctypes.Structure):
     _fields_ = [("kernel_class", ctypes.c_int32), ("rank", ctypes.c_int32),
                 ("extent", ctypes.c_int64 * MAX_DIMS), ("reduced", ctypes.c_int32 * MAX_DIMS),
@@ -101,6 +108,8 @@ _sigs = {
     "ewf_workspace_init": (_i32, [_vp, ctypes.c_size_t, _vp]),
     "ewf_run": (_i32, [_vp, ctypes.POINTER(ewf_tensor), _i32, ctypes.POINTER(ctypes.c_double), _i32,
                        ctypes.POINTER(ewf_tensor), _i32, _vp, ctypes.c_size_t, _vp]),
+    "ewf_run_call": (_i32, [ctypes.POINTER(ewf_call)]),
+    "ewf_run_sequence": (_i32, [ctypes.POINTER(ewf_call), _i32, ctypes.POINTER(_i32)]),
     "ewf_last_error": (ctypes.c_char_p, []),
     "ewf_debug_graph_count": (_i32, [_vp]),
     "ewf_debug_graph_node": (_i32, [_vp, _i32, ctypes.POINTER(ewf_node_info)]),
@@ -451,13 +460,47 @@ class BoundCall:
         self._tin, self._k1 = _marshal(inputs)
         self._tout, self._k2 = _marshal(outputs)
         self._sc = (ctypes.c_double * max(1, len(scalars)))(*[float(s) for s in scalars])
-        self._n = (len(inputs), len(scalars), len(outputs))
-        self._ws = ctypes.c_void_p(workspace.data_ptr() if workspace is not None else None)
-        self._wsb = ctypes.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0)
-        self._stream = ctypes.c_void_p(stream or None)
+        c = ewf_call()
+        c.exec = expr.handle
+        c.tin = ctypes.cast(self._tin, ctypes.POINTER(ewf_tensor))
+        c.tout = ctypes.cast(self._tout, ctypes.POINTER(ewf_tensor))
+        c.scalars = ctypes.cast(self._sc, ctypes.POINTER(ctypes.c_double))
+        c.workspace = workspace.data_ptr() if workspace is not None else None
+        c.workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        c.hip_stream = stream or None
+        c.nin, c.nout, c.nscalars = len(inputs), len(outputs), len(scalars)
+        self._call = c
+        self._ref = ctypes.byref(c)
+        self._run = _lib.ewf_run_call
+
+    @property
+    def _stream(self):
+        return self._call.hip_stream
+
+    @_stream.setter
+    def _stream(self, value) -> None:
+        self._call.hip_stream = value.value if isinstance(value, ctypes.c_void_p) else (value or None)
 
     def launch(self) -> None:
-        st = _lib.ewf_run(self.expr.handle, self._tin, self._n[0], self._sc, self._n[1], self._tout, self._n[2],
-                          self._ws, self._wsb, self._stream)
+        st = self._run(self._ref)
         if st < 0:
             raise EwfError(st, last_error())
+
+
+class CallSequence:
+    """Prepared calls run in order by one ewf_run_sequence call (the loop runs in the library).
+    Keeps the bound calls, and with them their tensors, alive."""
+
+    def __init__(self, calls: Sequence[BoundCall], stream: Optional[int] = None):
+        self._calls = list(calls)
+        self._arr = (ewf_call * max(1, len(self._calls)))()
+        for i, c in enumerate(self._calls):
+            ctypes.memmove(ctypes.byref(self._arr[i]), ctypes.byref(c._call), ctypes.sizeof(ewf_call))
+            if stream is not None:
+                self._arr[i].hip_stream = stream or None
+        self._failed = _i32(-1)
+
+    def launch(self) -> None:
+        st = _lib.ewf_run_sequence(self._arr, len(self._calls), ctypes.byref(self._failed))
+        if st < 0:
+            raise EwfError(st, f"call {self._failed.value}: {last_error()}")

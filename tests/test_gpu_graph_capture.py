@@ -74,3 +74,22 @@ def test_lstm_steps_in_a_captured_graph(oracle):
         # eager work between replays
         scratch = torch.randn(1 << 16, device="cuda").sum().item()
         assert np.isfinite(scratch)
+
+    # the same steps as one prepared sequence: the loop over the steps runs inside the library
+    calls = []
+    for t in range(T):
+        ins, outs = step_tensors(t)
+        calls.append(expr.bind(ins, outs, (), None, torch.cuda.current_stream().cuda_stream))
+    seq = ewf.CallSequence(calls)
+    for _ in range(2):
+        cbuf[0].copy_(c_start)
+        hbuf.zero_()
+        seq.launch()
+        torch.cuda.synchronize()
+        assert torch.equal(hbuf, eager_h) and torch.equal(cbuf[T % 2], eager_c)
+    # and a single prepared call
+    cbuf[0].copy_(c_start)
+    hbuf.zero_()
+    calls[0].launch()
+    torch.cuda.synchronize()
+    assert torch.equal(hbuf[0], eager_h[0])

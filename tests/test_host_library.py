@@ -586,3 +586,25 @@ def test_distinct_executables_plan_concurrently():
     for i in range(16):
         assert results[i][0] == "row" and (ops[i % len(ops)] in results[i][2] or ops[i % len(ops)] in ("neg", "abs", "sqr", "sqrt"))
         assert results[i][2] == results[(i + 8) % 16][2] or i % 2 != (i + 8) % 2     # same description and layout: same source
+
+
+def test_prepared_sequence_stops_at_the_failing_call():
+    import ctypes
+    s = GraphSpec(1)
+    x = s.input("f32", (False,)); a = s.scalar("f32")
+    s.output(s.mul(x, a), "f32")
+    e = ewf.Expression(s)
+    tin = ref(BASE, (64,)); tout = ref(BASE + 4096, (64,))
+    good = e.bind([tin], [tout], (2.0,), None, 0)
+    bad = e.bind([tin], [tout], (), None, 0)               # the scalar is missing: refused before any launch
+    seq = ewf.CallSequence([bad])
+    with pytest.raises(ewf.EwfError) as err:
+        seq.launch()
+    assert err.value.status == ewf.EINVAL and err.value.message.startswith("call 0:")
+    with pytest.raises(ewf.EwfError) as err:
+        bad.launch()
+    assert err.value.status == ewf.EINVAL and "scalar" in err.value.message
+    assert ewf._lib.ewf_run_sequence(None, 0, None) == 0    # an empty sequence is a no-op
+    assert ewf._lib.ewf_run_sequence(None, 3, None) == ewf.EINVAL
+    assert ewf._lib.ewf_run_call(None) == ewf.EINVAL
+    del good
