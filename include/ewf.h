@@ -219,7 +219,7 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
                    size_t workspace_bytes, void *hip_stream);
 
 /* The arguments of ewf_run gathered in one structure, for launch loops driven from another
- * language: a prepared call is passed as a single pointer (section 2.2.4, function execution:
+ * language: a prepared call is passed as a single pointer (section 2.3, function execution:
  * with many operations on small operands the overhead of each call from the calling language is
  * what counts).  Same semantics and errors as ewf_run; the structure and everything it points
  * to are the caller's and may be changed between calls. */
@@ -236,7 +236,7 @@ typedef struct {
 ewf_status ewf_run_call(const ewf_call *call);
 /* Runs `ncalls` prepared calls in order, each on its own hip_stream field -- the loop over the
  * steps of a prepared sequence runs inside the library, as the paper's C virtual machine runs
- * the loop over a function's nodes in C (section 2.2.4).  Stops at the first failing call,
+ * the loop over a function's nodes in C (section 2.3).  Stops at the first failing call,
  * returns its status and, when `failed` is not NULL, stores its index there. */
 ewf_status ewf_run_sequence(const ewf_call *calls, int32_t ncalls, int32_t *failed);
 
