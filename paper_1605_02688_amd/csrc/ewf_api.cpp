@@ -138,15 +138,17 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
     }
 
     plan->avoid_poor_rows = !e.is_stage || e.strict_rows;
+    plan->avoid_short_runs = !e.is_stage;
     st = single_kernel_plan(e, plan.get(), full);
     if (st == EWF_EUNSUPPORTED && !e.is_stage) {
         // no single kernel covers the expression (or only a poorly fitting one does): several
         // passes, reductions materialised; a softmax-style chain max -> sum of exp first
-        // becomes one level
+        // becomes one level, reductions over axes far apart in memory are taken in two steps
         const std::string why = get_error();
-        const bool refused = plan->row_refused;
+        const bool refused = plan->row_refused || plan->axes_refused;
         Graph split = e.g;
         fuse_shifted_exp_sums(split);
+        if (plan->axes_refused && split_reduction_axes(split, plan->red.axes, plan->split_outer_axes) < 0) split = e.g;
         st = plan_multi(e, split, true, in, nin, out, nout, *plan);
         if (st == EWF_EUNSUPPORTED) {
             plan->stages.clear();
@@ -154,7 +156,8 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
             if (refused) {
                 // the single kernel after all
                 plan->avoid_poor_rows = false;
-                plan->row_refused = false;
+                plan->avoid_short_runs = false;
+                plan->row_refused = plan->axes_refused = false;
                 st = single_kernel_plan(e, plan.get(), full);
             } else {
                 st = plan_multi(e, split, false, in, nin, out, nout, *plan);
@@ -218,6 +221,34 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
             plan->kclass = KernelClass::Row;
         } else {
             plan->kclass = KernelClass::TileReduce;
+            // Reduced axes that are not neighbours in memory: kk is the innermost kept dimension
+            // with reduced dimensions on both sides.  When the run inside it is short, the tiles
+            // (which never leave a reduction group) would be tiny.
+            int kk = -1;
+            bool seen_reduced = false;
+            for (int d = 0; d < c.rank; d++) {
+                if (c.reduced[d]) seen_reduced = true;
+                else if (seen_reduced) kk = d;
+            }
+            if (plan->avoid_short_runs && kk >= 0 && kk < c.rank - 1 && c.total >= ((int64_t)1 << 20)) {
+                int64_t inner = 1, outer = 1;
+                for (int d = 0; d < c.rank; d++) if (c.reduced[d]) (d > kk ? inner : outer) *= c.extent[d];
+                bool ops_ok = true;
+                for (int n : plan->red.level_nodes) {
+                    const Node &nd = e.g.nodes[n];
+                    ops_ok = ops_ok && nd.axes == plan->red.axes &&
+                             (nd.op == EWF_RSUM || nd.op == EWF_RPROD || nd.op == EWF_RMAX || nd.op == EWF_RMIN);
+                }
+                uint32_t outer_axes = 0;
+                for (int a = 0; a < e.g.ndim; a++)
+                    if ((plan->red.axes >> a & 1u) && c.dim_of_axis[a] >= 0 && c.dim_of_axis[a] < kk) outer_axes |= 1u << a;
+                if (ops_ok && inner < 2048 && outer >= 4 && outer_axes) {
+                    plan->axes_refused = true;
+                    plan->split_outer_axes = outer_axes;
+                    set_error("the reduced axes are not neighbours in memory and the innermost run is short (%lld elements)", (long long)inner);
+                    return EWF_EUNSUPPORTED;
+                }
+            }
         }
     }
 

@@ -211,7 +211,7 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
     // ---- iteration space
     c.total = 1;
     for (int d = 0; d < nd; d++) c.total *= full[d];
-    for (int d = 0; d < kMaxDims; d++) c.orig_of_axis[d] = -1;
+    for (int d = 0; d < kMaxDims; d++) c.orig_of_axis[d] = c.dim_of_axis[d] = -1;
     if (c.total == 0) { c.rank = 0; return EWF_OK; }
 
     // which axes an iota node reads (they must keep their identity)
@@ -247,10 +247,11 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
     std::stable_sort(dims.begin(), dims.end(), [&](int a, int b) { return key(a) > key(b); });
 
     // ---- merge neighbours that every operand walks contiguously
-    struct CD { int64_t ext; bool red; bool iota; int orig; std::vector<int64_t> st; };
+    struct CD { int64_t ext; bool red; bool iota; int orig; std::vector<int64_t> st; std::vector<int> origs; };
     std::vector<CD> cd;
     for (int d : dims) {
         CD x; x.ext = full[d]; x.red = (red.axes >> d) & 1u; x.iota = (iota_axes >> d) & 1u; x.orig = d;
+        x.origs.push_back(d);
         for (const Operand &op : c.ops) x.st.push_back(op.stride[d]);
         cd.push_back(x);
     }
@@ -260,6 +261,7 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
         for (size_t k = 0; ok && k < a.st.size(); k++) ok = (a.st[k] == b.st[k] * b.ext);
         if (!ok) continue;
         b.ext *= a.ext;
+        b.origs.insert(b.origs.end(), a.origs.begin(), a.origs.end());
         cd.erase(cd.begin() + i);
     }
     if (cd.empty()) {                       // a single element
@@ -273,6 +275,7 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
         c.extent[i] = cd[i].ext;
         c.reduced[i] = cd[i].red;
         if (cd[i].orig >= 0 && cd[i].iota) c.orig_of_axis[cd[i].orig] = i;
+        for (int o : cd[i].origs) c.dim_of_axis[o] = i;
         for (size_t k = 0; k < c.ops.size(); k++) c.ops[k].stride[i] = cd[i].st[k];
     }
     for (size_t k = 0; k < c.ops.size(); k++)

@@ -88,6 +88,7 @@ struct Canon {
     int64_t extent[kMaxDims] = {0};
     bool reduced[kMaxDims] = {false};     // member of the reduce axes of the fused reduction
     int orig_of_axis[kMaxDims];           // for iota: canonical dim that carries original axis d (-1: extent 1)
+    int dim_of_axis[kMaxDims];            // canonical dim that original axis d went into (-1: extent 1)
     std::vector<Operand> ops;             // inputs then outputs
     int vec = 1;
     bool idx64 = false;
@@ -165,6 +166,12 @@ struct Plan {
     // does not fit the registers of a workgroup or the rows are too few to occupy the chip, so
     // that the caller can try a plan in several passes first.
     bool avoid_poor_rows = false, row_refused = false;
+    // Likewise for reductions over axes that are not neighbours in memory (a kept dimension lies
+    // between them) with a short innermost run: the tile class would work on tiny tiles.  The
+    // planner first tries two passes, the outer axes (`split_outer_axes`, original axis mask)
+    // in a column kernel and the rest on its much smaller result.
+    bool avoid_short_runs = false, axes_refused = false;
+    uint32_t split_outer_axes = 0;
     KernelClass kclass = KernelClass::None;
     std::vector<Stage> stages;           // KernelClass::Multi only
     std::vector<Temp> temps;
@@ -222,6 +229,11 @@ int rewrite_graph(Graph &g);
 // Replaces every sum(exp(x - max(x))) over matching axes by one kRSumExpShifted node; in place.
 // Returns the number of replacements.
 int fuse_shifted_exp_sums(Graph &g);
+// Replaces every sum, product, max or min over exactly `axes` by the same reduction over `outer`
+// (kept as broadcastable) followed by one over `axes` again, which then only folds the rest
+// (reducing along an axis on which the argument is broadcastable is the identity).  In place;
+// returns the number of reductions split, or -1 if the graph could not be rebuilt.
+int split_reduction_axes(Graph &g, uint32_t axes, uint32_t outer);
 
 // ---- ewf_canon.cpp
 // Builds the canonical layout.  `in`/`out` give shapes and strides in the original rank

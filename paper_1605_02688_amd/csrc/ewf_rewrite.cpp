@@ -131,6 +131,38 @@ int fuse_shifted_exp_sums(Graph &g)
     return count;
 }
 
+int split_reduction_axes(Graph &g, uint32_t axes, uint32_t outer)
+{
+    if (!outer || (outer & ~axes) || outer == axes) return 0;
+    Graph out;
+    out.ndim = g.ndim; out.ninputs = g.ninputs; out.nscalars = g.nscalars;
+    const int N = (int)g.nodes.size();
+    std::vector<int> pos(N, -1);
+    int count = 0;
+    for (int n = 0; n < N; n++) {
+        Node nd = g.nodes[n];
+        for (int a = 0; a < nd.nargs; a++) nd.args[a] = pos[nd.args[a]];
+        const bool splittable = nd.kind == NodeKind::Reduce && nd.axes == axes &&
+                                (nd.op == EWF_RSUM || nd.op == EWF_RPROD || nd.op == EWF_RMAX || nd.op == EWF_RMIN);
+        if (splittable) {
+            Node first = nd;
+            first.axes = outer;
+            first.keep = true;
+            out.nodes.push_back(first);
+            nd.args[0] = (int)out.nodes.size() - 1;
+            count++;
+        }
+        pos[n] = (int)out.nodes.size();
+        out.nodes.push_back(nd);
+    }
+    for (int v : g.input_node) out.input_node.push_back(pos[v]);
+    for (int v : g.scalar_node) out.scalar_node.push_back(pos[v]);
+    for (const OutputDecl &od : g.outputs) out.outputs.push_back({pos[od.value], od.storage});
+    if (finalize_graph(out) != EWF_OK) return -1;
+    g = out;
+    return count;
+}
+
 int rewrite_graph(Graph &g)
 {
     const int N = (int)g.nodes.size();

@@ -832,3 +832,35 @@ def test_random_softmax_chains(seed, oracle, G):
             G.h.compare(name, g_, w_, *((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3)))
         else:
             G.h.compare(name, g_, w_, 1e-5, 2e-6)
+
+
+def test_reductions_over_axes_far_apart_in_memory(oracle, G):
+    # a kept dimension between the reduced ones and a short innermost run: the outer axes go
+    # first (column kernel), the rest on the much smaller result
+    rng = np.random.default_rng(191)
+    x = rng.uniform(0.5, 1.5, (40, 30, 50, 36)).astype(np.float32)
+    x *= np.where(rng.random(x.shape) < 0.5, -1, 1).astype(np.float32)
+    for axes in ((1, 3), (0, 3), (0, 1, 3)):
+        s = GraphSpec(4)
+        xi = s.input("f32", (False,) * 4)
+        s.output(s.reduce("sum", xi, axes), "f32"); s.output(s.reduce("max", xi, axes), "f32")
+        s.output(s.reduce("min", xi, axes, keep=True), "f32")
+        s.output(s.reduce("prod", s.add(s.mul(xi, s.const(0.01)), s.const(1.0)), axes), "f32")
+        s.output(s.apply("sqrt", s.reduce("sum", s.apply("sqr", xi), axes)), "f32")       # a value computed from a split reduction
+        print(f"[case] axes {axes}", flush=True)
+        expr, got = run_spec(G, s, [x])
+        assert expr.info()["kernel_class"] == "multi" and expr.info(0)["kernel_class"] == "col", expr.info()
+        want = oracle.evaluate(s, [x], nthreads=4)
+        assert [g_.shape for g_ in got] == [w_.shape for w_ in want]
+        G.h.compare("sum", got[0], want[0], 1e-5, 2e-5); G.h.compare("max", got[1], want[1], 0, 0)
+        G.h.compare("min", got[2], want[2], 0, 0); G.h.compare("prod", got[3], want[3], 2e-5, 1e-6)
+        G.h.compare("norm", got[4], want[4], 1e-5, 1e-6)
+    # a transposed view makes the same situation out of neighbouring axes
+    y = rng.standard_normal((300, 8, 700)).astype(np.float32)
+    s = GraphSpec(3)
+    yi = s.input("f32", (False,) * 3)
+    s.output(s.reduce("sum", yi, (0, 1)), "f32")
+    yt = np.ascontiguousarray(y.transpose(0, 2, 1)).transpose(0, 2, 1)      # axis 1 is now the fastest in memory
+    expr, got = run_spec(G, s, [yt])
+    assert expr.info()["kernel_class"] == "multi"
+    G.h.compare("sum01", got[0], oracle.evaluate(s, [yt])[0], 1e-5, 2e-5)
