@@ -248,7 +248,8 @@ typedef struct {
     int32_t kernel_class;     /* 0 none (empty), 1 tile element-wise, 2 tile + split reduce,
                                  3 row-resident reduce, 4 column reduce (kept axis fastest),
                                  5 several kernels (reductions materialised in the workspace;
-                                 grid_blocks then counts the kernels' stages)                 */
+                                 grid_blocks then counts the kernels' stages), 6 short rows,
+                                 one thread per row                                          */
     int32_t rank;             /* canonical rank after dropping/merging dimensions            */
     int64_t extent[EWF_MAX_DIMS];
     int32_t reduced[EWF_MAX_DIMS];  /* 1 if the canonical dimension is reduced                */

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libewf.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 
-HOST_SOURCES = ["ewf_ir.cpp", "ewf_rewrite.cpp", "ewf_grad.cpp", "ewf_canon.cpp", "ewf_codegen.cpp", "ewf_gen_tile.cpp", "ewf_gen_row.cpp", "ewf_gen_col.cpp", "ewf_rtc.cpp", "ewf_multi.cpp", "ewf_api.cpp"]
+HOST_SOURCES = ["ewf_ir.cpp", "ewf_rewrite.cpp", "ewf_grad.cpp", "ewf_canon.cpp", "ewf_codegen.cpp", "ewf_gen_tile.cpp", "ewf_gen_row.cpp", "ewf_gen_col.cpp", "ewf_gen_lane.cpp", "ewf_rtc.cpp", "ewf_multi.cpp", "ewf_api.cpp"]
 HIP_SOURCES = ["ewf_aux.hip"]
 # packed-fp32 instructions stay off in all device code of this library
 HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

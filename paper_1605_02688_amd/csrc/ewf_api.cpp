@@ -205,6 +205,12 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
                 set_error("unsupported: chained or cross-group reductions need the reduced axes to form the innermost contiguous dimension");
                 return EWF_EUNSUPPORTED;
             }
+            if (!plan->red.cross_nodes.empty() && rows > 65536 && (!e.is_stage || e.strict_rows)) {
+                // one workgroup folds the per-row values of a cross-row reduction: beyond some
+                // ten thousand rows a separate, parallel reduction over them is faster
+                set_error("unsupported: too many rows for the single-workgroup fold of a cross-row reduction");
+                return EWF_EUNSUPPORTED;
+            }
             if (!plan->red.cross_nodes.empty()) {
                 // the cross-group reduction must fold every remaining group
                 for (int d = 0; d < e.g.ndim; d++) {
@@ -252,7 +258,21 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
         }
     }
 
-    st = generate(e, *plan);
+    if (plan->kclass == KernelClass::Row) {
+        // rows of up to 512 bytes, many of them: several rows per wavefront instead of a wavefront
+        // (or more) per row.  Sum over float32 rows, 134 MB, row class / lane class in TB/s:
+        // 8 columns 0.4 / 5.1, 16: 0.8 / 5.1, 32: 1.5 / 5.3, 64: 2.8 / 5.3, 128: 4.7 / 5.4, 256: 6.1 / 5.2
+        int widest = 2;
+        for (const Operand &op : c.ops) if (op.stride[c.rank - 1] != 0) widest = std::max(widest, op.storage == EWF_F16 ? 2 : 4);
+        int64_t rows_ = 1;
+        for (int d = 0; d < c.rank - 1; d++) rows_ *= c.extent[d];
+        if (c.extent[c.rank - 1] * widest <= 512 && c.extent[c.rank - 1] <= 64 * c.vec && rows_ >= 4096 && e.opts.split_rows != 1) {
+            plan->kclass = KernelClass::Lane;
+            st = generate(e, *plan);
+            if (st == EWF_EUNSUPPORTED) plan->kclass = KernelClass::Row;      // e.g. too many row operands for one thread
+        }
+    }
+    if (plan->kclass != KernelClass::Lane) st = generate(e, *plan);
     if (st == EWF_EUNSUPPORTED && plan->row_refused && plan->kclass == KernelClass::Row && !row_only) {
         // plain row reductions do not need the row class
         plan->row_refused = false;

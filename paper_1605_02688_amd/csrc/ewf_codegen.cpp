@@ -20,6 +20,8 @@
 //               goes through the workspace and the same kind of second kernel.
 //   Col         reduced axes that are not the fastest-varying ones: lanes along the innermost
 //               kept dimension, rows spread over wavefronts and workgroups.
+//   Lane        short rows: several rows per wavefront, a power-of-two group of lanes each
+//               (ewf_gen_lane.cpp).
 #include "ewf_gen.h"
 
 namespace ewf {
@@ -82,6 +84,7 @@ ewf_status generate(const Exec &e, Plan &p)
     case KernelClass::TileReduce: return gen.gen_tile(true);
     case KernelClass::Row: return gen.gen_row();
     case KernelClass::Col: return gen.gen_col();
+    case KernelClass::Lane: return gen.gen_lane();
     default: set_error("no kernel class"); return EWF_EUNSUPPORTED;
     }
 }

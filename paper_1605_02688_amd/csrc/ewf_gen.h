@@ -618,7 +618,67 @@ struct Gen {
         }
     }
 
+    // One row's contribution to the cross-row reductions (the value of their arguments for this
+    // row, already emitted as v<n>) goes to partials[row].
+    void emit_cross_partial(const std::string &ind)
+    {
+        o << ind << "AccX ax = AccX_identity();\n";
+        for (size_t i = 0; i < red.cross_nodes.size(); i++) {
+            if (shared_slot(red.cross_nodes, i) >= 0) continue;
+            const Node &nd = g.nodes[red.cross_nodes[i]];
+            o << ind << "ax.a" << i << " = v" << nd.args[0] << ";\n";
+            if (nd.op == kRSumExpShifted) o << ind << "ax.b" << i << " = 1.0f;\n";
+            if (nd.op == EWF_RARGMAX) {
+                int cd = argmax_canon_dim(red.cross_nodes[i]);
+                o << ind << "ax.i" << i << " = (int)(" << (cd < 0 ? std::string("0") : "o" + std::to_string(cd)) << ");\n";
+            }
+        }
+        o << ind << "partials[row] = ax;\n";
+    }
+
+    // The per-row values are folded by a second, single-workgroup kernel: ordered by the kernel
+    // boundary, deterministic, and free of atomics.
+    // Returns the workgroup size of that kernel (more threads, and several loads in flight per
+    // thread, when there are thousands of rows).
+    int emit_cross_finish(const std::vector<int> &final_out_ops, int64_t nrows)
+    {
+        const int fb = nrows > 2048 ? 1024 : 256;
+        const int inflight = (int)std::min<int64_t>(8, std::max<int64_t>(1, (nrows + fb - 1) / fb));
+        o << "\nextern \"C\" __global__ void __launch_bounds__(" << fb << ") ewf_finish(const Params p)\n{\n";
+        o << "    const int tid = threadIdx.x;\n";
+        o << "    __shared__ AccX sm_accx[" << fb / 64 << "];\n";
+        o << "    const AccX *const partials = (const AccX *)p.ws_partials;\n";
+        o << "    AccX tot = AccX_identity();\n";
+        o << "    for (idx_t i0 = tid; i0 < p.nrows; i0 += " << fb * inflight << ") {\n";
+        o << "        AccX part_[" << inflight << "];\n";
+        o << "        #pragma unroll\n        for (int u = 0; u < " << inflight << "; ++u) {\n";
+        o << "            const idx_t i = i0 + (idx_t)u * " << fb << ";\n";
+        o << "            part_[u] = AccX_identity();\n";
+        o << "            if (i < p.nrows) part_[u] = partials[i];\n";
+        o << "        }\n";
+        o << "        #pragma unroll\n        for (int u = 0; u < " << inflight << "; ++u) tot = AccX_combine()(tot, part_[u]);\n";
+        o << "    }\n";
+        o << "    tot = ewf_block_reduce<" << fb / 64 << ">(tot, AccX_combine(), sm_accx, tid);\n";
+        o << "    if (tid == 0) {\n";
+        emit_results("tot", red.cross_nodes, "        ");
+        std::vector<int> tg;
+        for (int k : final_out_ops) tg.push_back(g.outputs[c.ops[k].index].value);
+        std::vector<char> need = needed(tg);
+        EmitCtx fx;
+        fx.input = [&](int k) { return "ewf_in(((const " + std::string(ctype(c.ops[k].storage)) + " *)p." + opname(k) + ")[0])"; };
+        fx.coord = [&](int) { return std::string("0"); };
+        emit_values(need, fx, "        ");
+        for (int k : final_out_ops) {
+            const Operand &op = c.ops[k];
+            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
+            o << "        ((" << ctype(op.storage) << " *)p." << opname(k) << ")[0] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
+        }
+        o << "    }\n}\n";
+        return fb;
+    }
+
     ewf_status gen_tile(bool with_reduce);
+    ewf_status gen_lane();
     ewf_status gen_row();
     ewf_status gen_col();
 };

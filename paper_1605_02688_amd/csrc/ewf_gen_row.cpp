@@ -281,52 +281,15 @@ ewf_status Gen::gen_row()
                 emit_base(k, outer, "            ");
                 o << "            q_" << opname(k) << "[0] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
             }
-            if (has_cross) {
-                o << "            AccX ax = AccX_identity();\n";
-                for (size_t i = 0; i < red.cross_nodes.size(); i++) {
-                    if (shared_slot(red.cross_nodes, i) >= 0) continue;
-                    const Node &nd = g.nodes[red.cross_nodes[i]];
-                    o << "            ax.a" << i << " = v" << nd.args[0] << ";\n";
-                    if (nd.op == kRSumExpShifted) o << "            ax.b" << i << " = 1.0f;\n";
-                    if (nd.op == EWF_RARGMAX) {
-                        int cd = argmax_canon_dim(red.cross_nodes[i]);
-                        o << "            ax.i" << i << " = (int)(" << (cd < 0 ? std::string("0") : "o" + std::to_string(cd)) << ");\n";
-                    }
-                }
-                o << "            partials[row] = ax;\n";
-            }
+            if (has_cross) emit_cross_partial("            ");
             o << "        }\n";
         }
     }
     o << "    }\n";
 
     o << "}\n";
-    if (has_cross) {
-        // the per-row values are folded by a second, single-workgroup kernel: ordered by the
-        // kernel boundary, deterministic, and free of atomics
-        o << "\nextern \"C\" __global__ void __launch_bounds__(EWF_FIN_BLOCK) ewf_finish(const Params p)\n{\n";
-        o << "    const int tid = threadIdx.x;\n";
-        o << "    __shared__ AccX sm_accx[EWF_FIN_BLOCK / 64];\n";
-        o << "    const AccX *const partials = (const AccX *)p.ws_partials;\n";
-        o << "    AccX tot = AccX_identity();\n";
-        o << "    for (idx_t i = tid; i < p.nrows; i += EWF_FIN_BLOCK) tot = AccX_combine()(tot, partials[i]);\n";
-        o << "    tot = ewf_block_reduce<EWF_FIN_BLOCK / 64>(tot, AccX_combine(), sm_accx, tid);\n";
-        o << "    if (tid == 0) {\n";
-        emit_results("tot", red.cross_nodes, "        ");
-        std::vector<int> tg;
-        for (int k : final_out_ops) tg.push_back(g.outputs[c.ops[k].index].value);
-        std::vector<char> need = needed(tg);
-        EmitCtx fx;
-        fx.input = [&](int k) { return "ewf_in(((const " + std::string(ctype(c.ops[k].storage)) + " *)p." + opname(k) + ")[0])"; };
-        fx.coord = [&](int) { return std::string("0"); };
-        emit_values(need, fx, "        ");
-        for (int k : final_out_ops) {
-            const Operand &op = c.ops[k];
-            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
-            o << "        ((" << ctype(op.storage) << " *)p." << opname(k) << ")[0] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
-        }
-        o << "    }\n}\n";
-    }
+    int cross_block = 256;
+    if (has_cross) cross_block = emit_cross_finish(final_out_ops, nrows);
 
     // ---- launch geometry and argument block
     p.grid = std::max<int64_t>(1, std::min(nrows, grid_cap));
@@ -336,7 +299,7 @@ ewf_status Gen::gen_row()
     if (has_cross) {
         p.workspace_bytes = (size_t)nrows * acc_bytes(red.cross_nodes);
         p.finish_grid = 1;
-        p.finish_block = 256;
+        p.finish_block = cross_block;
     }
     p.args.assign(p.layout.size, 0);
     auto put_idx = [&](const std::string &name, int i, int64_t v) {

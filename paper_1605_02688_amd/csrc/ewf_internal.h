@@ -99,7 +99,7 @@ struct Canon {
 // ---------------------------------------------------------------------------------------
 // Reduce structure of a graph (which kernel class can run it)
 
-enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3, Col = 4, Multi = 5 };
+enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3, Col = 4, Multi = 5, Lane = 6 };
 
 // A reduction the library introduces itself (never part of a caller's description):
 // sum over the axes of exp(x - max over the same axes of x), accumulated in one pass as a

@@ -35,7 +35,7 @@ OPS = {name: i for i, name in enumerate(
     ["add", "sub", "mul", "div", "neg", "abs", "exp", "log", "log1p", "sqrt", "tanh", "sigmoid", "max", "min",
      "pow", "where", "gt", "ge", "lt", "le", "eq", "ne", "expm1", "sqr", "recip"])}
 REDOPS = {"sum": 0, "max": 1, "min": 2, "prod": 3, "argmax": 4}
-KERNEL_CLASSES = {0: "none", 1: "tile", 2: "tile_reduce", 3: "row", 4: "col", 5: "multi"}
+KERNEL_CLASSES = {0: "none", 1: "tile", 2: "tile_reduce", 3: "row", 4: "col", 5: "multi", 6: "lane"}
 
 
 class EwfError(RuntimeError):

@@ -864,3 +864,52 @@ def test_reductions_over_axes_far_apart_in_memory(oracle, G):
     expr, got = run_spec(G, s, [yt])
     assert expr.info()["kernel_class"] == "multi"
     G.h.compare("sum01", got[0], oracle.evaluate(s, [yt])[0], 1e-5, 2e-5)
+
+
+# ------------------------------------------------------------------ short rows: several rows per wavefront
+
+@pytest.mark.parametrize("cols,storage", [(4, "f32"), (8, "f32"), (12, "f32"), (32, "f32"), (10, "f32"), (24, "f16"), (64, "f16"),
+                                          (100, "f32"), (256, "f32"), (200, "f16")])
+def test_short_rows_share_a_wavefront(cols, storage, oracle, G):
+    rng = np.random.default_rng(192 + cols)
+    rows = 5003
+    dt = np.float32 if storage == "f32" else np.float16
+    x = (rng.standard_normal((rows, cols)) * 3).astype(dt)
+    t = rng.integers(-1, cols + 1, (rows, 1)).astype(np.int32)          # some targets out of range
+    x[7, :] = 2.5                                                       # ties: the first index wins
+    x[8, cols - 1] = np.nan
+    s = GraphSpec(2)
+    xi = s.input(storage, (False, False)); ti = s.input("i32", (False, True))
+    m = s.reduce("max", xi, (1,), keep=True)
+    ex = s.apply("exp", s.sub(xi, m))
+    S = s.reduce("sum", ex, (1,), keep=True)
+    xt = s.reduce("sum", s.apply("where", s.apply("eq", s.iota(1), ti), xi, s.const(0.0)), (1,), keep=True)
+    loss = s.sub(s.add(m, s.apply("log", S)), xt)
+    s.output(s.div(ex, S), storage)                                     # softmax probabilities
+    s.output(loss, "f32")
+    s.output(s.reduce("argmax", xi, (1,)), "i32")
+    s.output(s.reduce("min", xi, (1,)), "f32")
+    s.output(s.div(s.reduce("sum", s.apply("where", s.apply("eq", loss, loss), loss, s.const(0.0)), (0,)), s.const(float(rows))), "f32")
+    print(f"[case] short rows {rows} x {cols} {storage}", flush=True)
+    expr, got = run_spec(G, s, [x, t])
+    itemsize = 4 if storage == "f32" else 2
+    assert expr.info()["kernel_class"] == ("lane" if cols * itemsize <= 512 else "row"), expr.info()
+    want = oracle.evaluate(s, [x, t], nthreads=4)
+    G.h.compare("p", got[0], want[0], *((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3)))
+    G.h.compare("loss", got[1], want[1], 1e-5, 2e-6)
+    assert np.array_equal(got[2], want[2]) and got[2][7] == 0
+    assert np.array_equal(got[3], want[3], equal_nan=True)
+    G.h.compare("mean_loss", got[4], want[4], 1e-5, 1e-6)
+    # strided rows (a slice of wider rows) and a row-constant operand
+    wide = (rng.standard_normal((rows, cols + 5)) * 2).astype(dt)
+    view = wide[:, 2:2 + cols]
+    s2 = GraphSpec(2)
+    vi = s2.input(storage, (False, False)); ci = s2.input("f32", (False, True))
+    s2.output(s2.reduce("sum", s2.mul(vi, ci), (1,)), "f32")
+    s2.output(s2.reduce("prod", s2.add(s2.mul(vi, s2.const(0.01)), s2.const(1.0)), (1,), keep=True), "f32")
+    scale = rng.standard_normal((rows, 1)).astype(np.float32)
+    expr, got = run_spec(G, s2, [view, scale])
+    # the slice is not aligned for wide accesses: single elements, up to 64 of them per row
+    assert expr.info()["kernel_class"] == ("lane" if cols <= 64 and cols * itemsize <= 512 else "row")
+    want = oracle.evaluate(s2, [view, scale], nthreads=4)
+    G.h.compare("wsum", got[0], want[0], 1e-5, 1e-5); G.h.compare("prod", got[1], want[1], 1e-5, 1e-6)

@@ -255,6 +255,27 @@ def test_long_or_few_rows_are_split_over_workgroups():
     assert e.info()["kernel_class"] == "tile_reduce"
 
 
+def test_short_rows_share_a_wavefront():
+    # softmax cross-entropy over 8 classes (32-byte rows): one thread per row when there are many rows
+    e = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=8))[0]
+    assert e.info()["kernel_class"] == "lane" and e.info()["grid_blocks"] == (50000 + 255) // 256
+    assert "ewf_lane_xor" not in e.source() and "ewf_block_reduce" in e.source()      # no lane exchange; the mean is folded by the second kernel
+    # 12 classes: four lanes per row (the fourth has no column), two butterfly steps
+    e = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=12))[0]
+    assert e.info()["kernel_class"] == "lane" and e.info()["grid_blocks"] == (50000 + 63) // 64
+    assert e.source().count("ewf_lane_xor(acc1, ") == 2
+    # rows of 100 float32: 32 lanes per row, five butterfly steps per reduction level
+    e = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=100))[0]
+    assert e.info()["kernel_class"] == "lane" and e.info()["grid_blocks"] == (50000 + 7) // 8
+    assert e.source().count("ewf_lane_xor(acc1, ") == 5 and "ewf_lane_xor(acc1, 16)" in e.source()
+    # few rows, or longer ones: a wavefront or more per row
+    assert plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=1000, vocab=12))[0].info()["kernel_class"] == "row"
+    assert plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=256))[0].info()["kernel_class"] == "row"
+    # more rows than one workgroup should fold: the mean becomes a pass of its own
+    e = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=200000, vocab=12))[0]
+    assert e.info()["kernel_class"] == "multi" and e.info(0)["kernel_class"] == "lane"
+
+
 # ------------------------------------------------------------------ shape / alias / argument errors
 
 def _add2():
