@@ -248,7 +248,7 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
                 uint32_t outer_axes = 0;
                 for (int a = 0; a < e.g.ndim; a++)
                     if ((plan->red.axes >> a & 1u) && c.dim_of_axis[a] >= 0 && c.dim_of_axis[a] < kk) outer_axes |= 1u << a;
-                if (ops_ok && inner < 2048 && outer >= 4 && outer_axes) {
+                if (ops_ok && inner < 2048 && outer >= 2 && outer_axes) {
                     plan->axes_refused = true;
                     plan->split_outer_axes = outer_axes;
                     set_error("the reduced axes are not neighbours in memory and the innermost run is short (%lld elements)", (long long)inner);

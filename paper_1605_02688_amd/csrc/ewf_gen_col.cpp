@@ -52,7 +52,23 @@ ewf_status Gen::gen_col()
         const int min_tx = std::max(1, 16 / VEC);
         while (TX > min_tx && ceil_div(c.extent[in_d], (int64_t)TX * VEC) * other < 64) TX /= 2;
     }
-    const int TY = block / TX;
+    // Few columns and few rows: the lanes that neither would use take neighbouring indices of
+    // the innermost other kept dimension (dK), TZ of them per workgroup, each with its own
+    // columns-by-rows patch that folds inside a wavefront.  ([2097152, 4, 8] summed over axis 1:
+    // two million 32-element tiles took 1.9 ms; with 32 outer indices per workgroup the tile is
+    // a contiguous 4 KB.)
+    int dK = -1;
+    for (int d = R - 2; d >= 0; d--) if (!c.reduced[d]) { dK = d; break; }
+    int TY = block / TX, TZ = 1;
+    {
+        int64_t rows_needed = c.extent[dR];
+        int ty = 1;
+        while (ty < rows_needed && ty < block / TX) ty *= 2;
+        if (dK >= 0 && nreduced == 1 && TX * ty <= 32 && c.extent[dK] >= 2 && e.opts.tile_elems <= 0) {
+            TY = ty;
+            TZ = block / (TX * TY);
+        }
+    }
     const int64_t TK = std::min<int64_t>(c.extent[in_d], (int64_t)TX * VEC);   // columns per tile
     // rows in flight per thread: four for streaming expressions, fewer when the expression is
     // heavy in transcendental operations (registers) or the problem is small (spread it out)
@@ -69,13 +85,14 @@ ewf_status Gen::gen_col()
     int64_t T[kMaxDims];
     for (int d = 0; d < kMaxDims; d++) T[d] = 1;
     T[in_d] = TK;
+    if (TZ > 1) T[dK] = std::min<int64_t>(c.extent[dK], TZ);
     {
         // rows per tile: enough tiles to fill the chip, but whole trips of the workgroup
         int64_t other = ceil_div(c.extent[in_d], TK);
         for (int d = 0; d < R - 1; d++) if (d != dR) other *= c.extent[d];
         const int64_t want = (int64_t)16 * device_cu_count();
         int64_t slices = std::max<int64_t>(1, std::min(ceil_div(want, other), ceil_div(c.extent[dR], (int64_t)TY * U)));
-        if (whole_columns) slices = 1;
+        if (whole_columns || TZ > 1) slices = 1;
         int64_t tr = ceil_div(c.extent[dR], slices);
         if (e.opts.tile_elems > 0) tr = std::max<int64_t>(1, e.opts.tile_elems / TK);
         T[dR] = std::min(c.extent[dR], tr);
@@ -102,7 +119,7 @@ ewf_status Gen::gen_col()
     std::vector<int> load_ops = inputs_of(need);
 
     emit_header(block);
-    o << "#define EWF_TX " << TX << "\n#define EWF_TY " << TY << "\n";
+    o << "#define EWF_TX " << TX << "\n#define EWF_TY " << TY << "\n#define EWF_TZ " << TZ << "\n";
     build_layout();
     emit_acc_struct("Acc", level);
     std::vector<int> all_dims;
@@ -114,6 +131,10 @@ ewf_status Gen::gen_col()
         const std::string nm = opname(k);
         std::string s;
         if (op.stride[dR] != 0) s = "(ioff_t)r_ * (ioff_t)p.st_" + nm + "[" + std::to_string(dR) + "]";
+        if (TZ > 1 && op.stride[dK] != 0) {
+            if (!s.empty()) s += " + ";
+            s += "(ioff_t)tz * (ioff_t)p.st_" + nm + "[" + std::to_string(dK) + "]";
+        }
         if (op.stride[in_d] != 0) {
             if (!s.empty()) s += " + ";
             s += op.stride[in_d] == 1 ? std::string("(ioff_t)cc_") : "(ioff_t)cc_ * (ioff_t)p.st_" + nm + "[" + std::to_string(in_d) + "]";
@@ -123,9 +144,10 @@ ewf_status Gen::gen_col()
 
     o << "extern \"C\" __global__ void __launch_bounds__(EWF_BLOCK) " << occupancy_attr() << "ewf_kernel(const Params p)\n{\n";
     o << "    const int tid = threadIdx.x;\n";
-    o << "    const int tx = tid & (EWF_TX - 1), ty = tid / EWF_TX;\n";
+    o << "    const int tx = tid & (EWF_TX - 1), ty = (tid / EWF_TX) & (EWF_TY - 1), tz = tid / (EWF_TX * EWF_TY);\n";
+    o << "    (void)tz;\n";
     if (!one_tile) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
-    if (NW > 1) o << "    __shared__ Acc sm_col[(EWF_NWAVES - 1) * EWF_TX * EWF_VEC];\n";
+    if (NW > 1 && TZ == 1) o << "    __shared__ Acc sm_col[(EWF_NWAVES - 1) * EWF_TX * EWF_VEC];\n";
     o << "    for (idx_t tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {\n";
     o << "        idx_t t_ = tile;\n";
     for (int d = R - 1; d >= 0; d--) {
@@ -137,7 +159,8 @@ ewf_status Gen::gen_col()
     for (int k : load_ops) emit_base(k, all_dims, ind);
     for (int k : ew_out_ops) emit_base(k, all_dims, ind);
     o << ind << "const int cc_ = tx * EWF_VEC;\n";
-    o << ind << "const bool colok_ = cc_ < " << TK << " && o" << in_d << " + cc_ < p.ext[" << in_d << "];\n";
+    o << ind << "const bool colok_ = cc_ < " << TK << " && o" << in_d << " + cc_ < p.ext[" << in_d << "]"
+      << (TZ > 1 ? " && o" + std::to_string(dK) + " + tz < p.ext[" + std::to_string(dK) + "]" : std::string("")) << ";\n";
     o << ind << "const int rows_ = (int)((p.ext[" << dR << "] - o" << dR << ") < " << TR << " ? (p.ext[" << dR << "] - o" << dR << ") : " << TR << ");\n";
     o << ind << "Acc acc[EWF_VEC];\n";
     o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_identity();\n";
@@ -180,6 +203,7 @@ ewf_status Gen::gen_col()
     cx.coord = [&](int d) {
         std::string s = "o" + std::to_string(d);
         if (d == dR) s += " + r_";
+        if (TZ > 1 && d == dK) s += " + tz";
         if (d == in_d) s += " + cc_ + e_";
         return s;
     };
@@ -207,9 +231,9 @@ ewf_status Gen::gen_col()
     // the row groups inside a wavefront (lanes that differ by a multiple of TX) fold with lane
     // exchanges in a fixed butterfly; the wavefronts then meet in LDS and the first folds them
     // in order
-    for (int m = TX; m < 64; m *= 2)
+    for (int m = TX; m < (TZ > 1 ? TX * TY : 64); m *= 2)
         o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], ewf_lane_xor(acc[e_], " << m << "));\n";
-    if (NW > 1) {
+    if (NW > 1 && TZ == 1) {
         o << ind << "if (tid >= 64 && (tid & 63) < EWF_TX) { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) sm_col[(((tid >> 6) - 1) * EWF_TX + tx) * EWF_VEC + e_] = acc[e_]; }\n";
         o << ind << "__syncthreads();\n";
         o << ind << "if (tid < EWF_TX) {\n";
@@ -217,11 +241,12 @@ ewf_status Gen::gen_col()
         o << ind << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], sm_col[(w_ * EWF_TX + tx) * EWF_VEC + e_]);\n";
         o << ind << "}\n";
     }
-    o << ind << "if (tid < EWF_TX && colok_) {\n";
+    o << ind << "if (" << (TZ > 1 ? "ty == 0" : "tid < EWF_TX") << " && colok_) {\n";
     o << ind << "    size_t group = 0, slot = 0;\n";
     for (int d = 0; d < R; d++) {
         if (c.reduced[d]) o << ind << "    slot = slot * (size_t)p.ntile[" << d << "] + (size_t)ti" << d << ";\n";
         else if (d == in_d) o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + cc_);\n";
+        else if (TZ > 1 && d == dK) o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + tz);\n";
         else o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)o" << d << ";\n";
     }
     if (one_tile) {
@@ -237,7 +262,7 @@ ewf_status Gen::gen_col()
     else if (fin_lanes) o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[(group + e_) * (size_t)p.nslots + slot] = acc[e_];\n";
     else o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[slot * (size_t)p.nrows + group + e_] = acc[e_];\n";
     o << ind << "}\n";
-    if (NW > 1) o << ind << "__syncthreads();\n";
+    if (NW > 1 && TZ == 1) o << ind << "__syncthreads();\n";
     o << "    }\n}\n";
 
     // ---- second kernel.  Many slots per column: the partials of a column are contiguous and a
@@ -283,7 +308,7 @@ ewf_status Gen::gen_col()
     // ---- launch geometry and argument block
     int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)1 << 22;
     p.grid = std::max<int64_t>(1, std::min(ntiles, cap));
-    p.lds_bytes = NW > 1 ? (int)((NW - 1) * TX * VEC * acc_bytes(level)) : 0;
+    p.lds_bytes = NW > 1 && TZ == 1 ? (int)((NW - 1) * TX * VEC * acc_bytes(level)) : 0;
     if (p.lds_bytes > 60 * 1024) return fail("too many reductions for one column kernel (LDS)");
     p.staged = 0;
     p.workspace_bytes = one_tile ? 0 : (size_t)ngroups * (size_t)nslots * acc_bytes(level);

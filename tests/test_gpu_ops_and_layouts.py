@@ -913,3 +913,25 @@ def test_short_rows_share_a_wavefront(cols, storage, oracle, G):
     assert expr.info()["kernel_class"] == ("lane" if cols <= 64 and cols * itemsize <= 512 else "row")
     want = oracle.evaluate(s2, [view, scale], nthreads=4)
     G.h.compare("wsum", got[0], want[0], 1e-5, 1e-5); G.h.compare("prod", got[1], want[1], 1e-5, 1e-6)
+
+
+@pytest.mark.parametrize("shape,axis", [((5001, 4, 8), 1), ((3000, 3, 12), 1), ((777, 2, 5, 6), 1), ((40000, 2, 2), 1), ((9, 1100, 5, 4), 2)])
+def test_short_middle_axis_with_few_columns(shape, axis, oracle, G):
+    # a short reduced axis in the middle and a tiny kept innermost axis: the lanes left over take
+    # neighbouring indices of the next kept dimension
+    rng = np.random.default_rng(193 + len(shape))
+    x = (rng.standard_normal(shape) * 2).astype(np.float32)
+    nd = len(shape)
+    s = GraphSpec(nd)
+    xi = s.input("f32", (False,) * nd)
+    s.output(s.reduce("sum", xi, (axis,)), "f32")
+    s.output(s.reduce("max", xi, (axis,), keep=True), "f32")
+    s.output(s.reduce("argmax", xi, (axis,)), "i32")
+    s.output(s.apply("tanh", xi), "f32")                               # an element-wise output in the same pass
+    print(f"[case] {shape} axis {axis}", flush=True)
+    expr, got = run_spec(G, s, [x])
+    assert expr.info()["kernel_class"] == "col", expr.info()
+    assert expr.info()["grid_blocks"] < int(np.prod(shape[:axis])) // 4       # many outer indices per workgroup
+    want = oracle.evaluate(s, [x], nthreads=4)
+    G.h.compare("sum", got[0], want[0], 1e-5, 2e-6); G.h.compare("max", got[1], want[1], 0, 0)
+    G.h.compare("argmax", got[2], want[2], 0, 0); G.h.compare("tanh", got[3], want[3], 2e-6, 1e-6)
