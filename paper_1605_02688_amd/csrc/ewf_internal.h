@@ -228,7 +228,9 @@ uint32_t all_mask(int ndim);
 int rewrite_graph(Graph &g);
 // Replaces every sum(exp(x - max(x))) over matching axes by one kRSumExpShifted node; in place.
 // Returns the number of replacements.
-int fuse_shifted_exp_sums(Graph &g);
+// With `unless_argmax` a chain whose maximum is also the key of an arg-max stays as it is (the
+// arg-max carries that maximum for free, so two sweeps over a row held in registers are cheaper).
+int fuse_shifted_exp_sums(Graph &g, bool unless_argmax = false);
 // Replaces every sum, product, max or min over exactly `axes` by the same reduction over `outer`
 // (kept as broadcastable) followed by one over `axes` again, which then only folds the rest
 // (reducing along an axis on which the argument is broadcastable is the identity).  In place;

@@ -111,7 +111,7 @@ bool commutative(int op)
 }  // namespace
 
 // Rewrites `g` in place.  Returns the number of nodes removed or replaced (for tests).
-int fuse_shifted_exp_sums(Graph &g)
+int fuse_shifted_exp_sums(Graph &g, bool unless_argmax)
 {
     int count = 0;
     for (Node &s : g.nodes) {
@@ -124,6 +124,12 @@ int fuse_shifted_exp_sums(Graph &g)
         const Node &m = g.nodes[sub.args[1]];
         if (m.kind != NodeKind::Reduce || m.op != EWF_RMAX || m.args[0] != x || m.axes != s.axes) continue;
         if (g.nodes[x].vtype != EWF_F32 || g.nodes[x].bcast != ex.bcast) continue;
+        if (unless_argmax) {
+            bool keyed = false;
+            for (const Node &o2 : g.nodes)
+                if (o2.kind == NodeKind::Reduce && o2.op == EWF_RARGMAX && o2.args[0] == x && o2.axes == s.axes) keyed = true;
+            if (keyed) continue;
+        }
         s.op = kRSumExpShifted;
         s.args[0] = x;
         count++;
