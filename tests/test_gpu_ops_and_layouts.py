@@ -935,3 +935,29 @@ def test_short_middle_axis_with_few_columns(shape, axis, oracle, G):
     want = oracle.evaluate(s, [x], nthreads=4)
     G.h.compare("sum", got[0], want[0], 1e-5, 2e-6); G.h.compare("max", got[1], want[1], 0, 0)
     G.h.compare("argmax", got[2], want[2], 0, 0); G.h.compare("tanh", got[3], want[3], 2e-6, 1e-6)
+
+
+def test_rank_zero_and_rank_eight(oracle, G):
+    # the smallest and the largest rank the library accepts
+    s = GraphSpec(0)
+    a = s.input("f32", ()); b = s.input("f32", ())
+    s.output(s.apply("tanh", s.add(a, b)), "f32")
+    expr, got = run_spec(G, s, [np.array(0.25, np.float32), np.array(-1.5, np.float32)])
+    G.h.compare("scalar", got[0], oracle.evaluate(s, [np.array(0.25, np.float32), np.array(-1.5, np.float32)])[0], 2e-6, 1e-6)
+    rng = np.random.default_rng(194)
+    shape = (2, 3, 4, 5, 2, 3, 4, 5)
+    x = rng.standard_normal(shape[::-1]).astype(np.float32).transpose(7, 6, 5, 4, 3, 2, 1, 0)     # nothing merges
+    y = rng.standard_normal((1, 3, 1, 5, 1, 3, 1, 5)).astype(np.float32)
+    s = GraphSpec(8)
+    xi = s.input("f32", (False,) * 8); yi = s.input("f32", (True, False) * 4)
+    v = s.mul(xi, yi)
+    s.output(s.apply("exp", v), "f32")
+    s.output(s.reduce("sum", v, (1, 3, 5, 7)), "f32")
+    s.output(s.reduce("max", v, (0, 2), keep=True), "f32")
+    s.output(s.reduce("argmax", xi, (7,)), "i32")
+    print("[case] rank 8", flush=True)
+    expr, got = run_spec(G, s, [x, y])
+    want = oracle.evaluate(s, [x, y])
+    assert [g_.shape for g_ in got] == [w_.shape for w_ in want] == [shape, (2, 4, 2, 4), (1, 3, 1, 5, 2, 3, 4, 5), shape[:7]]
+    G.h.compare("exp", got[0], want[0], 2e-6, 1e-6); G.h.compare("sum", got[1], want[1], 1e-5, 1e-5)
+    G.h.compare("max", got[2], want[2], 0, 0); G.h.compare("argmax", got[3], want[3], 0, 0)
