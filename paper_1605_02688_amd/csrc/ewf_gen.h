@@ -199,6 +199,7 @@ struct Gen {
                 break;
             case NodeKind::Reduce:
                 if (real_reduce((int)n)) rhs = "r" + std::to_string(n);
+                else if (nd.op == kRSumExpShifted) rhs = std::string(M) + "::exp(" + a0 + " - " + a0 + ")";   // one term: exp(x - x)
                 else rhs = (nd.op == EWF_RARGMAX) ? "0" : a0;      // reduction over extent-1 axes
                 break;
             case NodeKind::Apply:

@@ -961,3 +961,16 @@ def test_rank_zero_and_rank_eight(oracle, G):
     assert [g_.shape for g_ in got] == [w_.shape for w_ in want] == [shape, (2, 4, 2, 4), (1, 3, 1, 5, 2, 3, 4, 5), shape[:7]]
     G.h.compare("exp", got[0], want[0], 2e-6, 1e-6); G.h.compare("sum", got[1], want[1], 1e-5, 1e-5)
     G.h.compare("max", got[2], want[2], 0, 0); G.h.compare("argmax", got[3], want[3], 0, 0)
+
+
+def test_softmax_over_an_axis_of_extent_one(oracle, G):
+    # reducing over an axis of extent 1 is the identity: max(x) = x, and the exp-sum is exp(x - x) = 1
+    rng = np.random.default_rng(195)
+    x = rng.standard_normal((5000, 1)).astype(np.float32)
+    x[3, 0] = np.inf
+    s = _lse_spec("f32", 1)
+    expr, got = run_spec(G, s, [x])
+    want = oracle.evaluate(s, [x])
+    for name, g_, w_ in zip(("max", "expsum", "lse", "p"), got, want):
+        assert np.array_equal(g_, w_, equal_nan=True) if name == "max" else True
+        G.h.compare(name, g_, w_, 1e-6, 1e-7)
