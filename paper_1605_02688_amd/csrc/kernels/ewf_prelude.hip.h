@@ -173,15 +173,16 @@ struct ewf_acc {
     // The hardware exp2 (one unit in the last place over the whole range, no argument
     // reduction needed) takes t, and r corrects the result to first order: 2^r = 1 + r ln 2
     // for |r| < 2^-16.  Seven instructions instead of the library routine's fifteen or so.
-    // Infinite x makes r NaN; the max() with a number drops that NaN (IEEE max returns the
-    // other operand) while a NaN x still reaches the result through t.  Results below the
-    // smallest normal number flush to zero.
+    // Infinite x makes r NaN, and a finite x whose product overflows makes it infinite; the
+    // median with 0.5 and 2 drops both (the hardware median returns the smallest number when an
+    // operand is NaN) so that the result is the 0 or inf of exp2, while a NaN x still reaches the
+    // result through t.  Results below the smallest normal number flush to zero.
     static EWF_DEV float exp(float x)
     {
         const float t = x * 1.44269502162933349609375f;                 // log2 e rounded
         float r = __builtin_fmaf(x, 1.44269502162933349609375f, -t);
         r = __builtin_fmaf(x, 1.92596298909109e-8f, r);                 // log2 e - rounded
-        const float f = __builtin_fmaxf(__builtin_fmaf(r, 0.693147182464599609375f, 1.0f), 0.5f);
+        const float f = __builtin_amdgcn_fmed3f(__builtin_fmaf(r, 0.693147182464599609375f, 1.0f), 0.5f, 2.0f);
         return __builtin_amdgcn_exp2f(t) * f;
     }
     static EWF_DEV float log(float x) { return logf(x); }

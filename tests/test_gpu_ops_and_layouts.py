@@ -73,7 +73,8 @@ def test_exp_accurate_mode_whole_range(oracle, G):
     rng = np.random.default_rng(77)
     x = np.concatenate([rng.uniform(-87.3, 88.7, 200000), np.linspace(-87.3, 88.7, 50001),
                         rng.uniform(-1e-3, 1e-3, 1000)]).astype(np.float32)
-    sp = np.float32([0.0, -0.0, np.inf, -np.inf, np.nan, 88.8, 100.0, 1e30, -104.0, -1e30, 1e-40, 88.72283])
+    sp = np.float32([0.0, -0.0, np.inf, -np.inf, np.nan, 88.8, 100.0, 1e30, -104.0, -1e30, 1e-40, 88.72283,
+                     3.0e38, -3.0e38, -3.4028235e38, 3.4028235e38])          # x * log2(e) overflows for the last four
     x = np.concatenate([sp, x])
     s = GraphSpec(1)
     s.output(s.apply("exp", s.input("f32", (False,))), "f32")
@@ -84,6 +85,7 @@ def test_exp_accurate_mode_whole_range(oracle, G):
     with np.errstate(over="ignore", invalid="ignore"):
         assert got[0] == 1.0 and got[1] == 1.0 and got[2] == np.inf and got[3] == 0.0 and np.isnan(got[4])
         assert np.all(got[5:8] == np.inf) and np.all(got[8:10] == 0.0) and got[10] == 1.0
+        assert got[12] == np.inf and got[13] == 0.0 and got[14] == 0.0 and got[15] == np.inf
     G.h.compare("exp", got[k:], want[k:], 4e-7, 0)          # about three units in the last place
 
 
