@@ -96,7 +96,7 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
 
     std::unique_ptr<Plan> plan(new Plan());
     int64_t full[kMaxDims];
-    ewf_status st = infer_full_extents(e.g, in, nin, full);
+    ewf_status st = infer_full_extents(e.g, in, nin, full, e.has_forced_full ? e.forced_full : nullptr);
     if (st != EWF_OK) return st;
     uint32_t unit = 0;
     bool empty = false;

@@ -16,7 +16,7 @@ namespace ewf {
 
 static int itemsize(ewf_dtype t) { return t == EWF_F16 ? 2 : 4; }
 
-ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int64_t full[kMaxDims])
+ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int64_t full[kMaxDims], const int64_t *open_axes)
 {
     if (nin != g.ninputs) { set_error("expected %d input tensor(s), got %d", g.ninputs, nin); return EWF_EINVAL; }
     if (nin > 0 && !in) { set_error("null input array"); return EWF_EINVAL; }
@@ -41,7 +41,7 @@ ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int
             }
         }
     }
-    for (int d = 0; d < g.ndim; d++) if (full[d] < 0) full[d] = 1;
+    for (int d = 0; d < g.ndim; d++) if (full[d] < 0) full[d] = open_axes ? open_axes[d] : 1;
     return EWF_OK;
 }
 
@@ -135,7 +135,7 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
 {
     const Graph &g = e.g;
     const int nd = g.ndim;
-    ewf_status st = infer_full_extents(g, in, nin, full);
+    ewf_status st = infer_full_extents(g, in, nin, full, e.has_forced_full ? e.forced_full : nullptr);
     if (st != EWF_OK) return st;
     if (nout != (int)g.outputs.size()) { set_error("expected %d output tensor(s), got %d", (int)g.outputs.size(), nout); return EWF_EINVAL; }
     if (nout > 0 && !out) { set_error("null output array"); return EWF_EINVAL; }

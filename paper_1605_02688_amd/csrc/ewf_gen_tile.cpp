@@ -96,7 +96,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     if (!with_reduce && !e.opts.no_lds_staging && c.total >= 65536 && R >= 2) {
         for (int k = 0; k < nin && staged.empty(); k++) {
             const Operand &op = c.ops[k];
-            if (op.access != Access::Gather) continue;
+            if (op.access != Access::Gather || !live[g.input_node[k]]) continue;      // (an input no output uses is never read)
             bool full = true; int s0 = -1;
             for (int d = 0; d < R; d++) { if (op.stride[d] == 0) full = false; if (op.stride[d] == 1) s0 = d; }
             if (!full || s0 < 0 || c.extent[s0] < 16) continue;

@@ -204,6 +204,10 @@ struct Plan {
 struct Exec {
     bool is_stage = false;               // a stage of a multi-pass plan: must fit one kernel
     bool strict_rows = false;            // a stage that must not fall back on a poorly fitting row kernel
+    // A stage may not read any input that fixes the extent of an axis it iterates over (it
+    // reduces an index, say): the whole expression's extents, for the axes its own inputs leave open.
+    bool has_forced_full = false;
+    int64_t forced_full[kMaxDims] = {0};
     Graph g;
     ewf_options opts{};
     int math_flavour = 1;                // 1 accurate, 2 native rate with fix-ups, 3 native rate
@@ -245,7 +249,9 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
                         int64_t full_out[kMaxDims], std::vector<RawView> *raw_out = nullptr);
 // Overlap rules between outputs and inputs / other outputs, on the caller's views.
 ewf_status check_aliasing(const std::vector<RawView> &raw, int nin, int nout);
-ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int64_t full[kMaxDims]);
+// `open_axes` (optional): extents for the axes that no input fixes (otherwise 1).
+ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int64_t full[kMaxDims],
+                              const int64_t *open_axes = nullptr);
 
 // ---- ewf_codegen.cpp
 ewf_status generate(const Exec &e, Plan &p);

@@ -121,6 +121,11 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
         sg.exec->auto_math = e.auto_math;
         sg.exec->is_stage = true;
         sg.exec->strict_rows = strict_rows;
+        // only an index (iota) makes a stage depend on an axis that none of its inputs spans
+        uint32_t iota_axes = 0;
+        for (const Node &nd : sg.exec->g.nodes) if (nd.kind == NodeKind::Iota) iota_axes |= 1u << nd.index;
+        sg.exec->has_forced_full = iota_axes != 0;
+        for (int d = 0; d < kMaxDims; d++) sg.exec->forced_full[d] = (d < g.ndim && (iota_axes >> d & 1u)) ? full[d] : 1;
         ewf_status s2 = finalize_graph(sg.exec->g);
         if (s2 != EWF_OK) return s2;
         std::vector<ewf_tensor> tin, tout;

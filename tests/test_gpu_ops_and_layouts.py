@@ -976,3 +976,19 @@ def test_softmax_over_an_axis_of_extent_one(oracle, G):
     for name, g_, w_ in zip(("max", "expsum", "lse", "p"), got, want):
         assert np.array_equal(g_, w_, equal_nan=True) if name == "max" else True
         G.h.compare(name, g_, w_, 1e-6, 1e-7)
+
+
+def test_reductions_of_an_index_in_a_plan_of_several_passes(oracle, G):
+    rng = np.random.default_rng(196)
+    x = rng.standard_normal((3, 64)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    s.output(s.reduce("max", s.iota(1), (0, 1), keep=True), "i32")
+    s.output(s.reduce("min", xi, (1,)), "f32")
+    s.output(s.iota(0), "i32")
+    s.output(s.reduce("sum", s.apply("where", s.apply("gt", xi, s.const(0.0)), s.iota(1), s.const(0, "i32")), (0,)), "i32")
+    expr, got = run_spec(G, s, [x])
+    want = oracle.evaluate(s, [x])
+    assert got[0].item() == 63 and [g_.shape for g_ in got] == [(1, 1), (3,), (3, 1), (64,)]
+    for g_, w_ in zip(got, want):
+        assert np.array_equal(g_, w_)

@@ -629,3 +629,33 @@ def test_prepared_sequence_stops_at_the_failing_call():
     assert ewf._lib.ewf_run_sequence(None, 3, None) == ewf.EINVAL
     assert ewf._lib.ewf_run_call(None) == ewf.EINVAL
     del good
+
+
+def test_stages_inherit_the_extent_of_an_axis_only_an_index_spans():
+    # max over both axes of the column index, beside a reduction over another set of axes: the
+    # stage that reduces the index reads no input, so the extent of its axis comes from the whole expression
+    s = GraphSpec(2)
+    x = s.input("f32", (False, False))
+    s.output(s.reduce("max", s.iota(1), (0, 1), keep=True), "i32")
+    s.output(s.reduce("min", x, (0,)), "f32")
+    s.output(s.iota(0), "i32")                                      # an output that is an index: shape [rows, 1]
+    e = ewf.Expression(s)
+    ins = [ref(BASE, (3, 64))]
+    assert e.output_shapes(ins) == [(1, 1), (64,), (3, 1)]
+    e.plan(ins, [ref(BASE + 4096, (1, 1)), ref(BASE + 8192, (64,)), ref(BASE + 12288, (3, 1))])
+    info = e.info()
+    assert info["kernel_class"] == "multi"
+    stages = [(e.info(k)["extent"], e.source(k)) for k in range(info["grid_blocks"])]
+    index_stage = [ext for ext, src in stages if "p.in0" not in src.split("ewf_kernel", 1)[1]]
+    assert index_stage and all(int(np.prod(ext)) == 64 for ext in index_stage), [ext for ext, _ in stages]   # 64 columns, not a single element
+
+
+def test_an_input_no_output_uses_is_never_read():
+    # a permuted operand would be staged through LDS, but nothing uses it: it must not appear in the kernel
+    s = GraphSpec(2)
+    unused = s.input("f32", (False, False)); y = s.input("i32", (False, False))
+    s.apply("tanh", unused)
+    s.output(y, "i32")
+    e = ewf.Expression(s, block_threads=64)
+    e.plan([ref(BASE, (512, 300), (1, 512)), ref(BASE + (1 << 30), (512, 300))], [ref(BASE + (2 << 30), (512, 300))])
+    assert e.info()["staged_operands"] == 0 and "q_in0" not in e.source()
