@@ -1,0 +1,104 @@
+"""GPU parity on randomly drawn reduction workloads at sizes where the planner leaves the small-problem
+paths: many short rows (several rows per wavefront), softmax chains with and without an arg-max,
+row normalisation, and sums / minima over any set of axes of tensors of about a million elements
+(column kernels, lanes over an outer index, reductions taken in two steps)."""
+import numpy as np
+import pytest
+
+from workloads import GraphSpec
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx():
+    import torch
+    import tests.harness as h
+    from paper_1605_02688_amd import ewf
+
+    class Ctx:
+        pass
+    G = Ctx(); G.torch, G.h, G.ewf = torch, h, ewf
+    return G
+
+
+def _check(G, oracle, tag, s, inputs, tols):
+    import tests.test_gpu_ops_and_layouts as T
+    want = oracle.evaluate(s, inputs, nthreads=4)
+    expr, got = T.run_spec(G, s, inputs)
+    info = expr.info()
+    klass = info["kernel_class"]
+    if klass == "multi":
+        klass += ":" + "+".join(expr.info(i)["kernel_class"] for i in range(info["grid_blocks"]))
+    print(f"[ok-so-far] {tag} -> {klass}", flush=True)
+    for k, (g_, w_, (rtol, atol)) in enumerate(zip(got, want, tols)):
+        if rtol == 0 and atol == 0:
+            assert np.array_equal(g_, w_, equal_nan=True), f"{tag} output {k}: {np.argwhere(g_ != w_)[:3].tolist()}"
+        else:
+            G.h.compare(f"{tag}.out{k}", g_, w_, rtol, atol)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_short_rows(seed, oracle):
+    G = _ctx()
+    rng = np.random.default_rng(31000 + seed)
+    rows = int(rng.integers(4096, 12000))
+    cols = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 24, 31, 32, 48, 64, 100, 128]))
+    storage = "f16" if rng.integers(0, 3) == 0 else "f32"
+    dt = np.float16 if storage == "f16" else np.float32
+    pad = int(rng.choice([0, 0, 1, 4, 8]))
+    wide = (rng.standard_normal((rows, cols + pad)) * 2).astype(dt)
+    x = wide[:, :cols] if pad else wide
+    t = rng.integers(0, cols, (rows, 1)).astype(np.int32)
+    s = GraphSpec(2)
+    xi = s.input(storage, (False, False)); ti = s.input("i32", (False, True))
+    tols = []
+    kind = int(rng.integers(0, 4))
+    if kind == 0:                                            # plain reductions
+        s.output(s.reduce("sum", xi, (1,)), "f32"); tols.append((1e-5, 2e-5))
+        s.output(s.reduce("max", xi, (1,)), "f32"); tols.append((0, 0))
+        s.output(s.reduce("argmax", xi, (1,), keep=True), "i32"); tols.append((0, 0))
+    elif kind == 1:                                          # softmax probabilities and log-sum-exp
+        m = s.reduce("max", xi, (1,), keep=True); ex = s.apply("exp", s.sub(xi, m)); S = s.reduce("sum", ex, (1,), keep=True)
+        s.output(s.div(ex, S), storage); tols.append((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3))
+        s.output(s.add(m, s.apply("log", S)), "f32"); tols.append((1e-5, 2e-6))
+    elif kind == 2:                                          # cross-entropy with arg-max and mean
+        m = s.reduce("max", xi, (1,), keep=True); ex = s.apply("exp", s.sub(xi, m)); S = s.reduce("sum", ex, (1,), keep=True)
+        xt = s.reduce("sum", s.apply("where", s.apply("eq", s.iota(1), ti), xi, s.const(0.0)), (1,), keep=True)
+        loss = s.sub(s.add(m, s.apply("log", S)), xt)
+        s.output(loss, "f32"); tols.append((1e-5, 2e-6))
+        s.output(s.reduce("argmax", xi, (1,)), "i32"); tols.append((0, 0))
+        s.output(s.div(s.reduce("sum", loss, (0,)), s.const(float(rows))), "f32"); tols.append((1e-5, 1e-6))
+    else:                                                    # mean and variance along the row, normalised output
+        inv = s.const(1.0 / cols)
+        mean = s.mul(s.reduce("sum", xi, (1,), keep=True), inv)
+        cen = s.sub(xi, mean)
+        var = s.mul(s.reduce("sum", s.apply("sqr", cen), (1,), keep=True), inv)
+        s.output(s.div(cen, s.apply("sqrt", s.add(var, s.const(1e-3)))), "f32"); tols.append((5e-5, 5e-5))
+        s.output(var, "f32"); tols.append((2e-5, 1e-6))
+    tag = f"rows seed {seed}: {rows} x {cols} {storage} padded by {pad}, kind {kind}"
+    print(f"[case] {tag}", flush=True)
+    _check(G, oracle, tag, s, [x, t], tols)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_axis_masks(seed, oracle):
+    G = _ctx()
+    rng = np.random.default_rng(41000 + seed)
+    nd = int(rng.integers(3, 5))
+    dims = [int(rng.choice([2, 3, 4, 8, 16, 33, 64, 100])) for _ in range(nd)]
+    big = int(rng.integers(0, nd))
+    dims[big] = max(dims[big], int(1.2e6 / max(1, np.prod(dims) // dims[big])))
+    dims = [min(d, 200000) for d in dims]
+    if np.prod(dims) > 4e6:
+        dims[big] = max(2, int(4e6 / (np.prod(dims) // dims[big])))
+    axes = tuple(sorted(rng.choice(nd, size=int(rng.integers(1, nd)), replace=False).tolist()))
+    y = rng.uniform(0.5, 1.5, dims).astype(np.float32) * np.where(rng.random(dims) < 0.5, -1, 1).astype(np.float32)
+    s = GraphSpec(nd)
+    yi = s.input("f32", (False,) * nd)
+    s.output(s.reduce("sum", yi, axes), "f32"); s.output(s.reduce("min", yi, axes, keep=True), "f32")
+    tols = [(1e-5, 1e-4), (0, 0)]
+    if rng.integers(0, 2):
+        s.output(s.apply("abs", yi), "f32"); tols.append((0, 0))
+    tag = f"axes seed {seed}: {dims} reduced over {axes}"
+    print(f"[case] {tag}", flush=True)
+    _check(G, oracle, tag, s, [y], tols)
