@@ -992,3 +992,31 @@ def test_reductions_of_an_index_in_a_plan_of_several_passes(oracle, G):
     assert got[0].item() == 63 and [g_.shape for g_ in got] == [(1, 1), (3,), (3, 1), (64,)]
     for g_, w_ in zip(got, want):
         assert np.array_equal(g_, w_)
+
+
+@pytest.mark.parametrize("shape,axis,opts", [((300, 1000), 1, {}), ((6000, 12), 1, {}), ((5, 70000), 1, {}), ((300, 1000), 1, {"split_rows": 1}),
+                                             ((700, 40), 0, {}), ((64, 33, 20), 1, {})])
+def test_softmax_in_place(shape, axis, opts, oracle, G):
+    # the probabilities overwrite the logits (exact alias), in every kernel class and in plans of several passes:
+    # every element is read for the last time by the thread that then writes it, after all reductions are done
+    torch = G.torch
+    rng = np.random.default_rng(197)
+    x = (rng.standard_normal(shape) * 3).astype(np.float32)
+    nd = len(shape)
+    s = GraphSpec(nd)
+    xi = s.input("f32", (False,) * nd)
+    m = s.reduce("max", xi, (axis,), keep=True)
+    ex = s.apply("exp", s.sub(xi, m))
+    S = s.reduce("sum", ex, (axis,), keep=True)
+    s.output(s.div(ex, S), "f32")
+    s.output(s.add(m, s.apply("log", S)), "f32")
+    want_p, want_l = oracle.evaluate(s, [x], nthreads=4)
+    t = torch.from_numpy(x.copy()).cuda()
+    lse = torch.empty(want_l.shape, dtype=torch.float32, device="cuda")
+    expr = G.ewf.Expression(s, **opts)
+    ws = G.h.make_workspace(expr, [t], [t, lse])
+    print(f"[case] softmax in place {shape} axis {axis} {opts} -> {expr.info()['kernel_class']}", flush=True)
+    expr.run([t], [t, lse], (), ws, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    G.h.compare("p", t.cpu().numpy(), want_p, 1e-5, 1e-8)
+    G.h.compare("lse", lse.cpu().numpy(), want_l, 1e-5, 2e-6)
