@@ -1,5 +1,6 @@
 """GPU parity of the five workloads against the oracle, at sizes the oracle finishes in
 seconds that still span several tiles and a ragged tail."""
+import numpy as np
 import pytest
 
 from workloads import configs as wl
@@ -104,3 +105,25 @@ def test_options_do_not_change_results(case, oracle, H):
             H.compare(f"{w.name}.{name} {opts}", g, o, rtol, atol)
         ran += 1
     assert ran >= len(OPTION_SETS) - 3
+
+
+# Partial results are folded in a fixed order by a second kernel (no atomics), so a workload gives
+# the same bits on every run, whatever the workspace held before.
+@pytest.mark.parametrize("case", ["c3_rows64", "c4_small", "c2b_full", "c3b_rows64", "c4b_small"])
+def test_reductions_are_bitwise_reproducible(case, H):
+    import torch
+    from paper_1605_02688_amd import ewf
+    w = CASES[case]()
+    expr = ewf.Expression(w.spec)
+    _bufs, ins = H.device_inputs(w)
+    runs = []
+    for fill in (0, -1, 0x7fc00000):
+        outs = H.alloc_outputs(expr, w.spec, ins)
+        nbytes = expr.plan(ins, outs)
+        ws = torch.full((max(nbytes, 4) // 4 + 1,), fill, dtype=torch.int32, device="cuda") if nbytes else None
+        expr.run(ins, outs, w.scalars, ws, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        runs.append([o.cpu().numpy().view(np.uint8 if o.element_size() == 1 else (np.uint16 if o.element_size() == 2 else np.uint32)) for o in outs])
+    for other in runs[1:]:
+        for a, b in zip(runs[0], other):
+            assert np.array_equal(a, b)
