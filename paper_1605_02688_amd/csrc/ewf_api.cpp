@@ -259,14 +259,14 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
     }
 
     if (plan->kclass == KernelClass::Row) {
-        // rows of up to 512 bytes, many of them: several rows per wavefront instead of a wavefront
+        // rows of up to 1024 bytes, many of them: several rows per wavefront instead of a wavefront
         // (or more) per row.  Sum over float32 rows, 134 MB, row class / lane class in TB/s:
-        // 8 columns 0.4 / 5.1, 16: 0.8 / 5.1, 32: 1.5 / 5.3, 64: 2.8 / 5.3, 128: 4.7 / 5.4, 256: 6.1 / 5.2
+        // 8 columns 0.4 / 6.0, 16: 0.8 / 6.4, 32: 1.5 / 6.7, 64: 2.8 / 6.7, 128: 4.7 / 6.7, 256: 6.1 / 6.6
         int widest = 2;
         for (const Operand &op : c.ops) if (op.stride[c.rank - 1] != 0) widest = std::max(widest, op.storage == EWF_F16 ? 2 : 4);
         int64_t rows_ = 1;
         for (int d = 0; d < c.rank - 1; d++) rows_ *= c.extent[d];
-        if (c.extent[c.rank - 1] * widest <= 512 && c.extent[c.rank - 1] <= 64 * c.vec && rows_ >= 4096 && e.opts.split_rows != 1) {
+        if (c.extent[c.rank - 1] * widest <= 1024 && c.extent[c.rank - 1] <= 64 * c.vec && rows_ >= 4096 && e.opts.split_rows != 1) {
             plan->kclass = KernelClass::Lane;
             st = generate(e, *plan);
             if (st == EWF_EUNSUPPORTED) plan->kclass = KernelClass::Row;      // e.g. too many row operands for one thread

@@ -895,7 +895,7 @@ def test_short_rows_share_a_wavefront(cols, storage, oracle, G):
     print(f"[case] short rows {rows} x {cols} {storage}", flush=True)
     expr, got = run_spec(G, s, [x, t])
     itemsize = 4 if storage == "f32" else 2
-    assert expr.info()["kernel_class"] == ("lane" if cols * itemsize <= 512 else "row"), expr.info()
+    assert expr.info()["kernel_class"] == ("lane" if cols * itemsize <= 1024 else "row"), expr.info()
     want = oracle.evaluate(s, [x, t], nthreads=4)
     G.h.compare("p", got[0], want[0], *((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3)))
     G.h.compare("loss", got[1], want[1], 1e-5, 2e-6)
@@ -912,7 +912,7 @@ def test_short_rows_share_a_wavefront(cols, storage, oracle, G):
     scale = rng.standard_normal((rows, 1)).astype(np.float32)
     expr, got = run_spec(G, s2, [view, scale])
     # the slice is not aligned for wide accesses: single elements, up to 64 of them per row
-    assert expr.info()["kernel_class"] == ("lane" if cols <= 64 and cols * itemsize <= 512 else "row")
+    assert expr.info()["kernel_class"] == ("lane" if cols <= 64 and cols * itemsize <= 1024 else "row")
     want = oracle.evaluate(s2, [view, scale], nthreads=4)
     G.h.compare("wsum", got[0], want[0], 1e-5, 1e-5); G.h.compare("prod", got[1], want[1], 1e-5, 1e-6)
 
