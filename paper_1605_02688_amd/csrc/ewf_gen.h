@@ -563,21 +563,32 @@ struct Gen {
     // What one thread does with the folded accumulator `tot` of reduction group `group`: the
     // results of the reductions, the single-term sums it reads itself, the values computed from
     // them, and the stores of the per-group outputs.
+    // A caller that already has the group's coordinates passes their names in `coords` (one per
+    // dimension, read for the kept ones) and spares the divisions; `store`, when given, emits
+    // the store of output operand k instead of the plain scalar store.
+    typedef std::function<void(int k, const std::string &value, const std::string &ind)> GroupStore;
     void emit_group_epilogue(const std::vector<int> &level, const std::vector<int> &group_out_ops,
-                             const std::vector<Gather> &gathers, const std::string &ind)
+                             const std::vector<Gather> &gathers, const std::string &ind,
+                             const std::vector<std::string> *coords = nullptr, const GroupStore *store = nullptr)
     {
         std::vector<int> all_dims;
         for (int d = 0; d < R; d++) all_dims.push_back(d);
-        o << ind << "idx_t g_ = group;\n";
-        for (int d = R - 1; d >= 0; d--) {
-            if (c.reduced[d]) { o << ind << "const idx_t o" << d << " = 0;\n"; continue; }
-            bool last_kept = true;
-            for (int d2 = d - 1; d2 >= 0; d2--) if (!c.reduced[d2]) last_kept = false;
-            if (!last_kept) o << ind << "const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
-            else o << ind << "const idx_t o" << d << " = g_;\n";
+        if (coords) {
+            for (int d = 0; d < R; d++)
+                o << ind << "const idx_t o" << d << " = " << (c.reduced[d] ? std::string("0") : (*coords)[d]) << ";\n";
+        }
+        else {
+            o << ind << "idx_t g_ = group;\n";
+            for (int d = R - 1; d >= 0; d--) {
+                if (c.reduced[d]) { o << ind << "const idx_t o" << d << " = 0;\n"; continue; }
+                bool last_kept = true;
+                for (int d2 = d - 1; d2 >= 0; d2--) if (!c.reduced[d2]) last_kept = false;
+                if (!last_kept) o << ind << "const idx_t o" << d << " = g_ % p.ext[" << d << "]; g_ /= p.ext[" << d << "];\n";
+                else o << ind << "const idx_t o" << d << " = g_;\n";
+            }
+            o << ind << "(void)g_;\n";
         }
         for (int d = 0; d < R; d++) o << ind << "(void)o" << d << ";\n";
-        o << ind << "(void)g_;\n";
         emit_results("tot", level, ind);
         std::vector<int> gt;
         for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
@@ -615,7 +626,9 @@ struct Gen {
             int v = g.outputs[op.index].value;
             const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
             base_once(k);
-            o << ind << "q_" << opname(k) << "[0] = " << cv << "(v" << v << ");\n";
+            const std::string value = std::string(cv) + "(v" + std::to_string(v) + ")";
+            if (store) (*store)(k, value, ind);
+            else o << ind << "q_" << opname(k) << "[0] = " << value << ";\n";
         }
     }
 

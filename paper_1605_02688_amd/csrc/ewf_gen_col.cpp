@@ -61,10 +61,20 @@ ewf_status Gen::gen_col()
     for (int d = R - 2; d >= 0; d--) if (!c.reduced[d]) { dK = d; break; }
     int TY = block / TX, TZ = 1;
     {
-        int64_t rows_needed = c.extent[dR];
+        // (the patch of one outer index has to fit a wavefront, inside which its row groups fold)
+        // A thread takes up to four rows, but the lanes of one outer index should still read at
+        // least a 128-byte line together ([2097152, 4, 8] over axis 1: 3.1 TB/s with four row lanes,
+        // 1.7 TB/s with four rows per thread and 32-byte pieces; [262144, 16, 16]: 5.4 TB/s with four
+        // rows per thread, 3.0 TB/s with sixteen row lanes and a quarter of the work per workgroup).
+        int min_isz = 4;
+        for (const Operand &op : c.ops) if (op.stride[in_d] != 0) min_isz = std::min(min_isz, isz(op.storage));
+        const int rows_per_thread = e.opts.unroll > 0 ? e.opts.unroll : small ? 1 : 4;
+        int ty_cap = 1;
+        while (ty_cap < c.extent[dR] && ty_cap < block / TX) ty_cap *= 2;
         int ty = 1;
-        while (ty < rows_needed && ty < block / TX) ty *= 2;
-        if (dK >= 0 && nreduced == 1 && TX * ty <= 32 && c.extent[dK] >= 2 && e.opts.tile_elems <= 0) {
+        while (ty < ceil_div(c.extent[dR], rows_per_thread) && ty < ty_cap) ty *= 2;
+        while (ty < ty_cap && TX * ty * VEC * min_isz < 128) ty *= 2;
+        if (dK >= 0 && nreduced == 1 && TX * ty <= 64 && block / (TX * ty) >= 2 && c.extent[dK] >= 2 && e.opts.tile_elems <= 0) {
             TY = ty;
             TZ = block / (TX * TY);
         }
@@ -81,11 +91,22 @@ ewf_status Gen::gen_col()
         default: break;
         }
     }
-    const int U = e.opts.unroll > 0 ? e.opts.unroll : small ? 1 : heavy >= 4 ? 2 : 4;
+    int U = e.opts.unroll > 0 ? e.opts.unroll : small ? 1 : heavy >= 4 ? 2 : 4;
+    // Outer-index lanes whose rows need fewer loads than that take further outer indices, UZ in
+    // all, so that a thread still has U loads in flight: with one 16-byte load per thread and
+    // tile the kernel waits on memory latency (3.1 to 3.7 TB/s for [2097152, 4, 8] over axis 1).
+    int UZ = 1;
+    if (TZ > 1) {
+        const int rpt = (int)ceil_div(c.extent[dR], TY);
+        if (rpt <= U) {
+            while (UZ * 2 * rpt <= U && (int64_t)UZ * TZ < c.extent[dK]) UZ *= 2;
+            U = rpt;
+        }
+    }
     int64_t T[kMaxDims];
     for (int d = 0; d < kMaxDims; d++) T[d] = 1;
     T[in_d] = TK;
-    if (TZ > 1) T[dK] = std::min<int64_t>(c.extent[dK], TZ);
+    if (TZ > 1) T[dK] = std::min<int64_t>(c.extent[dK], (int64_t)TZ * UZ);
     {
         // rows per tile: enough tiles to fill the chip, but whole trips of the workgroup
         int64_t other = ceil_div(c.extent[in_d], TK);
@@ -125,6 +146,9 @@ ewf_status Gen::gen_col()
     std::vector<int> all_dims;
     for (int d = 0; d < R; d++) all_dims.push_back(d);
 
+    const std::string tzs = UZ > 1 ? "tzz_" : "tz";          // the thread's outer index inside the tile
+    const std::string okname = UZ > 1 ? "zok_" : "colok_";   // its columns (and outer index) exist
+    std::string xi = "u";                                    // where a row's loaded values are kept
     auto off_expr = [&](int k) {
         // offset of (row r_, column cc_) from the tile's origin
         const Operand &op = c.ops[k];
@@ -133,7 +157,7 @@ ewf_status Gen::gen_col()
         if (op.stride[dR] != 0) s = "(ioff_t)r_ * (ioff_t)p.st_" + nm + "[" + std::to_string(dR) + "]";
         if (TZ > 1 && op.stride[dK] != 0) {
             if (!s.empty()) s += " + ";
-            s += "(ioff_t)tz * (ioff_t)p.st_" + nm + "[" + std::to_string(dK) + "]";
+            s += "(ioff_t)" + tzs + " * (ioff_t)p.st_" + nm + "[" + std::to_string(dK) + "]";
         }
         if (op.stride[in_d] != 0) {
             if (!s.empty()) s += " + ";
@@ -160,109 +184,165 @@ ewf_status Gen::gen_col()
     for (int k : ew_out_ops) emit_base(k, all_dims, ind);
     o << ind << "const int cc_ = tx * EWF_VEC;\n";
     o << ind << "const bool colok_ = cc_ < " << TK << " && o" << in_d << " + cc_ < p.ext[" << in_d << "]"
-      << (TZ > 1 ? " && o" + std::to_string(dK) + " + tz < p.ext[" + std::to_string(dK) + "]" : std::string("")) << ";\n";
+      << (TZ > 1 && UZ == 1 ? " && o" + std::to_string(dK) + " + tz < p.ext[" + std::to_string(dK) + "]" : std::string("")) << ";\n";
     o << ind << "const int rows_ = (int)((p.ext[" << dR << "] - o" << dR << ") < " << TR << " ? (p.ext[" << dR << "] - o" << dR << ") : " << TR << ");\n";
-    o << ind << "Acc acc[EWF_VEC];\n";
-    o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_identity();\n";
-    o << ind << "for (int r0_ = ty; r0_ < rows_; r0_ += EWF_TY * " << U << ") {\n";
-    // loads of U rows, then their arithmetic
-    for (int k : load_ops) {
-        const Operand &op = c.ops[k];
-        if (op.stride[in_d] == 0) o << ind << "    " << ctype(op.storage) << " x_" << opname(k) << "[" << U << "];\n";
-        else o << ind << "    ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
-    }
-    o << ind << "    #pragma unroll\n" << ind << "    for (int u = 0; u < " << U << "; ++u) {\n";
-    o << ind << "        const int r_ = r0_ + u * EWF_TY;\n";
-    o << ind << "        if (!colok_ || r_ >= rows_) continue;\n";
-    for (int k : load_ops) {
-        const Operand &op = c.ops[k];
-        const std::string nm = opname(k);
-        if (op.stride[in_d] == 0)
-            o << ind << "        x_" << nm << "[u] = *ewf_at(q_" << nm << ", " << off_expr(k) << ");\n";
-        else if (op.access == Access::Vector)
-            o << ind << "        x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "));\n";
-        else {
-            o << ind << "        { const ioff_t b_ = " << off_expr(k) << ";\n";
-            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) x_" << nm << "[u].e[e_] = *ewf_at(q_" << nm
-              << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
-        }
-    }
-    o << ind << "    }\n";
-    o << ind << "    #pragma unroll\n" << ind << "    for (int u = 0; u < " << U << "; ++u) {\n";
-    o << ind << "        const int r_ = r0_ + u * EWF_TY;\n";
-    o << ind << "        if (!colok_ || r_ >= rows_) continue;\n";
-    for (int k : ew_out_ops) o << ind << "        ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
-    o << ind << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
     EmitCtx cx;
     cx.input = [&](int k) {
         const Operand &op = c.ops[k];
-        if (op.stride[in_d] == 0) return "ewf_in(x_" + opname(k) + "[u])";
-        if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(x_" + opname(k) + "[u], e_)";
-        return "ewf_in(x_" + opname(k) + "[u].e[e_])";
+        if (op.stride[in_d] == 0) return "ewf_in(x_" + opname(k) + "[" + xi + "])";
+        if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(x_" + opname(k) + "[" + xi + "], e_)";
+        return "ewf_in(x_" + opname(k) + "[" + xi + "].e[e_])";
     };
     cx.coord = [&](int d) {
         std::string s = "o" + std::to_string(d);
         if (d == dR) s += " + r_";
-        if (TZ > 1 && d == dK) s += " + tz";
+        if (TZ > 1 && d == dK) s += " + " + tzs;
         if (d == in_d) s += " + cc_ + e_";
         return s;
     };
-    emit_values(need, cx, ind + "            ");
-    emit_accumulate("acc[e_]", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "            ");
-    for (int k : ew_out_ops) {
-        const Operand &op = c.ops[k];
-        const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
-        o << ind << "            y_" << opname(k) << ".e[e_] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
-    }
-    o << ind << "        }\n";
-    for (int k : ew_out_ops) {
-        const Operand &op = c.ops[k];
-        const std::string nm = opname(k);
-        if (op.access == Access::Vector)
-            o << ind << "        " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "), y_" << nm << ");\n";
-        else {
-            o << ind << "        { const ioff_t b_ = " << off_expr(k) << ";\n";
-            o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) *ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
-              << "[" << in_d << "]) = y_" << nm << ".e[e_]; }\n";
+    auto emit_x_arrays = [&](const std::string &in2, int n) {
+        for (int k : load_ops) {
+            const Operand &op = c.ops[k];
+            if (op.stride[in_d] == 0) o << in2 << ctype(op.storage) << " x_" << opname(k) << "[" << n << "];\n";
+            else o << in2 << "ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << n << "];\n";
         }
-    }
-    o << ind << "    }\n";
-    o << ind << "}\n";
-    // the row groups inside a wavefront (lanes that differ by a multiple of TX) fold with lane
+    };
+    // the loads of the U rows of one trip (first row r0), kept at index xi
+    auto emit_loads = [&](const std::string &in2, const std::string &r0) {
+        o << in2 << "#pragma unroll\n" << in2 << "for (int u = 0; u < " << U << "; ++u) {\n";
+        o << in2 << "    const int r_ = " << r0 << " + u * EWF_TY;\n";
+        o << in2 << "    if (!" << okname << " || r_ >= rows_) continue;\n";
+        for (int k : load_ops) {
+            const Operand &op = c.ops[k];
+            const std::string nm = opname(k);
+            if (op.stride[in_d] == 0)
+                o << in2 << "    x_" << nm << "[" << xi << "] = *ewf_at(q_" << nm << ", " << off_expr(k) << ");\n";
+            else if (op.access == Access::Vector)
+                o << in2 << "    x_" << nm << "[" << xi << "] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "));\n";
+            else {
+                o << in2 << "    { const ioff_t b_ = " << off_expr(k) << ";\n";
+                o << in2 << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) x_" << nm << "[" << xi << "].e[e_] = *ewf_at(q_" << nm
+                  << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
+            }
+        }
+        o << in2 << "}\n";
+    };
+    // their arithmetic, accumulation and element-wise stores
+    auto emit_arith = [&](const std::string &in2, const std::string &r0) {
+        o << in2 << "#pragma unroll\n" << in2 << "for (int u = 0; u < " << U << "; ++u) {\n";
+        o << in2 << "    const int r_ = " << r0 << " + u * EWF_TY;\n";
+        o << in2 << "    if (!" << okname << " || r_ >= rows_) continue;\n";
+        for (int k : ew_out_ops) o << in2 << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
+        o << in2 << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+        emit_values(need, cx, in2 + "        ");
+        emit_accumulate("acc[e_]", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, in2 + "        ");
+        for (int k : ew_out_ops) {
+            const Operand &op = c.ops[k];
+            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
+            o << in2 << "        y_" << opname(k) << ".e[e_] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
+        }
+        o << in2 << "    }\n";
+        for (int k : ew_out_ops) {
+            const Operand &op = c.ops[k];
+            const std::string nm = opname(k);
+            if (op.access == Access::Vector)
+                o << in2 << "    " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "), y_" << nm << ");\n";
+            else {
+                o << in2 << "    { const ioff_t b_ = " << off_expr(k) << ";\n";
+                o << in2 << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) *ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
+                  << "[" << in_d << "]) = y_" << nm << ".e[e_]; }\n";
+            }
+        }
+        o << in2 << "}\n";
+    };
+    // The row groups inside a wavefront (lanes that differ by a multiple of TX) fold with lane
     // exchanges in a fixed butterfly; the wavefronts then meet in LDS and the first folds them
-    // in order
-    for (int m = TX; m < (TZ > 1 ? TX * TY : 64); m *= 2)
-        o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], ewf_lane_xor(acc[e_], " << m << "));\n";
-    if (NW > 1 && TZ == 1) {
-        o << ind << "if (tid >= 64 && (tid & 63) < EWF_TX) { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) sm_col[(((tid >> 6) - 1) * EWF_TX + tx) * EWF_VEC + e_] = acc[e_]; }\n";
-        o << ind << "__syncthreads();\n";
-        o << ind << "if (tid < EWF_TX) {\n";
-        o << ind << "    for (int w_ = 0; w_ < EWF_NWAVES - 1; ++w_)\n";
-        o << ind << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], sm_col[(w_ * EWF_TX + tx) * EWF_VEC + e_]);\n";
+    // in order.  Then the tile's partial results (or, with one tile per column, the results) go out.
+    auto emit_fold_and_write = [&](const std::string &in2) {
+        for (int m = TX; m < (TZ > 1 ? TX * TY : 64); m *= 2)
+            o << in2 << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], ewf_lane_xor(acc[e_], " << m << "));\n";
+        if (NW > 1 && TZ == 1) {
+            o << in2 << "if (tid >= 64 && (tid & 63) < EWF_TX) { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) sm_col[(((tid >> 6) - 1) * EWF_TX + tx) * EWF_VEC + e_] = acc[e_]; }\n";
+            o << in2 << "__syncthreads();\n";
+            o << in2 << "if (tid < EWF_TX) {\n";
+            o << in2 << "    for (int w_ = 0; w_ < EWF_NWAVES - 1; ++w_)\n";
+            o << in2 << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_combine()(acc[e_], sm_col[(w_ * EWF_TX + tx) * EWF_VEC + e_]);\n";
+            o << in2 << "}\n";
+        }
+        o << in2 << "if (" << (TZ > 1 ? "ty == 0" : "tid < EWF_TX") << " && " << okname << ") {\n";
+        o << in2 << "    size_t group = 0, slot = 0;\n";
+        for (int d = 0; d < R; d++) {
+            if (c.reduced[d]) o << in2 << "    slot = slot * (size_t)p.ntile[" << d << "] + (size_t)ti" << d << ";\n";
+            else if (d == in_d) o << in2 << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + cc_);\n";
+            else if (TZ > 1 && d == dK) o << in2 << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + " << tzs << ");\n";
+            else o << in2 << "    group = group * (size_t)p.ext[" << d << "] + (size_t)o" << d << ";\n";
+        }
+        if (one_tile) {
+            // every column is complete here: its results are written straight away, from the
+            // coordinates at hand, a vector of columns per store where the output allows it
+            // (element by element, the 4-byte stores of [2097152, 2, 16] summed over axis 1 took
+            // longer than reading the input)
+            o << in2 << "    (void)slot; (void)group;\n";
+            std::vector<std::string> coords(R);
+            for (int d = 0; d < R; d++) coords[d] = "gc" + std::to_string(d) + "_";
+            auto vector_out = [&](int k) { return VEC > 1 && c.ops[k].access == Access::Vector && c.ops[k].stride[in_d] == 1; };
+            for (int k : group_out_ops)
+                if (vector_out(k))
+                    o << in2 << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> yg_" << opname(k) << "; "
+                      << ctype(c.ops[k].storage) << " *qg_" << opname(k) << " = nullptr;\n";
+            o << in2 << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+            o << in2 << "        const Acc tot = acc[e_];\n";
+            for (int d = 0; d < R; d++) {
+                if (c.reduced[d]) continue;
+                o << in2 << "        const idx_t gc" << d << "_ = o" << d;
+                if (d == in_d) o << " + cc_ + e_";
+                else if (TZ > 1 && d == dK) o << " + " << tzs;
+                o << ";\n";
+            }
+            const GroupStore store = [&](int k, const std::string &value, const std::string &in3) {
+                const std::string nm = opname(k);
+                if (vector_out(k)) o << in3 << "if (e_ == 0) qg_" << nm << " = q_" << nm << ";\n" << in3 << "yg_" << nm << ".e[e_] = " << value << ";\n";
+                else o << in3 << "q_" << nm << "[0] = " << value << ";\n";
+            };
+            o << in2 << "        {\n";
+            emit_group_epilogue(level, group_out_ops, std::vector<Gather>(), in2 + "            ", &coords, &store);
+            o << in2 << "        }\n";
+            o << in2 << "    }\n";
+            for (int k : group_out_ops)
+                if (vector_out(k))
+                    o << in2 << "    " << (c.ops[k].stream ? "ewf_st_nt<" : "ewf_st<") << ctype(c.ops[k].storage) << ", EWF_VEC>(qg_" << opname(k) << ", yg_" << opname(k) << ");\n";
+        }
+        else if (fin_lanes) o << in2 << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[(group + e_) * (size_t)p.nslots + slot] = acc[e_];\n";
+        else o << in2 << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[slot * (size_t)p.nrows + group + e_] = acc[e_];\n";
+        o << in2 << "}\n";
+        if (NW > 1 && TZ == 1) o << in2 << "__syncthreads();\n";
+    };
+    const std::string acc_init = "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_identity();\n";
+    if (UZ == 1) {
+        o << ind << "Acc acc[EWF_VEC];\n" << ind << acc_init;
+        o << ind << "for (int r0_ = ty; r0_ < rows_; r0_ += EWF_TY * " << U << ") {\n";
+        emit_x_arrays(ind + "    ", U);
+        emit_loads(ind + "    ", "r0_");
+        emit_arith(ind + "    ", "r0_");
+        o << ind << "}\n";
+        emit_fold_and_write(ind);
+    }
+    else {
+        // all the rows of a patch fit one trip: the loads of the thread's UZ outer indices go out
+        // together, then each index is folded and written in turn
+        const std::string zhead = "    const int tzz_ = tz + z_ * EWF_TZ;\n" + ind +
+            "    const bool zok_ = colok_ && o" + std::to_string(dK) + " + tzz_ < p.ext[" + std::to_string(dK) + "];\n";
+        xi = "z_ * " + std::to_string(U) + " + u";
+        emit_x_arrays(ind, UZ * U);
+        o << ind << "#pragma unroll\n" << ind << "for (int z_ = 0; z_ < " << UZ << "; ++z_) {\n" << ind << zhead;
+        emit_loads(ind + "    ", "ty");
+        o << ind << "}\n";
+        o << ind << "#pragma unroll\n" << ind << "for (int z_ = 0; z_ < " << UZ << "; ++z_) {\n" << ind << zhead;
+        o << ind << "    Acc acc[EWF_VEC];\n" << ind << "    " << acc_init;
+        emit_arith(ind + "    ", "ty");
+        emit_fold_and_write(ind + "    ");
         o << ind << "}\n";
     }
-    o << ind << "if (" << (TZ > 1 ? "ty == 0" : "tid < EWF_TX") << " && colok_) {\n";
-    o << ind << "    size_t group = 0, slot = 0;\n";
-    for (int d = 0; d < R; d++) {
-        if (c.reduced[d]) o << ind << "    slot = slot * (size_t)p.ntile[" << d << "] + (size_t)ti" << d << ";\n";
-        else if (d == in_d) o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + cc_);\n";
-        else if (TZ > 1 && d == dK) o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)(o" << d << " + tz);\n";
-        else o << ind << "    group = group * (size_t)p.ext[" << d << "] + (size_t)o" << d << ";\n";
-    }
-    if (one_tile) {
-        // every column is complete here: its results are written straight away
-        o << ind << "    (void)slot;\n";
-        o << ind << "    const size_t group0_ = group;\n";
-        o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
-        o << ind << "        const Acc tot = acc[e_];\n";
-        o << ind << "        const idx_t group = (idx_t)(group0_ + e_);\n";
-        emit_group_epilogue(level, group_out_ops, std::vector<Gather>(), ind + "        ");
-        o << ind << "    }\n";
-    }
-    else if (fin_lanes) o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[(group + e_) * (size_t)p.nslots + slot] = acc[e_];\n";
-    else o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) partials[slot * (size_t)p.nrows + group + e_] = acc[e_];\n";
-    o << ind << "}\n";
-    if (NW > 1 && TZ == 1) o << ind << "__syncthreads();\n";
     o << "    }\n}\n";
 
     // ---- second kernel.  Many slots per column: the partials of a column are contiguous and a
@@ -306,7 +386,9 @@ ewf_status Gen::gen_col()
     }
 
     // ---- launch geometry and argument block
-    int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : (int64_t)1 << 22;
+    // With outer-index lanes a tile is a few KB, too little to pay for a workgroup's start: a
+    // resident grid that walks the tiles is 10 to 25 % faster there (and slower everywhere else).
+    int64_t cap = e.opts.max_blocks > 0 ? e.opts.max_blocks : TZ > 1 ? (int64_t)16 * device_cu_count() : (int64_t)1 << 22;
     p.grid = std::max<int64_t>(1, std::min(ntiles, cap));
     p.lds_bytes = NW > 1 && TZ == 1 ? (int)((NW - 1) * TX * VEC * acc_bytes(level)) : 0;
     if (p.lds_bytes > 60 * 1024) return fail("too many reductions for one column kernel (LDS)");

@@ -939,6 +939,40 @@ def test_short_middle_axis_with_few_columns(shape, axis, oracle, G):
     G.h.compare("argmax", got[2], want[2], 0, 0); G.h.compare("tanh", got[3], want[3], 2e-6, 1e-6)
 
 
+@pytest.mark.parametrize("storage", ["f32", "f16"])
+@pytest.mark.parametrize("shape,axis", [((70001, 4, 8), 1), ((50001, 2, 16), 1), ((20011, 8, 8), 1), ((9001, 16, 16), 1), ((3, 30001, 3, 24), 2)])
+def test_short_middle_axis_at_streaming_size(shape, axis, storage, oracle, G):
+    # the same layout past the size where a thread keeps several loads in flight: threads with few
+    # rows take several outer indices (a ragged count of them here), and the finishing threads
+    # write whole vectors of columns
+    rng = np.random.default_rng(197 + len(shape) + shape[-1])
+    x = (rng.standard_normal(shape) * 2).astype(np.float16 if storage == "f16" else np.float32)
+    nd = len(shape)
+    s = GraphSpec(nd)
+    xi = s.input(storage, (False,) * nd)
+    s.output(s.reduce("sum", xi, (axis,)), "f32")
+    s.output(s.reduce("max", xi, (axis,), keep=True), storage)
+    s.output(s.reduce("argmax", xi, (axis,)), "i32")
+    print(f"[case] {shape} axis {axis} {storage}", flush=True)
+    expr, got = run_spec(G, s, [x])
+    info = expr.info()
+    assert info["kernel_class"] == "col" and info["rank"] == 3 and info["tile"][0] > 1, info
+    assert "yg_out0" in expr.source() and "ewf_finish" not in expr.source()
+    want = oracle.evaluate(s, [x], nthreads=4)
+    G.h.compare("sum", got[0], want[0], 1e-5, 2e-6); G.h.compare("max", got[1], want[1], 0, 0)
+    G.h.compare("argmax", got[2], want[2], 0, 0)
+    # with an element-wise output and an output computed from the sums in the same pass
+    s2 = GraphSpec(nd)
+    xi = s2.input(storage, (False,) * nd)
+    s2.output(s2.apply("tanh", xi), storage)
+    s2.output(s2.apply("sqrt", s2.reduce("sum", s2.mul(xi, xi), (axis,))), "f32")
+    expr, got = run_spec(G, s2, [x])
+    assert expr.info()["kernel_class"] == "col", expr.info()
+    want = oracle.evaluate(s2, [x], nthreads=4)
+    tol = (2e-3, 2e-3) if storage == "f16" else (2e-6, 1e-6)
+    G.h.compare("tanh", got[0], want[0], *tol); G.h.compare("norm", got[1], want[1], 1e-5, 2e-6)
+
+
 def test_rank_zero_and_rank_eight(oracle, G):
     # the smallest and the largest rank the library accepts
     s = GraphSpec(0)
