@@ -108,13 +108,18 @@ ewf_status Gen::gen_col()
     T[in_d] = TK;
     if (TZ > 1) T[dK] = std::min<int64_t>(c.extent[dK], (int64_t)TZ * UZ);
     {
-        // rows per tile: enough tiles to fill the chip, but whole trips of the workgroup
+        // rows per tile: whole trips of the workgroup, and about five workgroups per CU, which all
+        // run at once.  (Measured on 16 MB to 1 GB: 1280 tiles beat 4096 by 5 to 25 % -- fewer
+        // partial results for the second kernel, no trailing round of workgroups -- and fewer
+        // than 1024 leave CUs short of loads in flight.)
         int64_t other = ceil_div(c.extent[in_d], TK);
         for (int d = 0; d < R - 1; d++) if (d != dR) other *= c.extent[d];
-        const int64_t want = (int64_t)16 * device_cu_count();
-        int64_t slices = std::max<int64_t>(1, std::min(ceil_div(want, other), ceil_div(c.extent[dR], (int64_t)TY * U)));
+        const int64_t want = (int64_t)5 * device_cu_count();
+        const int64_t trip = (int64_t)TY * U;
+        int64_t slices = std::max<int64_t>(1, std::min(ceil_div(want, other), ceil_div(c.extent[dR], trip)));
         if (whole_columns || TZ > 1) slices = 1;
         int64_t tr = ceil_div(c.extent[dR], slices);
+        if (slices > 1) tr = std::max(trip, (tr + trip / 2) / trip * trip);
         if (e.opts.tile_elems > 0) tr = std::max<int64_t>(1, e.opts.tile_elems / TK);
         T[dR] = std::min(c.extent[dR], tr);
     }
