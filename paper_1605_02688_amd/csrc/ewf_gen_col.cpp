@@ -74,7 +74,7 @@ ewf_status Gen::gen_col()
         int ty = 1;
         while (ty < ceil_div(c.extent[dR], rows_per_thread) && ty < ty_cap) ty *= 2;
         while (ty < ty_cap && TX * ty * VEC * min_isz < 128) ty *= 2;
-        if (dK >= 0 && nreduced == 1 && TX * ty <= 64 && block / (TX * ty) >= 2 && c.extent[dK] >= 2 && e.opts.tile_elems <= 0) {
+        if (dK >= 0 && TX * ty <= 64 && block / (TX * ty) >= 2 && c.extent[dK] >= 2 && e.opts.tile_elems <= 0) {
             TY = ty;
             TZ = block / (TX * TY);
         }
@@ -134,7 +134,11 @@ ewf_status Gen::gen_col()
 
     const bool one_tile = nslots == 1;
     const int NW = block / 64;
-    const bool fin_lanes = nslots > 16;
+    // The second kernel folds a column's partial results either with the lanes of a workgroup
+    // (many slots) or in one thread per column (few slots, or a moderate number under so many
+    // columns that the threads fill the chip anyway: 65536 columns of 32 slots took 28 us with a
+    // 64-lane workgroup each).
+    const bool fin_lanes = nslots > 16 && !(nslots <= 128 && ngroups >= 64 * nslots);
     const int fin_block = nslots > 256 ? 256 : 64;
 
     // ---- what to evaluate per element
@@ -360,7 +364,7 @@ ewf_status Gen::gen_col()
     o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
     o << "    for (idx_t group = blockIdx.x * 256 + threadIdx.x; group < p.nrows; group += gridDim.x * 256) {\n";
     o << "        Acc tot = partials[group];\n";
-    o << "        for (idx_t s_ = 1; s_ < p.nslots; ++s_) tot = Acc_combine()(tot, partials[(size_t)s_ * (size_t)p.nrows + (size_t)group]);\n";
+    o << "        _Pragma(\"unroll 8\") for (idx_t s_ = 1; s_ < p.nslots; ++s_) tot = Acc_combine()(tot, partials[(size_t)s_ * (size_t)p.nrows + (size_t)group]);\n";
     o << "        idx_t g_ = group;\n";
     for (int d = R - 1; d >= 0; d--) {
         if (c.reduced[d]) { o << "        const idx_t o" << d << " = 0;\n"; continue; }

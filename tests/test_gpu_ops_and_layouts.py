@@ -973,6 +973,27 @@ def test_short_middle_axis_at_streaming_size(shape, axis, storage, oracle, G):
     G.h.compare("tanh", got[0], want[0], *tol); G.h.compare("norm", got[1], want[1], 1e-5, 2e-6)
 
 
+@pytest.mark.parametrize("shape,axes", [((6, 5001, 7, 24), (0, 2)), ((3, 40, 3001, 4, 8), (0, 1, 3)), ((5, 70001, 2, 16), (0, 2))])
+def test_short_middle_axis_among_several_reduced_axes(shape, axes, oracle, G):
+    # outer-index lanes when further reduced axes lie outside: their indices become slots of
+    # partial results that the second kernel folds
+    rng = np.random.default_rng(199 + len(shape))
+    x = (rng.standard_normal(shape) * 2 + 3).astype(np.float32)        # (sums well away from zero)
+    nd = len(shape)
+    s = GraphSpec(nd)
+    xi = s.input("f32", (False,) * nd)
+    s.output(s.reduce("sum", xi, axes), "f32")
+    s.output(s.reduce("max", s.apply("abs", xi), axes, keep=True), "f32")
+    print(f"[case] {shape} axes {axes}", flush=True)
+    expr, got = run_spec(G, s, [x])
+    info = expr.info()
+    assert info["kernel_class"] == "col" and "ewf_finish" in expr.source(), info
+    kept = [d for d in range(info["rank"] - 1) if not info["reduced"][d]]
+    assert info["tile"][kept[-1]] > 1, info                                  # several outer indices per workgroup
+    want = oracle.evaluate(s, [x], nthreads=4)
+    G.h.compare("sum", got[0], want[0], 1e-5, 2e-6); G.h.compare("max", got[1], want[1], 0, 0)
+
+
 def test_rank_zero_and_rank_eight(oracle, G):
     # the smallest and the largest rank the library accepts
     s = GraphSpec(0)
