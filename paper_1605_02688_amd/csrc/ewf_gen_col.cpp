@@ -92,6 +92,9 @@ ewf_status Gen::gen_col()
         }
     }
     int U = e.opts.unroll > 0 ? e.opts.unroll : small ? 1 : heavy >= 4 ? 2 : 4;
+    // (with element-wise outputs, 16 elements per thread and trip: bias + ReLU + column sums on
+    // float16 [401408, 256] took 91 us with two rows of eight in flight, 119 us with four)
+    if (e.opts.unroll <= 0 && !ew_out_ops.empty() && U * VEC > 16) U = std::max(1, 16 / VEC);
     // Outer-index lanes whose rows need fewer loads than that take further outer indices, UZ in
     // all, so that a thread still has U loads in flight: with one 16-byte load per thread and
     // tile the kernel waits on memory latency (3.1 to 3.7 TB/s for [2097152, 4, 8] over axis 1).
@@ -114,9 +117,17 @@ ewf_status Gen::gen_col()
         // than 1024 leave CUs short of loads in flight.)
         int64_t other = ceil_div(c.extent[in_d], TK);
         for (int d = 0; d < R - 1; d++) if (d != dR) other *= c.extent[d];
-        const int64_t want = (int64_t)5 * device_cu_count();
+        // A kernel that also streams element-wise outputs wants every CU full of wavefronts
+        // instead, and short tiles: about 48 per CU (float32 [1605632, 64], bias + ReLU + column
+        // sums: 12544 tiles 146 us, 1255 tiles 165 us, 100352 tiles 194 us).
+        const int64_t want = (int64_t)(ew_out_ops.empty() ? 5 : 48) * device_cu_count();
         const int64_t trip = (int64_t)TY * U;
-        int64_t slices = std::max<int64_t>(1, std::min(ceil_div(want, other), ceil_div(c.extent[dR], trip)));
+        // (at least 128 bytes of every column per tile, or the partial results, one 4-byte value
+        // per column and tile, become a noticeable part of the traffic)
+        int in_sz = 4;
+        for (const Operand &op : c.ops) if (!op.is_output && op.stride[in_d] != 0) in_sz = std::min(in_sz, isz(op.storage));
+        const int64_t min_rows = std::max<int64_t>(trip, 128 / in_sz);
+        int64_t slices = std::max<int64_t>(1, std::min(ceil_div(want, other), ceil_div(c.extent[dR], min_rows)));
         if (whole_columns || TZ > 1) slices = 1;
         int64_t tr = ceil_div(c.extent[dR], slices);
         if (slices > 1) tr = std::max(trip, (tr + trip / 2) / trip * trip);
@@ -195,13 +206,42 @@ ewf_status Gen::gen_col()
     o << ind << "const bool colok_ = cc_ < " << TK << " && o" << in_d << " + cc_ < p.ext[" << in_d << "]"
       << (TZ > 1 && UZ == 1 ? " && o" + std::to_string(dK) + " + tz < p.ext[" + std::to_string(dK) + "]" : std::string("")) << ";\n";
     o << ind << "const int rows_ = (int)((p.ext[" << dR << "] - o" << dR << ") < " << TR << " ? (p.ext[" << dR << "] - o" << dR << ") : " << TR << ");\n";
+    // An operand that is the same for every row of the tile (a per-column bias) is loaded once
+    // per tile, not once per row: fewer load instructions and U times fewer registers.
+    auto tile_invariant = [&](int k) {
+        const Operand &op = c.ops[k];
+        return op.stride[dR] == 0 && (TZ == 1 || op.stride[dK] == 0);
+    };
     EmitCtx cx;
     cx.input = [&](int k) {
         const Operand &op = c.ops[k];
-        if (op.stride[in_d] == 0) return "ewf_in(x_" + opname(k) + "[" + xi + "])";
-        if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(x_" + opname(k) + "[" + xi + "], e_)";
-        return "ewf_in(x_" + opname(k) + "[" + xi + "].e[e_])";
+        const std::string at = tile_invariant(k) ? std::string("") : "[" + xi + "]";
+        if (op.stride[in_d] == 0) return "ewf_in(x_" + opname(k) + at + ")";
+        if (op.storage == EWF_F16 && VEC >= 2) return "ewf_in_h(x_" + opname(k) + at + ", e_)";
+        return "ewf_in(x_" + opname(k) + at + ".e[e_])";
     };
+    auto emit_load = [&](int k, const std::string &at, const std::string &in2) {
+        const Operand &op = c.ops[k];
+        const std::string nm = opname(k);
+        if (op.stride[in_d] == 0)
+            o << in2 << "x_" << nm << at << " = *ewf_at(q_" << nm << ", " << off_expr(k) << ");\n";
+        else if (op.access == Access::Vector)
+            o << in2 << "x_" << nm << at << " = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "));\n";
+        else {
+            o << in2 << "{ const ioff_t b_ = " << off_expr(k) << ";\n";
+            o << in2 << "  _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) x_" << nm << at << ".e[e_] = *ewf_at(q_" << nm
+              << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
+        }
+    };
+    for (int k : load_ops) {
+        if (!tile_invariant(k)) continue;
+        const Operand &op = c.ops[k];
+        if (op.stride[in_d] == 0) o << ind << ctype(op.storage) << " x_" << opname(k) << ";\n";
+        else o << ind << "ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << ";\n";
+        o << ind << "if (colok_) {\n";
+        emit_load(k, "", ind + "    ");
+        o << ind << "}\n";
+    }
     cx.coord = [&](int d) {
         std::string s = "o" + std::to_string(d);
         if (d == dR) s += " + r_";
@@ -212,35 +252,30 @@ ewf_status Gen::gen_col()
     auto emit_x_arrays = [&](const std::string &in2, int n) {
         for (int k : load_ops) {
             const Operand &op = c.ops[k];
+            if (tile_invariant(k)) continue;
             if (op.stride[in_d] == 0) o << in2 << ctype(op.storage) << " x_" << opname(k) << "[" << n << "];\n";
             else o << in2 << "ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << n << "];\n";
         }
     };
     // the loads of the U rows of one trip (first row r0), kept at index xi
-    auto emit_loads = [&](const std::string &in2, const std::string &r0) {
+    // (guard: 0 every row of the trip exists and the lane is in range -- no branch between the
+    // loads, which then go out back to back; 1 check the row; 2 check the row and the lane)
+    auto emit_guard = [&](const std::string &in2, int guard) {
+        if (guard == 1) o << in2 << "    if (r_ >= rows_) continue;\n";
+        if (guard == 2) o << in2 << "    if (!" << okname << " || r_ >= rows_) continue;\n";
+    };
+    auto emit_loads = [&](const std::string &in2, const std::string &r0, int guard) {
         o << in2 << "#pragma unroll\n" << in2 << "for (int u = 0; u < " << U << "; ++u) {\n";
         o << in2 << "    const int r_ = " << r0 << " + u * EWF_TY;\n";
-        o << in2 << "    if (!" << okname << " || r_ >= rows_) continue;\n";
-        for (int k : load_ops) {
-            const Operand &op = c.ops[k];
-            const std::string nm = opname(k);
-            if (op.stride[in_d] == 0)
-                o << in2 << "    x_" << nm << "[" << xi << "] = *ewf_at(q_" << nm << ", " << off_expr(k) << ");\n";
-            else if (op.access == Access::Vector)
-                o << in2 << "    x_" << nm << "[" << xi << "] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << off_expr(k) << "));\n";
-            else {
-                o << in2 << "    { const ioff_t b_ = " << off_expr(k) << ";\n";
-                o << in2 << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) x_" << nm << "[" << xi << "].e[e_] = *ewf_at(q_" << nm
-                  << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
-            }
-        }
+        emit_guard(in2, guard);
+        for (int k : load_ops) if (!tile_invariant(k)) emit_load(k, "[" + xi + "]", in2 + "    ");
         o << in2 << "}\n";
     };
     // their arithmetic, accumulation and element-wise stores
-    auto emit_arith = [&](const std::string &in2, const std::string &r0) {
+    auto emit_arith = [&](const std::string &in2, const std::string &r0, int guard) {
         o << in2 << "#pragma unroll\n" << in2 << "for (int u = 0; u < " << U << "; ++u) {\n";
         o << in2 << "    const int r_ = " << r0 << " + u * EWF_TY;\n";
-        o << in2 << "    if (!" << okname << " || r_ >= rows_) continue;\n";
+        emit_guard(in2, guard);
         for (int k : ew_out_ops) o << in2 << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
         o << in2 << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
         emit_values(need, cx, in2 + "        ");
@@ -329,10 +364,23 @@ ewf_status Gen::gen_col()
     const std::string acc_init = "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) acc[e_] = Acc_identity();\n";
     if (UZ == 1) {
         o << ind << "Acc acc[EWF_VEC];\n" << ind << acc_init;
-        o << ind << "for (int r0_ = ty; r0_ < rows_; r0_ += EWF_TY * " << U << ") {\n";
-        emit_x_arrays(ind + "    ", U);
-        emit_loads(ind + "    ", "r0_");
-        emit_arith(ind + "    ", "r0_");
+        // whole trips without a branch, then at most one trip that checks its rows (with the
+        // checks between them the loads waited for one another: bias + ReLU + column sums on
+        // float32 [401408, 256] ran at 5.2 TB/s)
+        o << ind << "if (colok_) {\n";
+        o << ind << "    int r0_ = ty;\n";
+        o << ind << "    for (; r0_ + " << (U - 1) << " * EWF_TY < rows_; r0_ += EWF_TY * " << U << ") {\n";
+        emit_x_arrays(ind + "        ", U);
+        emit_loads(ind + "        ", "r0_", 0);
+        emit_arith(ind + "        ", "r0_", 0);
+        o << ind << "    }\n";
+        if (U > 1) {
+            o << ind << "    if (r0_ < rows_) {\n";
+            emit_x_arrays(ind + "        ", U);
+            emit_loads(ind + "        ", "r0_", 1);
+            emit_arith(ind + "        ", "r0_", 1);
+            o << ind << "    }\n";
+        }
         o << ind << "}\n";
         emit_fold_and_write(ind);
     }
@@ -343,12 +391,19 @@ ewf_status Gen::gen_col()
             "    const bool zok_ = colok_ && o" + std::to_string(dK) + " + tzz_ < p.ext[" + std::to_string(dK) + "];\n";
         xi = "z_ * " + std::to_string(U) + " + u";
         emit_x_arrays(ind, UZ * U);
-        o << ind << "#pragma unroll\n" << ind << "for (int z_ = 0; z_ < " << UZ << "; ++z_) {\n" << ind << zhead;
-        emit_loads(ind + "    ", "ty");
-        o << ind << "}\n";
+        // (a thread whose outer indices and rows all exist issues its loads without a branch)
+        o << ind << "const bool all_ = colok_ && o" << dK << " + tz + " << (UZ - 1) << " * EWF_TZ < p.ext[" << dK << "] && ty + "
+          << (U - 1) << " * EWF_TY < rows_;\n";
+        for (int guard : {0, 2}) {
+            o << ind << (guard == 0 ? "if (all_) {\n" : "else {\n");
+            o << ind << "    #pragma unroll\n" << ind << "    for (int z_ = 0; z_ < " << UZ << "; ++z_) {\n" << ind << "    " << zhead;
+            o << ind << "        (void)zok_;\n";
+            emit_loads(ind + "        ", "ty", guard);
+            o << ind << "    }\n" << ind << "}\n";
+        }
         o << ind << "#pragma unroll\n" << ind << "for (int z_ = 0; z_ < " << UZ << "; ++z_) {\n" << ind << zhead;
         o << ind << "    Acc acc[EWF_VEC];\n" << ind << "    " << acc_init;
-        emit_arith(ind + "    ", "ty");
+        emit_arith(ind + "    ", "ty", 2);
         emit_fold_and_write(ind + "    ");
         o << ind << "}\n";
     }
