@@ -102,3 +102,64 @@ def test_random_axis_masks(seed, oracle):
     tag = f"axes seed {seed}: {dims} reduced over {axes}"
     print(f"[case] {tag}", flush=True)
     _check(G, oracle, tag, s, [y], tols)
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_column_plans_at_streaming_size(seed, oracle):
+    """Reductions over axes other than the innermost one, on half a million to four million
+    elements: past the small-problem shapes a thread keeps several loads in flight, short reduced
+    axes with few columns put outer indices on the spare lanes (several per thread when rows are
+    few), finishing threads write vectors, and element-wise outputs change the tile shape."""
+    G = _ctx()
+    rng = np.random.default_rng(91000 + seed)
+    nd = int(rng.integers(2, 5))
+    if seed % 3 == 0:                                        # a short reduced axis next to a few columns
+        nd = max(nd, 3)
+        shape = [int(rng.choice([2, 3, 5, 16])) for _ in range(nd - 3)] + [int(rng.choice([20011, 70001, 250007])),
+                 int(rng.choice([2, 3, 4, 8, 16])), int(rng.choice([4, 8, 16, 24]))]
+        while np.prod(shape) > 3e6:
+            shape[nd - 3] //= 2
+        axes = (nd - 2,) if rng.integers(0, 2) or nd == 3 else (0, nd - 2)
+    else:
+        inner = int(rng.choice([8, 16, 40, 64, 100, 224, 256, 520, 1024]))
+        shape = [int(rng.choice([2, 3, 4, 7, 16, 33, 64, 200, 1000, 5001])) for _ in range(nd - 1)] + [inner]
+        target = int(rng.choice([6e5, 1.5e6, 4e6]))
+        while np.prod(shape) > target:
+            k = int(np.argmax(shape[:-1])); shape[k] = max(2, shape[k] // 2)
+        while np.prod(shape) < target / 3:
+            k = int(rng.integers(nd - 1)); shape[k] = shape[k] * 2 + 1
+        axes = tuple(sorted(rng.choice(nd - 1, size=int(rng.integers(1, nd)), replace=False).tolist()))
+    storage = "f16" if rng.integers(0, 3) == 0 else "f32"
+    dt = np.float16 if storage == "f16" else np.float32
+    x = rng.uniform(0.25, 2.0, shape).astype(dt)
+    if rng.integers(0, 3) == 0:                              # rows with a pitch
+        big = rng.uniform(0.25, 2.0, [e + (8 if d == nd - 1 else 1) for d, e in enumerate(shape)]).astype(dt)
+        x = big[tuple(slice(0, e) for e in shape)]
+    s = GraphSpec(nd)
+    inputs = [x]
+    xi = s.input(storage, (False,) * nd)
+    v = xi
+    if rng.integers(0, 2):                                   # constant along the reduced axes: loaded once per tile
+        bc = tuple(d in axes for d in range(nd))
+        inputs.append(rng.uniform(-0.5, 0.5, [1 if d in axes else shape[d] for d in range(nd)]).astype(np.float32))
+        v = s.add(v, s.input("f32", bc))
+    if rng.integers(0, 2) and len(axes) < nd:                # varies along the reduced axes only
+        bc = tuple(d not in axes for d in range(nd))
+        inputs.append(rng.uniform(0.5, 1.5, [shape[d] if d in axes else 1 for d in range(nd)]).astype(np.float32))
+        v = s.mul(v, s.input("f32", bc))
+    if rng.integers(0, 2):
+        v = s.apply(["tanh", "sqrt", "sqr", "sigmoid"][int(rng.integers(4))], v)
+    tols = []
+    if rng.integers(0, 2):
+        s.output(s.apply("max", s.const(0.6), v), storage); tols.append((2e-6, 1e-6) if storage == "f32" else (2e-3, 2e-3))
+    keep = bool(rng.integers(0, 2))
+    for _ in range(int(rng.integers(1, 4))):
+        r = int(rng.integers(0, 5))
+        if r == 0: s.output(s.reduce("sum", v, axes, keep=keep), "f32"); tols.append((1e-5, 1e-5))
+        elif r == 1: s.output(s.reduce("max", v, axes, keep=keep), "f32"); tols.append((2e-6, 1e-6))
+        elif r == 2: s.output(s.reduce("min", xi, axes, keep=keep), storage); tols.append((0, 0))
+        elif r == 3: s.output(s.apply("log", s.reduce("sum", s.apply("sqr", v), axes, keep=keep)), "f32"); tols.append((1e-5, 1e-5))
+        else:
+            s.output(s.reduce("argmax", xi, (axes[-1],), keep=keep), "i32"); tols.append((0, 0))
+            break
+    _check(G, oracle, f"columns seed{seed} {storage} shape{shape} axes{axes}", s, inputs, tols)
