@@ -168,10 +168,11 @@ struct Plan {
     bool avoid_poor_rows = false, row_refused = false;
     // Likewise for reductions over axes that are not neighbours in memory (a kept dimension lies
     // between them) with a short innermost run: the tile class would work on tiny tiles.  The
-    // planner first tries two passes, the outer axes (`split_outer_axes`, original axis mask)
-    // in a column kernel and the rest on its much smaller result.
+    // planner first tries two passes: one part of the axes (`split_first_axes`, original axis
+    // mask: the outer ones in a column kernel, or the inner ones as short rows) and then the rest
+    // on the much smaller result.
     bool avoid_short_runs = false, axes_refused = false;
-    uint32_t split_outer_axes = 0;
+    uint32_t split_first_axes = 0;
     KernelClass kclass = KernelClass::None;
     std::vector<Stage> stages;           // KernelClass::Multi only
     std::vector<Temp> temps;

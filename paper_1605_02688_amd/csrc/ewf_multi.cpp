@@ -137,15 +137,51 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
         return EWF_OK;
     };
 
+    // Element-wise outputs that an earlier pass can write on its way.  A pass that materialises
+    // reductions and already walks the full extents evaluates such an output from the values it
+    // has in registers anyway; left to the last pass it costs one more sweep over the inputs
+    // (bias + ReLU + per-channel sums on [128, 512, 28, 28]: three sweeps instead of two).
+    // Only outputs that depend on no reduction, span every axis and share no memory with any
+    // input qualify (an in-place output would change what later passes read).
+    std::vector<char> written(nout, 0);
+    auto byte_span = [&](const ewf_tensor &t, int rank, int itemsize, uint64_t &lo, uint64_t &hi) {
+        int64_t below = 0, above = 0;                       // reach of the view from its pointer, in elements
+        bool empty = false;
+        for (int d = 0; d < rank; d++) {
+            if (t.shape[d] == 0) empty = true;
+            else if (t.strides[d] < 0) below += (t.shape[d] - 1) * -t.strides[d];
+            else above += (t.shape[d] - 1) * t.strides[d];
+        }
+        lo = (uint64_t)(uintptr_t)t.ptr - (uint64_t)below * itemsize;
+        hi = empty ? lo : (uint64_t)(uintptr_t)t.ptr + (uint64_t)(above + 1) * itemsize;
+    };
+    auto can_ride = [&](int k) {
+        const OutputDecl &od = g.outputs[k];
+        if (written[k] || (g.nodes[od.value].bcast & ~unit) || g.nodes[od.value].dropped) return false;
+        std::vector<char> cone(N, 0);
+        cone[od.value] = 1;
+        for (int n = N - 1; n >= 0; n--) {
+            if (!cone[n]) continue;
+            if (g.nodes[n].kind == NodeKind::Reduce || cuts.count(n)) return false;
+            for (int a = 0; a < g.nodes[n].nargs; a++) cone[g.nodes[n].args[a]] = 1;
+        }
+        uint64_t olo, ohi, ilo, ihi;
+        byte_span(out[k], g.ndim, od.storage == EWF_F16 ? 2 : 4, olo, ohi);
+        for (int i = 0; i < nin; i++) {
+            byte_span(in[i], g.ndim, g.nodes[g.input_node[i]].storage == EWF_F16 ? 2 : 4, ilo, ihi);
+            if (olo < ihi && ilo < ohi) return false;
+        }
+        return true;
+    };
+
     for (int round = 0; round < 16; round++) {
         // does what remains fit one kernel?
         {
             Stage fin;
             fin.exec.reset(new Exec());
             std::vector<std::pair<int, ewf_dtype>> targets;
-            for (const OutputDecl &o : g.outputs) targets.push_back({o.value, o.storage});
+            for (int k = 0; k < nout; k++) if (!written[k]) { targets.push_back({g.outputs[k].value, g.outputs[k].storage}); fin.out_dst.push_back(k); }
             build_stage(g, targets, false, cuts, *fin.exec, fin.in_src);
-            for (int k = 0; k < nout; k++) fin.out_dst.push_back(k);
             st = try_stage(fin);
             if (st == EWF_OK) {
                 plan.stages.push_back(std::move(fin));
@@ -191,8 +227,36 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
                 plan.temps.push_back(t);
                 sg.out_dst.push_back(-(int)plan.temps.size());
             }
-            st = try_stage(sg);
-            if (st != EWF_OK) return st;
+            // does this pass walk the full extents (then element-wise outputs can ride along)?
+            bool spans_all = true;
+            for (int d = 0; d < g.ndim && spans_all; d++) {
+                if (full[d] <= 1) continue;
+                bool some = false;
+                for (int node : sg.exec->g.input_node) if (!(sg.exec->g.nodes[node].bcast >> d & 1u)) some = true;
+                spans_all = some;
+            }
+            std::vector<int> riders;
+            if (spans_all && !e.opts.no_rewrite)
+                for (int k = 0; k < nout; k++) if (can_ride(k)) riders.push_back(k);
+            bool done = false;
+            if (!riders.empty()) {
+                Stage both;
+                both.exec.reset(new Exec());
+                std::vector<std::pair<int, ewf_dtype>> all = targets;
+                for (int k : riders) all.push_back({g.outputs[k].value, g.outputs[k].storage});
+                build_stage(g, all, true, cuts, *both.exec, both.in_src);
+                both.out_dst = sg.out_dst;
+                for (int k : riders) both.out_dst.push_back(k);
+                if (try_stage(both) == EWF_OK) {
+                    for (int k : riders) written[k] = 1;
+                    sg = std::move(both);
+                    done = true;
+                }
+            }
+            if (!done) {
+                st = try_stage(sg);
+                if (st != EWF_OK) return st;
+            }
             for (size_t i = 0; i < gr.second.size(); i++) cuts[gr.second[i]] = (int)plan.temps.size() - (int)gr.second.size() + (int)i;
             plan.stages.push_back(std::move(sg));
         }
