@@ -868,6 +868,44 @@ def test_reductions_over_axes_far_apart_in_memory(oracle, G):
     G.h.compare("sum01", got[0], oracle.evaluate(s, [yt])[0], 1e-5, 2e-5)
 
 
+@pytest.mark.parametrize("shape,first", [((128, 96, 14, 14), "col"), ((128, 336, 14, 14), "lane"), ((24, 448, 28, 28), "row")])
+def test_channel_statistics_of_late_layers_with_an_elementwise_output(shape, first, oracle, G):
+    # bias + ReLU + per-channel sum and maximum on feature maps whose planes are short: two passes,
+    # the element-wise output written by the first one (the second reads only the first's
+    # small result), the inner axes first once the tensor is large and a plane is long enough
+    rng = np.random.default_rng(198 + shape[1])
+    n, c, hh, ww = shape
+    x = rng.standard_normal(shape).astype(np.float32)
+    b = rng.standard_normal((1, c, 1, 1)).astype(np.float32)
+    s = GraphSpec(4)
+    xi = s.input("f32", (False,) * 4); bi = s.input("f32", (True, False, True, True))
+    y = s.apply("max", s.const(0.0), s.add(xi, bi))
+    s.output(y, "f32")
+    s.output(s.reduce("sum", y, (0, 2, 3)), "f32")
+    s.output(s.reduce("max", y, (0, 2, 3), keep=True), "f32")
+    print(f"[case] {shape}", flush=True)
+    expr, got = run_spec(G, s, [x, b])
+    info = expr.info()
+    assert info["kernel_class"] == "multi" and info["grid_blocks"] == 2, info
+    assert expr.info(0)["kernel_class"] == first and expr.info(0)["extent"] == (n, c, hh * ww), expr.info(0)
+    assert int(np.prod(expr.info(1)["extent"])) < x.size // 8, expr.info(1)           # nothing sweeps the tensor twice
+    want = oracle.evaluate(s, [x, b], nthreads=4)
+    G.h.compare("y", got[0], want[0], 2e-6, 1e-6); G.h.compare("sum", got[1], want[1], 1e-5, 1e-5)
+    G.h.compare("max", got[2], want[2], 0, 0)
+    # written over its input, the element-wise output waits for the last pass, which still finds
+    # the input intact
+    torch = G.torch
+    xd = torch.from_numpy(x).cuda(); bd = torch.from_numpy(b).cuda()
+    expr2 = G.ewf.Expression(s)
+    outs = [xd] + G.h.alloc_outputs(expr2, s, [xd, bd])[1:]
+    ws = G.h.make_workspace(expr2, [xd, bd], outs)
+    expr2.run([xd, bd], outs, (), ws, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert int(np.prod(expr2.info(expr2.info()["grid_blocks"] - 1)["extent"])) == x.size
+    G.h.compare("y in place", xd.cpu().numpy(), want[0], 2e-6, 1e-6)
+    G.h.compare("sum", outs[1].cpu().numpy(), want[1], 1e-5, 1e-5); G.h.compare("max", outs[2].cpu().numpy(), want[2], 0, 0)
+
+
 # ------------------------------------------------------------------ short rows: several rows per wavefront
 
 @pytest.mark.parametrize("cols,storage", [(4, "f32"), (8, "f32"), (12, "f32"), (32, "f32"), (10, "f32"), (24, "f16"), (64, "f16"),

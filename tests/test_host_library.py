@@ -560,6 +560,34 @@ def test_structures_beyond_one_kernel_are_planned_in_stages():
     assert expr.info()["kernel_class"] == "multi" and expr.info()["grid_blocks"] == 2
 
 
+def test_elementwise_outputs_ride_along_the_first_full_pass():
+    """Bias + ReLU + per-channel sums on feature maps with short planes: two passes.  The pass that
+    materialises the first partial sums walks the whole tensor and writes the element-wise output
+    on its way, unless that output lies over an input; which axes go first depends on the plane."""
+    def plan(shape, in_place=False, **opts):
+        n, c, h, w = shape
+        s = GraphSpec(4)
+        x = s.input("f32", (False,) * 4); b = s.input("f32", (True, False, True, True))
+        y = s.apply("max", s.const(0.0), s.add(x, b))
+        s.output(y, "f32"); s.output(s.reduce("sum", y, (0, 2, 3)), "f32")
+        e = ewf.Expression(s, **opts)
+        xr = ref(BASE, shape)
+        e.plan([xr, ref(BASE + (1 << 34), (1, c, 1, 1))], [xr if in_place else ref(BASE + (1 << 35), shape), ref(BASE + (1 << 36), (c,))])
+        return e
+    for shape, first in (((128, 1024, 14, 14), "lane"), ((128, 512, 28, 28), "row"), ((32, 2048, 7, 7), "col"), ((128, 96, 14, 14), "col")):
+        e = plan(shape)
+        n, c, h, w = shape
+        assert e.info()["kernel_class"] == "multi" and e.info()["grid_blocks"] == 2, (shape, e.info())
+        assert e.info(0)["kernel_class"] == first and e.info(0)["extent"] == (n, c, h * w), (shape, e.info(0))
+        assert len(e.info(1)["extent"]) == 2, (shape, e.info(1))                   # the second pass sees the small result only
+        assert "out0" in e.source(0) and "out1" in e.source(0)
+    # in place: the last pass writes the element-wise output, after every pass has read the input
+    e = plan((128, 1024, 14, 14), in_place=True)
+    assert e.info(1)["extent"] == (128, 1024, 196) and "out1" not in e.source(0)
+    # long planes never needed two passes
+    assert plan((128, 64, 112, 112)).info()["kernel_class"] == "tile_reduce"
+
+
 def test_run_argument_checks_without_device():
     expr = _add2()
     ins = [ref(BASE, (3, 4)), ref(BASE + (1 << 20), (1, 4))]
