@@ -279,7 +279,7 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
         for (const Operand &op : c.ops) if (op.stride[c.rank - 1] != 0) widest = std::max(widest, op.storage == EWF_F16 ? 2 : 4);
         int64_t rows_ = 1;
         for (int d = 0; d < c.rank - 1; d++) rows_ *= c.extent[d];
-        if (c.extent[c.rank - 1] * widest <= 1024 && c.extent[c.rank - 1] <= 64 * c.vec && rows_ >= 4096 && e.opts.split_rows != 1) {
+        if (c.extent[c.rank - 1] * widest <= 1024 && rows_ >= 4096 && e.opts.split_rows != 1) {
             plan->kclass = KernelClass::Lane;
             st = generate(e, *plan);
             if (st == EWF_EUNSUPPORTED) plan->kclass = KernelClass::Row;      // e.g. too many row operands for one thread
