@@ -279,7 +279,14 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
         for (const Operand &op : c.ops) if (op.stride[c.rank - 1] != 0) widest = std::max(widest, op.storage == EWF_F16 ? 2 : 4);
         int64_t rows_ = 1;
         for (int d = 0; d < c.rank - 1; d++) rows_ *= c.extent[d];
-        if (c.extent[c.rank - 1] * widest <= 1024 && rows_ >= 4096 && e.opts.split_rows != 1) {
+        // (rows that allow only narrow accesses -- an odd length, a misaligned slice -- up to 1024
+        // of them per row: the row class, one such access per thread in flight, reads rows of 289
+        // float32 at 2.8 TB/s)
+        int narrowest = 4;
+        for (const Operand &op : c.ops) if (op.stride[c.rank - 1] != 0) narrowest = std::min(narrowest, op.storage == EWF_F16 ? 2 : 4);
+        const bool narrow = c.vec * narrowest < 16;
+        const bool short_rows = c.extent[c.rank - 1] * widest <= 1024 || (narrow && c.extent[c.rank - 1] / c.vec <= 1024);
+        if (short_rows && rows_ >= 4096 && e.opts.split_rows != 1) {
             plan->kclass = KernelClass::Lane;
             st = generate(e, *plan);
             if (st == EWF_EUNSUPPORTED) plan->kclass = KernelClass::Row;      // e.g. too many row operands for one thread
