@@ -24,7 +24,15 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // every compute unit gets work and nobody loops
     const int64_t items = c.total / VEC;
     const bool small = items < (int64_t)256 * 512;
-    const int U = e.opts.unroll > 0 ? e.opts.unroll : ((heavy >= 4 || small) ? 1 : 2);
+    // (four where only narrow accesses are possible -- an odd row pitch, a misaligned view --
+    // so that a thread still has 16 bytes in flight: sums over float32 rows of 50257, 52 -> 43 us;
+    // softmax cross-entropy on them 92 -> 71 us; more than four is slower again)
+    int narrowest = 4;
+    for (const Operand &op : c.ops) if (op.stride[R - 1] != 0) narrowest = std::min(narrowest, isz(op.storage));
+    // (element-wise kernels, which also store, gain only with 2-byte accesses: float16 with an
+    // odd length 66 -> 53 us, float32 89 -> 92 us)
+    const bool narrow = with_reduce ? VEC * narrowest < 16 : VEC * narrowest <= 2;
+    const int U = e.opts.unroll > 0 ? e.opts.unroll : ((heavy >= 4 && !narrow) || small) ? 1 : narrow ? 4 : 2;
     // arithmetic-heavy expressions run best with larger workgroups (measured on the 21-op
     // float16 workload: 512 threads beat 256 by 4-8 %), streaming ones with 256
     int block = heavy >= 4 ? 512 : 256;
