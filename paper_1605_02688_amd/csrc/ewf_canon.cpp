@@ -308,6 +308,7 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
         }
         return true;
     };
+    c.vec_loose = vec;
     while (vec > 1 && !vec_ok(vec)) vec /= 2;
     c.vec = vec;
     for (Operand &op : c.ops) {

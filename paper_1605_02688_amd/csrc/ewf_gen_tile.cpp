@@ -51,6 +51,11 @@ ewf_status Gen::gen_tile(bool with_reduce)
         (group ? group_out_ops : ew_out_ops).push_back((int)k);
     }
 
+    // Vectors that assume element alignment only (see Plan::loose_vec): whole vectors of a row are
+    // read and written wide wherever the row starts; a row that ends inside a vector has that
+    // last vector handled element by element (`ragged`).
+    const bool loose = p.loose_vec;
+    const bool ragged = loose && c.extent[R - 1] % VEC != 0;
     // ---- tile shape: innermost dimensions first, never across a group boundary
     int64_t T[kMaxDims];
     for (int d = 0; d < kMaxDims; d++) T[d] = 1;
@@ -104,6 +109,11 @@ ewf_status Gen::gen_tile(bool with_reduce)
             break;
         }
     }
+    if (loose) {
+        // a tile holds whole vectors along the rows (its last one may reach past the row's end)
+        if (T[R - 1] < VEC) return fail("rows too short for wide accesses");
+        T[R - 1] = ceil_div(T[R - 1], VEC) * VEC;
+    }
     // ---- permuted operands: stage through LDS
     // An operand whose own fastest dimension is not the output's would be read with one
     // narrow access per element.  Instead the workgroup reads the operand's part of the tile
@@ -113,7 +123,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     std::vector<int> staged;                           // operand numbers
     std::vector<int> sdims;                            // dims ordered by the staged operand's stride
     int VS = 1;
-    if (!with_reduce && !e.opts.no_lds_staging && c.total >= 65536 && R >= 2) {
+    if (!with_reduce && !e.opts.no_lds_staging && c.total >= 65536 && R >= 2 && !loose) {
         for (int k = 0; k < nin && staged.empty(); k++) {
             const Operand &op = c.ops[k];
             if (op.access != Access::Gather || !live[g.input_node[k]]) continue;      // (an input no output uses is never read)
@@ -290,6 +300,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
 
     // what one trip of a thread holds in registers between its loads and its arithmetic
     o << "struct Item {\n    bool ok[" << U << "];\n    int L[" << U << "];\n";
+    if (ragged) o << "    int nv[" << U << "];\n";              // elements of the vector that lie inside the row
     for (int d : tiled) o << "    int c" << d << "[" << U << "];\n";
     for (int k : load_ops) {
         const Operand &op = c.ops[k];
@@ -437,6 +448,11 @@ ewf_status Gen::gen_tile(bool with_reduce)
                 if (c.extent[d] % T[d]) o << ind2 << "    k_ = k_ && (o" << d << " + it.c" << d << "[u] < p.ext[" << d << "]);\n";
             }
         }
+        if (ragged) {
+            // (the distance to the row's end in the index type: it need not fit an int)
+            o << ind2 << "    { const idx_t left_ = p.ext[" << in_d << "] - o" << in_d << " - (idx_t)it.c" << in_d << "[u];\n";
+            o << ind2 << "      it.nv[u] = left_ < (idx_t)EWF_VEC ? (int)left_ : EWF_VEC; }\n";
+        }
     });
     const std::string text_b = capture([&]() {
         const std::string &ind = ind2;
@@ -457,13 +473,21 @@ ewf_status Gen::gen_tile(bool with_reduce)
                     o << ind << "        _Pragma(\"unroll\") for (int i_ = 0; i_ < " << VEC / piece << "; ++i_) ((ewf_vec<" << ctype(op.storage) << ", " << piece
                       << "> *)&it.x_" << nm << "[u])[i_] = ewf_ld<" << ctype(op.storage) << ", " << piece << ">(&lds_" << nm << "[" << pos << " + i_ * " << piece << "]);\n";
             }
+            else if (op.access == Access::Vector && loose) {
+                o << ind << "        { const " << ctype(op.storage) << " *const a_ = ewf_at(q_" << nm << ", " << offset_expr(k, false) << ");\n";
+                if (ragged) {
+                    o << ind << "          if (it.nv[u] == EWF_VEC) it.x_" << nm << "[u] = ewf_ld_u<" << ctype(op.storage) << ", EWF_VEC>(a_);\n";
+                    o << ind << "          else { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC - 1; ++e_) if (e_ < it.nv[u]) it.x_" << nm << "[u].e[e_] = a_[e_]; } }\n";
+                }
+                else o << ind << "          it.x_" << nm << "[u] = ewf_ld_u<" << ctype(op.storage) << ", EWF_VEC>(a_); }\n";
+            }
             else if (op.access == Access::Vector)
                 o << ind << "        it.x_" << nm << "[u] = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "));\n";
             else if (op.access == Access::Splat)
                 o << ind << "        it.x_" << nm << "[u] = *ewf_at(q_" << nm << ", " << offset_expr(k, true) << ");\n";
             else {
                 o << ind << "        { const ioff_t b_ = " << offset_expr(k, false) << ";\n";
-                o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) it.x_" << nm << "[u].e[e_] = *ewf_at(q_" << nm
+                o << ind << "          _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) " << (ragged ? "if (e_ < it.nv[u]) " : "") << "it.x_" << nm << "[u].e[e_] = *ewf_at(q_" << nm
                   << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm << "[" << in_d << "]); }\n";
             }
         }
@@ -485,6 +509,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
             if (d == in_d) s += " + e_";
             return s;
         };
+        if (ragged) o << ind << "        if (e_ >= it.nv[u]) continue;\n";
         emit_values(need, cx, ind + "        ");
         if (with_reduce)
             emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ", ascending);
@@ -498,11 +523,19 @@ ewf_status Gen::gen_tile(bool with_reduce)
         for (int k : ew_out_ops) {
             const Operand &op = c.ops[k];
             std::string nm = opname(k);
-            if (op.access == Access::Vector)
+            if (op.access == Access::Vector && loose) {
+                o << ind << "    { " << ctype(op.storage) << " *const a_ = ewf_at(q_" << nm << ", " << offset_expr(k, false) << ");\n";
+                if (ragged) {
+                    o << ind << "      if (it.nv[u] == EWF_VEC) ewf_st_u<" << ctype(op.storage) << ", EWF_VEC>(a_, y_" << nm << ");\n";
+                    o << ind << "      else { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC - 1; ++e_) if (e_ < it.nv[u]) a_[e_] = y_" << nm << ".e[e_]; } }\n";
+                }
+                else o << ind << "      ewf_st_u<" << ctype(op.storage) << ", EWF_VEC>(a_, y_" << nm << "); }\n";
+            }
+            else if (op.access == Access::Vector)
                 o << ind << "    " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(ewf_at(q_" << nm << ", " << offset_expr(k, false) << "), y_" << nm << ");\n";
             else {
                 o << ind << "    { const ioff_t b_ = " << offset_expr(k, op.access == Access::Splat) << ";\n";
-                o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) *ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
+                o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) " << (ragged ? "if (e_ < it.nv[u]) " : "") << "*ewf_at(q_" << nm << ", b_ + (ioff_t)e_ * (ioff_t)p.st_" << nm
                   << "[" << in_d << "]) = y_" << nm << ".e[e_]; }\n";
             }
         }

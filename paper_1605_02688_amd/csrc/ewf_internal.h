@@ -91,6 +91,8 @@ struct Canon {
     int dim_of_axis[kMaxDims];            // canonical dim that original axis d went into (-1: extent 1)
     std::vector<Operand> ops;             // inputs then outputs
     int vec = 1;
+    int vec_loose = 1;                    // the width that unit-stride operands would allow if neither the
+                                          // alignment of their rows nor the row length had to fit it
     bool idx64 = false;
     bool byte32 = false;                  // every operand's byte span fits 32 bits
     int64_t total = 0;                    // product of extents
@@ -196,6 +198,10 @@ struct Plan {
     int64_t tile[kMaxDims] = {0};
     size_t workspace_bytes = 0;
     bool empty = false;                  // zero-size iteration space: nothing to traverse
+    // The kernel was generated for canon.vec_loose: rows may start at any element and end inside
+    // a vector.  Whole vectors are read and written with accesses that assume element alignment
+    // only, the last vector of a row element by element.
+    bool loose_vec = false;
     struct Fill { int output; int rank; int elem_bytes; uint32_t bits; };
     std::vector<Fill> fills;             // empty space: outputs that are reductions over an empty axis
     bool used_auto_occupancy = false;    // the generator asked for a register budget on its own

@@ -54,6 +54,24 @@ EWF_DEV void ewf_st(T *p, const ewf_vec<T, N> &v)
     *reinterpret_cast<ewf_vec<T, N> *>(p) = v;
 }
 
+// The same accesses for addresses that are aligned to the element only (rows with an odd pitch,
+// views that start inside a vector).  The memory instructions of this target take any address;
+// declaring the reduced alignment keeps the compiler from assuming more.
+template <typename T, int N>
+struct __attribute__((packed, aligned(sizeof(T)))) ewf_vec_u { ewf_vec<T, N> v; };
+
+template <typename T, int N>
+EWF_DEV ewf_vec<T, N> ewf_ld_u(const T *p)
+{
+    return reinterpret_cast<const ewf_vec_u<T, N> *>(p)->v;
+}
+
+template <typename T, int N>
+EWF_DEV void ewf_st_u(T *p, const ewf_vec<T, N> &v)
+{
+    reinterpret_cast<ewf_vec_u<T, N> *>(p)->v = v;
+}
+
 // A value at an address that is the same in every lane and that no lane of this launch writes
 // before reading it: read through the scalar unit (one request per wavefront, its own wait
 // counter, the result in a scalar register).

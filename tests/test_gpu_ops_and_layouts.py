@@ -1121,3 +1121,80 @@ def test_softmax_in_place(shape, axis, opts, oracle, G):
     torch.cuda.synchronize()
     G.h.compare("p", t.cpu().numpy(), want_p, 1e-5, 1e-8)
     G.h.compare("lse", lse.cpu().numpy(), want_l, 1e-5, 2e-6)
+
+
+# ------------------------------------------------------------------ rows that start anywhere and end inside a vector
+
+@pytest.mark.parametrize("rows,cols,storage", [(37, 50257, "f32"), (5, 131075, "f16"), (300, 4099, "f32"), (1, 1000003, "f16"), (64, 20001, "f16")])
+def test_wide_accesses_on_rows_of_odd_length(rows, cols, storage, oracle, G):
+    # reductions over rows whose pitch is odd (every row starts at a different alignment) and
+    # whose last vector is cut by the row's end: wide accesses that assume element alignment
+    # only, the cut vector element by element
+    rng = np.random.default_rng(200 + rows)
+    dt = np.float16 if storage == "f16" else np.float32
+    x = (rng.standard_normal((rows, cols)) * 2).astype(dt)
+    x[rows // 2, cols - 1] = 40.0                                        # the maximum in the very last element of a row
+    x[0, cols - 2] = -40.0
+    t = rng.integers(0, cols, (rows, 1)).astype(np.int32)
+    t[rows - 1, 0] = cols - 1
+    s = GraphSpec(2)
+    xi = s.input(storage, (False, False)); ti = s.input("i32", (False, True))
+    s.output(s.reduce("sum", s.apply("abs", xi), (1,)), "f32")
+    s.output(s.reduce("max", xi, (1,), keep=True), "f32")
+    s.output(s.reduce("argmax", xi, (1,)), "i32")
+    s.output(s.reduce("min", xi, (1,)), "f32")
+    s.output(s.reduce("sum", s.apply("where", s.apply("eq", s.iota(1), ti), xi, s.const(0.0)), (1,)), "f32")   # x[row, t[row]]
+    print(f"[case] odd rows {rows} x {cols} {storage}", flush=True)
+    expr, got = run_spec(G, s, [x, t])
+    info = expr.info()
+    assert info["kernel_class"] == "tile_reduce" and info["vec"] == 16 // x.itemsize and "ewf_ld_u<" in expr.source(), info
+    want = oracle.evaluate(s, [x, t], nthreads=4)
+    G.h.compare("sum", got[0], want[0], 1e-5, 1e-5); G.h.compare("max", got[1], want[1], 0, 0)
+    G.h.compare("argmax", got[2], want[2], 0, 0); G.h.compare("min", got[3], want[3], 0, 0)
+    G.h.compare("gather", got[4], want[4], 0, 0)
+    assert got[2][rows // 2] == cols - 1
+    # a view that starts at an odd element of a wider buffer, a second operand with another
+    # alignment, and a strided one, all in one kernel
+    wide = (rng.standard_normal((rows, cols + 7)) * 2).astype(dt)
+    other = rng.standard_normal((rows, cols + 2)).astype(np.float32)
+    twice = rng.standard_normal((rows, 2 * cols)).astype(np.float32)
+    va, vb, vc = wide[:, 3:3 + cols], other[:, 1:1 + cols], twice[:, ::2]
+    s2 = GraphSpec(2)
+    ai = s2.input(storage, (False, False)); bi = s2.input("f32", (False, False)); ci = s2.input("f32", (False, False))
+    v = s2.add(s2.mul(ai, bi), ci)
+    s2.output(s2.reduce("sum", v, (1,)), "f32"); s2.output(s2.reduce("max", v, (1,)), "f32")
+    expr, got = run_spec(G, s2, [va, vb, vc])
+    assert expr.info()["kernel_class"] == "tile_reduce" and expr.info()["vec"] == 16 // x.itemsize, expr.info()
+    want = oracle.evaluate(s2, [va, vb, vc], nthreads=4)
+    G.h.compare("sum", got[0], want[0], 1e-5, 1e-5 * max(1.0, cols / 4096)); G.h.compare("max", got[1], want[1], 2e-6 if storage == "f32" else 2e-3, 1e-6)
+
+
+@pytest.mark.parametrize("shape,offset", [((3000, 1023), 1), ((1, 5000001), 3), ((700, 4100), 5)])
+def test_wide_accesses_on_float16_views_from_an_odd_element(shape, offset, oracle, G):
+    # element-wise on float16: a view that starts at an odd element and rows of odd length,
+    # outputs with the same kind of layout (written wide where a vector lies inside the row)
+    rng = np.random.default_rng(201 + offset)
+    rows, cols = shape
+    base = (rng.standard_normal((rows, cols + 9)) * 2).astype(np.float16)
+    x = base[:, offset:offset + cols]
+    b = rng.standard_normal((1, cols)).astype(np.float16)
+    s = GraphSpec(2)
+    xi = s.input("f16", (False, False)); bi = s.input("f16", (rows > 1, False))
+    s.output(s.apply("tanh", s.add(xi, bi)), "f16")
+    s.output(s.mul(xi, s.const(0.5)), "f32")
+    print(f"[case] f16 view {shape} from element {offset}", flush=True)
+    torch = G.torch
+    tb = torch.from_numpy(base).cuda()
+    xd = tb[:, offset:offset + cols]; bd = torch.from_numpy(b).cuda()
+    outbuf = torch.full((rows, cols + 5), float("nan"), dtype=torch.float16, device="cuda")
+    out0 = outbuf[:, 2:2 + cols]                                          # an output view from an even but unaligned element
+    out1 = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    expr = G.ewf.Expression(s)
+    ws = G.h.make_workspace(expr, [xd, bd], [out0, out1])
+    expr.run([xd, bd], [out0, out1], (), ws, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert expr.info()["kernel_class"] == "tile" and expr.info()["vec"] == 8 and "ewf_st_u<" in expr.source(), expr.info()
+    want = oracle.evaluate(s, [x, b], nthreads=4)
+    G.h.compare("tanh", out0.cpu().numpy(), want[0], 2e-3, 2e-3); G.h.compare("half", out1.cpu().numpy(), want[1], 2e-6, 1e-6)
+    edge = outbuf.cpu().numpy()
+    assert np.isnan(edge[:, :2]).all() and np.isnan(edge[:, 2 + cols:]).all()         # nothing written outside the view

@@ -206,6 +206,34 @@ def test_vector_width_follows_alignment_and_extent():
     assert e2.info()["vec"] == 1
 
 
+def test_wide_accesses_where_only_the_element_is_aligned():
+    """Reducing tile kernels, and element-wise ones on 2-byte storage, keep the full vector width on
+    rows of odd pitch or length: accesses that assume element alignment, the vector that a row's
+    end cuts element by element.  Other classes and float32 element-wise kernels stay strict."""
+    s = GraphSpec(2)
+    x = s.input("f32", (False, False))
+    s.output(s.reduce("sum", x, (1,)), "f32"); s.output(s.reduce("max", x, (1,)), "f32")
+    e = ewf.Expression(s)
+    e.plan([ref(BASE, (40, 50257))], [ref(BASE + (1 << 30), (40,)), ref(BASE + (1 << 31), (40,))])
+    assert e.info()["kernel_class"] == "tile_reduce" and e.info()["vec"] == 4
+    src = e.source()
+    assert "ewf_ld_u<float, EWF_VEC>" in src and "it.nv[u]" in src and e.info()["tile"][1] % 4 == 0
+    # an even length behind an odd starting element: no vector is cut
+    e.plan([ref(BASE + 4, (40, 50256), (50260, 1))], [ref(BASE + (1 << 30), (40,)), ref(BASE + (1 << 31), (40,))])
+    assert e.info()["vec"] == 4 and "ewf_ld_u<" in e.source() and "it.nv" not in e.source()
+    # aligned rows: the ordinary accesses
+    e.plan([ref(BASE, (40, 50256))], [ref(BASE + (1 << 30), (40,)), ref(BASE + (1 << 31), (40,))])
+    assert e.info()["vec"] == 4 and "ewf_ld_u<" not in e.source()
+    assert ewf.Expression(s, force_scalar=1).plan([ref(BASE, (40, 50257))], [ref(BASE + (1 << 30), (40,)), ref(BASE + (1 << 31), (40,))]) >= 0
+    # element-wise: float16 yes, float32 no
+    for dt, vec in (("f16", 8), ("f32", 1)):
+        s2 = GraphSpec(1)
+        s2.output(s2.apply("tanh", s2.input(dt, (False,))), dt)
+        e2 = ewf.Expression(s2)
+        e2.plan([ref(BASE, ((1 << 22) + 3,))], [ref(BASE + (1 << 30), ((1 << 22) + 3,))])
+        assert e2.info()["vec"] == vec and ("ewf_st_u<" in e2.source()) == (dt == "f16"), (dt, e2.info())
+
+
 def test_index_width_selection():
     s = GraphSpec(2)
     s.output(s.apply("neg", s.input("f16", (False, False))), "f16")
