@@ -295,6 +295,16 @@ int rewrite_graph(Graph &g)
                 break;
             case EWF_DIV:
                 if (is_const(out, a1, 1.0)) keep_as(a0);
+                else if (f32 && arg(1).vtype == EWF_F32 && arg(0).vtype == EWF_F32 && (arg(1).bcast & ~arg(0).bcast) &&
+                         arg(1).kind != NodeKind::Const) {
+                    // a / k with k constant along an axis where a varies (a row's sum under its
+                    // elements): one reciprocal per k and a product per element instead of a
+                    // division per element -- about ten instructions less of the fifty that a
+                    // softmax element costs.  One rounding more (1.5 units in the last place at
+                    // most); a divisor below the smallest normal number overflows its reciprocal.
+                    const int rk = make_apply(EWF_RECIP, a1, -1, arg(1));
+                    r = make_apply(EWF_MUL, a0, rk, orig);
+                }
                 break;
             case EWF_NEG:
                 if (arg(0).kind == NodeKind::Apply && arg(0).op == EWF_NEG) keep_as(arg(0).args[0]);

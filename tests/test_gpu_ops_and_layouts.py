@@ -868,7 +868,7 @@ def test_reductions_over_axes_far_apart_in_memory(oracle, G):
     G.h.compare("sum01", got[0], oracle.evaluate(s, [yt])[0], 1e-5, 2e-5)
 
 
-@pytest.mark.parametrize("shape,first", [((128, 96, 14, 14), "col"), ((128, 336, 14, 14), "lane"), ((24, 448, 28, 28), "row")])
+@pytest.mark.parametrize("shape,first", [((128, 96, 14, 14), "col"), ((128, 336, 14, 14), "lane"), ((24, 448, 28, 28), "lane"), ((24, 288, 36, 36), "row")])
 def test_channel_statistics_of_late_layers_with_an_elementwise_output(shape, first, oracle, G):
     # bias + ReLU + per-channel sum and maximum on feature maps whose planes are short: two passes,
     # the element-wise output written by the first one (the second reads only the first's

@@ -298,7 +298,10 @@ def test_short_rows_share_a_wavefront():
     assert e.source().count("ewf_lane_xor(acc1, ") == 5 and "ewf_lane_xor(acc1, 16)" in e.source()
     # few rows, or longer ones: a wavefront or more per row
     assert plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=1000, vocab=12))[0].info()["kernel_class"] == "row"
-    assert plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=512))[0].info()["kernel_class"] == "row"
+    assert plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=2048))[0].info()["kernel_class"] == "row"
+    # rows of up to 4096 bytes: a wavefront per row, several vectors per lane, four rows per workgroup
+    e = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=512))[0]
+    assert e.info()["kernel_class"] == "lane" and e.info()["block_threads"] == 256 and "ewf_lane_xor(acc1, 32)" in e.source()
     # more rows than one workgroup should fold: the mean becomes a pass of its own
     e = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=200000, vocab=12))[0]
     assert e.info()["kernel_class"] == "multi" and e.info(0)["kernel_class"] == "lane"
@@ -406,7 +409,8 @@ def test_kernel_class_selection():
         outs = [ref(BASE + (1 << 36) + k * (1 << 32), sh) for k, sh in enumerate(expr.output_shapes(ins))]
         expr.plan(ins, outs)
         return expr.info()
-    assert red(2, (1,), (4096, 512))["kernel_class"] == "row"            # many short rows
+    assert red(2, (1,), (4096, 512))["kernel_class"] == "lane"           # many short rows: a wavefront each
+    assert red(2, (1,), (4096, 2048))["kernel_class"] == "row"           # longer ones: a workgroup each
     assert red(2, (1,), (4, 1 << 20))["kernel_class"] == "tile_reduce"    # few long rows: split them
     assert red(1, (0,), (1 << 20,))["kernel_class"] == "tile_reduce"      # full reduction
     assert red(3, (0, 2), (8, 16, 256))["kernel_class"] == "tile_reduce"
@@ -602,7 +606,7 @@ def test_elementwise_outputs_ride_along_the_first_full_pass():
         xr = ref(BASE, shape)
         e.plan([xr, ref(BASE + (1 << 34), (1, c, 1, 1))], [xr if in_place else ref(BASE + (1 << 35), shape), ref(BASE + (1 << 36), (c,))])
         return e
-    for shape, first in (((128, 1024, 14, 14), "lane"), ((128, 512, 28, 28), "row"), ((32, 2048, 7, 7), "col"), ((128, 96, 14, 14), "col")):
+    for shape, first in (((128, 1024, 14, 14), "lane"), ((128, 512, 28, 28), "lane"), ((64, 288, 36, 36), "row"), ((32, 2048, 7, 7), "col"), ((128, 96, 14, 14), "col")):
         e = plan(shape)
         n, c, h, w = shape
         assert e.info()["kernel_class"] == "multi" and e.info()["grid_blocks"] == 2, (shape, e.info())
