@@ -138,6 +138,10 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
     }
 
     plan->avoid_poor_rows = !e.is_stage || e.strict_rows;
+    {
+        Graph fused = e.g;
+        plan->fused_depth = fuse_shifted_exp_sums(fused) > 0 ? analyse_reductions(fused, unit).max_depth : plan->red.max_depth;
+    }
     plan->avoid_short_runs = !e.is_stage;
     st = single_kernel_plan(e, plan.get(), full);
     if (st == EWF_EUNSUPPORTED && !e.is_stage) {

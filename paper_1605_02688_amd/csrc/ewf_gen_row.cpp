@@ -48,11 +48,21 @@ ewf_status Gen::gen_row()
     std::vector<int> row_ops, splat_ops;
     for (int k : inputs_of(eneed)) (c.ops[k].stride[in_d] != 0 ? row_ops : splat_ops).push_back(k);
 
+    // Operands that only the element-wise outputs use (the scale and shift rows of a layer
+    // normalisation) are read where those outputs are written, not held under the reductions.
+    std::vector<char> late(c.ops.size(), 0);
+    {
+        std::vector<int> level_targets;
+        for (int l = 1; l <= D; l++) for (int n : lvl[l]) level_targets.push_back(g.nodes[n].args[0]);
+        std::vector<char> lneed = needed(level_targets);
+        std::vector<int> under = inputs_of(lneed);
+        for (int k : row_ops) if (std::find(under.begin(), under.end(), k) == under.end()) late[k] = 1;
+    }
     // ---- residency: keep the row in registers when it fits
     const int64_t per_iter = (int64_t)block * VEC;
     const int64_t NV = ceil_div(cols, per_iter);
     int regs = 0;
-    for (int k : row_ops) regs += (int)NV * VEC * isz(c.ops[k].storage) / 4;
+    for (int k : row_ops) if (!late[k]) regs += (int)NV * VEC * isz(c.ops[k].storage) / 4;
     const bool resident = NV <= 32 && regs <= 96;
     if (p.avoid_poor_rows && e.opts.split_rows != 2) {
         int64_t nr = 1;
@@ -61,7 +71,10 @@ ewf_status Gen::gen_row()
         // run at 5.3-5.5 TB/s up to 32768 columns but 4.1 TB/s at 65536 (64 registers per thread,
         // 1024 threads: one workgroup per compute unit), rows streamed once per level 2.7-3.4 TB/s;
         // split over workgroups 5.0-5.2 TB/s at any row length
-        const bool too_long = !resident || regs > 48;
+        // (a chain that a plan in passes cannot shorten -- layer normalisation of float32
+        // [4096, 16384] with its scale and shift rows: 96 registers of row data, 91 us here against
+        // 185 us in three passes -- keeps the row class as long as the row fits at all)
+        const bool too_long = !resident || (regs > 48 && p.fused_depth <= 1);
         if (too_long || (nr * 2 < device_cu_count() && cols >= 16384) || e.opts.split_rows == 1) {
             p.row_refused = true;
             return fail(too_long ? "a row does not fit the registers of a workgroup well: the row class would read it once per reduction level or run one workgroup per compute unit"
@@ -165,25 +178,24 @@ ewf_status Gen::gen_row()
         o << "        const " << ctype(c.ops[k].storage) << " g_" << opname(k) << " = ewf_ld_uniform(q_" << opname(k) << ");\n";
     }
     if (resident) {
-        for (int k : row_ops) o << "        ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
+        for (int k : row_ops) if (!late[k]) o << "        ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
         open_pass();
-        for (int k : row_ops) emit_row_load(k, "            ", "x_" + opname(k) + "[u]");
+        for (int k : row_ops) if (!late[k]) emit_row_load(k, "            ", "x_" + opname(k) + "[u]");
         close_pass();
     }
 
     EmitCtx cx;
     cx.input = [&](int k) {
         if (c.ops[k].stride[in_d] == 0) return "ewf_in(g_" + opname(k) + ")";
-        return resident ? "ewf_in(x_" + opname(k) + "[u].e[e_])" : "ewf_in(w_" + opname(k) + ".e[e_])";
+        return resident && !late[k] ? "ewf_in(x_" + opname(k) + "[u].e[e_])" : "ewf_in(w_" + opname(k) + ".e[e_])";
     };
     cx.coord = [&](int d) {
         if (d == in_d) return std::string("col + e_");
         return "o" + std::to_string(d);
     };
     auto stream_loads = [&](const std::vector<char> &need) {
-        if (resident) return;
         for (int k : inputs_of(need)) {
-            if (c.ops[k].stride[in_d] == 0) continue;
+            if (c.ops[k].stride[in_d] == 0 || (resident && !late[k])) continue;
             o << "            ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> w_" << opname(k) << ";\n";
             emit_row_load(k, "            ", "w_" + opname(k));
         }

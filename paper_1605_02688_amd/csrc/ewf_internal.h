@@ -168,6 +168,11 @@ struct Plan {
     // does not fit the registers of a workgroup or the rows are too few to occupy the chip, so
     // that the caller can try a plan in several passes first.
     bool avoid_poor_rows = false, row_refused = false;
+    // Depth of the reduction chain once a max -> sum-of-exp pair has become one level: what a plan
+    // in passes would have to sweep (one pass per level, and one for outputs that vary along the
+    // rows).  A chain that stays two deep (mean, then variance of the centred values) costs such
+    // a plan three sweeps, so rows that fit the registers at all stay with the row class.
+    int fused_depth = 1;
     // Likewise for reductions over axes that are not neighbours in memory (a kept dimension lies
     // between them) with a short innermost run: the tile class would work on tiny tiles.  The
     // planner first tries two passes: one part of the axes (`split_first_axes`, original axis

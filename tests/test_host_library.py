@@ -283,6 +283,29 @@ def test_long_or_few_rows_are_split_over_workgroups():
     assert e.info()["kernel_class"] == "tile_reduce"
 
 
+def test_chains_that_passes_cannot_shorten_stay_with_the_row_class():
+    # layer normalisation: mean, then the variance of the centred values, then an output that uses
+    # both and two more rows (scale, shift).  A plan in passes would sweep the tensor three times.
+    def plan(rows, cols, dt, **opts):
+        s = GraphSpec(2)
+        x = s.input(dt, (False, False)); ga = s.input("f32", (True, False)); be = s.input("f32", (True, False))
+        mean = s.mul(s.reduce("sum", x, (1,), keep=True), s.const(1.0 / cols))
+        xc = s.sub(x, mean)
+        var = s.mul(s.reduce("sum", s.mul(xc, xc), (1,), keep=True), s.const(1.0 / cols))
+        s.output(s.add(s.mul(s.mul(xc, s.apply("recip", s.apply("sqrt", s.add(var, s.const(1e-5))))), ga), be), dt)
+        e = ewf.Expression(s, **opts)
+        e.plan([ref(BASE, (rows, cols)), ref(BASE + (1 << 34), (1, cols)), ref(BASE + (1 << 35), (1, cols))], [ref(BASE + (1 << 36), (rows, cols))])
+        return e
+    for rows, cols, dt in ((4096, 16384, "f32"), (4096, 16384, "f16"), (1024, 65536, "f16"), (8192, 8192, "f32")):
+        e = plan(rows, cols, dt)
+        assert e.info()["kernel_class"] == "row", (rows, cols, dt, e.info())
+        src = e.source()
+        # the row itself is held in registers; scale and shift are read where the output is written
+        assert "x_in0[" in src and "x_in1[" not in src and "w_in1" in src and "w_in2" in src
+    assert plan(4096, 16384, "f32", split_rows=1).info()["kernel_class"] == "multi"
+    assert plan(50000, 512, "f32").info()["kernel_class"] == "lane"
+
+
 def test_short_rows_share_a_wavefront():
     # softmax cross-entropy over 8 classes (32-byte rows): one thread per row when there are many rows
     e = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=50000, vocab=8))[0]
