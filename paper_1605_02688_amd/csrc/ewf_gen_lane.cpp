@@ -34,11 +34,16 @@ ewf_status Gen::gen_lane()
     // the lane count that leaves the fewest lane slots idle, with at most 16 vectors per lane
     // (rows of 130 float32 are 65 pairs: 64 lanes would take two trips with 63 idle slots, 8 lanes
     // take nine with 7)
+    // (... and at most 64 registers of row data per lane: two float32 operands with rows of 784
+    // are held by 32 lanes, seven vectors of each, not by 16 lanes with thirteen)
     if (nvec > 64) {
+        int vec_regs = 0;                               // registers that one vector of every row operand takes
+        for (int k = 0; k < nin; k++)
+            if (c.ops[k].stride[in_d] != 0 && live[g.input_node[k]]) vec_regs += (VEC * isz(c.ops[k].storage) + 3) / 4;
         int64_t best_waste = -1;
         for (int l = 64; l >= 8; l /= 2) {
             const int64_t nv = ceil_div(nvec, (int64_t)l), waste = nv * l - nvec;
-            if (nv > 16) break;
+            if (nv > 16 || (l < 64 && nv * vec_regs > 64)) break;
             if (best_waste < 0 || waste < best_waste) { best_waste = waste; L = l; }
         }
     }
