@@ -78,7 +78,7 @@ void finish_layout(ParamLayout &L)
 
 ewf_status generate(const Exec &e, Plan &p)
 {
-    // The tile classes can use wide accesses on rows that start at any element and end inside a
+    // The tile and row classes can use wide accesses on rows that start at any element and end inside a
     // vector (an odd row pitch -- a vocabulary of 50257 --, a view that begins at an odd
     // element): softmax cross-entropy statistics on [1280, 50257] 73 us element by element.
     // Element-wise kernels gain only where the strict width leaves 2-byte accesses (float16 of odd
@@ -88,13 +88,14 @@ ewf_status generate(const Exec &e, Plan &p)
     const Canon &c = p.canon;
     int narrowest = 4;
     for (const Operand &op : c.ops) if (op.stride[c.rank - 1] != 0) narrowest = std::min(narrowest, op.storage == EWF_F16 ? 2 : 4);
-    const bool worth = p.kclass == KernelClass::TileReduce || (p.kclass == KernelClass::Tile && c.vec * narrowest <= 2);
+    const bool worth = p.kclass == KernelClass::TileReduce || p.kclass == KernelClass::Row ||
+                       (p.kclass == KernelClass::Tile && c.vec * narrowest <= 2);
     if (worth && c.vec_loose > c.vec && !e.opts.force_scalar && c.extent[c.rank - 1] >= 4 * c.vec_loose) {
         const int strict = c.vec;
         p.canon.vec = c.vec_loose;
         p.loose_vec = true;
         Gen wide(e, p);
-        ewf_status st = wide.gen_tile(p.kclass == KernelClass::TileReduce);
+        ewf_status st = p.kclass == KernelClass::Row ? wide.gen_row() : wide.gen_tile(p.kclass == KernelClass::TileReduce);
         if (st == EWF_OK) return st;
         p.canon.vec = strict;
         p.loose_vec = false;

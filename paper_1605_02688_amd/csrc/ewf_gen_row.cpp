@@ -156,13 +156,28 @@ ewf_status Gen::gen_row()
         o << "        }\n";
         if (!resident) o << "        }\n";
     };
+    // Vectors that assume element alignment only (see Plan::loose_vec): a row may start at any
+    // element, and when its length is no whole number of vectors the last one is cut (`ragged`)
+    // and handled element by element.  The steps below NFULL hold whole vectors for every thread,
+    // which the unrolled code knows at compile time.
+    const bool loose = p.loose_vec;
+    const bool ragged = loose && cols % VEC != 0;
+    const std::string whole = "(u < " + std::to_string(NFULL) + " || col + EWF_VEC <= cols)";
+    const std::string inside = ragged ? "if (u < " + std::to_string(NFULL) + " || col + e_ < cols) " : std::string("");
     auto emit_row_load = [&](int k, const std::string &ind, const std::string &dst) {
         const Operand &op = c.ops[k];
         std::string nm = opname(k);
-        if (op.access == Access::Vector)
+        if (op.access == Access::Vector && loose) {
+            if (ragged) {
+                o << ind << "if " << whole << " " << dst << " = ewf_ld_u<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col);\n";
+                o << ind << "else { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC - 1; ++e_) if (col + e_ < cols) " << dst << ".e[e_] = q_" << nm << "[col + e_]; }\n";
+            }
+            else o << ind << dst << " = ewf_ld_u<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col);\n";
+        }
+        else if (op.access == Access::Vector)
             o << ind << dst << " = " << (op.stream ? "ewf_ld_nt<" : "ewf_ld<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col);\n";
         else
-            o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) " << dst << ".e[e_] = q_" << nm
+            o << ind << "_Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) " << inside << dst << ".e[e_] = q_" << nm
               << "[(col + e_) * p.st_" << nm << "[" << in_d << "]];\n";
     };
 
@@ -234,6 +249,7 @@ ewf_status Gen::gen_row()
         open_pass();
         stream_loads(need);
         o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+        if (ragged) o << "                if (u >= " << NFULL << " && col + e_ >= cols) continue;\n";
         emit_values(need, cx, "                ");
         emit_accumulate(av, lvl[l], [&](int node) { return cx.coord(argmax_canon_dim(node)); }, "                ", true);
         o << "            }\n";
@@ -252,6 +268,7 @@ ewf_status Gen::gen_row()
         stream_loads(need);
         for (int k : full_out_ops) o << "            ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
         o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+        if (ragged) o << "                if (u >= " << NFULL << " && col + e_ >= cols) continue;\n";
         emit_values(need, cx, "                ");
         for (int k : full_out_ops) {
             const Operand &op = c.ops[k];
@@ -262,10 +279,17 @@ ewf_status Gen::gen_row()
         for (int k : full_out_ops) {
             const Operand &op = c.ops[k];
             std::string nm = opname(k);
-            if (op.access == Access::Vector)
+            if (op.access == Access::Vector && loose) {
+                if (ragged) {
+                    o << "            if " << whole << " ewf_st_u<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col, y_" << nm << ");\n";
+                    o << "            else { _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC - 1; ++e_) if (col + e_ < cols) q_" << nm << "[col + e_] = y_" << nm << ".e[e_]; }\n";
+                }
+                else o << "            ewf_st_u<" << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col, y_" << nm << ");\n";
+            }
+            else if (op.access == Access::Vector)
                 o << "            " << (op.stream ? "ewf_st_nt<" : "ewf_st<") << ctype(op.storage) << ", EWF_VEC>(q_" << nm << " + col, y_" << nm << ");\n";
             else
-                o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) q_" << nm << "[(col + e_) * p.st_" << nm
+                o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) " << inside << "q_" << nm << "[(col + e_) * p.st_" << nm
                   << "[" << in_d << "]] = y_" << nm << ".e[e_];\n";
         }
         close_pass();

@@ -1198,3 +1198,40 @@ def test_wide_accesses_on_float16_views_from_an_odd_element(shape, offset, oracl
     G.h.compare("tanh", out0.cpu().numpy(), want[0], 2e-3, 2e-3); G.h.compare("half", out1.cpu().numpy(), want[1], 2e-6, 1e-6)
     edge = outbuf.cpu().numpy()
     assert np.isnan(edge[:, :2]).all() and np.isnan(edge[:, 2 + cols:]).all()         # nothing written outside the view
+
+
+@pytest.mark.parametrize("rows,vocab", [(61, 10001), (40, 2051), (300, 20003)])
+def test_rows_of_odd_length_held_in_registers(rows, vocab, oracle, G):
+    # softmax cross-entropy and its gradient on vocabularies of odd size: one workgroup per row,
+    # the row read with element-aligned wide accesses, its cut last vector element by element;
+    # the gradient is written the same way
+    from workloads import configs as wl
+    for maker in (wl.c3_softmax_xent, wl.c3_softmax_xent_backward):
+        w = maker(rows=rows, vocab=vocab)
+        print(f"[case] {w.name} {rows} x {vocab}", flush=True)
+        expr, stats = G.h.check_workload(w, oracle, nthreads=4)
+        info = expr.info()
+        assert info["kernel_class"] == "row" and info["vec"] == 4 and "ewf_ld_u<float, EWF_VEC>" in expr.source(), info
+    # softmax probabilities in float16 on rows of odd length and pitch, written over a padded buffer
+    rng = np.random.default_rng(202 + rows)
+    base = (rng.standard_normal((rows, vocab + 3)) * 3).astype(np.float16)
+    x = base[:, 1:1 + vocab]
+    s = GraphSpec(2)
+    xi = s.input("f16", (False, False))
+    m = s.reduce("max", xi, (1,), keep=True); ex = s.apply("exp", s.sub(xi, m)); S = s.reduce("sum", ex, (1,), keep=True)
+    s.output(s.div(ex, S), "f16"); s.output(s.reduce("argmax", xi, (1,)), "i32")
+    torch = G.torch
+    tb = torch.from_numpy(base).cuda()
+    xd = tb[:, 1:1 + vocab]
+    outbuf = torch.full((rows, vocab + 5), float("nan"), dtype=torch.float16, device="cuda")
+    out0 = outbuf[:, 3:3 + vocab]
+    out1 = torch.empty((rows,), dtype=torch.int32, device="cuda")
+    expr = G.ewf.Expression(s)
+    ws = G.h.make_workspace(expr, [xd], [out0, out1])
+    expr.run([xd], [out0, out1], (), ws, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert expr.info()["kernel_class"] == "row" and expr.info()["vec"] == 8 and "ewf_st_u<" in expr.source(), expr.info()
+    want = oracle.evaluate(s, [x], nthreads=4)
+    G.h.compare("p", out0.cpu().numpy(), want[0], 2e-3, 1e-3); G.h.compare("argmax", out1.cpu().numpy(), want[1], 0, 0)
+    edge = outbuf.cpu().numpy()
+    assert np.isnan(edge[:, :3]).all() and np.isnan(edge[:, 3 + vocab:]).all()         # nothing written outside the view

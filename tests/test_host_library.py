@@ -225,6 +225,10 @@ def test_wide_accesses_where_only_the_element_is_aligned():
     e.plan([ref(BASE, (40, 50256))], [ref(BASE + (1 << 30), (40,)), ref(BASE + (1 << 31), (40,))])
     assert e.info()["vec"] == 4 and "ewf_ld_u<" not in e.source()
     assert ewf.Expression(s, force_scalar=1).plan([ref(BASE, (40, 50257))], [ref(BASE + (1 << 30), (40,)), ref(BASE + (1 << 31), (40,))]) >= 0
+    # the row class does the same for rows it holds in registers
+    e3 = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=1280, vocab=10001))[0]
+    assert e3.info()["kernel_class"] == "row" and e3.info()["vec"] == 4 and e3.info()["block_threads"] == 256
+    assert "ewf_ld_u<float, EWF_VEC>" in e3.source() and "col + e_ >= cols" in e3.source()
     # element-wise: float16 yes, float32 no
     for dt, vec in (("f16", 8), ("f32", 1)):
         s2 = GraphSpec(1)
