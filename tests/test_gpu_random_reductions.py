@@ -163,3 +163,30 @@ def test_random_column_plans_at_streaming_size(seed, oracle):
             s.output(s.reduce("argmax", xi, (axes[-1],), keep=keep), "i32"); tols.append((0, 0))
             break
     _check(G, oracle, f"columns seed{seed} {storage} shape{shape} axes{axes}", s, inputs, tols)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_column_plans_with_few_or_odd_columns(seed, oracle):
+    """Sums, maxima and arg-maxima over outer axes of tensors whose innermost axis has 3 to 1001
+    elements, an odd count: only narrow accesses are possible, several rows are kept in flight."""
+    G = _ctx()
+    rng = np.random.default_rng(95000 + seed)
+    nd = int(rng.integers(2, 4))
+    cols = int(rng.choice([3, 5, 7, 13, 21, 49, 51, 255, 1001]))
+    if nd == 2:
+        shape = [int(rng.integers(600000, 2500000)) // cols, cols]; axes = (0,)
+    else:
+        mid = int(rng.choice([2, 3, 7, 16, 50]))
+        shape = [int(rng.integers(600000, 2500000)) // cols // mid, mid, cols]
+        axes = (0,) if rng.integers(0, 2) else ((1,) if rng.integers(0, 2) else (0, 1))
+    storage = "f16" if rng.integers(0, 2) else "f32"
+    x = rng.uniform(0.25, 2.0, shape).astype(np.float16 if storage == "f16" else np.float32)
+    if rng.integers(0, 3) == 0:                              # rows with a pitch, from an odd element
+        big = rng.uniform(0.25, 2.0, shape[:-1] + [cols + 3]).astype(x.dtype); x = big[..., 1:1 + cols]
+    s = GraphSpec(nd)
+    xi = s.input(storage, (False,) * nd)
+    s.output(s.reduce("sum", xi, axes), "f32"); s.output(s.reduce("max", xi, axes, keep=True), storage)
+    tols = [(1e-5, 1e-5), (0, 0)]
+    if len(axes) == 1:
+        s.output(s.reduce("argmax", xi, axes), "i32"); tols.append((0, 0))
+    _check(G, oracle, f"narrow columns seed{seed} {storage} shape{shape} axes{axes}", s, [x], tols)
