@@ -340,9 +340,12 @@ ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **o
     x->e.nodes_before = (int)x->e.g.nodes.size();
     if (!x->e.opts.no_rewrite) {
         rewrite_graph(x->e.g);
-        // max -> sum of exp(x - max) as one rescaled level: one sweep and one workgroup fold less
-        // (softmax cross-entropy backward on [1280,10000]: 19.5 us against 20.6 us)
-        fuse_shifted_exp_sums(x->e.g, true);
+        // (The chain max -> sum of exp(x - max) stays two levels here.  As one rescaled level it
+        // saves a sweep only where rows are split over workgroups, and the planner makes it one
+        // there; over rows held in registers the rescaled update costs more per element than it
+        // saves: softmax probabilities, float16 [131072, 512] 65 us fused against 41 us, float32
+        // [1048576, 64] 100 against 79 us, the gradient of softmax cross-entropy on [1280, 10000]
+        // 21.0 against 21.2 us.)
         st = finalize_graph(x->e.g);
         if (st != EWF_OK) { delete x; return st; }
     }

@@ -84,6 +84,11 @@ ewf_status generate(const Exec &e, Plan &p)
     // Element-wise kernels gain only where the strict width leaves 2-byte accesses (float16 of odd
     // length 53 -> 48 us, a float16 view from an odd element 66 -> 49 us; float32 streams as well
     // element by element: 89 us against 101 us with the checks that rows ending inside a vector need).
+    // (a plan can come here more than once -- another class after a refusal, the same class again
+    // without a register hint that made the compiler spill -- so every call starts from the
+    // canonicaliser's width)
+    if (p.strict_vec == 0) p.strict_vec = p.canon.vec;
+    p.canon.vec = p.strict_vec;
     p.loose_vec = false;
     const Canon &c = p.canon;
     int narrowest = 4;

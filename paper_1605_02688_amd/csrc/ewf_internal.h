@@ -207,6 +207,7 @@ struct Plan {
     // a vector.  Whole vectors are read and written with accesses that assume element alignment
     // only, the last vector of a row element by element.
     bool loose_vec = false;
+    int strict_vec = 0;                  // canon.vec as the canonicaliser set it (0: not recorded yet)
     struct Fill { int output; int rank; int elem_bytes; uint32_t bits; };
     std::vector<Fill> fills;             // empty space: outputs that are reductions over an empty axis
     bool used_auto_occupancy = false;    // the generator asked for a register budget on its own

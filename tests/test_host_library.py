@@ -229,6 +229,11 @@ def test_wide_accesses_where_only_the_element_is_aligned():
     e3 = plan_workload(wl.layout_only(wl.c3_softmax_xent, rows=1280, vocab=10001))[0]
     assert e3.info()["kernel_class"] == "row" and e3.info()["vec"] == 4 and e3.info()["block_threads"] == 256
     assert "ewf_ld_u<float, EWF_VEC>" in e3.source() and "col + e_ >= cols" in e3.source()
+    # a plan that is generated more than once (another block size after the first attempt) keeps
+    # the accesses that go with its width
+    e4 = plan_workload(wl.layout_only(wl.c3_softmax_xent_backward, rows=300, vocab=20003))[0]
+    assert e4.info()["kernel_class"] == "row" and e4.info()["vec"] == 4 and e4.info()["block_threads"] == 512
+    assert "ewf_ld_u<float, EWF_VEC>" in e4.source() and "ewf_ld<float, EWF_VEC>" not in e4.source() and "ewf_st_u<float, EWF_VEC>" in e4.source()
     # element-wise: float16 yes, float32 no
     for dt, vec in (("f16", 8), ("f32", 1)):
         s2 = GraphSpec(1)
