@@ -46,6 +46,20 @@ struct Builder {
         Node n; n.kind = NodeKind::Reduce; n.op = EWF_RSUM; n.nargs = 1; n.args[0] = v; n.axes = axes; n.keep = true;
         return push(n);
     }
+    // The same value, but varying along `axes` too (one copy per index): where(iota >= 0, v, v).
+    // The graph has no operation that only widens a pattern; this one keeps the value bit for bit
+    // and survives the rewriter, which never changes a value's pattern.
+    int expand(int v, uint32_t axes)
+    {
+        for (int d = 0; d < g.ndim; d++) {
+            if (!(axes >> d & 1)) continue;
+            Node io; io.kind = NodeKind::Iota; io.index = d;
+            Node z; z.kind = NodeKind::Const; z.vtype = EWF_I32; z.cval = 0.0;
+            const int everywhere = ap(EWF_GE, push(io), push(z));
+            v = ap(EWF_WHERE, everywhere, v, v);
+        }
+        return v;
+    }
 };
 
 }  // namespace
@@ -79,16 +93,22 @@ extern "C" ewf_status ewf_grad(ewf_graph *graph, const ewf_value *y, const ewf_v
 
     Builder b(g);
     std::vector<int> adj(N, -1);                        // accumulated cotangent of each node
-    // A contribution that varies along axes on which the value itself is constant is summed over
-    // them first (the value was broadcast there in the forward pass); only then do contributions
-    // add up -- a contribution that is itself constant along such an axis counts once.
-    auto accumulate = [&](int n, int contribution) {
+    // `pattern` is the broadcast pattern of the value the contribution comes through (the forward
+    // consumer of n): the contribution stands for one term per index of that value, whether or not
+    // its own expression varies there.  Along an axis where n is constant and the consumer is not,
+    // n was used once per index, so the terms are summed: a contribution whose expression varies
+    // there directly, one that is constant there (the cotangent of a sum handed on to an operand that
+    // is itself constant along the summed axis) after it has been given one copy per index, so that
+    // it counts extent times.  A cotangent wider than its value is summed the same way.
+    auto accumulate_through = [&](int n, int contribution, uint32_t pattern) {
         if (!below[n] || !above[n] || b.failed) return;
-        const uint32_t extra = g.nodes[n].bcast & ~g.nodes[contribution].bcast;
-        if (extra) contribution = b.sum_over(contribution, extra);
+        const uint32_t cb = g.nodes[contribution].bcast;
+        const uint32_t over = g.nodes[n].bcast & ~(pattern & cb);
+        if (over & cb) contribution = b.expand(contribution, over & cb);
+        if (over) contribution = b.sum_over(contribution, over);
         adj[n] = adj[n] < 0 ? contribution : b.ap(EWF_ADD, adj[n], contribution);
     };
-    for (int k = 0; k < ny; k++) accumulate(y[k], ybar[k]);
+    for (int k = 0; k < ny; k++) accumulate_through(y[k], ybar[k], g.nodes[y[k]].bcast);
 
     for (int n = N - 1; n >= 0 && !b.failed; n--) {
         if (adj[n] < 0) continue;
@@ -96,6 +116,10 @@ extern "C" ewf_status ewf_grad(ewf_graph *graph, const ewf_value *y, const ewf_v
         const int G = adj[n];
         const int a0 = nd.args[0], a1 = nd.args[1], a2 = nd.args[2];
         auto live = [&](int a) { return a >= 0 && below[a] && g.nodes[a].vtype == EWF_F32; };
+        // a reduction hands its cotangent to an argument of its own pattern (every reduced element
+        // receives it once); everything else is used once per index of the node's own pattern
+        const uint32_t pattern = nd.kind == NodeKind::Reduce ? g.nodes[a0].bcast : nd.bcast;
+        auto accumulate = [&](int a, int contribution) { accumulate_through(a, contribution, pattern); };
         switch (nd.kind) {
         case NodeKind::Cast:
             // float32 and float16 casts pass the cotangent through (rounding has derivative one
@@ -179,6 +203,10 @@ extern "C" ewf_status ewf_grad(ewf_graph *graph, const ewf_value *y, const ewf_v
             // no differentiated value depends on it: a zero with the value's own pattern
             v = b.ap(EWF_MUL, wrt[j], b.lit(0.0));
         }
+        // an accumulated cotangent may be constant where the value varies (the gradient of a plain
+        // sum is the same for every element): the result takes the value's own pattern
+        const uint32_t narrow = g.nodes[v].bcast & ~g.nodes[wrt[j]].bcast;
+        if (narrow) v = b.expand(v, narrow);
         if (b.failed) return EWF_EINVAL;
         grads[j] = v;
     }

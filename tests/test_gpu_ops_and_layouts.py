@@ -528,6 +528,30 @@ def test_gradient_of_a_product_reduction(oracle, G):
     G.h.compare("dprod", got[0], want[0], 3e-5, 1e-7)
 
 
+def test_gradient_through_a_sum_reaches_operands_constant_along_it(oracle, G):
+    # y = sum over rows of (x * w + b): b is used once per row, so db = rows * ybar; dx has x's shape
+    # although nothing it is computed from varies along the rows
+    rng = np.random.default_rng(188)
+    R, C = 301, 1030
+    x = rng.standard_normal((R, C)).astype(np.float32)
+    w = rng.uniform(0.5, 1.5, (1, C)).astype(np.float32); b = rng.standard_normal((1, C)).astype(np.float32)
+    ybar = rng.standard_normal((1, C)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False)); wi = s.input("f32", (True, False)); bi = s.input("f32", (True, False))
+    yb = s.input("f32", (True, False))
+    y = s.reduce("sum", s.add(s.mul(xi, wi), bi), (0,), keep=True)
+    for g_ in s.grad([y], [yb], [xi, wi, bi]):
+        s.output(g_, "f32")
+    print("[case] gradient of a column sum with respect to row operands", flush=True)
+    expr, got = run_spec(G, s, [x, w, b, ybar])
+    want = oracle.evaluate(G.ewf.export_spec(s), [x, w, b, ybar])
+    assert got[0].shape == (R, C) and got[1].shape == (1, C) and got[2].shape == (1, C)
+    assert np.array_equal(want[0], np.broadcast_to(ybar * w, (R, C))) and np.array_equal(want[2], np.float32(R) * ybar)
+    G.h.compare("dx", got[0], want[0], 2e-6, 1e-6)
+    G.h.compare("dw", got[1], want[1], 1e-5, 1e-4)      # a sum of 301 terms of either sign: bar relative to the terms
+    G.h.compare("db", got[2], want[2], 1e-5, 1e-6)
+
+
 def test_argmax_ties_take_the_first_index(oracle, G):
     x = np.zeros((70, 5000), np.float32)
     x[:, 4000] = 3.0; x[:, 123] = 3.0; x[5, 7] = 3.0

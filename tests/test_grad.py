@@ -178,6 +178,88 @@ def test_lstm_cell_gradient(oracle):
     check(oracle, cell, zs + bs + [cprev], list(range(9)))
 
 
+def _flags(shape, full):
+    return tuple(e == 1 and f > 1 for e, f in zip(shape, full))
+
+
+def check_narrow(oracle, build, inputs, wrt, cot, tol=3e-3):
+    """Like `check`, for cotangents that are constant along axes where their value varies: `cot`
+    lists, per differentiated value, a float (a literal cotangent) or an array broadcastable to
+    the value's shape.  The gradients must come back with the shape of the inputs."""
+    full = tuple(max(a.shape[d] for a in inputs) for d in range(inputs[0].ndim))
+    s = GraphSpec(len(full))
+    xs = [s.input("f32", _flags(a.shape, full)) for a in inputs]
+    ys = build(s, xs)
+    fwd = GraphSpec(len(full)); fwd.nodes = list(s.nodes); fwd.n_inputs = s.n_inputs
+    for y in ys:
+        fwd.output(y, "f32")
+    y_vals = oracle.evaluate(fwd, inputs)
+    cs, extra = [], []
+    for c in cot:
+        if isinstance(c, float):
+            cs.append(s.const(c))
+        else:
+            cs.append(s.input("f32", _flags(c.shape, full))); extra.append(c)
+    gs = s.grad(ys, cs, [xs[k] for k in wrt])
+    for g_ in gs:
+        s.output(g_, "f32")
+    got = oracle.evaluate(ewf.export_spec(s), list(inputs) + extra)
+    # (a value that dropped its reduced axes has a lower rank than its cotangent operand)
+    cot_full = [c.reshape(y.shape) if not isinstance(c, float) and c.size == y.size else np.broadcast_to(np.float32(c), y.shape)
+                for c, y in zip(cot, y_vals)]
+    for j, k in enumerate(wrt):
+        want = numeric_grad(oracle, fwd, inputs, cot_full, k)
+        assert got[j].shape == inputs[k].shape, (k, got[j].shape, inputs[k].shape)
+        err = np.abs(got[j] - want).max()
+        assert err <= tol * max(1.0, np.abs(want).max()), (k, err, got[j], want)
+
+
+def test_cotangent_constant_along_an_axis_the_consumer_spans(oracle):
+    """The cotangent of a sum is the same for every summed element: an operand that is itself
+    constant along the summed axis receives it once per index (extent times), and an operand that
+    varies there receives a gradient of its own shape."""
+    rng = np.random.default_rng(12)
+    x = grid(rng, (3, 4), -1, 1); b = grid(rng, (1, 4), -1, 1); w = grid(rng, (1, 4), 0.5, 1.5)
+    col = grid(rng, (3, 1), -1, 1)
+    ybar = grid(rng, (1, 4), -1, 1)
+    # y = sum_0(x + b): db = 3 ybar, dx = ybar on every row
+    def s0(s, xs): return [s.reduce("sum", s.add(xs[0], xs[1]), (0,), keep=True)]
+    check(oracle, s0, [x, b], [0, 1])
+    check_narrow(oracle, s0, [x, b], [0, 1], [ybar])
+    check_narrow(oracle, s0, [x, b], [0, 1], [1.0])
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False)); bi = s.input("f32", (True, False)); yb = s.input("f32", (True, False))
+    gx, gb = s.grad([s.reduce("sum", s.add(xi, bi), (0,), keep=True)], [yb], [xi, bi])
+    s.output(gx, "f32"); s.output(gb, "f32")
+    dx, db = oracle.evaluate(ewf.export_spec(s), [x, b, ybar])
+    assert dx.shape == (3, 4) and np.array_equal(dx, np.broadcast_to(ybar, (3, 4)))
+    assert db.shape == (1, 4) and np.array_equal(db, 3 * ybar)
+    # sum((x + b) * b): the factor b is constant along the summed axis as well
+    check(oracle, lambda s, xs: [s.reduce("sum", s.mul(s.add(xs[0], xs[1]), xs[1]), (0,), keep=True)], [x, b], [0, 1])
+    # mean over both axes of x * w + b, with respect to everything
+    def mean(s, xs):
+        return [s.mul(s.reduce("sum", s.add(s.mul(xs[0], xs[1]), xs[2]), (0, 1), keep=True), s.const(1.0 / 12))]
+    check(oracle, mean, [x, w, b], [0, 1, 2])
+    check_narrow(oracle, mean, [x, w, b], [0, 1, 2], [1.0])
+    # the same through sub, neg and a column operand; reductions without keep
+    check(oracle, lambda s, xs: [s.reduce("sum", s.sub(s.apply("neg", xs[1]), s.add(xs[0], xs[2])), (1,), keep=True)],
+          [x, b, col], [0, 1, 2])
+    check_narrow(oracle, lambda s, xs: [s.reduce("sum", s.add(xs[0], xs[1]), (0,), keep=False)], [x, b], [0, 1], [ybar])
+    # a literal cotangent on a full-rank value, with respect to broadcast operands
+    full = lambda s, xs: [s.apply("tanh", s.add(s.mul(xs[0], xs[1]), xs[2]))]
+    check_narrow(oracle, full, [x, w, col], [0, 1, 2], [1.0])
+    check_narrow(oracle, full, [x, w, col], [0, 1, 2], [ybar])
+    # element-wise values only, nothing varies along axis 0 in the cotangent or the operand
+    check_narrow(oracle, lambda s, xs: [s.add(xs[0], xs[1])], [x, b], [0, 1], [ybar])
+    # a chain of two sums: the inner sum's cotangent is constant along both axes
+    check_narrow(oracle, lambda s, xs: [s.reduce("sum", s.reduce("sum", s.add(xs[0], xs[1]), (1,), keep=True), (0,), keep=True)],
+                 [x, b], [0, 1], [1.0])
+    # max-reduction and product reduction downstream of a broadcast operand
+    xm = x.copy(); xm[1, :] += np.float32(3.0)
+    check(oracle, lambda s, xs: [s.reduce("max", s.add(xs[0], xs[1]), (0,), keep=True)], [xm, b], [0, 1])
+    check(oracle, lambda s, xs: [s.reduce("prod", s.add(xs[0], xs[1]), (0,), keep=True)], [x + np.float32(2.0), b], [0, 1])
+
+
 def test_conventions_and_errors():
     s = GraphSpec(1)
     x = s.input("f32", (False,)); y = s.input("f32", (False,))
