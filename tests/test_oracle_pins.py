@@ -562,3 +562,178 @@ def test_threads_do_not_change_results(oracle):
     b = oracle.evaluate(w.spec, wl.host_inputs(w), nthreads=5)
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+# ------------------------------------------------------------------ reductions: NaN order, int32, dropped axes
+
+def _reduce_spec(red, storage, axes=(1,), keep=False, ndim=2, out=None):
+    s = GraphSpec(ndim)
+    v = s.reduce(red, s.input(storage, (False,) * ndim), axes, keep=keep)
+    s.output(v, out or ("i32" if red == "argmax" or storage == "i32" else "f32"))
+    return s
+
+
+@pytest.mark.parametrize("where_nan", ["first", "middle", "last", "two", "all", "after_inf"])
+def test_reduce_max_min_argmax_with_nan(oracle, where_nan):
+    """max and min over an axis propagate NaN wherever it stands (numpy's max/min do the same);
+    for arg-max a NaN ranks above every number, +inf included, and the first NaN wins (numpy's
+    argmax has the same convention).  Rows without NaN sit beside the NaN rows."""
+    nan, inf = np.float32("nan"), np.float32("inf")
+    x = np.array([[3, 1, 4, 1, 5, 9, 2], [2, 7, 1, 8, 2, 8, 1], [-1, -2, -3, -1, -5, -6, -7]], np.float32)
+    x = np.repeat(x[None], 2, 0).reshape(6, 7).copy()          # rows 3..5 stay free of NaN
+    pos = {"first": [0], "middle": [3], "last": [6], "two": [2, 5], "all": list(range(7)), "after_inf": [4]}[where_nan]
+    x[:3, pos] = nan
+    if where_nan == "after_inf":
+        x[:3, 1] = inf                                           # +inf before the NaN: the NaN still wins
+    for red, fn in (("max", np.max), ("min", np.min)):
+        got = oracle.evaluate(_reduce_spec(red, "f32"), [x])[0]
+        with np.errstate(invalid="ignore"):
+            want = fn(x, axis=1)
+        assert np.isnan(got[:3]).all() and np.array_equal(got, want, equal_nan=True), red
+        # the same along the other axis, through a transposed view
+        got_t = oracle.evaluate(_reduce_spec(red, "f32", axes=(0,)), [x.T])[0]
+        assert np.array_equal(got_t, want, equal_nan=True), red
+    got = oracle.evaluate(_reduce_spec("argmax", "f32"), [x])[0]
+    assert got.dtype == np.int32
+    assert np.array_equal(got, np.argmax(x, axis=1))
+    assert list(got[:3]) == [pos[0]] * 3
+    assert list(got[3:]) == [5, 3, 0]                            # ties: the first of the two 8s, of the two -1s
+
+
+def test_reduce_max_min_nan_through_an_expression(oracle):
+    # the NaN is made by the expression under the reduction (0 * inf), not read from memory
+    x = np.array([[1, 2, 3, 4], [1, np.inf, 3, 4], [5, 6, 7, np.inf]], np.float32)
+    s = GraphSpec(2)
+    v = s.mul(s.input("f32", (False, False)), s.const(0.0))
+    s.output(s.reduce("max", v, (1,)), "f32"); s.output(s.reduce("argmax", v, (1,)), "i32")
+    mx, am = oracle.evaluate(s, [x])
+    assert np.array_equal(mx, np.float32([0, np.nan, np.nan]), equal_nan=True)
+    assert list(am) == [0, 1, 3]
+
+
+def test_int32_unary_ops_wrap_like_twos_complement(oracle):
+    lo, hi = -2**31, 2**31 - 1
+    a = np.array([lo, lo + 1, -46341, -46340, -7, -1, 0, 1, 7, 46340, 46341, 65536, hi - 1, hi], np.int32)
+    with np.errstate(over="ignore"):
+        want = {"neg": np.negative(a), "abs": np.abs(a), "sqr": a * a}
+    # hand values for the corner cases (numpy wraps too, but these do not depend on it)
+    assert want["neg"][0] == lo and want["abs"][0] == lo and want["sqr"][0] == 0
+    assert want["sqr"][10] == np.int32(46341 * 46341 - 2**32) and want["sqr"][11] == 0
+    assert want["sqr"][-1] == 1 and want["abs"][1] == hi and want["neg"][-1] == lo + 1
+    for op in ("neg", "abs", "sqr"):
+        got = oracle.evaluate(unary_spec(op, storage="i32", out="i32"), [a])[0]
+        assert got.dtype == np.int32 and np.array_equal(got, want[op]), op
+
+
+def test_int32_reductions_wrap_and_order(oracle):
+    hi = 2**31 - 1
+    a = np.array([[hi, 1, 5, -3], [hi, hi, hi, hi], [-2**31, -1, 0, 0], [65536, 65536, 3, 1],
+                  [7, -2, 7, 3], [46341, 46341, 2, 1]], np.int32)
+    with np.errstate(over="ignore"):
+        want_sum = a.sum(axis=1, dtype=np.int32); want_prod = a.prod(axis=1, dtype=np.int32)
+    # by hand: hi + 1 wraps to -2^31, then + 5 - 3; four times hi = -4 mod 2^32; 65536^2 = 2^32 = 0
+    assert want_sum[0] == -2**31 + 2 and want_sum[1] == -4 and want_sum[2] == hi and want_prod[3] == 0
+    assert want_prod[1] == 1                                     # (-1)^4 mod 2^32
+    assert want_prod[5] == (46341 * 46341 * 2) % 2**32 == 9266
+    for red, want in (("sum", want_sum), ("prod", want_prod), ("max", a.max(1)), ("min", a.min(1)),
+                      ("argmax", a.argmax(1))):
+        got = oracle.evaluate(_reduce_spec(red, "i32"), [a])[0]
+        assert got.dtype == np.int32 and np.array_equal(got, want), red
+        # column direction on the transposed view: same numbers
+        got_t = oracle.evaluate(_reduce_spec(red, "i32", axes=(0,)), [a.T])[0]
+        assert np.array_equal(got_t, want), red
+    assert list(oracle.evaluate(_reduce_spec("argmax", "i32"), [a])[0]) == [0, 0, 2, 0, 0, 0]   # ties: first
+    # over both axes at once, and a sum of an int32 expression (iota) that needs no memory
+    with np.errstate(over="ignore"):
+        assert oracle.evaluate(_reduce_spec("sum", "i32", axes=(0, 1)), [a])[0] == a.sum(dtype=np.int32)
+    s = GraphSpec(2)
+    x = s.input("i32", (False, False))
+    s.output(s.reduce("sum", s.add(s.mul(s.iota(1), s.const(2**30, "i32")), s.mul(x, s.const(0, "i32"))), (1,)), "i32")
+    # 2^30 * (0+1+2+3) = 6 * 2^30 = 2^32 + 2^31, which is -2^31 in 32 bits (the terms themselves are
+    # 0, 2^30, -2^31 and -2^30 after wrapping; their wrapped running sums 0, 2^30, -2^30, -2^31)
+    assert list(oracle.evaluate(s, [a])[0]) == [-2**31] * 6
+
+
+def _np_shape_rule(spec, full):
+    """Broadcast pattern and dropped axes per node, from the stated rule: a reduction makes its
+    axes broadcastable and, without keep, dropped; a point-wise value is broadcastable where all
+    operands are and drops what any operand dropped, as far as it is broadcastable there."""
+    nd = spec.ndim
+    bc, dr = [], []
+    for node in spec.nodes:
+        k = node[0]
+        if k == "input": bc.append(set(d for d in range(nd) if node[3][d])); dr.append(set())
+        elif k in ("scalar", "const"): bc.append(set(range(nd))); dr.append(set())
+        elif k == "iota": bc.append(set(range(nd)) - {node[1]}); dr.append(set())
+        elif k == "cast": bc.append(set(bc[node[1]])); dr.append(set(dr[node[1]]))
+        elif k == "apply":
+            b = set(range(nd)); u = set()
+            for a in node[2]: b &= bc[a]; u |= dr[a]
+            bc.append(b); dr.append(u & b)
+        else:
+            b = bc[node[2]] | set(node[3]); u = dr[node[2]] | (set() if node[4] else set(node[3]))
+            bc.append(b); dr.append(u & b)
+    return bc, dr
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_graphs_with_dropped_axes_vs_numpy(oracle, seed):
+    """Reductions over one or several axes with and without keep inside random expressions: values
+    against numpy float64 (kept dimensions), shapes against the rule written out above."""
+    rng = np.random.default_rng(5000 + seed)
+    ndim = int(rng.integers(2, 5))
+    full = [int(rng.integers(2, 5)) for _ in range(ndim)]
+    s = GraphSpec(ndim)
+    inputs, vals = [], []
+    for k in range(int(rng.integers(1, 4))):
+        bc = tuple(bool(k > 0 and rng.integers(0, 3) == 0) for _ in range(ndim))
+        shp = [1 if b else e for b, e in zip(bc, full)]
+        inputs.append(rng.uniform(0.5, 1.5, shp).astype(np.float32))
+        vals.append(s.input("f32", bc))
+    n_red = 0
+    for _ in range(int(rng.integers(3, 8))):
+        r = rng.integers(0, 10)
+        if r < 5 or n_red >= 3:
+            op = ["add", "sub", "mul", "max", "min"][int(rng.integers(5))]
+            v = s.apply(op, vals[int(rng.integers(len(vals)))], vals[int(rng.integers(len(vals)))])
+        else:
+            axes = tuple(sorted(set(int(x) for x in rng.integers(0, ndim, int(rng.integers(1, ndim + 1))))))
+            red = ["sum", "max", "min", "prod"][int(rng.integers(4))]
+            v = s.reduce(red, vals[int(rng.integers(len(vals)))], axes, keep=bool(rng.integers(0, 2)))
+            n_red += 1
+        vals.append(v)
+    outs = [vals[-1], vals[-2], vals[len(vals) // 2]]
+    for v in outs:
+        s.output(v, "f32")
+    ref = _np_eval(s, inputs, [], full)
+    bc, dr = _np_shape_rule(s, full)
+    got = oracle.evaluate(s, inputs)
+    for v, g in zip(outs, got):
+        want = np.asarray(ref[v], dtype=np.float64)
+        want = want.reshape((1,) * (ndim - want.ndim) + want.shape)
+        want = np.broadcast_to(want, [1 if d in bc[v] else full[d] for d in range(ndim)])
+        want = want.reshape([want.shape[d] for d in range(ndim) if d not in dr[v]])
+        assert g.shape == want.shape, (g.shape, want.shape, sorted(dr[v]))
+        assert np.allclose(g, want.astype(np.float32), rtol=3e-7, atol=0)
+
+
+def test_multi_axis_reductions_without_keep_have_the_rank_of_the_kept_axes(oracle):
+    rng = np.random.default_rng(77)
+    X = rng.integers(-4, 5, (3, 4, 5, 2)).astype(np.float32)
+    for axes in [(0, 1), (1, 3), (0, 2, 3), (0, 1, 2, 3), (2,)]:
+        for red, fn in (("sum", np.sum), ("max", np.max), ("min", np.min), ("prod", np.prod)):
+            got = oracle.evaluate(_reduce_spec(red, "f32", axes=axes, keep=False, ndim=4), [X])[0]
+            want = fn(X.astype(np.float64), axis=axes)
+            assert got.shape == want.shape and np.array_equal(got, want), (red, axes)
+    # a value computed from two reductions: an axis dropped by either stays dropped where the
+    # result is constant along it, and comes back where the other operand varies along it
+    s = GraphSpec(3)
+    x = s.input("f32", (False, False, False))
+    a = s.reduce("sum", x, (0, 2), keep=False); b = s.reduce("max", x, (2,), keep=False); c = s.reduce("sum", x, (0,), keep=True)
+    s.output(s.mul(a, b), "f32"); s.output(s.add(a, c), "f32"); s.output(s.add(a, x), "f32")
+    Y = rng.integers(-3, 4, (2, 3, 4)).astype(np.float32); Y64 = Y.astype(np.float64)
+    ab, ac, ax = oracle.evaluate(s, [Y])
+    assert ab.shape == (2, 3) and np.array_equal(ab, Y64.sum((0, 2))[None, :] * Y64.max(2))
+    # axis 0: dropped by a, kept (as extent 1) by c, constant in the sum -> stays dropped
+    assert ac.shape == (3, 4) and np.array_equal(ac, (Y64.sum((0, 2), keepdims=True) + Y64.sum(0, keepdims=True))[0])
+    assert ax.shape == (2, 3, 4) and np.array_equal(ax, Y64.sum((0, 2), keepdims=True) + Y64)
