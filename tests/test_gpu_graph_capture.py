@@ -52,8 +52,8 @@ def test_lstm_steps_in_a_captured_graph(oracle):
         ins = [np.ascontiguousarray(P_all[t][:, k * Hd:(k + 1) * Hd]) for k in range(4)]
         ins += [np.ascontiguousarray(bias[:, k * Hd:(k + 1) * Hd]) for k in range(4)] + [c]
         hh, c = oracle.evaluate(w.spec, ins)
-        h.compare(f"h[{t}]", eager_h[t].cpu().numpy(), hh, 2e-5, 2e-6)    # rounding compounds over the steps
-    h.compare("c[T]", eager_c.cpu().numpy(), c, 2e-5, 2e-6)
+        h.compare(f"h[{t}]", eager_h[t].cpu().numpy(), hh, 2e-6, 1e-6)
+    h.compare("c[T]", eager_c.cpu().numpy(), c, 2e-6, 1e-6)
 
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()

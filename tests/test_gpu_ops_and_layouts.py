@@ -477,7 +477,7 @@ def test_plans_in_several_passes(oracle, G):
     expr, got = run_spec(G, s, [x])
     assert expr.info()["kernel_class"] == "multi" and expr.info()["grid_blocks"] == 3
     want = oracle.evaluate(s, [x])
-    G.h.compare("normalised", got[0], want[0], 2e-5, 2e-6)
+    G.h.compare("normalised", got[0], want[0], 1e-5, 1e-6)
     G.h.compare("mean", got[1], want[1], 1e-5, 1e-6); G.h.compare("var", got[2], want[2], 1e-5, 1e-6)
     # reductions over unrelated axis sets, an arg-max among them, dropped axes in the outputs
     y = rng.standard_normal((40, 50, 12)).astype(np.float32)
@@ -508,7 +508,7 @@ def test_plans_in_several_passes(oracle, G):
     expr, got = run_spec(G, s, [z])
     assert expr.info()["kernel_class"] == "multi"
     want = oracle.evaluate(s, [z])
-    G.h.compare("p", got[0], want[0], 1e-5, 1e-7); G.h.compare("centred", got[1], want[1], 2e-5, 2e-6)
+    G.h.compare("p", got[0], want[0], 1e-5, 1e-7); G.h.compare("centred", got[1], want[1], 1e-5, 1e-6)
 
 
 def test_gradient_of_a_product_reduction(oracle, G):
@@ -525,7 +525,7 @@ def test_gradient_of_a_product_reduction(oracle, G):
     expr, got = run_spec(G, s, [x, c])
     want = oracle.evaluate(G.ewf.export_spec(s), [x, c])
     assert np.count_nonzero(want[0][9]) == 0 and np.count_nonzero(want[0][5]) == 1
-    G.h.compare("dprod", got[0], want[0], 3e-5, 1e-7)
+    G.h.compare("dprod", got[0], want[0], 1e-5, 1e-6)
 
 
 def test_gradient_through_a_sum_reaches_operands_constant_along_it(oracle, G):
@@ -548,7 +548,7 @@ def test_gradient_through_a_sum_reaches_operands_constant_along_it(oracle, G):
     assert got[0].shape == (R, C) and got[1].shape == (1, C) and got[2].shape == (1, C)
     assert np.array_equal(want[0], np.broadcast_to(ybar * w, (R, C))) and np.array_equal(want[2], np.float32(R) * ybar)
     G.h.compare("dx", got[0], want[0], 2e-6, 1e-6)
-    G.h.compare("dw", got[1], want[1], 1e-5, 1e-4)      # a sum of 301 terms of either sign: bar relative to the terms
+    G.h.compare("dw", got[1], want[1], 1e-5, 1e-6, scale=np.abs(ybar.astype(np.float64) * x).sum(0, keepdims=True))   # terms of either sign
     G.h.compare("db", got[2], want[2], 1e-5, 1e-6)
 
 
@@ -714,33 +714,55 @@ def random_case(seed):
         v = s.apply("tanh", v) if rng.integers(0, 3) == 0 else v
         vals.append(v)
     s.output(vals[-1], "f32")
+    kinds, aux_outputs = ["elementwise"], []
     if reduce_axes is not None:
         x0 = vals[0]
         red = ["sum", "max", "min"][int(rng.integers(3))]
-        r_ = s.reduce(red, s.apply("tanh", s.mul(x0, vals[-1])), reduce_axes, keep=bool(seed % 3 == 2))
-        s.output(r_, "f32")
-        if seed % 3 == 2:                                   # a value normalised by the reduction (may need several passes)
-            s.output(s.sub(vals[-1], r_), "f32")
-        s.outputs = s.outputs[int(rng.integers(0, 2)):]     # sometimes reduce-only
-    return s, inputs, [float(rng.uniform(0.5, 1.5))]
+        keep = bool(seed % 3 == 2)
+        term = s.apply("tanh", s.mul(x0, vals[-1]))
+        r_ = s.reduce(red, term, reduce_axes, keep=keep)
+        s.output(r_, "f32"); kinds.append(red)
+        if keep:                                            # a value normalised by the reduction (may need several passes)
+            s.output(s.sub(vals[-1], r_), "f32"); kinds.append("normalised")
+        first = int(rng.integers(0, 2))                     # sometimes reduce-only
+        s.outputs = s.outputs[first:]; kinds = kinds[first:]
+        aux_outputs = [("sum" if red == "sum" else "max", term, reduce_axes, keep), vals[-1]]
+    # what the bars of the outputs are relative to, as a description of its own for the oracle: for a
+    # sum the sum of the magnitudes of its terms (for max / min the largest magnitude), and |last value|
+    aux = GraphSpec(ndim); aux.nodes = list(s.nodes); aux.n_inputs = s.n_inputs; aux.n_scalars = s.n_scalars
+    if aux_outputs:
+        (red, term, axes, keep), last = aux_outputs
+        aux.output(aux.reduce(red, aux.apply("abs", term), axes, keep=keep), "f32")
+        aux.output(aux.apply("abs", last), "f32")
+    return s, inputs, [float(rng.uniform(0.5, 1.5))], aux, kinds
 
 
 @pytest.mark.parametrize("seed", range(60))
 def test_random_graphs_and_layouts(seed, oracle, G):
-    s, inputs, scal = random_case(seed)
+    s, inputs, scal, aux, kinds = random_case(seed)
     print(f"[case] fuzz seed {seed} ndim {s.ndim} shapes {[a.shape for a in inputs]} strides "
           f"{[tuple(x // 4 for x in a.strides) for a in inputs]} outputs {len(s.outputs)}", flush=True)
     want = oracle.evaluate(s, inputs, scal)
+    magnitude = [m.astype(np.float64) for m in oracle.evaluate(aux, inputs, scal)] if aux.outputs else []
     try:
         expr, got = run_spec(G, s, inputs, scal)
     except G.ewf.EwfError as e:
         if e.status == G.ewf.EUNSUPPORTED:
             pytest.skip(f"layout not covered by a kernel class: {e.message}")
         raise
-    for k, (g_, w_) in enumerate(zip(got, want)):
-        # structural test (indexing, broadcast, strides): looser than the per-op accuracy bar
-        # because random chains amplify float32 rounding
-        G.h.compare(f"seed{seed}.out{k}", g_, w_, 2e-4, 2e-5)
+    for k, (g_, w_, kind, (v, _)) in enumerate(zip(got, want, kinds, s.outputs)):
+        # A chain of d rounding operations: d times the element-wise bar (every operation adds its
+        # own rounding to what it received; the generator keeps arguments where no operation
+        # amplifies that by more than the bar allows for).  A sum adds the bar for reductions,
+        # relative to the magnitudes of its terms; a value minus a reduction is held to the
+        # magnitudes of both.
+        d = G.h.rounding_depth(s, v)
+        if kind in ("elementwise", "max", "min"):
+            G.h.compare(f"seed{seed}.out{k}", g_, w_, 2e-6 * d, 1e-6 * d)
+        elif kind == "sum":
+            G.h.compare(f"seed{seed}.out{k}", g_, w_, 1e-5 + 2e-6 * d, 1e-6 * d, scale=magnitude[0])
+        else:
+            G.h.compare(f"seed{seed}.out{k}", g_, w_, 1e-5 + 2e-6 * d, 1e-6 * d, scale=magnitude[0] + magnitude[1])
 
 
 # ------------------------------------------------------------------ softmax chains split over workgroups
@@ -859,7 +881,7 @@ def test_random_softmax_chains(seed, oracle, G):
         elif name == "p":
             G.h.compare(name, g_, w_, *((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3)))
         else:
-            G.h.compare(name, g_, w_, 1e-5, 2e-6)
+            G.h.compare(name, g_, w_, 1e-5, 1e-6)
 
 
 def test_reductions_over_axes_far_apart_in_memory(oracle, G):
@@ -880,8 +902,8 @@ def test_reductions_over_axes_far_apart_in_memory(oracle, G):
         assert expr.info()["kernel_class"] == "multi" and expr.info(0)["kernel_class"] == "col", expr.info()
         want = oracle.evaluate(s, [x], nthreads=4)
         assert [g_.shape for g_ in got] == [w_.shape for w_ in want]
-        G.h.compare("sum", got[0], want[0], 1e-5, 2e-5); G.h.compare("max", got[1], want[1], 0, 0)
-        G.h.compare("min", got[2], want[2], 0, 0); G.h.compare("prod", got[3], want[3], 2e-5, 1e-6)
+        G.h.compare("sum", got[0], want[0], 1e-5, 1e-6, scale=np.abs(x.astype(np.float64)).sum(axes)); G.h.compare("max", got[1], want[1], 0, 0)
+        G.h.compare("min", got[2], want[2], 0, 0); G.h.compare("prod", got[3], want[3], G.h.product_rtol(x.size // want[3].size), 1e-6)
         G.h.compare("norm", got[4], want[4], 1e-5, 1e-6)
     # a transposed view makes the same situation out of neighbouring axes
     y = rng.standard_normal((300, 8, 700)).astype(np.float32)
@@ -891,7 +913,7 @@ def test_reductions_over_axes_far_apart_in_memory(oracle, G):
     yt = np.ascontiguousarray(y.transpose(0, 2, 1)).transpose(0, 2, 1)      # axis 1 is now the fastest in memory
     expr, got = run_spec(G, s, [yt])
     assert expr.info()["kernel_class"] == "multi"
-    G.h.compare("sum01", got[0], oracle.evaluate(s, [yt])[0], 1e-5, 2e-5)
+    G.h.compare("sum01", got[0], oracle.evaluate(s, [yt])[0], 1e-5, 1e-6, scale=np.abs(y.astype(np.float64)).sum((0, 1)))
 
 
 @pytest.mark.parametrize("shape,first", [((128, 96, 14, 14), "col"), ((128, 336, 14, 14), "lane"), ((24, 448, 28, 28), "lane"), ((24, 288, 36, 36), "row")])
@@ -916,7 +938,7 @@ def test_channel_statistics_of_late_layers_with_an_elementwise_output(shape, fir
     assert expr.info(0)["kernel_class"] == first and expr.info(0)["extent"] == (n, c, hh * ww), expr.info(0)
     assert int(np.prod(expr.info(1)["extent"])) < x.size // 8, expr.info(1)           # nothing sweeps the tensor twice
     want = oracle.evaluate(s, [x, b], nthreads=4)
-    G.h.compare("y", got[0], want[0], 2e-6, 1e-6); G.h.compare("sum", got[1], want[1], 1e-5, 1e-5)
+    G.h.compare("y", got[0], want[0], 2e-6, 1e-6); G.h.compare("sum", got[1], want[1], 1e-5, 1e-6)
     G.h.compare("max", got[2], want[2], 0, 0)
     # written over its input, the element-wise output waits for the last pass, which still finds
     # the input intact
@@ -929,7 +951,7 @@ def test_channel_statistics_of_late_layers_with_an_elementwise_output(shape, fir
     torch.cuda.synchronize()
     assert int(np.prod(expr2.info(expr2.info()["grid_blocks"] - 1)["extent"])) == x.size
     G.h.compare("y in place", xd.cpu().numpy(), want[0], 2e-6, 1e-6)
-    G.h.compare("sum", outs[1].cpu().numpy(), want[1], 1e-5, 1e-5); G.h.compare("max", outs[2].cpu().numpy(), want[2], 0, 0)
+    G.h.compare("sum", outs[1].cpu().numpy(), want[1], 1e-5, 1e-6); G.h.compare("max", outs[2].cpu().numpy(), want[2], 0, 0)
 
 
 # ------------------------------------------------------------------ short rows: several rows per wavefront
@@ -969,7 +991,7 @@ def test_short_rows_share_a_wavefront(cols, storage, oracle, G):
     assert expr.info()["kernel_class"] == lanes_expected(expr.info()), expr.info()
     want = oracle.evaluate(s, [x, t], nthreads=4)
     G.h.compare("p", got[0], want[0], *((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3)))
-    G.h.compare("loss", got[1], want[1], 1e-5, 2e-6)
+    G.h.compare("loss", got[1], want[1], 1e-5, 1e-6)
     assert np.array_equal(got[2], want[2]) and got[2][7] == 0
     assert np.array_equal(got[3], want[3], equal_nan=True)
     G.h.compare("mean_loss", got[4], want[4], 1e-5, 1e-6)
@@ -985,8 +1007,9 @@ def test_short_rows_share_a_wavefront(cols, storage, oracle, G):
     # the slice is not aligned for wide accesses: single elements, several of them per lane
     assert expr.info()["vec"] == 1 and expr.info()["kernel_class"] == lanes_expected(expr.info())
     want = oracle.evaluate(s2, [view, scale], nthreads=4)
-    # (a sum of cols terms of either sign and size about 2: the absolute bar grows with the row)
-    G.h.compare("wsum", got[0], want[0], 1e-5, 1e-5 * max(1.0, cols / 128)); G.h.compare("prod", got[1], want[1], 1e-5, 1e-6)
+    # (terms of either sign: the bar is relative to the sum of their magnitudes)
+    G.h.compare("wsum", got[0], want[0], 1e-5, 1e-6, scale=np.abs(view.astype(np.float64) * scale).sum(1))
+    G.h.compare("prod", got[1], want[1], 1e-5, 1e-6)
 
 
 @pytest.mark.parametrize("shape,axis", [((5001, 4, 8), 1), ((3000, 3, 12), 1), ((777, 2, 5, 6), 1), ((40000, 2, 2), 1), ((9, 1100, 5, 4), 2)])
@@ -1007,7 +1030,7 @@ def test_short_middle_axis_with_few_columns(shape, axis, oracle, G):
     assert expr.info()["kernel_class"] == "col", expr.info()
     assert expr.info()["grid_blocks"] < int(np.prod(shape[:axis])) // 4       # many outer indices per workgroup
     want = oracle.evaluate(s, [x], nthreads=4)
-    G.h.compare("sum", got[0], want[0], 1e-5, 2e-6); G.h.compare("max", got[1], want[1], 0, 0)
+    G.h.compare("sum", got[0], want[0], 1e-5, 1e-6, scale=np.abs(x.astype(np.float64)).sum(axis)); G.h.compare("max", got[1], want[1], 0, 0)
     G.h.compare("argmax", got[2], want[2], 0, 0); G.h.compare("tanh", got[3], want[3], 2e-6, 1e-6)
 
 
@@ -1031,7 +1054,7 @@ def test_short_middle_axis_at_streaming_size(shape, axis, storage, oracle, G):
     assert info["kernel_class"] == "col" and info["rank"] == 3 and info["tile"][0] > 1, info
     assert "yg_out0" in expr.source() and "ewf_finish" not in expr.source()
     want = oracle.evaluate(s, [x], nthreads=4)
-    G.h.compare("sum", got[0], want[0], 1e-5, 2e-6); G.h.compare("max", got[1], want[1], 0, 0)
+    G.h.compare("sum", got[0], want[0], 1e-5, 1e-6, scale=np.abs(x.astype(np.float64)).sum(axis)); G.h.compare("max", got[1], want[1], 0, 0)
     G.h.compare("argmax", got[2], want[2], 0, 0)
     # with an element-wise output and an output computed from the sums in the same pass
     s2 = GraphSpec(nd)
@@ -1041,8 +1064,8 @@ def test_short_middle_axis_at_streaming_size(shape, axis, storage, oracle, G):
     expr, got = run_spec(G, s2, [x])
     assert expr.info()["kernel_class"] == "col", expr.info()
     want = oracle.evaluate(s2, [x], nthreads=4)
-    tol = (2e-3, 2e-3) if storage == "f16" else (2e-6, 1e-6)
-    G.h.compare("tanh", got[0], want[0], *tol); G.h.compare("norm", got[1], want[1], 1e-5, 2e-6)
+    tol = (2e-3, 1e-3) if storage == "f16" else (2e-6, 1e-6)
+    G.h.compare("tanh", got[0], want[0], *tol); G.h.compare("norm", got[1], want[1], 1e-5, 1e-6)
 
 
 @pytest.mark.parametrize("shape,axes", [((6, 5001, 7, 24), (0, 2)), ((3, 40, 3001, 4, 8), (0, 1, 3)), ((5, 70001, 2, 16), (0, 2))])
@@ -1063,7 +1086,7 @@ def test_short_middle_axis_among_several_reduced_axes(shape, axes, oracle, G):
     kept = [d for d in range(info["rank"] - 1) if not info["reduced"][d]]
     assert info["tile"][kept[-1]] > 1, info                                  # several outer indices per workgroup
     want = oracle.evaluate(s, [x], nthreads=4)
-    G.h.compare("sum", got[0], want[0], 1e-5, 2e-6); G.h.compare("max", got[1], want[1], 0, 0)
+    G.h.compare("sum", got[0], want[0], 1e-5, 1e-6, scale=np.abs(x.astype(np.float64)).sum(axes)); G.h.compare("max", got[1], want[1], 0, 0)
 
 
 def test_rank_zero_and_rank_eight(oracle, G):
@@ -1088,7 +1111,8 @@ def test_rank_zero_and_rank_eight(oracle, G):
     expr, got = run_spec(G, s, [x, y])
     want = oracle.evaluate(s, [x, y])
     assert [g_.shape for g_ in got] == [w_.shape for w_ in want] == [shape, (2, 4, 2, 4), (1, 3, 1, 5, 2, 3, 4, 5), shape[:7]]
-    G.h.compare("exp", got[0], want[0], 2e-6, 1e-6); G.h.compare("sum", got[1], want[1], 1e-5, 1e-5)
+    G.h.compare("exp", got[0], want[0], 2e-6, 1e-6)
+    G.h.compare("sum", got[1], want[1], 1e-5, 1e-6, scale=np.abs(x.astype(np.float64) * y).sum((1, 3, 5, 7)))
     G.h.compare("max", got[2], want[2], 0, 0); G.h.compare("argmax", got[3], want[3], 0, 0)
 
 
@@ -1146,7 +1170,7 @@ def test_softmax_in_place(shape, axis, opts, oracle, G):
     expr.run([t], [t, lse], (), ws, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     G.h.compare("p", t.cpu().numpy(), want_p, 1e-5, 1e-8)
-    G.h.compare("lse", lse.cpu().numpy(), want_l, 1e-5, 2e-6)
+    G.h.compare("lse", lse.cpu().numpy(), want_l, 1e-5, 1e-6)
 
 
 # ------------------------------------------------------------------ rows that start anywhere and end inside a vector
@@ -1175,7 +1199,7 @@ def test_wide_accesses_on_rows_of_odd_length(rows, cols, storage, oracle, G):
     info = expr.info()
     assert info["kernel_class"] == "tile_reduce" and info["vec"] == 16 // x.itemsize and "ewf_ld_u<" in expr.source(), info
     want = oracle.evaluate(s, [x, t], nthreads=4)
-    G.h.compare("sum", got[0], want[0], 1e-5, 1e-5); G.h.compare("max", got[1], want[1], 0, 0)
+    G.h.compare("sum", got[0], want[0], 1e-5, 1e-6); G.h.compare("max", got[1], want[1], 0, 0)
     G.h.compare("argmax", got[2], want[2], 0, 0); G.h.compare("min", got[3], want[3], 0, 0)
     G.h.compare("gather", got[4], want[4], 0, 0)
     assert got[2][rows // 2] == cols - 1
@@ -1192,7 +1216,8 @@ def test_wide_accesses_on_rows_of_odd_length(rows, cols, storage, oracle, G):
     expr, got = run_spec(G, s2, [va, vb, vc])
     assert expr.info()["kernel_class"] == "tile_reduce" and expr.info()["vec"] == 16 // x.itemsize, expr.info()
     want = oracle.evaluate(s2, [va, vb, vc], nthreads=4)
-    G.h.compare("sum", got[0], want[0], 1e-5, 1e-5 * max(1.0, cols / 4096)); G.h.compare("max", got[1], want[1], 2e-6 if storage == "f32" else 2e-3, 1e-6)
+    terms = np.abs(va.astype(np.float64) * vb) + np.abs(vc.astype(np.float64))            # either sign: bar relative to their magnitudes
+    G.h.compare("sum", got[0], want[0], 1e-5, 1e-6, scale=terms.sum(1)); G.h.compare("max", got[1], want[1], 2e-6, 1e-6)
 
 
 @pytest.mark.parametrize("shape,offset", [((3000, 1023), 1), ((1, 5000001), 3), ((700, 4100), 5)])
@@ -1221,7 +1246,7 @@ def test_wide_accesses_on_float16_views_from_an_odd_element(shape, offset, oracl
     torch.cuda.synchronize()
     assert expr.info()["kernel_class"] == "tile" and expr.info()["vec"] == 8 and "ewf_st_u<" in expr.source(), expr.info()
     want = oracle.evaluate(s, [x, b], nthreads=4)
-    G.h.compare("tanh", out0.cpu().numpy(), want[0], 2e-3, 2e-3); G.h.compare("half", out1.cpu().numpy(), want[1], 2e-6, 1e-6)
+    G.h.compare("tanh", out0.cpu().numpy(), want[0], 2e-3, 1e-3); G.h.compare("half", out1.cpu().numpy(), want[1], 2e-6, 1e-6)
     edge = outbuf.cpu().numpy()
     assert np.isnan(edge[:, :2]).all() and np.isnan(edge[:, 2 + cols:]).all()         # nothing written outside the view
 

@@ -76,7 +76,7 @@ def random_mixed_case(seed):
     fv, iv = fvals[-1], ivals[-1]
     if rng.integers(0, 2):
         st = "f16" if rng.integers(0, 2) else "f32"
-        s.output(fv, st); tols.append((2e-4, 2e-5) if st == "f32" else (3e-3, 2e-3))
+        s.output(fv, st); tols.append((2e-6, 1e-6) if st == "f32" else (2e-3, 1e-3))
     if rng.integers(0, 3) == 0:
         s.output(iv, "i32"); tols.append((0, 0))
     axes = tuple(sorted(rng.choice(nd, size=int(rng.integers(1, nd + 1)), replace=False).tolist()))
@@ -84,9 +84,9 @@ def random_mixed_case(seed):
     for _ in range(int(rng.integers(0 if tols else 1, 4))):
         r = int(rng.integers(0, 6))
         if r == 0:
-            s.output(s.reduce("sum", fv, axes, keep=keep), "f32"); tols.append((2e-4, 1e-3))
+            s.output(s.reduce("sum", fv, axes, keep=keep), "f32"); tols.append((1e-5, 1e-6))
         elif r == 1:
-            s.output(s.reduce("max", fv, axes, keep=keep), "f32"); tols.append((2e-4, 2e-5))
+            s.output(s.reduce("max", fv, axes, keep=keep), "f32"); tols.append((2e-6, 1e-6))
         elif r == 2:
             s.output(s.reduce("min", fvals[0], axes, keep=keep), "f32"); tols.append((0, 0))
         elif r == 3:

@@ -30,11 +30,12 @@ def _check(G, oracle, tag, s, inputs, tols):
     if klass == "multi":
         klass += ":" + "+".join(expr.info(i)["kernel_class"] for i in range(info["grid_blocks"]))
     print(f"[ok-so-far] {tag} -> {klass}", flush=True)
-    for k, (g_, w_, (rtol, atol)) in enumerate(zip(got, want, tols)):
+    for k, (g_, w_, tol) in enumerate(zip(got, want, tols)):
+        rtol, atol = tol[:2]
         if rtol == 0 and atol == 0:
             assert np.array_equal(g_, w_, equal_nan=True), f"{tag} output {k}: {np.argwhere(g_ != w_)[:3].tolist()}"
-        else:
-            G.h.compare(f"{tag}.out{k}", g_, w_, rtol, atol)
+        else:               # (a third entry: the sum of the magnitudes of a sum's terms, which the bar is then relative to)
+            G.h.compare(f"{tag}.out{k}", g_, w_, rtol, atol, scale=tol[2] if len(tol) > 2 else None)
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -54,18 +55,18 @@ def test_random_short_rows(seed, oracle):
     tols = []
     kind = int(rng.integers(0, 4))
     if kind == 0:                                            # plain reductions
-        s.output(s.reduce("sum", xi, (1,)), "f32"); tols.append((1e-5, 2e-5))
+        s.output(s.reduce("sum", xi, (1,)), "f32"); tols.append((1e-5, 1e-6, np.abs(x.astype(np.float64)).sum(1)))
         s.output(s.reduce("max", xi, (1,)), "f32"); tols.append((0, 0))
         s.output(s.reduce("argmax", xi, (1,), keep=True), "i32"); tols.append((0, 0))
     elif kind == 1:                                          # softmax probabilities and log-sum-exp
         m = s.reduce("max", xi, (1,), keep=True); ex = s.apply("exp", s.sub(xi, m)); S = s.reduce("sum", ex, (1,), keep=True)
         s.output(s.div(ex, S), storage); tols.append((1e-5, 1e-8) if storage == "f32" else (2e-3, 1e-3))
-        s.output(s.add(m, s.apply("log", S)), "f32"); tols.append((1e-5, 2e-6))
+        s.output(s.add(m, s.apply("log", S)), "f32"); tols.append((1e-5, 1e-6))
     elif kind == 2:                                          # cross-entropy with arg-max and mean
         m = s.reduce("max", xi, (1,), keep=True); ex = s.apply("exp", s.sub(xi, m)); S = s.reduce("sum", ex, (1,), keep=True)
         xt = s.reduce("sum", s.apply("where", s.apply("eq", s.iota(1), ti), xi, s.const(0.0)), (1,), keep=True)
         loss = s.sub(s.add(m, s.apply("log", S)), xt)
-        s.output(loss, "f32"); tols.append((1e-5, 2e-6))
+        s.output(loss, "f32"); tols.append((1e-5, 1e-6))
         s.output(s.reduce("argmax", xi, (1,)), "i32"); tols.append((0, 0))
         s.output(s.div(s.reduce("sum", loss, (0,)), s.const(float(rows))), "f32"); tols.append((1e-5, 1e-6))
     else:                                                    # mean and variance along the row, normalised output
@@ -73,8 +74,8 @@ def test_random_short_rows(seed, oracle):
         mean = s.mul(s.reduce("sum", xi, (1,), keep=True), inv)
         cen = s.sub(xi, mean)
         var = s.mul(s.reduce("sum", s.apply("sqr", cen), (1,), keep=True), inv)
-        s.output(s.div(cen, s.apply("sqrt", s.add(var, s.const(1e-3)))), "f32"); tols.append((5e-5, 5e-5))
-        s.output(var, "f32"); tols.append((2e-5, 1e-6))
+        s.output(s.div(cen, s.apply("sqrt", s.add(var, s.const(1e-3)))), "f32"); tols.append((1e-5, 1e-6))
+        s.output(var, "f32"); tols.append((1e-5, 1e-6))
     tag = f"rows seed {seed}: {rows} x {cols} {storage} padded by {pad}, kind {kind}"
     print(f"[case] {tag}", flush=True)
     _check(G, oracle, tag, s, [x, t], tols)
@@ -96,7 +97,7 @@ def test_random_axis_masks(seed, oracle):
     s = GraphSpec(nd)
     yi = s.input("f32", (False,) * nd)
     s.output(s.reduce("sum", yi, axes), "f32"); s.output(s.reduce("min", yi, axes, keep=True), "f32")
-    tols = [(1e-5, 1e-4), (0, 0)]
+    tols = [(1e-5, 1e-6, np.abs(y.astype(np.float64)).sum(axes)), (0, 0)]      # terms of either sign
     if rng.integers(0, 2):
         s.output(s.apply("abs", yi), "f32"); tols.append((0, 0))
     tag = f"axes seed {seed}: {dims} reduced over {axes}"
@@ -151,14 +152,14 @@ def test_random_column_plans_at_streaming_size(seed, oracle):
         v = s.apply(["tanh", "sqrt", "sqr", "sigmoid"][int(rng.integers(4))], v)
     tols = []
     if rng.integers(0, 2):
-        s.output(s.apply("max", s.const(0.6), v), storage); tols.append((2e-6, 1e-6) if storage == "f32" else (2e-3, 2e-3))
+        s.output(s.apply("max", s.const(0.6), v), storage); tols.append((2e-6, 1e-6) if storage == "f32" else (2e-3, 1e-3))
     keep = bool(rng.integers(0, 2))
     for _ in range(int(rng.integers(1, 4))):
         r = int(rng.integers(0, 5))
-        if r == 0: s.output(s.reduce("sum", v, axes, keep=keep), "f32"); tols.append((1e-5, 1e-5))
+        if r == 0: s.output(s.reduce("sum", v, axes, keep=keep), "f32"); tols.append((1e-5, 1e-6))
         elif r == 1: s.output(s.reduce("max", v, axes, keep=keep), "f32"); tols.append((2e-6, 1e-6))
         elif r == 2: s.output(s.reduce("min", xi, axes, keep=keep), storage); tols.append((0, 0))
-        elif r == 3: s.output(s.apply("log", s.reduce("sum", s.apply("sqr", v), axes, keep=keep)), "f32"); tols.append((1e-5, 1e-5))
+        elif r == 3: s.output(s.apply("log", s.reduce("sum", s.apply("sqr", v), axes, keep=keep)), "f32"); tols.append((1e-5, 1e-6))
         else:
             s.output(s.reduce("argmax", xi, (axes[-1],), keep=keep), "i32"); tols.append((0, 0))
             break
@@ -186,7 +187,7 @@ def test_random_column_plans_with_few_or_odd_columns(seed, oracle):
     s = GraphSpec(nd)
     xi = s.input(storage, (False,) * nd)
     s.output(s.reduce("sum", xi, axes), "f32"); s.output(s.reduce("max", xi, axes, keep=True), storage)
-    tols = [(1e-5, 1e-5), (0, 0)]
+    tols = [(1e-5, 1e-6), (0, 0)]
     if len(axes) == 1:
         s.output(s.reduce("argmax", xi, axes), "i32"); tols.append((0, 0))
     _check(G, oracle, f"narrow columns seed{seed} {storage} shape{shape} axes{axes}", s, [x], tols)
