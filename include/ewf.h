@@ -16,6 +16,7 @@
  *   ewf_plan                      canonicalise shapes/strides, generate and compile the
  *                                 gfx950 kernel for this layout class, cache it (no launch)
  *   ewf_run                       launch on the caller's stream              (asynchronous)
+ *   ewf_run_static                the same without a caller's workspace      (asynchronous)
  *
  * Conventions
  *   - Every function returns 0 (EWF_OK) or a negative ewf_status.  No C++ exception crosses
@@ -217,6 +218,20 @@ ewf_status ewf_workspace_init(void *workspace, size_t workspace_bytes, void *hip
 ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double *scalars,
                    int32_t nscalars, const ewf_tensor *out, int32_t nout, void *workspace,
                    size_t workspace_bytes, void *hip_stream);
+
+/* ewf_run for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and results as ewf_run, but
+ * the workspace is a static device array of EWF_STATIC_WORKSPACE_BYTES inside the library (each
+ * GPU the library runs on holds it until the process ends), and the call sets nothing up: it
+ * calls no hipMalloc, hipFree, compiler or module loader.  The layout must have been planned
+ * before with ewf_plan while the same device was current (that compiles the kernels and loads
+ * them); otherwise EWF_EINVAL.  A layout whose plan needs a larger workspace is EWF_ENOMEM: use
+ * ewf_run with a workspace of your own.  Every call on one GPU shares that GPU's array: calls
+ * that may overlap in time (different streams, threads or processes' worth of executables) race;
+ * calls on one stream do not.  Nothing needs clearing between calls (see ewf_workspace_init). */
+#define EWF_STATIC_WORKSPACE_BYTES (4u << 20)
+ewf_status ewf_run_static(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double *scalars,
+                          int32_t nscalars, const ewf_tensor *out, int32_t nout, void *hip_stream);
 
 /* The arguments of ewf_run gathered in one structure, for launch loops driven from another
  * language: a prepared call is passed as a single pointer (section 2.3, function execution:

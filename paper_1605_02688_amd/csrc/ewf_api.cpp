@@ -21,8 +21,6 @@ void aux_fill_view(void *ptr, int rank, const int64_t *shape, const int64_t *str
 
 using namespace ewf;
 
-struct ewf_exec { Exec e; };
-
 namespace {
 
 std::string layout_signature(const Graph &g, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout)
@@ -65,7 +63,7 @@ namespace ewf {
 
 static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full);
 
-ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result)
+ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result, bool lookup_only)
 {
     if (!args_present(e.g, in, nin, out, nout)) {
         set_error("expected %d input and %d output tensors with shape and strides", e.g.ninputs, (int)e.g.outputs.size());
@@ -94,6 +92,10 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
         return EWF_OK;
     }
 
+    if (lookup_only) {
+        set_error("this layout has not been planned: call ewf_plan for it first (this entry point compiles nothing)");
+        return EWF_EINVAL;
+    }
     std::unique_ptr<Plan> plan(new Plan());
     int64_t full[kMaxDims];
     ewf_status st = infer_full_extents(e.g, in, nin, full, e.has_forced_full ? e.forced_full : nullptr);
@@ -389,6 +391,11 @@ ewf_status ewf_plan(ewf_exec *e, const ewf_tensor *in, int32_t nin, const ewf_te
     ewf_status st = make_plan(e->e, in, nin, out, nout, &p);
     if (st != EWF_OK) return st;
     if (workspace_bytes) *workspace_bytes = p->workspace_bytes;
+    // with a device at hand the kernels are loaded now rather than by the first launch (planning
+    // itself needs no device: the run-time compiler cross-compiles)
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) return load_plan_functions(*p);
+    (void)hipGetLastError();
     return EWF_OK;
 }
 
@@ -413,15 +420,38 @@ ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double 
 
 namespace ewf {
 
+ewf_status load_plan_functions(Plan &p)
+{
+    if (p.empty) return EWF_OK;
+    if (p.kclass == KernelClass::Multi) {
+        for (Stage &sg : p.stages) {
+            if (!sg.exec->last) continue;
+            ewf_status st = load_plan_functions(*sg.exec->last);
+            if (st != EWF_OK) return st;
+        }
+        return EWF_OK;
+    }
+    int dev = -1;
+    if (p.function && hipGetDevice(&dev) == hipSuccess && dev == p.function_device) return EWF_OK;
+    ewf_status st = load_function(p.code, "ewf_kernel", &p.function, &p.function_device);
+    if (st != EWF_OK) return st;
+    if (p.finish_grid > 0) {
+        st = load_function(p.code, "ewf_finish", &p.finish_function, &p.function_device);
+        if (st != EWF_OK) { p.function = nullptr; return st; }
+    }
+    return EWF_OK;
+}
+
 ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
-                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream)
+                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream,
+                    bool no_setup)
 {
     if (nscalars != x.g.nscalars || (nscalars > 0 && !scalars)) {
         set_error("expected %d run-time scalar(s), got %d", x.g.nscalars, nscalars);
         return EWF_EINVAL;
     }
     Plan *p = nullptr;
-    ewf_status st = make_plan(x, in, nin, out, nout, &p);
+    ewf_status st = make_plan(x, in, nin, out, nout, &p, no_setup);
     if (st != EWF_OK) return st;
     if (p->empty) {
         for (const Plan::Fill &f : p->fills) {
@@ -440,15 +470,15 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
         if ((uintptr_t)workspace & 15) { set_error("workspace must be 16-byte aligned"); return EWF_EINVAL; }
     }
     if (p->kclass == KernelClass::Multi)
-        return run_multi(x, *p, in, nin, scalars, nscalars, out, nout, workspace, workspace_bytes, hip_stream);
+        return run_multi(x, *p, in, nin, scalars, nscalars, out, nout, workspace, workspace_bytes, hip_stream, no_setup);
     int dev = -1;
     if (!p->function || hipGetDevice(&dev) != hipSuccess || dev != p->function_device) {
-        st = load_function(p->code, "ewf_kernel", &p->function, &p->function_device);
-        if (st != EWF_OK) return st;
-        if (p->finish_grid > 0) {
-            st = load_function(p->code, "ewf_finish", &p->finish_function, &p->function_device);
-            if (st != EWF_OK) { p->function = nullptr; return st; }
+        if (no_setup) {
+            set_error("the kernels of this layout are not loaded on the current device: call ewf_plan with that device current first");
+            return EWF_EINVAL;
         }
+        st = load_plan_functions(*p);
+        if (st != EWF_OK) return st;
     }
 
     // patch pointers and scalars into a copy of the prepared argument block

@@ -1,10 +1,14 @@
-// Two small ahead-of-time kernels for gfx950: a zero fill for workspace bookkeeping (a fill
-// kernel rather than a memset so that callers may record it into a HIP graph) and the plain
-// dwordx4 grid-stride copy that bandwidth figures are quoted against.
+// Small ahead-of-time device code for gfx950: a zero fill for workspace bookkeeping (a fill
+// kernel rather than a memset so that callers may record it into a HIP graph), the plain
+// dwordx4 grid-stride copy that bandwidth figures are quoted against, and the library's own
+// static workspace with the entry point that uses it.
 #include <hip/hip_runtime.h>
 
 #include <cstddef>
 #include <cstdint>
+#include <mutex>
+
+#include "ewf_internal.h"
 
 namespace ewf {
 
@@ -86,3 +90,66 @@ void aux_copy(void *dst, const void *src, size_t nbytes, hipStream_t stream)
 }
 
 }  // namespace ewf
+
+// =========================================================================================
+// ewf_run_static: ewf_run for callers that cannot allocate device memory.
+//
+// The workspace (partial results of reductions split over workgroups, temporaries of plans in
+// several passes) lives in `scratch`, a static device array that every GPU the library runs on
+// holds until the process ends.  In host code the array's name is only a handle for the symbol,
+// not a device address: its address on the current device is asked for once per device and kept;
+// everything that touches the memory -- kernel arguments here -- uses that address.
+
+static __device__ __align__(256) unsigned char scratch[EWF_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Address of `scratch` on the current device (looked up on the first call per device).
+ewf_status static_workspace(void **ptr)
+{
+    int dev = -1;
+    hipError_t he = hipGetDevice(&dev);
+    if (he != hipSuccess) { ewf::set_error("no HIP device: %s", hipGetErrorString(he)); return EWF_EHIP; }
+    if (dev < 0 || dev >= kMaxDevices) { ewf::set_error("device ordinal %d is beyond the %d this entry point supports", dev, kMaxDevices); return EWF_EINVAL; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        he = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (he != hipSuccess || !p) {
+            ewf::set_error("hipGetSymbolAddress(static workspace): %s", hipGetErrorString(he));
+            return EWF_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return EWF_OK;
+}
+
+}  // namespace
+
+extern "C" ewf_status ewf_run_static(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
+                                     const ewf_tensor *out, int32_t nout, void *hip_stream)
+{
+    if (!e) { ewf::set_error("null executable"); return EWF_EINVAL; }
+    // the layout must have been planned (ewf_plan compiles and, with a device current, loads the
+    // kernels): nothing is compiled, loaded or allocated from here on
+    ewf::Plan *p = nullptr;
+    ewf_status st = ewf::make_plan(e->e, in, nin, out, nout, &p, /*lookup_only=*/true);
+    if (st != EWF_OK) return st;
+    if (p->workspace_bytes > (size_t)EWF_STATIC_WORKSPACE_BYTES) {
+        ewf::set_error("this layout needs a workspace of %zu bytes, the static one holds %zu: use ewf_run with a workspace of your own",
+                       p->workspace_bytes, (size_t)EWF_STATIC_WORKSPACE_BYTES);
+        return EWF_ENOMEM;
+    }
+    void *ws = nullptr;
+    st = static_workspace(&ws);
+    if (st != EWF_OK) return st;
+    // (the kernels write every workspace word before they read it: what the previous call left
+    // in the array needs no clearing)
+    return ewf::run_exec(e->e, in, nin, scalars, nscalars, out, nout, ws, (size_t)EWF_STATIC_WORKSPACE_BYTES, hip_stream,
+                         /*no_setup=*/true);
+}

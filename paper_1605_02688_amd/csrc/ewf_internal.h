@@ -270,9 +270,16 @@ ewf_status infer_full_extents(const Graph &g, const ewf_tensor *in, int nin, int
 ewf_status generate(const Exec &e, Plan &p);
 
 // ---- ewf_api.cpp
-ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result);
+// With `lookup_only` a layout that has not been planned is an error (nothing is generated or compiled).
+ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result,
+                     bool lookup_only = false);
+// With `no_setup` the call only launches: a layout that has not been planned, or kernels that are
+// not loaded on the current device yet, are errors instead of being compiled and loaded here.
 ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
-                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream);
+                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream,
+                    bool no_setup = false);
+// Loads the kernels of a plan (of every stage of a plan in passes) on the current device.
+ewf_status load_plan_functions(Plan &p);
 
 // ---- ewf_multi.cpp
 // Splits an expression that no single kernel class covers into stages: first-level reductions
@@ -281,7 +288,8 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
 // With `strict_rows` no stage may use the row class where it fits poorly (see Plan::avoid_poor_rows).
 ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan);
 ewf_status run_multi(Exec &e, Plan &p, const ewf_tensor *in, int nin, const double *scalars, int nscalars,
-                     const ewf_tensor *out, int nout, void *workspace, size_t workspace_bytes, void *hip_stream);
+                     const ewf_tensor *out, int nout, void *workspace, size_t workspace_bytes, void *hip_stream,
+                     bool no_setup = false);
 
 // ---- ewf_rtc.cpp
 // Compiles HIP source for gfx950 (no device needed); identical sources share one code object.
@@ -295,3 +303,5 @@ void cache_stats(int *mem_hits, int *disk_hits, int *compiles);
 int64_t code_scratch_bytes(const std::vector<char> &code);
 
 }  // namespace ewf
+
+struct ewf_exec { ewf::Exec e; };

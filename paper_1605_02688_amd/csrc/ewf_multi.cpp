@@ -273,7 +273,7 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
 }
 
 ewf_status run_multi(Exec &, Plan &p, const ewf_tensor *in, int, const double *scalars, int nscalars,
-                     const ewf_tensor *out, int, void *workspace, size_t, void *hip_stream)
+                     const ewf_tensor *out, int, void *workspace, size_t, void *hip_stream, bool no_setup)
 {
     char *base = (char *)workspace;
     std::vector<ewf_tensor> tin, tout;
@@ -288,7 +288,7 @@ ewf_status run_multi(Exec &, Plan &p, const ewf_tensor *in, int, const double *s
             else { const Temp &t = p.temps[-d - 1]; tout.push_back({base + t.offset, t.shape, t.strides}); }
         }
         ewf_status st = run_exec(*sg.exec, tin.data(), (int)tin.size(), scalars, nscalars, tout.data(), (int)tout.size(),
-                                 sg.ws_bytes ? base + sg.ws_offset : nullptr, sg.ws_bytes, hip_stream);
+                                 sg.ws_bytes ? base + sg.ws_offset : nullptr, sg.ws_bytes, hip_stream, no_setup);
         if (st != EWF_OK) return st;
     }
     return EWF_OK;

@@ -108,6 +108,8 @@ _sigs = {
     "ewf_workspace_init": (_i32, [_vp, ctypes.c_size_t, _vp]),
     "ewf_run": (_i32, [_vp, ctypes.POINTER(ewf_tensor), _i32, ctypes.POINTER(ctypes.c_double), _i32,
                        ctypes.POINTER(ewf_tensor), _i32, _vp, ctypes.c_size_t, _vp]),
+    "ewf_run_static": (_i32, [_vp, ctypes.POINTER(ewf_tensor), _i32, ctypes.POINTER(ctypes.c_double), _i32,
+                              ctypes.POINTER(ewf_tensor), _i32, _vp]),
     "ewf_run_call": (_i32, [ctypes.POINTER(ewf_call)]),
     "ewf_run_sequence": (_i32, [ctypes.POINTER(ewf_call), _i32, ctypes.POINTER(_i32)]),
     "ewf_last_error": (ctypes.c_char_p, []),
@@ -264,6 +266,16 @@ def run(e: int, inputs: Sequence, scalars: Sequence[float], outputs: Sequence, w
     sc = (ctypes.c_double * max(1, len(scalars)))(*[float(s) for s in scalars])
     _check(_lib.ewf_run(e, tin, len(inputs), sc, len(scalars), tout, len(outputs), workspace_ptr or None,
                         workspace_bytes, stream or None))
+
+
+STATIC_WORKSPACE_BYTES = 4 << 20
+
+
+def run_static(e: int, inputs: Sequence, scalars: Sequence[float], outputs: Sequence, stream: int = 0) -> None:
+    tin, _k1 = _marshal(inputs)
+    tout, _k2 = _marshal(outputs)
+    sc = (ctypes.c_double * max(1, len(scalars)))(*[float(s) for s in scalars])
+    _check(_lib.ewf_run_static(e, tin, len(inputs), sc, len(scalars), tout, len(outputs), stream or None))
 
 
 def debug_plan_info(e: int, stage: int = -1) -> dict:
@@ -434,6 +446,11 @@ class Expression:
         wptr = workspace.data_ptr() if workspace is not None else 0
         wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
         run(self.handle, inputs, scalars, outputs, wptr, wbytes, stream)
+
+    def run_static(self, inputs, outputs, scalars=(), stream: int = 0) -> None:
+        """ewf_run_static: the library's static workspace, nothing set up or allocated by the call
+        (the layout must have been planned with `plan`)."""
+        run_static(self.handle, inputs, scalars, outputs, stream)
 
     def bind(self, inputs, outputs, scalars=(), workspace=None, stream: int = 0) -> "BoundCall":
         """Marshals the arguments once; ``BoundCall.launch()`` is then a single ewf_run call."""

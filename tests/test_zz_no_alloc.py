@@ -1,0 +1,100 @@
+"""The entry point for callers that cannot allocate (ewf_run_static: the workspace is a static
+device array inside the library, nothing is compiled, loaded or allocated by the call), checked
+through the C ABI against ewf_run with a caller's workspace and against the CPU oracle: two calls
+in a row per workload, the second on a smaller input, so that the second call finds the array as
+the first one left it."""
+import numpy as np
+import pytest
+
+from workloads import GraphSpec
+from workloads import configs as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _batch_norm(rows, cols):
+    """mean, variance of the centred values and the normalised tensor over axis 0: a plan in
+    three passes whose temporaries live in the workspace."""
+    rng = np.random.default_rng(700 + rows)
+    x = rng.standard_normal((rows, cols)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    inv_n = s.const(1.0 / rows)
+    mean = s.mul(s.reduce("sum", xi, (0,), keep=True), inv_n)
+    cen = s.sub(xi, mean)
+    var = s.mul(s.reduce("sum", s.apply("sqr", cen), (0,), keep=True), inv_n)
+    s.output(s.div(cen, s.apply("sqrt", s.add(var, s.const(1e-5)))), "f32")
+    s.output(mean, "f32"); s.output(var, "f32")
+    return wl.Workload(f"batch_norm_{rows}x{cols}", s, [x], [wl.View(0, 0, x.shape, (cols, 1))], [], ["normalised", "mean", "var"],
+                       [wl.TOL_F32_REDUCE] * 3, x.size, 2 * x.nbytes)
+
+
+CASES = {
+    # name: (first call, second call on a smaller input, kernel class expected)
+    "c4": (lambda: wl.c4_bias_relu_chansum(n=8, c=16, h=28, w=28), lambda: wl.c4_bias_relu_chansum(n=2, c=8, h=14, w=14), "tile_reduce"),
+    "c3": (lambda: wl.c3_softmax_xent(rows=600, vocab=5000), lambda: wl.c3_softmax_xent(rows=520, vocab=1000), "row"),
+    "c4b": (lambda: wl.c4_bias_relu_chansum_backward(n=8, c=16, h=28, w=28), lambda: wl.c4_bias_relu_chansum_backward(n=2, c=8, h=14, w=14), "tile_reduce"),
+    "c3_long_rows": (lambda: wl.c3_softmax_xent(rows=9, vocab=150001), lambda: wl.c3_softmax_xent(rows=5, vocab=70001), "multi"),
+    "batch_norm": (lambda: _batch_norm(300, 70), lambda: _batch_norm(120, 30), "multi"),
+    "c1_no_workspace": (lambda: wl.c1_affine_tanh(rows=64, cols=256), lambda: wl.c1_affine_tanh(rows=16, cols=64), "tile"),
+}
+
+
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_static_workspace_matches_caller_workspace(case, oracle):
+    import torch
+    import tests.harness as h
+    from paper_1605_02688_amd import ewf
+    first, second, klass = CASES[case]
+    stream = torch.cuda.current_stream().cuda_stream
+    for make in (first, second):
+        w = make()
+        print(f"[case] {case}: {w.name} {[v.shape for v in w.views]}", flush=True)
+        expr = ewf.Expression(w.spec)
+        _bufs, ins = h.device_inputs(w)
+        ref = h.alloc_outputs(expr, w.spec, ins, fill=0)
+        got = h.alloc_outputs(expr, w.spec, ins, fill=0)
+        # the layout is unknown to the executable: the static entry point sets nothing up
+        with pytest.raises(ewf.EwfError) as err:
+            expr.run_static(ins, got, w.scalars, stream)
+        assert err.value.status == ewf.EINVAL and "planned" in err.value.message
+        nbytes = expr.plan(ins, got)
+        assert expr.info()["kernel_class"] == klass, expr.info()
+        assert nbytes <= ewf.STATIC_WORKSPACE_BYTES and (nbytes > 0) == (case != "c1_no_workspace")
+        # ewf_run with a caller's workspace full of NaN patterns: nothing needs clearing
+        ws = torch.full(((nbytes + 3) // 4,), -1, dtype=torch.int32, device="cuda") if nbytes else None
+        expr.run(ins, ref, w.scalars, ws, stream)
+        before = torch.cuda.memory_allocated()
+        expr.run_static(ins, got, w.scalars, stream)
+        assert torch.cuda.memory_allocated() == before
+        torch.cuda.synchronize()
+        want = oracle.evaluate(w.oracle_spec or w.spec, wl.host_inputs(w), w.scalars, nthreads=4)
+        for name, g, r, o, (rtol, atol) in zip(w.out_names, got, ref, want, w.tol):
+            g = g.cpu().numpy(); r = r.cpu().numpy()
+            # the same kernels, launch shapes and order of operations: the same bits
+            assert np.array_equal(g, r, equal_nan=True), f"{w.name}.{name}: static workspace differs from the caller's"
+            h.compare(f"{w.name}.{name} static", g, o, rtol, atol)
+
+
+def test_static_workspace_refuses_what_does_not_fit():
+    from paper_1605_02688_amd import ewf
+    from paper_1605_02688_amd.selfcheck import plan_layout
+    # planned on made-up addresses: the call must fail before anything is launched
+    w = wl.layout_only(wl.c4_bias_relu_chansum, n=1024)
+    expr = ewf.Expression(w.spec)
+    nbytes, _ = plan_layout(expr, w.spec, w.views, [w.buffers[v.buffer].itemsize for v in w.views])
+    assert nbytes > ewf.STATIC_WORKSPACE_BYTES
+    base, addr, ins = 0x7F0000000000, {}, []
+    for v in w.views:
+        if v.buffer not in addr:
+            addr[v.buffer] = base; base += 1 << 32
+        ins.append(ewf.TensorRef(addr[v.buffer] + v.offset * 4, tuple(v.shape), tuple(v.strides)))
+    outs = []
+    for shape in expr.output_shapes(ins):
+        st, acc = [], 1
+        for e in reversed(shape):
+            st.append(acc); acc *= e
+        outs.append(ewf.TensorRef(base, shape, tuple(reversed(st)))); base += 1 << 32
+    with pytest.raises(ewf.EwfError) as err:
+        expr.run_static(ins, outs, w.scalars, 0)
+    assert err.value.status == ewf.ENOMEM and "workspace of your own" in err.value.message
