@@ -319,6 +319,17 @@ ewf_status ewf_debug_cache_stats(int32_t *memory_hits, int32_t *disk_hits, int32
 
 /* ---- measurement aid ---- */
 
+/* Times the main kernel of the following ewf_run calls on this executable (the streaming pass;
+ * not the small second kernel that folds partial results; every stage of a plan in several
+ * passes): each such launch gets a pair of HIP events tied to that dispatch alone, so the
+ * durations are the kernel's own, as a profiler's kernel trace reports them, without the cost
+ * of recording events around a launch call.  `slots` = number of kernel launches to record
+ * (events are created here, none by ewf_run); 0 turns timing off. */
+ewf_status ewf_debug_time_kernels(ewf_exec *e, int32_t slots);
+/* Waits for the recorded launches and writes their durations in milliseconds, in launch order;
+ * *count = how many were written.  Recording starts again from the first slot. */
+ewf_status ewf_debug_kernel_times(ewf_exec *e, float *ms, int32_t capacity, int32_t *count);
+
 /* Plain device-to-device copy of nbytes (multiple of 16, 16-byte aligned pointers) with the
  * library's own dwordx4 grid-stride kernel: the measured ceiling that bandwidth figures and
  * hardware-counter scale factors are quoted against. */

@@ -7,6 +7,13 @@
 // computations are asynchronous so the host can run ahead).
 #include <hip/hip_runtime.h>
 
+// (declared here: the runtime's extension header needs the device compiler's front end)
+extern "C" hipError_t hipExtModuleLaunchKernel(hipFunction_t f, uint32_t globalWorkSizeX, uint32_t globalWorkSizeY,
+                                               uint32_t globalWorkSizeZ, uint32_t localWorkSizeX, uint32_t localWorkSizeY,
+                                               uint32_t localWorkSizeZ, size_t sharedMemBytes, hipStream_t hStream,
+                                               void **kernelParams, void **extra, hipEvent_t startEvent, hipEvent_t stopEvent,
+                                               uint32_t flags);
+
 #include <cstring>
 
 #include "ewf_internal.h"
@@ -60,6 +67,18 @@ bool args_present(const Graph &g, const ewf_tensor *in, int nin, const ewf_tenso
 }  // namespace
 
 namespace ewf {
+
+// Measurement aid: pairs of events, each tied to one dispatch of a main kernel (they carry that
+// dispatch's own begin and end time stamps, unlike events recorded around a launch call).
+struct KernelTiming {
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+    ~KernelTiming()
+    {
+        for (hipEvent_t ev : start) (void)hipEventDestroy(ev);
+        for (hipEvent_t ev : stop) (void)hipEventDestroy(ev);
+    }
+};
 
 static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full);
 
@@ -362,7 +381,49 @@ ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **o
     return EWF_OK;
 }
 
-void ewf_exec_destroy(ewf_exec *e) { delete e; }
+void ewf_exec_destroy(ewf_exec *e)
+{
+    if (e) { delete e->e.timing; e->e.timing = nullptr; }
+    delete e;
+}
+
+ewf_status ewf_debug_time_kernels(ewf_exec *e, int32_t slots)
+{
+    if (!e || slots < 0 || slots > (1 << 20)) { set_error("bad argument"); return EWF_EINVAL; }
+    delete e->e.timing;
+    e->e.timing = nullptr;
+    if (slots == 0) return EWF_OK;
+    KernelTiming *t = new (std::nothrow) KernelTiming();
+    if (!t) return EWF_ENOMEM;
+    for (int i = 0; i < slots; i++) {
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+            if (a) (void)hipEventDestroy(a);
+            delete t;
+            set_error("hipEventCreate failed");
+            return EWF_EHIP;
+        }
+        t->start.push_back(a); t->stop.push_back(b);
+    }
+    e->e.timing = t;
+    return EWF_OK;
+}
+
+ewf_status ewf_debug_kernel_times(ewf_exec *e, float *ms, int32_t capacity, int32_t *count)
+{
+    if (!e || !count || (capacity > 0 && !ms)) { set_error("null argument"); return EWF_EINVAL; }
+    *count = 0;
+    KernelTiming *t = e->e.timing;
+    if (!t) return EWF_OK;
+    for (int i = 0; i < t->used && i < capacity; i++) {
+        hipError_t he = hipEventSynchronize(t->stop[i]);
+        if (he == hipSuccess) he = hipEventElapsedTime(&ms[i], t->start[i], t->stop[i]);
+        if (he != hipSuccess) { set_error("kernel timing: %s", hipGetErrorString(he)); return EWF_EHIP; }
+        *count = i + 1;
+    }
+    t->used = 0;
+    return EWF_OK;
+}
 
 ewf_status ewf_output_shape(ewf_exec *e, const ewf_tensor *in, int32_t nin, int32_t k, int32_t *rank_out,
                             int64_t *shape_out)
@@ -500,8 +561,17 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
     }
     size_t arg_size = p->args.size();
     void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
-    hipError_t he = hipModuleLaunchKernel((hipFunction_t)p->function, (unsigned)p->grid, 1, 1, (unsigned)p->block, 1, 1,
-                                          0 /* LDS is declared statically in the kernels */, (hipStream_t)hip_stream, nullptr, config);
+    hipError_t he;
+    KernelTiming *tm = x.timing;
+    if (tm && tm->used < (int)tm->start.size() && p->grid * p->block < ((int64_t)1 << 32)) {
+        // a timed run: the same launch with a pair of events attached to this dispatch
+        const int slot = tm->used++;
+        he = hipExtModuleLaunchKernel((hipFunction_t)p->function, (uint32_t)(p->grid * p->block), 1, 1, (uint32_t)p->block, 1, 1, 0,
+                                      (hipStream_t)hip_stream, nullptr, config, tm->start[slot], tm->stop[slot], 0);
+    } else {
+        he = hipModuleLaunchKernel((hipFunction_t)p->function, (unsigned)p->grid, 1, 1, (unsigned)p->block, 1, 1,
+                                   0 /* LDS is declared statically in the kernels */, (hipStream_t)hip_stream, nullptr, config);
+    }
     if (he != hipSuccess) { set_error("kernel launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
     if (p->finish_grid > 0) {
         // partial results are folded by a second kernel on the same stream

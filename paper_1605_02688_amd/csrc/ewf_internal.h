@@ -135,6 +135,7 @@ struct ParamField {
 
 struct Plan;
 struct Exec;
+struct KernelTiming;                     // event pairs around the main kernels of timed runs (ewf_api.cpp)
 
 // Packs kernel arguments with C layout rules for the struct the generator declares.
 struct ParamLayout {
@@ -229,6 +230,7 @@ struct Exec {
     Plan *last = nullptr;
     int compile_count = 0;
     int nodes_before = 0, nodes_after = 0;   // size of the scalar graph before / after the rewrites
+    KernelTiming *timing = nullptr;          // measurement aid; owned by the top-level executable, lent to stages
 };
 
 // ---- ewf_ir.cpp

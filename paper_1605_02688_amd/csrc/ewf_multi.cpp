@@ -272,7 +272,7 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
     return EWF_OK;
 }
 
-ewf_status run_multi(Exec &, Plan &p, const ewf_tensor *in, int, const double *scalars, int nscalars,
+ewf_status run_multi(Exec &x, Plan &p, const ewf_tensor *in, int, const double *scalars, int nscalars,
                      const ewf_tensor *out, int, void *workspace, size_t, void *hip_stream, bool no_setup)
 {
     char *base = (char *)workspace;
@@ -287,6 +287,7 @@ ewf_status run_multi(Exec &, Plan &p, const ewf_tensor *in, int, const double *s
             if (d >= 0) tout.push_back(out[d]);
             else { const Temp &t = p.temps[-d - 1]; tout.push_back({base + t.offset, t.shape, t.strides}); }
         }
+        sg.exec->timing = x.timing;                 // timed runs record every stage's main kernel
         ewf_status st = run_exec(*sg.exec, tin.data(), (int)tin.size(), scalars, nscalars, tout.data(), (int)tout.size(),
                                  sg.ws_bytes ? base + sg.ws_offset : nullptr, sg.ws_bytes, hip_stream, no_setup);
         if (st != EWF_OK) return st;

@@ -123,6 +123,8 @@ _sigs = {
     "ewf_debug_compile_count": (_i32, [_vp]),
     "ewf_debug_graph_size": (_i32, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "ewf_copy_bytes": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
+    "ewf_debug_time_kernels": (_i32, [_vp, _i32]),
+    "ewf_debug_kernel_times": (_i32, [_vp, ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
     "ewf_set_cache_dir": (_i32, [ctypes.c_char_p]),
     "ewf_debug_cache_stats": (_i32, [ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
 }
@@ -325,6 +327,18 @@ def debug_cache_stats() -> dict:
     a, b, c = _i32(), _i32(), _i32()
     _check(_lib.ewf_debug_cache_stats(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
     return {"memory_hits": a.value, "disk_hits": b.value, "compiles": c.value}
+
+
+def debug_time_kernels(e: int, slots: int) -> None:
+    _check(_lib.ewf_debug_time_kernels(e, slots))
+
+
+def debug_kernel_times(e: int, capacity: int) -> List[float]:
+    """Durations in milliseconds of the main kernels launched since timing was turned on."""
+    ms = (ctypes.c_float * max(1, capacity))()
+    n = _i32(0)
+    _check(_lib.ewf_debug_kernel_times(e, ms, capacity, ctypes.byref(n)))
+    return [float(ms[i]) for i in range(n.value)]
 
 
 def copy_bytes(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:

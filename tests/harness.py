@@ -1,6 +1,6 @@
-"""Shared helpers of the GPU parity tests: binds a workload's host buffers to device tensors
-(same bytes, same strided views), runs the library through its C ABI binding, runs the
-oracle on the host arrays, compares."""
+"""Shared helpers of the GPU parity tests: runs a workload through the library's C ABI binding
+(device memory from `paper_1605_02688_amd.torchmem`), runs the oracle on the host arrays,
+compares."""
 from __future__ import annotations
 
 import os
@@ -11,43 +11,8 @@ import torch
 from paper_1605_02688_amd import ewf
 from workloads import configs as wl
 
-_TORCH = {"f32": torch.float32, "f16": torch.float16, "i32": torch.int32}
-
-
-def device_inputs(w, device="cuda"):
-    bufs = [torch.from_numpy(np.ascontiguousarray(b)).to(device) for b in w.buffers]
-    views = [torch.as_strided(bufs[v.buffer].view(-1), v.shape, v.strides, v.offset) for v in w.views]
-    return bufs, views
-
-
-def alloc_outputs(expr, spec, inputs, device="cuda", fill=None):
-    outs = []
-    for (v, storage), shape in zip(spec.outputs, expr.output_shapes(inputs)):
-        t = torch.empty(shape, dtype=_TORCH[storage], device=device)
-        if fill is not None:
-            t.fill_(fill)
-        outs.append(t)
-    return outs
-
-
-def make_workspace(expr, inputs, outputs, device="cuda"):
-    nbytes = expr.plan(inputs, outputs)
-    if nbytes == 0:
-        return None
-    ws = torch.empty((nbytes + 3) // 4, dtype=torch.int32, device=device)
-    ewf.workspace_init(ws.data_ptr(), ws.numel() * 4, torch.cuda.current_stream().cuda_stream)
-    return ws
-
-
-def run_gpu(w, expr=None, **opts):
-    """Returns (expression, outputs on the host as numpy arrays)."""
-    expr = expr or ewf.Expression(w.spec, **opts)
-    _bufs, ins = device_inputs(w)
-    outs = alloc_outputs(expr, w.spec, ins)
-    ws = make_workspace(expr, ins, outs)
-    expr.run(ins, outs, w.scalars, ws, torch.cuda.current_stream().cuda_stream)
-    torch.cuda.synchronize()
-    return expr, [o.cpu().numpy() for o in outs]
+from paper_1605_02688_amd.torchmem import alloc_outputs, device_inputs, make_workspace  # noqa: F401  (used by the tests)
+from paper_1605_02688_amd.torchmem import run_workload as run_gpu  # noqa: F401
 
 
 # The three bars the parity tests are held to (relative, absolute).
