@@ -34,9 +34,9 @@
  *   - An output may alias an input only exactly (same pointer, shape and strides; section
  *     2.2.1: element-wise operations may overwrite an input); any other overlap between an
  *     output and an input or another output is EWF_EALIAS.
- *   - A tensor with a zero extent is legal: success, nothing traversed.  An output that is a
- *     sum or a product over an empty axis is filled with 0 or 1; any other value computed from
- *     a reduction over an empty axis (max, min, arg-max, expressions of them) is EWF_ESHAPE.
+ *   - A tensor with a zero extent is legal: success, nothing traversed.  A sum or a product
+ *     over an empty axis is 0 or 1, also inside an expression; a maximum, minimum or arg-max over
+ *     an empty axis (or anything computed from one) is EWF_ESHAPE.
  *   - Thread safety: different ewf_exec handles may be used concurrently; one handle must be
  *     externally synchronised.
  */
@@ -316,6 +316,17 @@ ewf_status ewf_debug_graph_size(ewf_exec *e, int32_t *nodes_described, int32_t *
 
 /* Process-wide counts of kernel sources served from memory, from the disk cache, and compiled. */
 ewf_status ewf_debug_cache_stats(int32_t *memory_hits, int32_t *disk_hits, int32_t *compiles);
+
+/* The most run-time compilations that were in progress at the same moment so far in this process
+ * (distinct kernel sources are compiled concurrently; a second request for a source that is
+ * being compiled waits for the first). */
+ewf_status ewf_debug_peak_concurrent_compiles(int32_t *peak);
+/* Test hook for the rule that no C++ exception crosses this boundary: arms a fault on the calling
+ * thread.  The library passes fault points where it asks for host memory (adding a graph node,
+ * looking a plan up or making one); after `after` further points the next one throws --
+ * kind 1 as running out of memory (the call then returns EWF_ENOMEM), kind 2 as any other
+ * exception (EWF_EINVAL, its text in ewf_last_error); kind 0 disarms.  A fault fires once. */
+ewf_status ewf_debug_inject_fault(int32_t kind, int32_t after);
 
 /* ---- measurement aid ---- */
 

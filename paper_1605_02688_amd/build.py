@@ -2,6 +2,14 @@
 
     python -m paper_1605_02688_amd.build
 
+With ``--sanitize`` it builds libewf_asan.so instead: the host code (everything but the kernels)
+under AddressSanitizer and UndefinedBehaviorSanitizer.  The host-only tests then run as
+
+    python -m paper_1605_02688_amd.build --sanitize
+    EWF_LIBRARY=$PWD/paper_1605_02688_amd/libewf_asan.so \
+        LD_PRELOAD="$(gcc -print-file-name=libasan.so) $(gcc -print-file-name=libubsan.so)" \
+        ASAN_OPTIONS=detect_leaks=0 python -m pytest tests -m "not gpu" -q
+
 The kernel prelude (csrc/kernels/ewf_prelude.hip.h) is embedded into the library as a
 string so that the run-time compiler can see it on machines without the source tree.
 """
@@ -35,21 +43,22 @@ def _embed_prelude() -> None:
             f.write(f'R"{delim}({c}){delim}"\n')
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, sanitize: bool = False) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
     _embed_prelude()
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     common = ["-O2", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-I", BUILD_DIR,
               "-Wall", "-Wno-unused-result"]
+    san = ["-fsanitize=address,undefined", "-fno-omit-frame-pointer", "-g"] if sanitize else []
     procs = []
     for s in HOST_SOURCES + HIP_SOURCES:
-        obj = os.path.join(BUILD_DIR, s + ".o")
-        if s.endswith(".hip"):
+        obj = os.path.join(BUILD_DIR, s + (".asan.o" if sanitize else ".o"))
+        if s.endswith(".hip"):      # (device code is never instrumented: host side only)
             cmd = [hipcc, "-c", os.path.join(CSRC, s), "-o", obj] + common + HIP_FLAGS
         else:       # plain C++: no device code in the host sources
             cmd = ["g++", "-c", os.path.join(CSRC, s), "-o", obj, "-D__HIP_PLATFORM_AMD__",
-                   "-I", "/opt/rocm/include"] + common
+                   "-I", "/opt/rocm/include"] + common + san
         if verbose:
             print(" ".join(cmd))
         procs.append((s, subprocess.Popen(cmd)))
@@ -57,12 +66,17 @@ def build(verbose: bool = False) -> str:
     for s, p in procs:
         if p.wait() != 0:
             raise RuntimeError(f"compiling {s} failed")
-    tmp = LIB + f".tmp{os.getpid()}"
+    lib = os.path.join(HERE, "libewf_asan.so") if sanitize else LIB
+    tmp = lib + f".tmp{os.getpid()}"
     cmd = [hipcc, "-shared", "-o", tmp] + objs + ["-lhiprtc", "--offload-arch=gfx950"]
+    if sanitize:    # the sanitizer's run-time library comes from the process (LD_PRELOAD), as for any instrumented plug-in
+        cmd += ["-Wl,--allow-shlib-undefined"]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
+    if sanitize:
+        return lib
     # the plain C program that drives the library through its C ABI (used by a GPU test)
     csrc = os.path.join(ROOT, "tests", "c_abi", "c1_from_c.c")
     if os.path.exists(csrc):
@@ -76,4 +90,4 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, sanitize="--sanitize" in sys.argv))

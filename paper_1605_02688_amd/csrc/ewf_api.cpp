@@ -88,6 +88,7 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
         set_error("expected %d input and %d output tensors with shape and strides", e.g.ninputs, (int)e.g.outputs.size());
         return EWF_EINVAL;
     }
+    fault_point();
     std::string sig = layout_signature(e.g, in, nin, out, nout);
     auto it = e.plans.find(sig);
     if (it != e.plans.end()) {
@@ -103,6 +104,13 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
             if (!p->empty)
                 for (int k = 0; k < nin + nout; k++)
                     if (!p->raw[k].addr) { p->raw[0].addr = ~(uint64_t)0; set_error("operand %d: null pointer", k); return EWF_EINVAL; }
+            // nothing to traverse, but outputs that are sums or products over the empty axis are
+            // still filled: those need memory behind them
+            for (const Plan::Fill &f : p->fills)
+                if (!p->raw[nin + f.output].addr) { p->raw[0].addr = ~(uint64_t)0; set_error("output %d: null pointer", f.output); return EWF_EINVAL; }
+            for (const Stage &sg : p->stages)
+                for (int d : sg.out_dst)
+                    if (d >= 0 && !p->raw[nin + d].addr) { p->raw[0].addr = ~(uint64_t)0; set_error("output %d: null pointer", d); return EWF_EINVAL; }
             ewf_status st = check_aliasing(p->raw, nin, nout);
             if (st != EWF_OK) { p->raw[0].addr = ~(uint64_t)0; return st; }
         }
@@ -128,6 +136,7 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
 
     if (empty) {
         // nothing to traverse; reductions over an empty axis still define their outputs
+        std::vector<int> rest;                          // outputs computed from such reductions
         for (size_t k = 0; k < e.g.outputs.size(); k++) {
             const Node &v = e.g.nodes[e.g.outputs[k].value];
             bool out_empty = false;
@@ -143,15 +152,17 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
                     else if (e.g.outputs[k].storage == EWF_F16) bits = 0x3c00u;
                     else bits = 0x3f800000u;
                 }
-                if (!ok) {
-                    set_error("output %d reduces over an empty axis: only a plain sum (0) or product (1) is defined there", (int)k);
-                    return EWF_ESHAPE;
-                }
+                if (!ok) { rest.push_back((int)k); continue; }
                 plan->fills.push_back({(int)k, orank, e.g.outputs[k].storage == EWF_F16 ? 2 : 4, bits});
             }
         }
+        if (!rest.empty()) {
+            st = plan_empty_rest(e, full, in, nin, out, nout, rest, *plan);
+            if (st != EWF_OK) return st;
+        }
         plan->empty = true;
-        plan->kclass = KernelClass::None;
+        plan->kclass = rest.empty() ? KernelClass::None : KernelClass::Multi;
+        plan->grid = (int64_t)plan->stages.size();
         e.last = plan.get();
         *result = e.last;
         e.plans.emplace(sig, std::move(plan));
@@ -351,34 +362,36 @@ extern "C" {
 
 ewf_status ewf_compile(const ewf_graph *g, const ewf_options *opts, ewf_exec **out)
 {
-    if (!g || !out) { set_error("null argument"); return EWF_EINVAL; }
-    ewf_exec *x = new (std::nothrow) ewf_exec();
-    if (!x) return EWF_ENOMEM;
-    x->e.g = graph_of(g);
-    if (opts) x->e.opts = *opts;
-    ewf_status st = finalize_graph(x->e.g);
-    if (st != EWF_OK) { delete x; return st; }
-    x->e.nodes_before = (int)x->e.g.nodes.size();
-    if (!x->e.opts.no_rewrite) {
-        rewrite_graph(x->e.g);
-        // (The chain max -> sum of exp(x - max) stays two levels here.  As one rescaled level it
-        // saves a sweep only where rows are split over workgroups, and the planner makes it one
-        // there; over rows held in registers the rescaled update costs more per element than it
-        // saves: softmax probabilities, float16 [131072, 512] 65 us fused against 41 us, float32
-        // [1048576, 64] 100 against 79 us, the gradient of softmax cross-entropy on [1280, 10000]
-        // 21.0 against 21.2 us.)
-        st = finalize_graph(x->e.g);
+    return guarded([&]() -> ewf_status {
+        if (!g || !out) { set_error("null argument"); return EWF_EINVAL; }
+        ewf_exec *x = new (std::nothrow) ewf_exec();
+        if (!x) return EWF_ENOMEM;
+        x->e.g = graph_of(g);
+        if (opts) x->e.opts = *opts;
+        ewf_status st = finalize_graph(x->e.g);
         if (st != EWF_OK) { delete x; return st; }
-    }
-    x->e.nodes_after = (int)x->e.g.nodes.size();
-    bool all_f16 = true;
-    for (const OutputDecl &o : x->e.g.outputs) if (o.storage != EWF_F16) all_f16 = false;
-    const int mm = x->e.opts.math_mode;
-    if (mm < 0 || mm > 3) { delete x; set_error("math_mode must be 0..3"); return EWF_EINVAL; }
-    x->e.math_flavour = mm == 0 ? (all_f16 ? 3 : 1) : mm;
-    x->e.auto_math = mm == 0;
-    *out = x;
-    return EWF_OK;
+        x->e.nodes_before = (int)x->e.g.nodes.size();
+        if (!x->e.opts.no_rewrite) {
+            rewrite_graph(x->e.g);
+            // (The chain max -> sum of exp(x - max) stays two levels here.  As one rescaled level it
+            // saves a sweep only where rows are split over workgroups, and the planner makes it one
+            // there; over rows held in registers the rescaled update costs more per element than it
+            // saves: softmax probabilities, float16 [131072, 512] 65 us fused against 41 us, float32
+            // [1048576, 64] 100 against 79 us, the gradient of softmax cross-entropy on [1280, 10000]
+            // 21.0 against 21.2 us.)
+            st = finalize_graph(x->e.g);
+            if (st != EWF_OK) { delete x; return st; }
+        }
+        x->e.nodes_after = (int)x->e.g.nodes.size();
+        bool all_f16 = true;
+        for (const OutputDecl &o : x->e.g.outputs) if (o.storage != EWF_F16) all_f16 = false;
+        const int mm = x->e.opts.math_mode;
+        if (mm < 0 || mm > 3) { delete x; set_error("math_mode must be 0..3"); return EWF_EINVAL; }
+        x->e.math_flavour = mm == 0 ? (all_f16 ? 3 : 1) : mm;
+        x->e.auto_math = mm == 0;
+        *out = x;
+        return EWF_OK;
+    });
 }
 
 void ewf_exec_destroy(ewf_exec *e)
@@ -389,92 +402,104 @@ void ewf_exec_destroy(ewf_exec *e)
 
 ewf_status ewf_debug_time_kernels(ewf_exec *e, int32_t slots)
 {
-    if (!e || slots < 0 || slots > (1 << 20)) { set_error("bad argument"); return EWF_EINVAL; }
-    delete e->e.timing;
-    e->e.timing = nullptr;
-    if (slots == 0) return EWF_OK;
-    KernelTiming *t = new (std::nothrow) KernelTiming();
-    if (!t) return EWF_ENOMEM;
-    for (int i = 0; i < slots; i++) {
-        hipEvent_t a = nullptr, b = nullptr;
-        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
-            if (a) (void)hipEventDestroy(a);
-            delete t;
-            set_error("hipEventCreate failed");
-            return EWF_EHIP;
+    return guarded([&]() -> ewf_status {
+        if (!e || slots < 0 || slots > (1 << 20)) { set_error("bad argument"); return EWF_EINVAL; }
+        delete e->e.timing;
+        e->e.timing = nullptr;
+        if (slots == 0) return EWF_OK;
+        KernelTiming *t = new (std::nothrow) KernelTiming();
+        if (!t) return EWF_ENOMEM;
+        for (int i = 0; i < slots; i++) {
+            hipEvent_t a = nullptr, b = nullptr;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+                if (a) (void)hipEventDestroy(a);
+                delete t;
+                set_error("hipEventCreate failed");
+                return EWF_EHIP;
+            }
+            t->start.push_back(a); t->stop.push_back(b);
         }
-        t->start.push_back(a); t->stop.push_back(b);
-    }
-    e->e.timing = t;
-    return EWF_OK;
+        e->e.timing = t;
+        return EWF_OK;
+    });
 }
 
 ewf_status ewf_debug_kernel_times(ewf_exec *e, float *ms, int32_t capacity, int32_t *count)
 {
-    if (!e || !count || (capacity > 0 && !ms)) { set_error("null argument"); return EWF_EINVAL; }
-    *count = 0;
-    KernelTiming *t = e->e.timing;
-    if (!t) return EWF_OK;
-    for (int i = 0; i < t->used && i < capacity; i++) {
-        hipError_t he = hipEventSynchronize(t->stop[i]);
-        if (he == hipSuccess) he = hipEventElapsedTime(&ms[i], t->start[i], t->stop[i]);
-        if (he != hipSuccess) { set_error("kernel timing: %s", hipGetErrorString(he)); return EWF_EHIP; }
-        *count = i + 1;
-    }
-    t->used = 0;
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!e || !count || (capacity > 0 && !ms)) { set_error("null argument"); return EWF_EINVAL; }
+        *count = 0;
+        KernelTiming *t = e->e.timing;
+        if (!t) return EWF_OK;
+        for (int i = 0; i < t->used && i < capacity; i++) {
+            hipError_t he = hipEventSynchronize(t->stop[i]);
+            if (he == hipSuccess) he = hipEventElapsedTime(&ms[i], t->start[i], t->stop[i]);
+            if (he != hipSuccess) { set_error("kernel timing: %s", hipGetErrorString(he)); return EWF_EHIP; }
+            *count = i + 1;
+        }
+        t->used = 0;
+        return EWF_OK;
+    });
 }
 
 ewf_status ewf_output_shape(ewf_exec *e, const ewf_tensor *in, int32_t nin, int32_t k, int32_t *rank_out,
                             int64_t *shape_out)
 {
-    if (!e || !rank_out || !shape_out) { set_error("null argument"); return EWF_EINVAL; }
-    const Graph &g = e->e.g;
-    if (k < 0 || k >= (int)g.outputs.size()) { set_error("no such output"); return EWF_EINVAL; }
-    int64_t full[kMaxDims];
-    ewf_status st = infer_full_extents(g, in, nin, full);
-    if (st != EWF_OK) return st;
-    const Node &v = g.nodes[g.outputs[k].value];
-    int r = 0;
-    for (int d = 0; d < g.ndim; d++) {
-        if (v.dropped & (1u << d)) continue;
-        shape_out[r++] = (v.bcast & (1u << d)) ? 1 : full[d];
-    }
-    *rank_out = r;
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!e || !rank_out || !shape_out) { set_error("null argument"); return EWF_EINVAL; }
+        const Graph &g = e->e.g;
+        if (k < 0 || k >= (int)g.outputs.size()) { set_error("no such output"); return EWF_EINVAL; }
+        int64_t full[kMaxDims];
+        ewf_status st = infer_full_extents(g, in, nin, full);
+        if (st != EWF_OK) return st;
+        const Node &v = g.nodes[g.outputs[k].value];
+        int r = 0;
+        for (int d = 0; d < g.ndim; d++) {
+            if (v.dropped & (1u << d)) continue;
+            shape_out[r++] = (v.bcast & (1u << d)) ? 1 : full[d];
+        }
+        *rank_out = r;
+        return EWF_OK;
+    });
 }
 
 ewf_status ewf_plan(ewf_exec *e, const ewf_tensor *in, int32_t nin, const ewf_tensor *out, int32_t nout,
                     size_t *workspace_bytes)
 {
-    if (!e) { set_error("null executable"); return EWF_EINVAL; }
-    Plan *p = nullptr;
-    ewf_status st = make_plan(e->e, in, nin, out, nout, &p);
-    if (st != EWF_OK) return st;
-    if (workspace_bytes) *workspace_bytes = p->workspace_bytes;
-    // with a device at hand the kernels are loaded now rather than by the first launch (planning
-    // itself needs no device: the run-time compiler cross-compiles)
-    int ndev = 0;
-    if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) return load_plan_functions(*p);
-    (void)hipGetLastError();
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!e) { set_error("null executable"); return EWF_EINVAL; }
+        Plan *p = nullptr;
+        ewf_status st = make_plan(e->e, in, nin, out, nout, &p);
+        if (st != EWF_OK) return st;
+        if (workspace_bytes) *workspace_bytes = p->workspace_bytes;
+        // with a device at hand the kernels are loaded now rather than by the first launch (planning
+        // itself needs no device: the run-time compiler cross-compiles)
+        int ndev = 0;
+        if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) return load_plan_functions(*p);
+        (void)hipGetLastError();
+        return EWF_OK;
+    });
 }
 
 ewf_status ewf_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (workspace_bytes == 0) return EWF_OK;
-    if (!workspace || ((uintptr_t)workspace & 15)) { set_error("workspace must be a 16-byte aligned device pointer"); return EWF_EINVAL; }
-    aux_fill_zero(workspace, workspace_bytes, (hipStream_t)hip_stream);
-    hipError_t he = hipGetLastError();
-    if (he != hipSuccess) { set_error("workspace fill: %s", hipGetErrorString(he)); return EWF_EHIP; }
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (workspace_bytes == 0) return EWF_OK;
+        if (!workspace || ((uintptr_t)workspace & 15)) { set_error("workspace must be a 16-byte aligned device pointer"); return EWF_EINVAL; }
+        aux_fill_zero(workspace, workspace_bytes, (hipStream_t)hip_stream);
+        hipError_t he = hipGetLastError();
+        if (he != hipSuccess) { set_error("workspace fill: %s", hipGetErrorString(he)); return EWF_EHIP; }
+        return EWF_OK;
+    });
 }
 
 ewf_status ewf_run(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
                    const ewf_tensor *out, int32_t nout, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!e) { set_error("null executable"); return EWF_EINVAL; }
-    return run_exec(e->e, in, nin, scalars, nscalars, out, nout, workspace, workspace_bytes, hip_stream);
+    return guarded([&]() -> ewf_status {
+        if (!e) { set_error("null executable"); return EWF_EINVAL; }
+        return run_exec(e->e, in, nin, scalars, nscalars, out, nout, workspace, workspace_bytes, hip_stream);
+    });
 }
 
 }  // extern "C"
@@ -483,7 +508,7 @@ namespace ewf {
 
 ewf_status load_plan_functions(Plan &p)
 {
-    if (p.empty) return EWF_OK;
+    if (p.empty && p.stages.empty()) return EWF_OK;
     if (p.kclass == KernelClass::Multi) {
         for (Stage &sg : p.stages) {
             if (!sg.exec->last) continue;
@@ -521,7 +546,21 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
             hipError_t he = hipGetLastError();
             if (he != hipSuccess) { set_error("fill launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
         }
-        return EWF_OK;
+        if (p->stages.empty()) return EWF_OK;
+        // values computed from reductions over an empty axis: the reductions are temporaries set
+        // to their identity, then one stage computes the outputs
+        if (!workspace || workspace_bytes < p->workspace_bytes) {
+            set_error("workspace of %zu bytes needed, %zu given", p->workspace_bytes, workspace ? workspace_bytes : (size_t)0);
+            return EWF_ENOMEM;
+        }
+        if ((uintptr_t)workspace & 15) { set_error("workspace must be 16-byte aligned"); return EWF_EINVAL; }
+        for (const Plan::TempFill &tf : p->temp_fills) {
+            const Temp &t = p->temps[tf.temp];
+            aux_fill_view((char *)workspace + t.offset, x.g.ndim, t.shape, t.strides, 4, tf.bits, (hipStream_t)hip_stream);
+            hipError_t he = hipGetLastError();
+            if (he != hipSuccess) { set_error("fill launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
+        }
+        return run_multi(x, *p, in, nin, scalars, nscalars, out, nout, workspace, workspace_bytes, hip_stream, no_setup);
     }
     if (p->workspace_bytes > 0) {
         if (!workspace || workspace_bytes < p->workspace_bytes) {
@@ -588,35 +627,41 @@ extern "C" {
 
 ewf_status ewf_run_call(const ewf_call *c)
 {
-    if (!c) { set_error("null argument"); return EWF_EINVAL; }
-    return ewf_run(c->exec, c->in, c->nin, c->scalars, c->nscalars, c->out, c->nout, c->workspace, c->workspace_bytes,
-                   c->hip_stream);
+    return guarded([&]() -> ewf_status {
+        if (!c) { set_error("null argument"); return EWF_EINVAL; }
+        return ewf_run(c->exec, c->in, c->nin, c->scalars, c->nscalars, c->out, c->nout, c->workspace, c->workspace_bytes,
+                       c->hip_stream);
+    });
 }
 
 ewf_status ewf_run_sequence(const ewf_call *calls, int32_t ncalls, int32_t *failed)
 {
-    if (ncalls < 0 || (ncalls > 0 && !calls)) { set_error("null or negative argument"); return EWF_EINVAL; }
-    for (int32_t i = 0; i < ncalls; i++) {
-        const ewf_call &c = calls[i];
-        ewf_status st = ewf_run(c.exec, c.in, c.nin, c.scalars, c.nscalars, c.out, c.nout, c.workspace, c.workspace_bytes,
-                                c.hip_stream);
-        if (st != EWF_OK) {
-            if (failed) *failed = i;
-            return st;
+    return guarded([&]() -> ewf_status {
+        if (ncalls < 0 || (ncalls > 0 && !calls)) { set_error("null or negative argument"); return EWF_EINVAL; }
+        for (int32_t i = 0; i < ncalls; i++) {
+            const ewf_call &c = calls[i];
+            ewf_status st = ewf_run(c.exec, c.in, c.nin, c.scalars, c.nscalars, c.out, c.nout, c.workspace, c.workspace_bytes,
+                                    c.hip_stream);
+            if (st != EWF_OK) {
+                if (failed) *failed = i;
+                return st;
+            }
         }
-    }
-    return EWF_OK;
+        return EWF_OK;
+    });
 }
 
 static void fill_plan_info(const Plan *p, ewf_plan_info *info);
 
 ewf_status ewf_debug_plan_info(ewf_exec *e, ewf_plan_info *info)
 {
-    if (!e || !info) { set_error("null argument"); return EWF_EINVAL; }
-    const Plan *p = e->e.last;
-    if (!p) { set_error("no plan yet"); return EWF_EINVAL; }
-    fill_plan_info(p, info);
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!e || !info) { set_error("null argument"); return EWF_EINVAL; }
+        const Plan *p = e->e.last;
+        if (!p) { set_error("no plan yet"); return EWF_EINVAL; }
+        fill_plan_info(p, info);
+        return EWF_OK;
+    });
 }
 
 static const Plan *stage_plan(ewf_exec *e, int32_t stage)
@@ -627,10 +672,12 @@ static const Plan *stage_plan(ewf_exec *e, int32_t stage)
 
 ewf_status ewf_debug_stage_plan_info(ewf_exec *e, int32_t stage, ewf_plan_info *info)
 {
-    const Plan *p = stage_plan(e, stage);
-    if (!p || !info) { set_error("no such stage"); return EWF_EINVAL; }
-    fill_plan_info(p, info);
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        const Plan *p = stage_plan(e, stage);
+        if (!p || !info) { set_error("no such stage"); return EWF_EINVAL; }
+        fill_plan_info(p, info);
+        return EWF_OK;
+    });
 }
 
 const char *ewf_debug_stage_source(ewf_exec *e, int32_t stage)
@@ -660,11 +707,13 @@ static void fill_plan_info(const Plan *p, ewf_plan_info *info)
 
 ewf_status ewf_debug_operand_strides(ewf_exec *e, int32_t k, int64_t *strides_out)
 {
-    if (!e || !strides_out) { set_error("null argument"); return EWF_EINVAL; }
-    const Plan *p = e->e.last;
-    if (!p || k < 0 || k >= (int)p->canon.ops.size()) { set_error("no such operand"); return EWF_EINVAL; }
-    for (int d = 0; d < p->canon.rank; d++) strides_out[d] = p->canon.ops[k].stride[d];
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!e || !strides_out) { set_error("null argument"); return EWF_EINVAL; }
+        const Plan *p = e->e.last;
+        if (!p || k < 0 || k >= (int)p->canon.ops.size()) { set_error("no such operand"); return EWF_EINVAL; }
+        for (int d = 0; d < p->canon.rank; d++) strides_out[d] = p->canon.ops[k].stride[d];
+        return EWF_OK;
+    });
 }
 
 const char *ewf_debug_source(ewf_exec *e)
@@ -677,38 +726,60 @@ int32_t ewf_debug_compile_count(ewf_exec *e) { return e ? e->e.compile_count : 0
 
 ewf_status ewf_debug_graph_size(ewf_exec *e, int32_t *nodes_described, int32_t *nodes_compiled)
 {
-    if (!e || !nodes_described || !nodes_compiled) { set_error("null argument"); return EWF_EINVAL; }
-    *nodes_described = e->e.nodes_before;
-    *nodes_compiled = e->e.nodes_after;
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!e || !nodes_described || !nodes_compiled) { set_error("null argument"); return EWF_EINVAL; }
+        *nodes_described = e->e.nodes_before;
+        *nodes_compiled = e->e.nodes_after;
+        return EWF_OK;
+    });
 }
 
 ewf_status ewf_set_cache_dir(const char *path)
 {
-    set_cache_dir(path);
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        set_cache_dir(path);
+        return EWF_OK;
+    });
 }
 
 ewf_status ewf_debug_cache_stats(int32_t *memory_hits, int32_t *disk_hits, int32_t *compiles)
 {
-    if (!memory_hits || !disk_hits || !compiles) { set_error("null argument"); return EWF_EINVAL; }
-    int a, b, c;
-    cache_stats(&a, &b, &c);
-    *memory_hits = a; *disk_hits = b; *compiles = c;
+    return guarded([&]() -> ewf_status {
+        if (!memory_hits || !disk_hits || !compiles) { set_error("null argument"); return EWF_EINVAL; }
+        int a, b, c;
+        cache_stats(&a, &b, &c);
+        *memory_hits = a; *disk_hits = b; *compiles = c;
+        return EWF_OK;
+    });
+}
+
+ewf_status ewf_debug_inject_fault(int32_t kind, int32_t after)
+{
+    if (kind < 0 || kind > 2 || after < 0) { set_error("bad argument"); return EWF_EINVAL; }
+    arm_fault(kind, after);
+    return EWF_OK;
+}
+
+ewf_status ewf_debug_peak_concurrent_compiles(int32_t *peak)
+{
+    if (!peak) { set_error("null argument"); return EWF_EINVAL; }
+    *peak = peak_concurrent_compiles();
     return EWF_OK;
 }
 
 ewf_status ewf_copy_bytes(void *dst, const void *src, size_t nbytes, void *hip_stream)
 {
-    if (nbytes == 0) return EWF_OK;
-    if (!dst || !src || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) {
-        set_error("copy needs 16-byte aligned pointers and a multiple of 16 bytes");
-        return EWF_EINVAL;
-    }
-    aux_copy(dst, src, nbytes, (hipStream_t)hip_stream);
-    hipError_t he = hipGetLastError();
-    if (he != hipSuccess) { set_error("copy launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (nbytes == 0) return EWF_OK;
+        if (!dst || !src || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) {
+            set_error("copy needs 16-byte aligned pointers and a multiple of 16 bytes");
+            return EWF_EINVAL;
+        }
+        aux_copy(dst, src, nbytes, (hipStream_t)hip_stream);
+        hipError_t he = hipGetLastError();
+        if (he != hipSuccess) { set_error("copy launch: %s", hipGetErrorString(he)); return EWF_EHIP; }
+        return EWF_OK;
+    });
 }
 
 }  // extern "C"

@@ -143,22 +143,24 @@ ewf_status static_workspace(void **ptr)
 extern "C" ewf_status ewf_run_static(ewf_exec *e, const ewf_tensor *in, int32_t nin, const double *scalars, int32_t nscalars,
                                      const ewf_tensor *out, int32_t nout, void *hip_stream)
 {
-    if (!e) { ewf::set_error("null executable"); return EWF_EINVAL; }
-    // the layout must have been planned (ewf_plan compiles and, with a device current, loads the
-    // kernels): nothing is compiled, loaded or allocated from here on
-    ewf::Plan *p = nullptr;
-    ewf_status st = ewf::make_plan(e->e, in, nin, out, nout, &p, /*lookup_only=*/true);
-    if (st != EWF_OK) return st;
-    if (p->workspace_bytes > (size_t)EWF_STATIC_WORKSPACE_BYTES) {
-        ewf::set_error("this layout needs a workspace of %zu bytes, the static one holds %zu: use ewf_run with a workspace of your own",
-                       p->workspace_bytes, (size_t)EWF_STATIC_WORKSPACE_BYTES);
-        return EWF_ENOMEM;
-    }
-    void *ws = nullptr;
-    st = static_workspace(&ws);
-    if (st != EWF_OK) return st;
-    // (the kernels write every workspace word before they read it: what the previous call left
-    // in the array needs no clearing)
-    return ewf::run_exec(e->e, in, nin, scalars, nscalars, out, nout, ws, (size_t)EWF_STATIC_WORKSPACE_BYTES, hip_stream,
-                         /*no_setup=*/true);
+    return ewf::guarded([&]() -> ewf_status {
+        if (!e) { ewf::set_error("null executable"); return EWF_EINVAL; }
+        // the layout must have been planned (ewf_plan compiles and, with a device current, loads the
+        // kernels): nothing is compiled, loaded or allocated from here on
+        ewf::Plan *p = nullptr;
+        ewf_status st = ewf::make_plan(e->e, in, nin, out, nout, &p, /*lookup_only=*/true);
+        if (st != EWF_OK) return st;
+        if (p->workspace_bytes > (size_t)EWF_STATIC_WORKSPACE_BYTES) {
+            ewf::set_error("this layout needs a workspace of %zu bytes, the static one holds %zu: use ewf_run with a workspace of your own",
+                           p->workspace_bytes, (size_t)EWF_STATIC_WORKSPACE_BYTES);
+            return EWF_ENOMEM;
+        }
+        void *ws = nullptr;
+        st = static_workspace(&ws);
+        if (st != EWF_OK) return st;
+        // (the kernels write every workspace word before they read it: what the previous call left
+        // in the array needs no clearing)
+        return ewf::run_exec(e->e, in, nin, scalars, nscalars, out, nout, ws, (size_t)EWF_STATIC_WORKSPACE_BYTES, hip_stream,
+                             /*no_setup=*/true);
+    });
 }

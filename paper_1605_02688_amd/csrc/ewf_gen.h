@@ -326,12 +326,14 @@ struct Gen {
             case EWF_RARGMAX: {
                 std::string ia = "x.i" + std::to_string(i), ib = "y.i" + std::to_string(i);
                 if (isint) {
-                    o << "        { const bool t = (" << b << " > " << a << ") || (" << b << " == " << a << " && " << ib << " < " << ia << ");\n";
+                    o << "        { const bool t = (" << b << " > " << a << ") | ((" << b << " == " << a << ") & (" << ib << " < " << ia << "));\n";
                 } else {
-                    // NaN ranks above every number; equal keys keep the lower index
-                    o << "        { const bool gt = (" << b << " > " << a << ") || (" << b << " != " << b << " && " << a << " == " << a << ");\n"
-                      << "          const bool eq = (" << b << " == " << a << ") || (" << b << " != " << b << " && " << a << " != " << a << ");\n"
-                      << "          const bool t = gt || (eq && " << ib << " < " << ia << ");\n";
+                    // NaN ranks above every number; equal keys keep the lower index.  (Plain
+                    // and / or of the comparison results, not the short-circuit forms: those
+                    // become branches in every step of a lane fold.)
+                    o << "        { const bool gt = (" << b << " > " << a << ") | ((" << b << " != " << b << ") & (" << a << " == " << a << "));\n"
+                      << "          const bool eq = (" << b << " == " << a << ") | ((" << b << " != " << b << ") & (" << a << " != " << a << "));\n"
+                      << "          const bool t = gt | (eq & (" << ib << " < " << ia << "));\n";
                 }
                 o << "          r.a" << i << " = t ? " << b << " : " << a << "; r.i" << i << " = t ? " << ib << " : " << ia << "; }\n";
                 break;
@@ -393,13 +395,13 @@ struct Gen {
                     o << ind << "{ const bool t = " << v << " > " << a << ";\n";
                 } else if (ascending) {
                     // greater, or the first NaN; a NaN already held stays
-                    o << ind << "{ const bool t = !(" << v << " <= " << a << ") && (" << a << " == " << a << ");\n";
+                    o << ind << "{ const bool t = !(" << v << " <= " << a << ") & (" << a << " == " << a << ");\n";
                 } else if (isint) {
-                    o << ind << "{ const bool t = (" << v << " > " << a << ") || (" << v << " == " << a << " && " << ib << " < " << ia << ");\n";
+                    o << ind << "{ const bool t = (" << v << " > " << a << ") | ((" << v << " == " << a << ") & (" << ib << " < " << ia << "));\n";
                 } else {
-                    o << ind << "{ const bool gt = (" << v << " > " << a << ") || (" << v << " != " << v << " && " << a << " == " << a << ");\n"
-                      << ind << "  const bool eq = (" << v << " == " << a << ") || (" << v << " != " << v << " && " << a << " != " << a << ");\n"
-                      << ind << "  const bool t = gt || (eq && " << ib << " < " << ia << ");\n";
+                    o << ind << "{ const bool gt = (" << v << " > " << a << ") | ((" << v << " != " << v << ") & (" << a << " == " << a << "));\n"
+                      << ind << "  const bool eq = (" << v << " == " << a << ") | ((" << v << " != " << v << ") & (" << a << " != " << a << "));\n"
+                      << ind << "  const bool t = gt | (eq & (" << ib << " < " << ia << "));\n";
                 }
                 o << ind << "  " << a << " = t ? " << v << " : " << a << "; " << ia << " = t ? " << ib << " : " << ia << "; }\n";
                 break;

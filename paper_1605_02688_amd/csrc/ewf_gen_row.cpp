@@ -256,7 +256,9 @@ ewf_status Gen::gen_row()
         close_pass();
         // every thread walks its columns in increasing order, starting at tid * EWF_VEC
         emit_first_index(av, lvl[l], "(idx_t)tid * EWF_VEC < cols", "tid * EWF_VEC", "        ");
-        o << "        " << av << " = ewf_block_reduce<EWF_NWAVES>(" << av << ", " << an << "_combine(), sm_acc" << l << ", tid);\n";
+        // (every level has a buffer of its own: without a loop over rows it is written once)
+        o << "        " << av << " = " << (nrows <= grid_cap ? "ewf_block_reduce_once" : "ewf_block_reduce") << "<EWF_NWAVES>(" << av << ", "
+          << an << "_combine(), sm_acc" << l << ", tid);\n";
         emit_results(av, lvl[l], "        ");
     }
 

@@ -6,8 +6,10 @@
 #pragma once
 
 #include <cstdint>
+#include <exception>
 #include <map>
 #include <memory>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -211,6 +213,10 @@ struct Plan {
     int strict_vec = 0;                  // canon.vec as the canonicaliser set it (0: not recorded yet)
     struct Fill { int output; int rank; int elem_bytes; uint32_t bits; };
     std::vector<Fill> fills;             // empty space: outputs that are reductions over an empty axis
+    // empty space: values computed from such reductions.  The reductions are temporaries that a fill
+    // kernel sets to the identity; one stage computes the outputs from them and the inputs.
+    struct TempFill { int temp; uint32_t bits; };
+    std::vector<TempFill> temp_fills;
     bool used_auto_occupancy = false;    // the generator asked for a register budget on its own
     bool no_auto_occupancy = false;      // ... and must not (it made the compiler spill)
 };
@@ -234,6 +240,32 @@ struct Exec {
 };
 
 // ---- ewf_ir.cpp
+// No C++ exception may cross the C ABI: every exported function runs its body through one of
+// these.  Host memory running out is EWF_ENOMEM, anything else EWF_EINVAL with the exception's
+// text as the error message (which is set without allocating where that is what failed).
+void set_error_static(const char *text) noexcept;
+void set_error_str(const std::string &s);
+template <typename F>
+ewf_status guarded(F &&body) noexcept
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        set_error_static("out of host memory");
+        return EWF_ENOMEM;
+    } catch (const std::exception &ex) {
+        try { set_error_str(std::string("internal error: ") + ex.what()); } catch (...) { set_error_static("internal error"); }
+        return EWF_EINVAL;
+    } catch (...) {
+        set_error_static("internal error");
+        return EWF_EINVAL;
+    }
+}
+// Test hook (ewf_debug_inject_fault): the points of the library where host memory is typically
+// asked for call this; when armed on the calling thread it throws there.
+void fault_point();
+void arm_fault(int kind, int after);
+
 void set_error(const char *fmt, ...);
 const char *get_error();
 ewf_status finalize_graph(Graph &g);     // recompute derived fields, validate outputs
@@ -289,6 +321,11 @@ ewf_status load_plan_functions(Plan &p);
 // `g` is e.g or a rewritten copy of it with the same inputs, scalars and outputs.
 // With `strict_rows` no stage may use the row class where it fits poorly (see Plan::avoid_poor_rows).
 ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan &plan);
+// The iteration space is empty (some axis has extent 0) but the outputs `outs` are not: they are
+// constant along every empty axis and computed from sums or products over one.  Plans one stage
+// that reads those reductions as temporaries holding the identity.
+ewf_status plan_empty_rest(Exec &e, const int64_t *full, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout,
+                           const std::vector<int> &outs, Plan &plan);
 ewf_status run_multi(Exec &e, Plan &p, const ewf_tensor *in, int nin, const double *scalars, int nscalars,
                      const ewf_tensor *out, int nout, void *workspace, size_t workspace_bytes, void *hip_stream,
                      bool no_setup = false);
@@ -303,6 +340,7 @@ int device_cu_count();
 void set_cache_dir(const char *path);
 void cache_stats(int *mem_hits, int *disk_hits, int *compiles);
 int64_t code_scratch_bytes(const std::vector<char> &code);
+int peak_concurrent_compiles();
 
 }  // namespace ewf
 

@@ -4,12 +4,14 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <stdexcept>
 
 #include "ewf_internal.h"
 
 namespace ewf {
 
 static thread_local std::string g_error;
+static thread_local const char *g_static_error = nullptr;   // a message that needed no memory (takes precedence)
 
 void set_error(const char *fmt, ...)
 {
@@ -18,11 +20,28 @@ void set_error(const char *fmt, ...)
     va_start(ap, fmt);
     vsnprintf(buf, sizeof buf, fmt, ap);
     va_end(ap);
+    g_static_error = nullptr;
     g_error = buf;
 }
 
-void set_error_str(const std::string &s) { g_error = s; }
-const char *get_error() { return g_error.c_str(); }
+void set_error_str(const std::string &s) { g_static_error = nullptr; g_error = s; }
+void set_error_static(const char *text) noexcept { g_static_error = text; }
+const char *get_error() { return g_static_error ? g_static_error : g_error.c_str(); }
+
+// fault injection for tests of the ABI's exception barrier: 0 off, 1 std::bad_alloc, 2 std::runtime_error
+static thread_local int g_fault_kind = 0, g_fault_after = 0;
+
+void arm_fault(int kind, int after) { g_fault_kind = kind; g_fault_after = after; }
+
+void fault_point()
+{
+    if (g_fault_kind == 0) return;
+    if (g_fault_after-- > 0) return;
+    const int kind = g_fault_kind;
+    g_fault_kind = 0;
+    if (kind == 1) throw std::bad_alloc();
+    throw std::runtime_error("injected fault");
+}
 
 uint32_t all_mask(int ndim) { return ndim >= 32 ? 0xffffffffu : ((1u << ndim) - 1u); }
 
@@ -136,6 +155,7 @@ static ewf_value push_node(Graph *g, Node nd)
 {
     if (!g) { set_error("null graph"); return EWF_EINVAL; }
     if (g->nodes.size() >= 4096) { set_error("graph too large"); return EWF_EINVAL; }
+    fault_point();
     g->nodes.push_back(nd);
     int id = (int)g->nodes.size() - 1;
     ewf_status st = infer_node(*g, id);
@@ -247,122 +267,140 @@ extern "C" {
 
 ewf_status ewf_graph_create(int32_t ndim, ewf_graph **out)
 {
-    if (!out || ndim < 0 || ndim > EWF_MAX_DIMS) { set_error("bad rank"); return EWF_EINVAL; }
-    ewf_graph *g = new (std::nothrow) ewf_graph();
-    if (!g) return EWF_ENOMEM;
-    g->g.ndim = ndim;
-    *out = g;
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!out || ndim < 0 || ndim > EWF_MAX_DIMS) { set_error("bad rank"); return EWF_EINVAL; }
+        ewf_graph *g = new (std::nothrow) ewf_graph();
+        if (!g) return EWF_ENOMEM;
+        g->g.ndim = ndim;
+        *out = g;
+        return EWF_OK;
+    });
 }
 
 void ewf_graph_destroy(ewf_graph *g) { delete g; }
 
 ewf_value ewf_input(ewf_graph *g, ewf_dtype storage, const uint8_t *bcast_flags)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if (storage != EWF_F32 && storage != EWF_F16 && storage != EWF_I32) { set_error("bad storage type"); return EWF_ETYPE; }
-    if (g->g.ndim > 0 && !bcast_flags) { set_error("null broadcast pattern"); return EWF_EINVAL; }
-    Node nd;
-    nd.kind = NodeKind::Input;
-    nd.storage = storage;
-    nd.index = g->g.ninputs;
-    for (int d = 0; d < g->g.ndim; d++) if (bcast_flags[d]) nd.bcast |= 1u << d;
-    ewf_value v = push_node(&g->g, nd);
-    if (v >= 0) { g->g.ninputs++; g->g.input_node.push_back(v); }
-    return v;
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if (storage != EWF_F32 && storage != EWF_F16 && storage != EWF_I32) { set_error("bad storage type"); return EWF_ETYPE; }
+        if (g->g.ndim > 0 && !bcast_flags) { set_error("null broadcast pattern"); return EWF_EINVAL; }
+        Node nd;
+        nd.kind = NodeKind::Input;
+        nd.storage = storage;
+        nd.index = g->g.ninputs;
+        for (int d = 0; d < g->g.ndim; d++) if (bcast_flags[d]) nd.bcast |= 1u << d;
+        ewf_value v = push_node(&g->g, nd);
+        if (v >= 0) { g->g.ninputs++; g->g.input_node.push_back(v); }
+        return v;
+    });
 }
 
 ewf_value ewf_scalar(ewf_graph *g, ewf_dtype dtype)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if (!is_value_type(dtype)) { set_error("scalar type must be float32 or int32"); return EWF_ETYPE; }
-    Node nd;
-    nd.kind = NodeKind::Scalar;
-    nd.vtype = dtype;
-    nd.index = g->g.nscalars;
-    ewf_value v = push_node(&g->g, nd);
-    if (v >= 0) { g->g.nscalars++; g->g.scalar_node.push_back(v); }
-    return v;
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if (!is_value_type(dtype)) { set_error("scalar type must be float32 or int32"); return EWF_ETYPE; }
+        Node nd;
+        nd.kind = NodeKind::Scalar;
+        nd.vtype = dtype;
+        nd.index = g->g.nscalars;
+        ewf_value v = push_node(&g->g, nd);
+        if (v >= 0) { g->g.nscalars++; g->g.scalar_node.push_back(v); }
+        return v;
+    });
 }
 
 ewf_value ewf_const(ewf_graph *g, ewf_dtype dtype, double value)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if (!is_value_type(dtype)) { set_error("literal type must be float32 or int32"); return EWF_ETYPE; }
-    Node nd;
-    nd.kind = NodeKind::Const;
-    nd.vtype = dtype;
-    nd.cval = value;
-    return push_node(&g->g, nd);
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if (!is_value_type(dtype)) { set_error("literal type must be float32 or int32"); return EWF_ETYPE; }
+        Node nd;
+        nd.kind = NodeKind::Const;
+        nd.vtype = dtype;
+        nd.cval = value;
+        return push_node(&g->g, nd);
+    });
 }
 
 ewf_value ewf_iota(ewf_graph *g, int32_t axis)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if (axis < 0 || axis >= g->g.ndim) { set_error("iota axis out of range"); return EWF_EINVAL; }
-    Node nd;
-    nd.kind = NodeKind::Iota;
-    nd.index = axis;
-    return push_node(&g->g, nd);
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if (axis < 0 || axis >= g->g.ndim) { set_error("iota axis out of range"); return EWF_EINVAL; }
+        Node nd;
+        nd.kind = NodeKind::Iota;
+        nd.index = axis;
+        return push_node(&g->g, nd);
+    });
 }
 
 ewf_value ewf_apply(ewf_graph *g, ewf_op op, const ewf_value *args, int32_t nargs)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if (nargs < 1 || nargs > 3 || !args) { set_error("bad argument count"); return EWF_EINVAL; }
-    if ((int)op < 0 || op >= EWF_OP_COUNT) { set_error("unknown operation"); return EWF_EINVAL; }
-    Node nd;
-    nd.kind = NodeKind::Apply;
-    nd.op = op;
-    nd.nargs = nargs;
-    for (int a = 0; a < nargs; a++) nd.args[a] = args[a];
-    return push_node(&g->g, nd);
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if (nargs < 1 || nargs > 3 || !args) { set_error("bad argument count"); return EWF_EINVAL; }
+        if ((int)op < 0 || op >= EWF_OP_COUNT) { set_error("unknown operation"); return EWF_EINVAL; }
+        Node nd;
+        nd.kind = NodeKind::Apply;
+        nd.op = op;
+        nd.nargs = nargs;
+        for (int a = 0; a < nargs; a++) nd.args[a] = args[a];
+        return push_node(&g->g, nd);
+    });
 }
 
 ewf_value ewf_cast(ewf_graph *g, ewf_value v, ewf_dtype to)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if (to != EWF_F32 && to != EWF_F16 && to != EWF_I32) { set_error("bad cast target"); return EWF_ETYPE; }
-    Node nd;
-    nd.kind = NodeKind::Cast;
-    nd.op = to;
-    nd.nargs = 1;
-    nd.args[0] = v;
-    return push_node(&g->g, nd);
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if (to != EWF_F32 && to != EWF_F16 && to != EWF_I32) { set_error("bad cast target"); return EWF_ETYPE; }
+        Node nd;
+        nd.kind = NodeKind::Cast;
+        nd.op = to;
+        nd.nargs = 1;
+        nd.args[0] = v;
+        return push_node(&g->g, nd);
+    });
 }
 
 ewf_value ewf_reduce(ewf_graph *g, ewf_redop op, ewf_value v, const int32_t *axes, int32_t naxes,
                      int32_t keep_as_bcast)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if ((int)op < 0 || op > EWF_RARGMAX) { set_error("unknown reduction"); return EWF_EINVAL; }
-    if (naxes < 1 || !axes) { set_error("reduce needs at least one axis"); return EWF_EINVAL; }
-    Node nd;
-    nd.kind = NodeKind::Reduce;
-    nd.op = op;
-    nd.nargs = 1;
-    nd.args[0] = v;
-    nd.keep = keep_as_bcast != 0;
-    for (int a = 0; a < naxes; a++) {
-        if (axes[a] < 0 || axes[a] >= g->g.ndim) { set_error("reduce axis out of range"); return EWF_EINVAL; }
-        if (nd.axes & (1u << axes[a])) { set_error("reduce axis repeated"); return EWF_EINVAL; }
-        nd.axes |= 1u << axes[a];
-    }
-    return push_node(&g->g, nd);
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if ((int)op < 0 || op > EWF_RARGMAX) { set_error("unknown reduction"); return EWF_EINVAL; }
+        if (naxes < 1 || !axes) { set_error("reduce needs at least one axis"); return EWF_EINVAL; }
+        Node nd;
+        nd.kind = NodeKind::Reduce;
+        nd.op = op;
+        nd.nargs = 1;
+        nd.args[0] = v;
+        nd.keep = keep_as_bcast != 0;
+        for (int a = 0; a < naxes; a++) {
+            if (axes[a] < 0 || axes[a] >= g->g.ndim) { set_error("reduce axis out of range"); return EWF_EINVAL; }
+            if (nd.axes & (1u << axes[a])) { set_error("reduce axis repeated"); return EWF_EINVAL; }
+            nd.axes |= 1u << axes[a];
+        }
+        return push_node(&g->g, nd);
+    });
 }
 
 ewf_status ewf_output(ewf_graph *g, ewf_value v, ewf_dtype storage)
 {
-    if (!g) { set_error("null graph"); return EWF_EINVAL; }
-    if (v < 0 || v >= (int)g->g.nodes.size()) { set_error("output of an unknown value"); return EWF_EINVAL; }
-    if (storage != EWF_F32 && storage != EWF_F16 && storage != EWF_I32) { set_error("bad storage type"); return EWF_ETYPE; }
-    const Node &nd = g->g.nodes[v];
-    if ((nd.vtype == EWF_I32) != (storage == EWF_I32)) {
-        set_error("output storage type does not match the value type (insert a cast)");
-        return EWF_ETYPE;
-    }
-    g->g.outputs.push_back({v, storage});
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!g) { set_error("null graph"); return EWF_EINVAL; }
+        if (v < 0 || v >= (int)g->g.nodes.size()) { set_error("output of an unknown value"); return EWF_EINVAL; }
+        if (storage != EWF_F32 && storage != EWF_F16 && storage != EWF_I32) { set_error("bad storage type"); return EWF_ETYPE; }
+        const Node &nd = g->g.nodes[v];
+        if ((nd.vtype == EWF_I32) != (storage == EWF_I32)) {
+            set_error("output storage type does not match the value type (insert a cast)");
+            return EWF_ETYPE;
+        }
+        g->g.outputs.push_back({v, storage});
+        return EWF_OK;
+    });
 }
 
 const char *ewf_last_error(void) { return get_error(); }
@@ -371,20 +409,22 @@ int32_t ewf_debug_graph_count(const ewf_graph *g) { return g ? (int32_t)g->g.nod
 
 ewf_status ewf_debug_graph_node(const ewf_graph *g, int32_t i, ewf_node_info *info)
 {
-    if (!g || !info || i < 0 || i >= (int32_t)g->g.nodes.size()) { set_error("no such node"); return EWF_EINVAL; }
-    const Node &nd = g->g.nodes[i];
-    info->kind = (int32_t)nd.kind;
-    info->op = nd.op;
-    info->nargs = nd.nargs;
-    for (int a = 0; a < 3; a++) info->args[a] = nd.args[a];
-    info->index = nd.index;
-    info->axes = nd.axes;
-    info->keep = nd.keep ? 1 : 0;
-    info->vtype = (int32_t)nd.vtype;
-    info->storage = (int32_t)nd.storage;
-    info->bcast = nd.bcast;
-    info->cval = nd.cval;
-    return EWF_OK;
+    return guarded([&]() -> ewf_status {
+        if (!g || !info || i < 0 || i >= (int32_t)g->g.nodes.size()) { set_error("no such node"); return EWF_EINVAL; }
+        const Node &nd = g->g.nodes[i];
+        info->kind = (int32_t)nd.kind;
+        info->op = nd.op;
+        info->nargs = nd.nargs;
+        for (int a = 0; a < 3; a++) info->args[a] = nd.args[a];
+        info->index = nd.index;
+        info->axes = nd.axes;
+        info->keep = nd.keep ? 1 : 0;
+        info->vtype = (int32_t)nd.vtype;
+        info->storage = (int32_t)nd.storage;
+        info->bcast = nd.bcast;
+        info->cval = nd.cval;
+        return EWF_OK;
+    });
 }
 
 }  // extern "C"

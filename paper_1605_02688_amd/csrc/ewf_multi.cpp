@@ -272,6 +272,81 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
     return EWF_OK;
 }
 
+ewf_status plan_empty_rest(Exec &e, const int64_t *full, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout,
+                           const std::vector<int> &outs, Plan &plan)
+{
+    (void)nin; (void)nout;
+    const Graph &g = e.g;
+    const int N = (int)g.nodes.size();
+    auto align_up = [](size_t v) { return (v + 255) / 256 * 256; };
+    std::vector<char> need(N, 0);
+    for (int k : outs) need[g.outputs[k].value] = 1;
+    std::map<int, int> cuts;
+    size_t ws = 0;
+    for (int n = N - 1; n >= 0; n--) {
+        if (!need[n]) continue;
+        const Node &nd = g.nodes[n];
+        bool over_empty = false;
+        if (nd.kind == NodeKind::Reduce)
+            for (int d = 0; d < g.ndim; d++)
+                if ((nd.axes >> d & 1u) && full[d] == 0 && !(g.nodes[nd.args[0]].bcast >> d & 1u)) over_empty = true;
+        if (!over_empty) {
+            for (int a = 0; a < nd.nargs; a++) need[nd.args[a]] = 1;
+            continue;
+        }
+        if (nd.op != EWF_RSUM && nd.op != EWF_RPROD) {
+            set_error("a value is computed from a maximum, minimum or arg-max over an empty axis: only sums (0) and products (1) are defined there");
+            return EWF_ESHAPE;
+        }
+        Temp t;
+        t.dtype = nd.vtype == EWF_I32 ? EWF_I32 : EWF_F32;
+        int64_t count = 1;
+        for (int d = g.ndim - 1; d >= 0; d--) {
+            t.shape[d] = (nd.bcast >> d & 1u) ? 1 : full[d];
+            t.strides[d] = count;
+            count *= t.shape[d];
+        }
+        if (count <= 0) { set_error("internal: an empty value under an output that is not"); return EWF_ESHAPE; }
+        t.bytes = (size_t)count * 4;
+        t.offset = ws;
+        ws = align_up(ws + t.bytes);
+        plan.temps.push_back(t);
+        cuts[n] = (int)plan.temps.size() - 1;
+        const uint32_t one = t.dtype == EWF_I32 ? 1u : 0x3f800000u;
+        plan.temp_fills.push_back({(int)plan.temps.size() - 1, nd.op == EWF_RPROD ? one : 0u});
+    }
+    Stage sg;
+    sg.exec.reset(new Exec());
+    std::vector<std::pair<int, ewf_dtype>> targets;
+    for (int k : outs) { targets.push_back({g.outputs[k].value, g.outputs[k].storage}); sg.out_dst.push_back(k); }
+    build_stage(g, targets, false, cuts, *sg.exec, sg.in_src);
+    sg.exec->opts = e.opts;
+    sg.exec->math_flavour = e.math_flavour;
+    sg.exec->auto_math = e.auto_math;
+    sg.exec->is_stage = true;
+    uint32_t iota_axes = 0;
+    for (const Node &nd : sg.exec->g.nodes) if (nd.kind == NodeKind::Iota) iota_axes |= 1u << nd.index;
+    sg.exec->has_forced_full = iota_axes != 0;
+    for (int d = 0; d < kMaxDims; d++) sg.exec->forced_full[d] = (d < g.ndim && (iota_axes >> d & 1u)) ? full[d] : 1;
+    ewf_status st = finalize_graph(sg.exec->g);
+    if (st != EWF_OK) return st;
+    std::vector<ewf_tensor> tin, tout;
+    for (int s : sg.in_src) {
+        if (s >= 0) tin.push_back(in[s]);
+        else { const Temp &t = plan.temps[-s - 1]; tin.push_back({(void *)(uintptr_t)(kFakeBase + t.offset), t.shape, t.strides}); }
+    }
+    for (int d : sg.out_dst) tout.push_back(out[d]);
+    Plan *sp = nullptr;
+    st = make_plan(*sg.exec, tin.data(), (int)tin.size(), tout.data(), (int)tout.size(), &sp);
+    if (st != EWF_OK) return st;
+    sg.ws_bytes = sp->workspace_bytes;
+    sg.ws_offset = ws;
+    ws = align_up(ws + sg.ws_bytes);
+    plan.stages.push_back(std::move(sg));
+    plan.workspace_bytes = ws;
+    return EWF_OK;
+}
+
 ewf_status run_multi(Exec &x, Plan &p, const ewf_tensor *in, int, const double *scalars, int nscalars,
                      const ewf_tensor *out, int, void *workspace, size_t, void *hip_stream, bool no_setup)
 {

@@ -9,8 +9,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <condition_variable>
 #include <mutex>
 #include <unordered_map>
+#include <unordered_set>
 
 #include "ewf_internal.h"
 
@@ -47,19 +49,26 @@ std::string disk_name(const std::string &keyed)
     return g_cache_dir + buf;
 }
 
-// File layout: "EWFC1\n", the length of the keyed source text (8 bytes), the code object.
+// File layout: "EWFC2\n", the length of the keyed source text (8 bytes), that text, the code
+// object.  The file name is only a hash of the text; the text itself decides whether the file
+// is the one asked for.
 bool disk_load(const std::string &keyed, std::vector<char> &code)
 {
     FILE *f = fopen(disk_name(keyed).c_str(), "rb");
     if (!f) return false;
     char magic[6];
     uint64_t len = 0;
-    bool ok = fread(magic, 1, 6, f) == 6 && memcmp(magic, "EWFC1\n", 6) == 0 && fread(&len, 8, 1, f) == 1 && len == keyed.size();
+    bool ok = fread(magic, 1, 6, f) == 6 && memcmp(magic, "EWFC2\n", 6) == 0 && fread(&len, 8, 1, f) == 1 && len == keyed.size();
     if (ok) {
+        std::string stored(keyed.size(), '\0');
+        ok = fread(&stored[0], 1, stored.size(), f) == stored.size() && stored == keyed;
+    }
+    if (ok) {
+        const long at = ftell(f);
         fseek(f, 0, SEEK_END);
-        long sz = ftell(f) - 14;
-        fseek(f, 14, SEEK_SET);
-        ok = sz > 0;
+        const long sz = ftell(f) - at;
+        fseek(f, at, SEEK_SET);
+        ok = at > 0 && sz > 0;
         if (ok) { code.resize((size_t)sz); ok = fread(code.data(), 1, (size_t)sz, f) == (size_t)sz; }
     }
     fclose(f);
@@ -73,40 +82,74 @@ void disk_store(const std::string &keyed, const std::vector<char> &code)
     FILE *f = fopen(tmp.c_str(), "wb");
     if (!f) return;                                     // an unwritable cache is not an error
     uint64_t len = keyed.size();
-    bool ok = fwrite("EWFC1\n", 1, 6, f) == 6 && fwrite(&len, 8, 1, f) == 1 && fwrite(code.data(), 1, code.size(), f) == code.size();
+    bool ok = fwrite("EWFC2\n", 1, 6, f) == 6 && fwrite(&len, 8, 1, f) == 1 && fwrite(keyed.data(), 1, keyed.size(), f) == keyed.size() &&
+              fwrite(code.data(), 1, code.size(), f) == code.size();
     ok = (fclose(f) == 0) && ok;
     if (!ok || rename(tmp.c_str(), name.c_str()) != 0) remove(tmp.c_str());
 }
 std::unordered_map<std::string, std::vector<char>> g_code;                 // source -> code object
+std::unordered_set<std::string> g_in_flight;                               // sources being compiled right now
+std::condition_variable g_in_flight_done;
+int g_compiling_now = 0, g_compiling_peak = 0;                             // compiler runs in progress, and the most at once
 struct Loaded { hipModule_t module; std::unordered_map<std::string, hipFunction_t> fn; };
-std::unordered_map<std::string, Loaded> g_loaded;                          // device:hash -> module
+std::unordered_map<std::string, Loaded> g_loaded;                          // device ordinal + code object bytes -> module
 }  // namespace
 
+// The lock covers the tables only.  A source that is being compiled is marked as in flight:
+// another thread that wants the same source waits for it, threads with other sources compile at
+// the same time.
 ewf_status compile_source(const std::string &source, std::vector<char> &code, bool *was_cached)
 {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    auto it = g_code.find(source);
-    if (it != g_code.end()) {
-        code = it->second;
-        if (was_cached) *was_cached = true;
-        g_stat_mem_hits++;
-        return EWF_OK;
+    std::string cache_dir;
+    {
+        std::unique_lock<std::mutex> lock(g_mutex);
+        for (;;) {
+            auto it = g_code.find(source);
+            if (it != g_code.end()) {
+                code = it->second;
+                if (was_cached) *was_cached = true;
+                g_stat_mem_hits++;
+                return EWF_OK;
+            }
+            if (!g_in_flight.count(source)) break;
+            g_in_flight_done.wait(lock);
+        }
+        g_in_flight.insert(source);
+        cache_dir = g_cache_dir;
     }
     if (was_cached) *was_cached = false;
+    // whatever happens below, the mark comes off and the waiting threads look again
+    struct Unmark {
+        const std::string &src;
+        ~Unmark()
+        {
+            std::lock_guard<std::mutex> lock(g_mutex);
+            g_in_flight.erase(src);
+            g_in_flight_done.notify_all();
+        }
+    } unmark{source};
+
     // second level: code objects kept on disk across processes, named by a hash of everything
     // that determines them (device helpers, generated text, compiler options and version)
     std::string keyed;
-    if (!g_cache_dir.empty()) {
+    if (!cache_dir.empty()) {
         int major = 0, minor = 0;
         hiprtcVersion(&major, &minor);
         keyed = "gfx950 -O3 no-packed-fp32 hiprtc " + std::to_string(major) + "." + std::to_string(minor) + "\n" + kPrelude + "\n" + source;
         if (disk_load(keyed, code)) {
+            std::lock_guard<std::mutex> lock(g_mutex);
             g_code.emplace(source, code);
             g_stat_disk_hits++;
             return EWF_OK;
         }
     }
-    g_stat_compiles++;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_stat_compiles++;
+        g_compiling_now++;
+        if (g_compiling_now > g_compiling_peak) g_compiling_peak = g_compiling_now;
+    }
+    struct Leave { ~Leave() { std::lock_guard<std::mutex> lock(g_mutex); g_compiling_now--; } } leave;
     hiprtcProgram prog;
     const char *hdr_src[] = {kPrelude};
     const char *hdr_name[] = {"ewf_prelude.hip.h"};
@@ -132,8 +175,11 @@ ewf_status compile_source(const std::string &source, std::vector<char> &code, bo
     code.resize(sz);
     hiprtcGetCode(prog, code.data());
     hiprtcDestroyProgram(&prog);
-    g_code.emplace(source, code);
-    if (!g_cache_dir.empty()) disk_store(keyed, code);
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_code.emplace(source, code);
+    }
+    if (!cache_dir.empty()) disk_store(keyed, code);
     return EWF_OK;
 }
 
@@ -156,13 +202,20 @@ void cache_stats(int *mem_hits, int *disk_hits, int *compiles)
     *mem_hits = g_stat_mem_hits; *disk_hits = g_stat_disk_hits; *compiles = g_stat_compiles;
 }
 
+int peak_concurrent_compiles()
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    return g_compiling_peak;
+}
+
 ewf_status load_function(const std::vector<char> &code, const std::string &entry, void **function, int *device)
 {
     int dev = -1;
     hipError_t he = hipGetDevice(&dev);
     if (he != hipSuccess) { set_error("no HIP device: %s", hipGetErrorString(he)); return EWF_EHIP; }
-    std::string key = std::to_string(dev) + ":" + std::to_string(std::hash<std::string>()(std::string(code.data(), code.size()))) +
-                      ":" + std::to_string(code.size());
+    // (keyed by the code object itself: a hash of it could hand out another expression's kernel)
+    std::string key = std::to_string(dev) + ":";
+    key.append(code.data(), code.size());
     std::lock_guard<std::mutex> lock(g_mutex);
     auto it = g_loaded.find(key);
     if (it == g_loaded.end()) {

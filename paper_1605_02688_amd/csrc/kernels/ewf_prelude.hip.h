@@ -169,8 +169,8 @@ EWF_DEV float ewf_bits_f32(ewf_u32 b) { return __uint_as_float(b); }
 // ------------------------------------------------------------------ scalar operations
 
 // max / min propagate NaN from either operand
-EWF_DEV float ewf_max(float a, float b) { return (a > b || a != a) ? a : b; }
-EWF_DEV float ewf_min(float a, float b) { return (a < b || a != a) ? a : b; }
+EWF_DEV float ewf_max(float a, float b) { return ((a > b) | (a != a)) ? a : b; }
+EWF_DEV float ewf_min(float a, float b) { return ((a < b) | (a != a)) ? a : b; }
 EWF_DEV int ewf_max(int a, int b) { return a > b ? a : b; }
 EWF_DEV int ewf_min(int a, int b) { return a < b ? a : b; }
 EWF_DEV float ewf_abs(float a) { return fabsf(a); }
@@ -399,6 +399,21 @@ EWF_DEV T ewf_block_reduce(T v, F op, T *smem, int tid)
 #pragma unroll
     for (int w = 1; w < NWAVES; w++) r = op(r, smem[w]);
     __syncthreads();
+    return r;
+}
+
+// The same for a buffer that is written once per kernel (no loop around the call): the barrier
+// that protects the buffer from the next round of writes is not needed.
+template <int NWAVES, typename T, typename F>
+EWF_DEV T ewf_block_reduce_once(T v, F op, T *smem, int tid)
+{
+    v = ewf_wave_reduce(v, op);
+    if (NWAVES == 1) return v;
+    if ((tid & 63) == 0) smem[tid >> 6] = v;
+    __syncthreads();
+    T r = smem[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; w++) r = op(r, smem[w]);
     return r;
 }
 

@@ -13,7 +13,8 @@ from dataclasses import dataclass
 from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libewf.so")
+# EWF_LIBRARY names another build of the same library (the host-sanitizer build, say)
+LIB_PATH = os.environ.get("EWF_LIBRARY") or os.path.join(_HERE, "libewf.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1605_02688_amd.build`")
 # PyTorch ships a HIP runtime of its own.  The dynamic loader keeps one runtime per process, the
@@ -123,6 +124,8 @@ _sigs = {
     "ewf_debug_compile_count": (_i32, [_vp]),
     "ewf_debug_graph_size": (_i32, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "ewf_copy_bytes": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
+    "ewf_debug_peak_concurrent_compiles": (_i32, [ctypes.POINTER(_i32)]),
+    "ewf_debug_inject_fault": (_i32, [_i32, _i32]),
     "ewf_debug_time_kernels": (_i32, [_vp, _i32]),
     "ewf_debug_kernel_times": (_i32, [_vp, ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
     "ewf_set_cache_dir": (_i32, [ctypes.c_char_p]),
@@ -327,6 +330,16 @@ def debug_cache_stats() -> dict:
     a, b, c = _i32(), _i32(), _i32()
     _check(_lib.ewf_debug_cache_stats(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
     return {"memory_hits": a.value, "disk_hits": b.value, "compiles": c.value}
+
+
+def debug_peak_concurrent_compiles() -> int:
+    n = _i32(0)
+    _check(_lib.ewf_debug_peak_concurrent_compiles(ctypes.byref(n)))
+    return n.value
+
+
+def debug_inject_fault(kind: int, after: int = 0) -> None:
+    _check(_lib.ewf_debug_inject_fault(kind, after))
 
 
 def debug_time_kernels(e: int, slots: int) -> None:

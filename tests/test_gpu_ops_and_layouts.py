@@ -364,6 +364,37 @@ def test_reductions_over_an_empty_axis_give_the_identity(oracle, G):
     assert torch.all(big[:, 1::2] == 7.0)                     # the strided fill stayed inside its view
 
 
+def test_values_computed_from_reductions_over_an_empty_axis(oracle, G):
+    # log(1 + sum) + b and prod * b over an empty middle axis, next to a plain sum and an empty output
+    rng = np.random.default_rng(17)
+    x = np.zeros((5, 0, 3), np.float32)
+    b = rng.standard_normal((5, 1, 3)).astype(np.float32)
+    s = GraphSpec(3)
+    xi = s.input("f32", (False,) * 3); bi = s.input("f32", (False, True, False))
+    total = s.reduce("sum", xi, (1,), keep=True)
+    s.output(s.add(s.apply("log1p", total), bi), "f32")
+    s.output(s.mul(s.reduce("prod", s.mul(xi, bi), (1,)), s.const(3.0)), "f32")
+    s.output(s.reduce("sum", xi, (1,)), "f32")
+    s.output(s.mul(xi, bi), "f32")
+    print("[case] expressions of reductions over an empty axis", flush=True)
+    expr, got = run_spec(G, s, [x, b])
+    assert expr.info()["kernel_class"] == "multi"
+    want = oracle.evaluate(s, [x, b])
+    assert [g_.shape for g_ in got] == [(5, 1, 3), (5, 3), (5, 3), (5, 0, 3)]
+    for g_, w_ in zip(got, want):
+        assert np.array_equal(g_, w_)
+    assert np.array_equal(got[0], b) and np.all(got[1] == 3.0)
+    # the same through the entry point that uses the library's own workspace
+    import torch
+    dev = [torch.from_numpy(x).cuda(), torch.from_numpy(b).cuda()]
+    outs = G.h.alloc_outputs(expr, s, dev, fill=7)
+    expr.plan(dev, outs)
+    expr.run_static(dev, outs, (), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for o_, w_ in zip(outs, want):
+        assert np.array_equal(o_.cpu().numpy(), w_)
+
+
 def test_every_reduction_kind_row_and_split(oracle, G):
     rng = np.random.default_rng(18)
     for shape, axes in [((200, 333), (1,)), ((3, 40000), (1,)), ((6, 5, 2000), (0, 2))]:

@@ -412,15 +412,21 @@ def test_zero_size_is_success_without_kernel():
     with pytest.raises(ewf.EwfError) as e:
         ewf.Expression(s).plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))])
     assert e.value.status == ewf.ESHAPE
-    # a sum or a product over an empty axis has an identity: planned (a fill at run time); an
-    # expression of it has no such shortcut
+    # a sum or a product over an empty axis has an identity: planned (a fill at run time)
     for red_ in ("sum", "prod"):
         s = GraphSpec(2)
         s.output(s.reduce(red_, s.input("f32", (False, False)), (1,)), "f32")
         e3 = ewf.Expression(s)
         assert e3.plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))]) == 0 and e3.info()["kernel_class"] == "none"
+    # a value computed from such a reduction: the reduction becomes a temporary holding the identity
+    # and one kernel computes the value from it
     s = GraphSpec(2)
     s.output(s.apply("exp", s.reduce("sum", s.input("f32", (False, False)), (1,))), "f32")
+    e4 = ewf.Expression(s)
+    assert e4.plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))]) >= 12
+    assert e4.info()["kernel_class"] == "multi" and e4.info()["grid_blocks"] == 1 and e4.info(0)["kernel_class"] == "tile"
+    s = GraphSpec(2)
+    s.output(s.apply("exp", s.reduce("max", s.input("f32", (False, False)), (1,))), "f32")
     with pytest.raises(ewf.EwfError) as e:
         ewf.Expression(s).plan([ref(BASE, (3, 0))], [ref(BASE + 4096, (3,))])
     assert e.value.status == ewf.ESHAPE
@@ -696,6 +702,8 @@ def test_distinct_executables_plan_concurrently():
         t.join()
     assert not errors, errors
     assert len(results) == 16
+    # distinct sources were in the compiler at the same time (the lock covers the tables only)
+    assert ewf.debug_peak_concurrent_compiles() >= 2
     for i in range(16):
         assert results[i][0] == "row" and (ops[i % len(ops)] in results[i][2] or ops[i % len(ops)] in ("neg", "abs", "sqr", "sqrt"))
         assert results[i][2] == results[(i + 8) % 16][2] or i % 2 != (i + 8) % 2     # same description and layout: same source
@@ -751,3 +759,59 @@ def test_an_input_no_output_uses_is_never_read():
     e = ewf.Expression(s, block_threads=64)
     e.plan([ref(BASE, (512, 300), (1, 512)), ref(BASE + (1 << 30), (512, 300))], [ref(BASE + (2 << 30), (512, 300))])
     assert e.info()["staged_operands"] == 0 and "q_in0" not in e.source()
+
+
+# ------------------------------------------------------------------ the ABI's exception barrier
+
+def test_no_exception_crosses_the_abi():
+    """Faults injected where the library asks for host memory come back as status codes with a
+    message, from graph building, compilation, planning and the gradient call alike; the handles
+    stay usable afterwards."""
+    g = ewf.graph_create(2)
+    x = ewf.input(g, ewf.F32, [0, 0])
+    for kind, status, text in ((1, ewf.ENOMEM, "memory"), (2, ewf.EINVAL, "injected fault")):
+        ewf.debug_inject_fault(kind, 0)
+        with pytest.raises(ewf.EwfError) as err:
+            ewf.apply(g, ewf.OPS["tanh"], [x])
+        assert err.value.status == status and text in err.value.message
+    y = ewf.apply(g, ewf.OPS["tanh"], [x])                 # the fault fired once; the graph is intact
+    assert y == x + 1
+    # inside ewf_grad, a few nodes into the traversal
+    ewf.debug_inject_fault(1, 2)
+    with pytest.raises(ewf.EwfError) as err:
+        ewf.grad(g, [y], [ewf.const(g, ewf.F32, 1.0)], [x])
+    assert err.value.status == ewf.ENOMEM
+    ewf.debug_inject_fault(0, 0)
+    ewf.output(g, y, ewf.F32)
+    e = ewf.compile(g)
+    ewf.graph_destroy(g)
+    ins = [ref(BASE, (8, 16))]; outs = [ref(BASE + (1 << 30), (8, 16))]
+    for kind, status in ((1, ewf.ENOMEM), (2, ewf.EINVAL)):
+        ewf.debug_inject_fault(kind, 0)
+        with pytest.raises(ewf.EwfError) as err:
+            ewf.plan(e, ins, outs)
+        assert err.value.status == status
+    assert ewf.plan(e, ins, outs) == 0 and ewf.debug_plan_info(e)["kernel_class"] == "tile"
+    # the run call passes the same point before it touches the device
+    ewf.debug_inject_fault(2, 0)
+    with pytest.raises(ewf.EwfError) as err:
+        ewf.run(e, ins, [], outs)
+    assert err.value.status == ewf.EINVAL and "injected" in err.value.message
+    ewf.debug_inject_fault(0, 0)
+    ewf.exec_destroy(e)
+
+
+def test_an_empty_plan_checks_the_pointers_it_fills_on_every_call():
+    # a sum over an empty axis is filled with 0 by a kernel: a plan found in the cache must
+    # refuse a null output pointer just as the first call does
+    s = GraphSpec(2)
+    s.output(s.reduce("sum", s.input("f32", (False, False)), (1,)), "f32")
+    e = ewf.Expression(s)
+    ins = [ref(BASE, (5, 0))]
+    assert e.plan(ins, [ref(BASE + (1 << 30), (5,))]) == 0
+    with pytest.raises(ewf.EwfError) as err:
+        e.plan(ins, [ref(0, (5,))])
+    assert err.value.status == ewf.EINVAL and "null" in err.value.message
+    with pytest.raises(ewf.EwfError) as err:
+        e.run(ins, [ref(0, (5,))])
+    assert err.value.status == ewf.EINVAL
