@@ -184,6 +184,8 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
         const bool refused = plan->row_refused || plan->axes_refused;
         Graph split = e.g;
         fuse_shifted_exp_sums(split);
+        // likewise mean -> sum of squared deviations from it: one sweep instead of two
+        if (!e.opts.no_rewrite) fuse_centred_squares(split, full);
         if (plan->axes_refused && split_reduction_axes(split, plan->red.axes, plan->split_first_axes) < 0) split = e.g;
         st = plan_multi(e, split, true, in, nin, out, nout, *plan);
         if (st == EWF_EUNSUPPORTED) {

@@ -200,6 +200,7 @@ struct Gen {
             case NodeKind::Reduce:
                 if (real_reduce((int)n)) rhs = "r" + std::to_string(n);
                 else if (nd.op == kRSumExpShifted) rhs = std::string(M) + "::exp(" + a0 + " - " + a0 + ")";   // one term: exp(x - x)
+                else if (nd.op == kRSumSqCentred) rhs = "(" + a0 + " - " + a0 + ") * (" + a0 + " - " + a0 + ")";   // one term: (x - x)^2
                 else rhs = (nd.op == EWF_RARGMAX) ? "0" : a0;      // reduction over extent-1 axes
                 break;
             case NodeKind::Apply:
@@ -259,7 +260,7 @@ struct Gen {
         for (size_t i = 0; i < nodes.size(); i++) {
             if (shared_slot(nodes, i) >= 0) continue;
             const int op = g.nodes[nodes[i]].op;
-            b += (op == EWF_RARGMAX || op == kRSumExpShifted) ? 8 : 4;
+            b += op == kRSumSqCentred ? 12 : (op == EWF_RARGMAX || op == kRSumExpShifted) ? 8 : 4;
         }
         return b;
     }
@@ -283,6 +284,7 @@ struct Gen {
             const Node &arg = g.nodes[nd.args[0]];
             if (nd.op == EWF_RARGMAX) o << "    " << vtype_c(arg.vtype) << " a" << i << "; int i" << i << ";\n";
             else if (nd.op == kRSumExpShifted) o << "    float a" << i << ", b" << i << ";      // running maximum, sum of exp(x - maximum)\n";
+            else if (nd.op == kRSumSqCentred) o << "    float n" << i << ", a" << i << ", b" << i << ";      // count, running mean, sum of squared deviations from it\n";
             else o << "    " << vtype_c(nd.vtype) << " a" << i << ";\n";
         }
         o << "};\n";
@@ -300,6 +302,7 @@ struct Gen {
             // the most negative finite number, not -inf: x - maximum then never is inf - inf
             // for an element that is -inf, and exp(x - maximum) is 0 for it as it should be
             case kRSumExpShifted: id = "ewf_bits_f32(0xff7fffffu)"; o << "    a.b" << i << " = 0.0f;\n"; break;
+            case kRSumSqCentred: id = "0.0f"; o << "    a.n" << i << " = 0.0f;\n    a.b" << i << " = 0.0f;\n"; break;
             }
             o << "    a.a" << i << " = " << id << ";\n";
             if (nd.op == EWF_RARGMAX) o << "    a.i" << i << " = 2147483647;\n";
@@ -322,6 +325,16 @@ struct Gen {
                 o << "        r.a" << i << " = ewf_max(" << a << ", " << b << ");\n"
                   << "        r.b" << i << " = x.b" << i << " * " << sum_math() << "::exp(" << a << " - r.a" << i << ") + y.b" << i << " * "
                   << sum_math() << "::exp(" << b << " - r.a" << i << ");\n";
+                break;
+            case kRSumSqCentred:
+                // two groups of elements become one: the means meet at their weighted average and
+                // the distance between them adds to the squared deviations
+                o << "        { const float n_ = x.n" << i << " + y.n" << i << ";\n"
+                  << "          const float r_ = n_ > 0.0f ? 1.0f / n_ : 0.0f;\n"
+                  << "          const float d_ = " << b << " - " << a << ";\n"
+                  << "          r.n" << i << " = n_;\n"
+                  << "          r.a" << i << " = " << a << " + d_ * (y.n" << i << " * r_);\n"
+                  << "          r.b" << i << " = x.b" << i << " + y.b" << i << " + d_ * d_ * (x.n" << i << " * y.n" << i << " * r_); }\n";
                 break;
             case EWF_RARGMAX: {
                 std::string ia = "x.i" + std::to_string(i), ib = "y.i" + std::to_string(i);
@@ -355,6 +368,7 @@ struct Gen {
                 // inf - inf for some element, so the sum as described is NaN
                 o << ind << "const float r" << nodes[i] << " = (" << acc << ".b" << i << " == 0.0f || " << acc << ".a" << i
                   << " == ewf_bits_f32(0x7f800000u)) ? ewf_bits_f32(0x7fc00000u) : " << acc << ".b" << i << ";\n";
+            else if (nd.op == kRSumSqCentred) o << ind << "const float r" << nodes[i] << " = " << acc << ".b" << i << ";\n";
             else o << ind << "const " << vtype_c(nd.vtype) << " r" << nodes[i] << " = " << acc << ".a" << (sh >= 0 ? sh : (int)i) << ";\n";
         }
     }
@@ -386,6 +400,16 @@ struct Gen {
                   << ind << "  const float w_ = " << sum_math() << "::exp(-__builtin_fabsf(d_));\n"
                   << ind << "  " << b << " = d_ > 0.0f ? " << b << " * w_ + 1.0f : " << b << " + w_;\n"
                   << ind << "  " << a << " = ewf_max(" << a << ", " << v << "); }\n";
+                break;
+            }
+            case kRSumSqCentred: {
+                // the single-pass update: the mean moves by its share of the new deviation, and
+                // the product of the deviations before and after the move is the element's part
+                const std::string nn = acc + ".n" + std::to_string(i), b = acc + ".b" + std::to_string(i);
+                o << ind << "{ " << nn << " += 1.0f;\n"
+                  << ind << "  const float d_ = " << v << " - " << a << ";\n"
+                  << ind << "  " << a << " = __builtin_fmaf(d_, __builtin_amdgcn_rcpf(" << nn << "), " << a << ");\n"
+                  << ind << "  " << b << " = __builtin_fmaf(d_, " << v << " - " << a << ", " << b << "); }\n";
                 break;
             }
             case EWF_RARGMAX: {
@@ -644,6 +668,7 @@ struct Gen {
             const Node &nd = g.nodes[red.cross_nodes[i]];
             o << ind << "ax.a" << i << " = v" << nd.args[0] << ";\n";
             if (nd.op == kRSumExpShifted) o << ind << "ax.b" << i << " = 1.0f;\n";
+            if (nd.op == kRSumSqCentred) o << ind << "ax.n" << i << " = 1.0f;\n" << ind << "ax.b" << i << " = 0.0f;\n";
             if (nd.op == EWF_RARGMAX) {
                 int cd = argmax_canon_dim(red.cross_nodes[i]);
                 o << ind << "ax.i" << i << " = (int)(" << (cd < 0 ? std::string("0") : "o" + std::to_string(cd)) << ");\n";

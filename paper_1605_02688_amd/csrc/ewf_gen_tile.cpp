@@ -81,7 +81,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // (light accumulations only: with the rescaled exp-sum and an arg-max, 512 rows of 131072
     // float32 took 53.0 us with these tiles against 51.0 us with 8192-element ones)
     bool light = heavy == 0;
-    for (int n : red.level_nodes) light = light && g.nodes[n].op != EWF_RARGMAX && g.nodes[n].op != kRSumExpShifted;
+    for (int n : red.level_nodes) light = light && g.nodes[n].op != EWF_RARGMAX && g.nodes[n].op != kRSumExpShifted && g.nodes[n].op != kRSumSqCentred;
     if (with_reduce && ew_out_ops.empty() && light) {
         int in_sz = 4;
         for (int k = 0; k < nin; k++) in_sz = std::min(in_sz, isz(c.ops[k].storage));

@@ -111,6 +111,12 @@ enum class KernelClass : int { None = 0, Tile = 1, TileReduce = 2, Row = 3, Col 
 // It turns the two chained reductions of a softmax or log-sum-exp into one level, so rows of
 // any length can be split over workgroups.
 constexpr int kRSumExpShifted = 64;
+// Another one: sum over the axes of (x - mean of x over the same axes) squared, accumulated in
+// one pass as a (count, running mean, sum of squared deviations) triple -- the published
+// single-pass update for the variance, whose pairwise combine rule lets it fold across lanes,
+// wavefronts and workgroups like any other accumulator.  It turns mean -> variance of the
+// centred values (two chained reductions, two sweeps over memory) into one level.
+constexpr int kRSumSqCentred = 65;
 
 struct ReduceInfo {
     bool has_reduce = false;
@@ -287,6 +293,10 @@ int fuse_shifted_exp_sums(Graph &g, bool unless_argmax = false);
 // (reducing along an axis on which the argument is broadcastable is the identity).  In place;
 // returns the number of reductions split, or -1 if the graph could not be rebuilt.
 int split_reduction_axes(Graph &g, uint32_t axes, uint32_t outer);
+// Replaces every sum over axes A of (x - m)^2 where m is the mean of x over A -- sum(x) over A times
+// the literal 1/n or divided by the literal n, n the number of elements along A in this call
+// (`full`: the extents) -- by one kRSumSqCentred node.  Returns the number of replacements.
+int fuse_centred_squares(Graph &g, const int64_t *full);
 
 // ---- ewf_canon.cpp
 // Builds the canonical layout.  `in`/`out` give shapes and strides in the original rank

@@ -137,6 +137,40 @@ int fuse_shifted_exp_sums(Graph &g, bool unless_argmax)
     return count;
 }
 
+int fuse_centred_squares(Graph &g, const int64_t *full)
+{
+    int count = 0;
+    for (Node &q : g.nodes) {
+        if (q.kind != NodeKind::Reduce || q.op != EWF_RSUM || q.vtype != EWF_F32) continue;
+        const Node &sq = g.nodes[q.args[0]];
+        if (sq.kind != NodeKind::Apply) continue;
+        if (!(sq.op == EWF_SQR || (sq.op == EWF_MUL && sq.args[0] == sq.args[1]))) continue;
+        const Node &sub = g.nodes[sq.args[0]];
+        if (sub.kind != NodeKind::Apply || sub.op != EWF_SUB) continue;
+        const int x = sub.args[0];
+        if (g.nodes[x].vtype != EWF_F32 || (g.nodes[x].bcast & q.axes)) continue;   // x varies along every reduced axis
+        const Node &m = g.nodes[sub.args[1]];
+        if (m.kind != NodeKind::Apply || (m.op != EWF_MUL && m.op != EWF_DIV)) continue;
+        double n = 1.0;
+        for (int d = 0; d < g.ndim; d++) if (q.axes >> d & 1u) n *= (double)full[d];
+        if (n < 1.0) continue;
+        int s = -1;
+        for (int side = 0; side < 2 && s < 0; side++) {
+            const Node &a = g.nodes[m.args[side]], &k = g.nodes[m.args[1 - side]];
+            if (m.op == EWF_DIV && side == 1) break;                                // sum / n only, not n / sum
+            if (a.kind != NodeKind::Reduce || a.op != EWF_RSUM || a.axes != q.axes || a.args[0] != x) continue;
+            if (k.kind != NodeKind::Const || k.vtype != EWF_F32) continue;
+            const float want = m.op == EWF_DIV ? (float)n : (float)(1.0 / n);
+            if ((float)k.cval == want) s = m.args[side];
+        }
+        if (s < 0) continue;
+        q.op = kRSumSqCentred;
+        q.args[0] = x;
+        count++;
+    }
+    return count;
+}
+
 int split_reduction_axes(Graph &g, uint32_t axes, uint32_t outer)
 {
     if (!outer || (outer & ~axes) || outer == axes) return 0;

@@ -506,7 +506,9 @@ def test_plans_in_several_passes(oracle, G):
     s.output(mean, "f32"); s.output(var, "f32")
     print("[case] batch normalisation in stages", flush=True)
     expr, got = run_spec(G, s, [x])
-    assert expr.info()["kernel_class"] == "multi" and expr.info()["grid_blocks"] == 3
+    # mean and sum of squared deviations in one sweep (single-pass accumulator), the normalised tensor in a second
+    assert expr.info()["kernel_class"] == "multi" and expr.info()["grid_blocks"] == 2
+    assert "sum of squared deviations" in expr.source(0)
     want = oracle.evaluate(s, [x])
     G.h.compare("normalised", got[0], want[0], 1e-5, 1e-6)
     G.h.compare("mean", got[1], want[1], 1e-5, 1e-6); G.h.compare("var", got[2], want[2], 1e-5, 1e-6)
@@ -540,6 +542,67 @@ def test_plans_in_several_passes(oracle, G):
     assert expr.info()["kernel_class"] == "multi"
     want = oracle.evaluate(s, [z])
     G.h.compare("p", got[0], want[0], 1e-5, 1e-7); G.h.compare("centred", got[1], want[1], 1e-5, 1e-6)
+
+
+def _moments_spec(ndim, axes, n, storage="f32", divide=False):
+    """mean, variance of the centred values (biased), and the normalised tensor over `axes`."""
+    s = GraphSpec(ndim)
+    xi = s.input(storage, (False,) * ndim)
+    total = s.reduce("sum", xi, axes, keep=True)
+    mean = s.div(total, s.const(float(n))) if divide else s.mul(total, s.const(1.0 / n))
+    cen = s.sub(xi, mean)
+    var = s.mul(s.reduce("sum", s.mul(cen, cen), axes, keep=True), s.const(1.0 / n))
+    s.output(mean, "f32"); s.output(var, "f32")
+    s.output(s.mul(cen, s.apply("recip", s.apply("sqrt", s.add(var, s.const(1e-5))))), storage)
+    return s
+
+
+@pytest.mark.parametrize("shape,axes,storage,offset,first", [
+    ((4099, 300), (0,), "f32", 0.0, "col"),             # batch normalisation of a matrix
+    ((4099, 300), (0,), "f32", 1000.0, "col"),          # a mean a thousand deviations away from zero
+    ((70001, 24), (0,), "f16", 3.0, "col"),
+    ((33, 20, 17, 19), (0, 2, 3), "f32", -50.0, "tile_reduce"),   # per-channel statistics of feature maps
+    ((6, 150001), (1,), "f32", 10.0, "tile_reduce"),    # rows too long for the registers of a workgroup
+    ((3, 5, 7), (0, 1, 2), "f32", 2.0, None),
+])
+def test_mean_and_variance_in_one_sweep(shape, axes, storage, offset, first, oracle, G):
+    """mean -> variance of the centred values is a chain of two reductions; outside the row class
+    (where the data waits in registers) the planner makes it one level with the single-pass
+    (count, mean, sum of squared deviations) accumulator, so the tensor is read twice, not three
+    times.  Against the oracle's two-pass evaluation in float64."""
+    rng = np.random.default_rng(300 + len(shape) + int(offset))
+    x = (rng.standard_normal(shape) * 1.5 + offset).astype(np.float16 if storage == "f16" else np.float32)
+    n = int(np.prod([shape[d] for d in axes]))
+    for divide in (False, True):
+        s = _moments_spec(len(shape), axes, n, storage, divide)
+        print(f"[case] moments {shape} over {axes} {storage} offset {offset} divide {divide}", flush=True)
+        expr, got = run_spec(G, s, [x])
+        info = expr.info()
+        if first is not None:
+            assert info["kernel_class"] == "multi" and info["grid_blocks"] == 2, info
+            assert expr.info(0)["kernel_class"] == first and "sum of squared deviations" in expr.source(0)
+        want = oracle.evaluate(s, [x], nthreads=4)
+        x64 = x.astype(np.float64)
+        G.h.compare("mean", got[0], want[0], 1e-5, 1e-6, scale=np.abs(x64).sum(axes, keepdims=True) / n)
+        G.h.compare("var", got[1], want[1], 1e-5, 1e-6)
+        # x - mean cancels: the rounding of x and of the mean, relative to the deviation, is what the
+        # float32 result can know, so the bar is relative to (|x| + |mean|) / deviation
+        spread = np.sqrt(x64.var(axes, keepdims=True) + 1e-5)
+        if storage == "f32":
+            G.h.compare("normalised", got[2], want[2], 1e-5, 1e-6, scale=(np.abs(x64) + np.abs(x64.mean(axes, keepdims=True))) / spread)
+        else:
+            G.h.compare("normalised", got[2], want[2], 2e-3, 1e-3)
+    # a divisor that is not the number of elements is not a mean: the chain stays as described
+    # (checked where the data is not far from zero: as described in float32, the subtraction of a
+    # rounded mean of about 1000 alone costs more than the bar allows)
+    if abs(offset) > 10:
+        return
+    s = _moments_spec(len(shape), axes, n + 1, storage)
+    expr, got = run_spec(G, s, [x])
+    stages = expr.info()["grid_blocks"] if expr.info()["kernel_class"] == "multi" else 0
+    assert "sum of squared deviations" not in expr.source() + "".join(expr.source(k) for k in range(stages))
+    want = oracle.evaluate(s, [x], nthreads=4)
+    G.h.compare("var with another divisor", got[1], want[1], 1e-5, 1e-6)
 
 
 def test_gradient_of_a_product_reduction(oracle, G):
