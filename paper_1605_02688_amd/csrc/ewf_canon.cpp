@@ -311,6 +311,15 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
     c.vec_loose = vec;
     while (vec > 1 && !vec_ok(vec)) vec /= 2;
     c.vec = vec;
+    // what the launch moves through operands that are touched once: from 64 MiB on (twice the
+    // level-two caches of all dies together) nothing of it is still cached when its turn comes again
+    int64_t moved_once = 0;
+    for (const Operand &op : c.ops) {
+        int64_t footprint = itemsize(op.storage);
+        bool once = true;
+        for (int i = 0; i < c.rank; i++) { if (op.stride[i] != 0) footprint *= c.extent[i]; else if (!(op.is_output && c.reduced[i])) once = false; }
+        if (once || op.is_output) moved_once += footprint;
+    }
     for (Operand &op : c.ops) {
         if (op.stride[in_d] == 1 || c.extent[in_d] == 1) op.access = Access::Vector;
         else if (op.stride[in_d] == 0) op.access = Access::Splat;
@@ -323,7 +332,8 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
         for (int i = 0; i < c.rank; i++) { if (op.stride[i] != 0) footprint *= c.extent[i]; else if (!(op.is_output && c.reduced[i])) once = false; }
         if (op.is_output) once = true;
         op.stream = op.access == Access::Vector && once &&
-                    (e.opts.streaming == 1 || (e.opts.streaming == 0 && footprint >= ((int64_t)32 << 20)));
+                    (e.opts.streaming == 1 ||
+                     (e.opts.streaming == 0 && (footprint >= ((int64_t)32 << 20) || (moved_once >= ((int64_t)64 << 20) && footprint >= ((int64_t)4 << 20)))));
     }
     return EWF_OK;
 }

@@ -125,8 +125,23 @@ struct Gen {
             for (int a = 0; a < g.nodes[n].nargs; a++) if (after_cross[g.nodes[n].args[a]]) after_cross[n] = 1;
         }
         analyse_signs();
-        std::vector<char> direct(N, 0);
-        for (const OutputDecl &od : g.outputs) direct[od.value] = 1;
+        // Which values must meet the element-wise bar: those that reach an output that depends on
+        // no reduction, through no float32 sum.  An output computed from a reduction is held to the
+        // bar for reductions (1e-5), which the native-rate flavour with fix-ups meets (see sum_only).
+        std::vector<char> direct(N, 0), below_reduce(N, 0);
+        for (int n = 0; n < N; n++) {
+            const Node &nd = g.nodes[n];
+            if (nd.kind == NodeKind::Reduce && real_reduce(n)) below_reduce[n] = 1;
+            for (int a = 0; a < nd.nargs; a++) if (below_reduce[nd.args[a]]) below_reduce[n] = 1;
+        }
+        for (const OutputDecl &od : g.outputs) if (!below_reduce[od.value]) direct[od.value] = 1;
+        // (what a product, maximum, minimum or arg-max folds stays accurate: a product compounds
+        // the error of its factors, and an extreme value or its index can flip on a rounding)
+        for (int n = 0; n < N; n++) {
+            const Node &nd = g.nodes[n];
+            if (live[n] && nd.kind == NodeKind::Reduce && real_reduce(n) && !(nd.op == EWF_RSUM && nd.vtype == EWF_F32) &&
+                nd.op != kRSumExpShifted) direct[nd.args[0]] = 1;
+        }
         for (int n = N - 1; n >= 0; n--) {
             if (!direct[n]) continue;
             const Node &nd = g.nodes[n];
