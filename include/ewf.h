@@ -122,7 +122,11 @@ typedef struct {
                                level that is rescaled as the maximum grows).  0 automatic: split
                                when a row does not fit the registers or the rows are too few to
                                occupy the chip; 1 always split; 2 never                       */
-    int32_t reserved[2];
+    int32_t plain_extremes; /* 1: a row's maximum and arg-max are always folded with the rules that
+                               rank NaN (default 0: rows held in registers take the hardware
+                               maximum first, find the index afterwards, and fall back on those
+                               rules only for rows that hold a NaN or an infinity)             */
+    int32_t reserved[1];
 } ewf_options;
 
 /* A strided n-d view of caller-owned device memory.  rank is implied by the graph (inputs:

@@ -83,6 +83,29 @@ ewf_status Gen::gen_row()
     }
     const int U = resident ? (int)NV : (e.opts.unroll > 0 ? e.opts.unroll : 4);
     p.tile[in_d] = cols;
+    // Maxima and arg-maxima of a float input row that waits in registers are taken the cheap way
+    // first: the hardware maximum (which drops NaN) next to a check word that turns NaN when the
+    // row holds a NaN or an infinity, then the index by the threads that hold the maximum.  Only a
+    // row whose check word is NaN is folded again with the rules that rank NaN.  (Per element: one
+    // and a half instructions instead of five on a dependent chain.)
+    std::vector<std::vector<int>> fastn(D + 1);
+    std::vector<int> fast_op(D + 1, -1);
+    if (resident && !e.opts.plain_extremes) {
+        for (int l = 1; l <= D; l++) {
+            int arg = -1;
+            std::vector<int> rest;
+            for (int n : lvl[l]) {
+                const Node &nd = g.nodes[n];
+                const Node &a = g.nodes[nd.args[0]];
+                bool take = (nd.op == EWF_RMAX || nd.op == EWF_RARGMAX) && a.vtype == EWF_F32 && a.kind == NodeKind::Input &&
+                            std::find(row_ops.begin(), row_ops.end(), a.index) != row_ops.end() && !late[a.index] &&
+                            (arg < 0 || arg == nd.args[0]);
+                if (take) { arg = nd.args[0]; fastn[l].push_back(n); fast_op[l] = a.index; }
+                else rest.push_back(n);
+            }
+            lvl[l] = rest;
+        }
+    }
     {
         // When all rows can be resident on the chip at once there is no second round of
         // workgroups (whose tail would idle most of the chip): ask the compiler for the
@@ -101,6 +124,7 @@ ewf_status Gen::gen_row()
     emit_header(block);
     build_layout();
     for (int l = 1; l <= D; l++) if (!lvl[l].empty()) emit_acc_struct("Acc" + std::to_string(l), lvl[l]);
+    for (int l = 1; l <= D; l++) if (!fastn[l].empty()) emit_acc_struct("AccS" + std::to_string(l), fastn[l]);
     const bool has_cross = !red.cross_nodes.empty();
     if (has_cross) emit_acc_struct("AccX", red.cross_nodes);
 
@@ -108,6 +132,10 @@ ewf_status Gen::gen_row()
     o << "    const int tid = threadIdx.x;\n";
     o << "    const idx_t cols = p.ext[" << in_d << "];\n";
     for (int l = 1; l <= D; l++) if (!lvl[l].empty()) o << "    __shared__ Acc" << l << " sm_acc" << l << "[EWF_NWAVES];\n";
+    for (int l = 1; l <= D; l++)
+        if (!fastn[l].empty())
+            o << "    __shared__ AccS" << l << " sm_accs" << l << "[EWF_NWAVES];\n    __shared__ ewf_fmax sm_fm" << l
+              << "[EWF_NWAVES];\n    __shared__ int sm_ix" << l << "[EWF_NWAVES];\n";
     if (has_cross) o << "    AccX *const partials = (AccX *)p.ws_partials;\n";
     // one workgroup per row when the grid can hold them all: no loop, so nothing is hoisted
     // out of it into registers that the row needs
@@ -239,6 +267,64 @@ ewf_status Gen::gen_row()
               << (c.ops[ga.input].stride[in_d] == 1 ? std::string("") : " * p.st_" + nm + "[" + std::to_string(in_d) + "]")
               << "]);\n";
             o << "            r" << ga.node << " = in_ ? x_ + 0.0f : 0.0f;\n        }\n";
+        }
+        if (!fastn[l].empty()) {
+            const std::string L = std::to_string(l), xr = "x_" + opname(fast_op[l]);
+            const char *fold = nrows <= grid_cap ? "ewf_block_reduce_once" : "ewf_block_reduce";
+            o << "        float rr_max" << L << "; int rr_arg" << L << ";\n        {\n";
+            o << "        ewf_fmax fm_; fm_.m = ewf_bits_f32(0xff800000u); fm_.c = 0.0f;\n";
+            open_pass();
+            o << "            { float s_ = 0.0f;\n";
+            o << "              _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+            if (ragged) o << "                if (u >= " << NFULL << " && col + e_ >= cols) continue;\n";
+            o << "                const float t_ = ewf_in(" << xr << "[u].e[e_]);\n";
+            o << "                fm_.m = __builtin_fmaxf(fm_.m, t_); s_ += t_;\n              }\n";
+            o << "              fm_.c = __builtin_fmaf(s_, 0.0f, fm_.c); }\n";
+            close_pass();
+            o << "        const float tm_ = fm_.m;\n";
+            o << "        fm_ = " << fold << "<EWF_NWAVES>(fm_, ewf_fmax_combine(), sm_fm" << L << ", tid);\n";
+            o << "        if (fm_.c == fm_.c) {\n";
+            // the same bits in every thread (each folds the same per-wavefront values in the same
+            // order), so the branch is uniform across the workgroup
+            o << "            int ix_ = 2147483647;\n";
+            o << "            if (tm_ == fm_.m) {\n";
+            o << "                #pragma unroll\n                for (int u = " << U - 1 << "; u >= 0; --u) {\n";
+            o << "                    const idx_t col = (idx_t)(u * EWF_BLOCK + tid) * EWF_VEC;\n";
+            o << "                    if (u >= " << NFULL << " && col >= cols) continue;\n";
+            o << "                    _Pragma(\"unroll\") for (int e_ = EWF_VEC - 1; e_ >= 0; --e_) {\n";
+            if (ragged) o << "                        if (u >= " << NFULL << " && col + e_ >= cols) continue;\n";
+            o << "                        if (ewf_in(" << xr << "[u].e[e_]) == fm_.m) ix_ = (int)(col + e_);\n";
+            o << "                    }\n                }\n            }\n";
+            o << "            ix_ = " << fold << "<EWF_NWAVES>(ix_, ewf_imin(), sm_ix" << L << ", tid);\n";
+            o << "            rr_max" << L << " = fm_.m; rr_arg" << L << " = ix_;\n";
+            o << "        } else {\n";
+            {
+                // a NaN or an infinity somewhere in the row: the fold that ranks them
+                std::string an = "AccS" + L, av = "accs" + L;
+                std::vector<int> tg;
+                for (int n : fastn[l]) tg.push_back(g.nodes[n].args[0]);
+                std::vector<char> need = needed(tg);
+                o << "        " << an << " " << av << " = " << an << "_identity();\n";
+                open_pass();
+                o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+                if (ragged) o << "                if (u >= " << NFULL << " && col + e_ >= cols) continue;\n";
+                emit_values(need, cx, "                ");
+                emit_accumulate(av, fastn[l], [&](int node) { return cx.coord(argmax_canon_dim(node)); }, "                ", true);
+                o << "            }\n";
+                close_pass();
+                emit_first_index(av, fastn[l], "(idx_t)tid * EWF_VEC < cols", "tid * EWF_VEC", "        ");
+                o << "        " << av << " = " << fold << "<EWF_NWAVES>(" << av << ", " << an << "_combine(), sm_accs" << L << ", tid);\n";
+                o << "        {\n";
+                emit_results(av, fastn[l], "        ");
+                for (int n : fastn[l])
+                    o << "        rr_" << (g.nodes[n].op == EWF_RARGMAX ? "arg" : "max") << L << " = r" << n << ";\n";
+                // (an arg-max alone leaves the maximum unset, a maximum alone the index: neither is read)
+                o << "        }\n";
+            }
+            o << "        }\n        }\n";
+            for (int n : fastn[l])
+                o << "        const " << (g.nodes[n].op == EWF_RARGMAX ? "int" : "float") << " r" << n << " = rr_"
+                  << (g.nodes[n].op == EWF_RARGMAX ? "arg" : "max") << L << ";\n";
         }
         if (lvl[l].empty()) continue;
         std::string an = "Acc" + std::to_string(l), av = "acc" + std::to_string(l);

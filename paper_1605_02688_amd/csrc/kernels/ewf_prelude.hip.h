@@ -417,4 +417,19 @@ EWF_DEV T ewf_block_reduce_once(T v, F op, T *smem, int tid)
     return r;
 }
 
+// A maximum taken the cheap way (the hardware maximum drops NaN) next to a check word that turns
+// NaN as soon as an element is NaN or infinite: the sum of the elements times zero.  While the
+// check word is a number the maximum is the one the NaN-aware rules would have given.
+struct ewf_fmax { float m, c; };
+struct ewf_fmax_combine {
+    EWF_DEV ewf_fmax operator()(const ewf_fmax &x, const ewf_fmax &y) const
+    {
+        ewf_fmax r;
+        r.m = __builtin_fmaxf(x.m, y.m);
+        r.c = x.c + y.c;
+        return r;
+    }
+};
+struct ewf_imin { EWF_DEV int operator()(int a, int b) const { return a < b ? a : b; } };
+
 #endif  // EWF_PRELUDE_H

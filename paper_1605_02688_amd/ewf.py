@@ -54,7 +54,7 @@ class ewf_options(ctypes.Structure):
                 ("tile_elems", ctypes.c_int32), ("waves_per_simd", ctypes.c_int32),
                 ("no_prefetch", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
                 ("no_rewrite", ctypes.c_int32), ("split_rows", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 2)]
+                ("plain_extremes", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
 
 
 class ewf_tensor(ctypes.Structure):
