@@ -227,7 +227,21 @@ struct Gen {
                 case EWF_DIV: rhs = std::string(M) + "::div(" + a0 + ", " + a1 + ")"; break;
                 case EWF_NEG: rhs = isint ? "ewf_negi(" + a0 + ")" : "-" + a0; break;
                 case EWF_ABS: rhs = "ewf_abs(" + a0 + ")"; break;
-                case EWF_EXP: rhs = std::string(M) + "::exp(" + a0 + ")"; break;
+                case EWF_EXP: {
+                    // exp(k * s), k a literal, with the native-rate flavours: one multiplication
+                    // by k * log2 e (folded here) and the hardware exp2
+                    const Node &arg = g.nodes[nd.args[0]];
+                    int kside = -1;
+                    if (fl >= 2 && arg.kind == NodeKind::Apply && arg.op == EWF_MUL)
+                        for (int sd = 0; sd < 2; sd++) if (g.nodes[arg.args[sd]].kind == NodeKind::Const) kside = sd;
+                    if (kside >= 0) {
+                        const double k = (double)(float)g.nodes[arg.args[kside]].cval;
+                        rhs = "__builtin_amdgcn_exp2f(v" + std::to_string(arg.args[1 - kside]) + " * " + f32_literal(k * 1.44269504088896340736) + ")";
+                    } else {
+                        rhs = std::string(M) + "::exp(" + a0 + ")";
+                    }
+                    break;
+                }
                 case EWF_LOG: rhs = std::string(M) + "::log(" + a0 + ")"; break;
                 case EWF_LOG1P: rhs = std::string(M) + "::log1p(" + a0 + ")"; break;
                 case EWF_EXPM1: rhs = std::string(M) + "::expm1(" + a0 + ")"; break;

@@ -175,6 +175,9 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
     };
 
     for (int round = 0; round < 16; round++) {
+        bool all_written = true;
+        for (int k = 0; k < nout; k++) all_written = all_written && written[k];
+        if (all_written && !plan.stages.empty()) break;
         // does what remains fit one kernel?
         {
             Stage fin;
@@ -207,58 +210,111 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
         }
         if (groups.empty()) { set_error("no reduction left to split off"); return EWF_EUNSUPPORTED; }
         for (auto &gr : groups) {
-            Stage sg;
-            sg.exec.reset(new Exec());
-            std::vector<std::pair<int, ewf_dtype>> targets;
-            for (int n : gr.second) targets.push_back({n, g.nodes[n].vtype == EWF_I32 ? EWF_I32 : EWF_F32});
-            build_stage(g, targets, true, cuts, *sg.exec, sg.in_src);
-            for (int n : gr.second) {
-                Temp t;
-                t.dtype = g.nodes[n].vtype == EWF_I32 ? EWF_I32 : EWF_F32;
-                int64_t count = 1;
-                for (int d = g.ndim - 1; d >= 0; d--) {
-                    t.shape[d] = (g.nodes[n].bcast & (1u << d)) ? 1 : full[d];
-                    t.strides[d] = count;
-                    count *= t.shape[d];
+            // Values computed from this stage's reductions that are still constant along the reduced
+            // axes (the reciprocal deviation of a normalisation: one number per column) are
+            // evaluated once per group by this stage and handed on as temporaries too; a later,
+            // element-wise stage would evaluate them once per element.
+            std::vector<int> handed = gr.second;
+            std::vector<char> glevel(N, 0), dep(N, 0);
+            if (!e.opts.no_rewrite) {
+                const uint32_t eff = gr.first;
+                std::vector<char> mine(N, 0);
+                for (int n : gr.second) mine[n] = 1;
+                for (int n = 0; n < N; n++) {
+                    const Node &nd = g.nodes[n];
+                    if (mine[n]) { glevel[n] = dep[n] = 1; continue; }
+                    if (cuts.count(n) || nd.kind == NodeKind::Input || nd.kind == NodeKind::Scalar || nd.kind == NodeKind::Const ||
+                        nd.kind == NodeKind::Iota) { glevel[n] = ((nd.bcast | unit) & eff) == eff; continue; }
+                    if (nd.kind == NodeKind::Reduce) continue;
+                    bool all = nd.nargs > 0, any = false;
+                    for (int a = 0; a < nd.nargs; a++) { all = all && glevel[nd.args[a]]; any = any || dep[nd.args[a]]; }
+                    glevel[n] = all && any;
+                    dep[n] = glevel[n];
                 }
-                t.bytes = (size_t)count * 4;
-                t.offset = ws;
-                ws = align_up(ws + t.bytes);
-                plan.temps.push_back(t);
-                sg.out_dst.push_back(-(int)plan.temps.size());
-            }
-            // does this pass walk the full extents (then element-wise outputs can ride along)?
-            bool spans_all = true;
-            for (int d = 0; d < g.ndim && spans_all; d++) {
-                if (full[d] <= 1) continue;
-                bool some = false;
-                for (int node : sg.exec->g.input_node) if (!(sg.exec->g.nodes[node].bcast >> d & 1u)) some = true;
-                spans_all = some;
-            }
-            std::vector<int> riders;
-            if (spans_all && !e.opts.no_rewrite)
-                for (int k = 0; k < nout; k++) if (can_ride(k)) riders.push_back(k);
-            bool done = false;
-            if (!riders.empty()) {
-                Stage both;
-                both.exec.reset(new Exec());
-                std::vector<std::pair<int, ewf_dtype>> all = targets;
-                for (int k : riders) all.push_back({g.outputs[k].value, g.outputs[k].storage});
-                build_stage(g, all, true, cuts, *both.exec, both.in_src);
-                both.out_dst = sg.out_dst;
-                for (int k : riders) both.out_dst.push_back(k);
-                if (try_stage(both) == EWF_OK) {
-                    for (int k : riders) written[k] = 1;
-                    sg = std::move(both);
-                    done = true;
+                // the outermost such values: used by something that varies along the reduced axes
+                std::vector<char> used_outside(N, 0);
+                for (int n = 0; n < N; n++) {
+                    if (!live[n] || glevel[n]) continue;
+                    for (int a = 0; a < g.nodes[n].nargs; a++) used_outside[g.nodes[n].args[a]] = 1;
                 }
+                for (int n = 0; n < N; n++)
+                    if (live[n] && glevel[n] && dep[n] && !mine[n] && !cuts.count(n) && used_outside[n] && g.nodes[n].kind != NodeKind::Reduce)
+                        handed.push_back(n);
             }
-            if (!done) {
-                st = try_stage(sg);
-                if (st != EWF_OK) return st;
-            }
-            for (size_t i = 0; i < gr.second.size(); i++) cuts[gr.second[i]] = (int)plan.temps.size() - (int)gr.second.size() + (int)i;
-            plan.stages.push_back(std::move(sg));
+            // one attempt with a given list of values to hand on; a failed attempt leaves no trace
+            // Outputs that are such values (a mean, a variance: one number per group) are written by
+            // this stage as well: left to an element-wise stage, every element of the group would
+            // store the same number to the same place.
+            auto attempt = [&](const std::vector<int> &hand, bool group_outputs) -> ewf_status {
+                const size_t ntemps = plan.temps.size(), ws0 = ws;
+                Stage sg;
+                sg.exec.reset(new Exec());
+                std::vector<std::pair<int, ewf_dtype>> targets;
+                for (int n : hand) targets.push_back({n, g.nodes[n].vtype == EWF_I32 ? EWF_I32 : EWF_F32});
+                build_stage(g, targets, true, cuts, *sg.exec, sg.in_src);
+                for (int n : hand) {
+                    Temp t;
+                    t.dtype = g.nodes[n].vtype == EWF_I32 ? EWF_I32 : EWF_F32;
+                    int64_t count = 1;
+                    for (int d = g.ndim - 1; d >= 0; d--) {
+                        t.shape[d] = (g.nodes[n].bcast & (1u << d)) ? 1 : full[d];
+                        t.strides[d] = count;
+                        count *= t.shape[d];
+                    }
+                    t.bytes = (size_t)count * 4;
+                    t.offset = ws;
+                    ws = align_up(ws + t.bytes);
+                    plan.temps.push_back(t);
+                    sg.out_dst.push_back(-(int)plan.temps.size());
+                }
+                std::vector<int> gouts;
+                if (group_outputs)
+                    for (int k = 0; k < nout; k++) {
+                        const int v = g.outputs[k].value;
+                        if (!written[k] && glevel[v] && dep[v] && !g.nodes[v].dropped) gouts.push_back(k);
+                    }
+                if (!gouts.empty()) {
+                    for (int k : gouts) { targets.push_back({g.outputs[k].value, g.outputs[k].storage}); sg.out_dst.push_back(k); }
+                    build_stage(g, targets, true, cuts, *sg.exec, sg.in_src);
+                }
+                // does this pass walk the full extents (then element-wise outputs can ride along)?
+                bool spans_all = true;
+                for (int d = 0; d < g.ndim && spans_all; d++) {
+                    if (full[d] <= 1) continue;
+                    bool some = false;
+                    for (int node : sg.exec->g.input_node) if (!(sg.exec->g.nodes[node].bcast >> d & 1u)) some = true;
+                    spans_all = some;
+                }
+                std::vector<int> riders;
+                if (spans_all && !e.opts.no_rewrite)
+                    for (int k = 0; k < nout; k++) if (can_ride(k)) riders.push_back(k);
+                bool done = false;
+                if (!riders.empty()) {
+                    Stage both;
+                    both.exec.reset(new Exec());
+                    std::vector<std::pair<int, ewf_dtype>> all = targets;
+                    for (int k : riders) all.push_back({g.outputs[k].value, g.outputs[k].storage});
+                    build_stage(g, all, true, cuts, *both.exec, both.in_src);
+                    both.out_dst = sg.out_dst;
+                    for (int k : riders) both.out_dst.push_back(k);
+                    if (try_stage(both) == EWF_OK) {
+                        for (int k : riders) written[k] = 1;
+                        sg = std::move(both);
+                        done = true;
+                    }
+                }
+                if (!done) {
+                    const ewf_status s3 = try_stage(sg);
+                    if (s3 != EWF_OK) { plan.temps.resize(ntemps); ws = ws0; return s3; }
+                }
+                for (int k : gouts) written[k] = 1;
+                for (size_t i = 0; i < hand.size(); i++) cuts[hand[i]] = (int)plan.temps.size() - (int)hand.size() + (int)i;
+                plan.stages.push_back(std::move(sg));
+                return EWF_OK;
+            };
+            st = attempt(handed, !e.opts.no_rewrite);
+            if (st != EWF_OK && !e.opts.no_rewrite) st = attempt(gr.second, false);
+            if (st != EWF_OK) return st;
         }
         if (round == 15) { set_error("too many reduction levels"); return EWF_EUNSUPPORTED; }
     }

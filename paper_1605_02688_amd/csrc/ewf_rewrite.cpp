@@ -315,6 +315,31 @@ int rewrite_graph(Graph &g)
                 if (a0 == a1) r = make_apply(EWF_SQR, a0, -1, orig);                    // x * x
                 else if (is_const(out, a1, 1.0)) keep_as(a0);
                 else if (is_const(out, a0, 1.0)) keep_as(a1);
+                else if (f32) {
+                    // (k * y) * z with k a power of two: k * (y * z), bit for bit the same (scaling by
+                    // a power of two rounds nothing), and y * z is often a square or exists already;
+                    // the factor then sits next to what consumes the product (exp(k * s) is one
+                    // multiplication by k * log2 e and the hardware exp2)
+                    for (int side = 0; side < 2 && r < 0; side++) {
+                        const Node &m = out.nodes[nd.args[side]];
+                        const int z = nd.args[1 - side];
+                        if (m.kind != NodeKind::Apply || m.op != EWF_MUL || m.vtype != EWF_F32) continue;
+                        for (int ks = 0; ks < 2 && r < 0; ks++) {
+                            const Node &k = out.nodes[m.args[ks]];
+                            if (k.kind != NodeKind::Const || k.vtype != EWF_F32) continue;
+                            int ex = 0;
+                            const float kv = (float)k.cval;
+                            if (!(std::fabs(kv) >= 0x1p-20f && std::fabs(kv) <= 0x1p20f) || std::frexp(std::fabs(kv), &ex) != 0.5f) continue;
+                            const int y = m.args[1 - ks];
+                            Node like = orig;               // y * z varies wherever y or z does: the pattern of the whole product
+                            like.bcast = out.nodes[y].bcast & out.nodes[z].bcast;
+                            like.dropped = (out.nodes[y].dropped | out.nodes[z].dropped) & like.bcast;
+                            if (like.bcast != orig.bcast || like.dropped != orig.dropped) continue;
+                            const int inner = y == z ? make_apply(EWF_SQR, y, -1, like) : make_apply(EWF_MUL, y, z, like);
+                            r = make_apply(EWF_MUL, m.args[ks], inner, orig);
+                        }
+                    }
+                }
                 break;
             case EWF_ADD:
                 // x + 0 (the sum of -0 and +0 is +0; the difference cannot be seen through a
