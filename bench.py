@@ -292,7 +292,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="time one workload (c1,c2,c3,c4,c5a,c5b,c2b,c3b,c4b,c3_long) as the headline")
+    ap.add_argument("--only", default="", help="time one workload (c1,c2,c3,c4,c5a,c5b,c2b,c3b,c4b,c3_long,bn) as the headline")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -309,6 +309,7 @@ def main():
     makers = dict(wl.FULL_SIZE)
     makers.update(wl.BACKWARD)
     makers["c3_long"] = lambda: wl.c3_softmax_xent(rows=512, vocab=131072)      # rows split over workgroups
+    makers["bn"] = wl.batch_norm_axis0                                          # a plan in two stages
     hw = makers[head_name]()
     # small workloads rotate through enough buffer sets to exceed the on-chip cache
     head_sets = max(1, min(300, int(600e6 // max(1, hw.algorithmic_bytes)) + 1)) if hw.algorithmic_bytes < 300e6 else 1
@@ -396,7 +397,8 @@ def main():
         # workloads (whose C1 / C2 sizes are launch-bound)
         scaled = {}
         for name, make in (("c1_x64", lambda: wl.c1_affine_tanh(rows=65536)), ("c2_x64", lambda: wl.c2_lstm_cell(batch=4096)),
-                           ("c3_512x131072", lambda: wl.c3_softmax_xent(rows=512, vocab=131072))):
+                           ("c3_512x131072", lambda: wl.c3_softmax_xent(rows=512, vocab=131072)),
+                           ("batch_norm_65536x1024", wl.batch_norm_axis0)):
             wk = make()
             nsets = max(1, int(600e6 // wk.algorithmic_bytes) + 1)
             case = Case(wk, nsets=nsets)

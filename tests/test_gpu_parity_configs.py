@@ -38,6 +38,9 @@ CASES = {
     "c3b_ragged": lambda: wl.c3_softmax_xent_backward(rows=37, vocab=1003),
     "c4b_small": lambda: wl.c4_bias_relu_chansum_backward(n=4, c=64, h=112, w=112),
     "c4b_ragged": lambda: wl.c4_bias_relu_chansum_backward(n=3, c=5, h=13, w=17),
+    # a plan in stages: statistics over the outer axis in one sweep, the normalised tensor in a second
+    "bn_ragged": lambda: wl.batch_norm_axis0(rows=1237, cols=77),
+    "bn_f16": lambda: wl.batch_norm_axis0(rows=5000, cols=264, storage="f16"),
 }
 
 
@@ -58,6 +61,7 @@ FULL = {
     "c5b_full": lambda: wl.c5_stress(reading="B"),
     "c3b_full": lambda: wl.c3_softmax_xent_backward(),
     "c4b_full": lambda: wl.c4_bias_relu_chansum_backward(),
+    "bn_full": lambda: wl.batch_norm_axis0(),
 }
 
 
@@ -83,7 +87,7 @@ OPTION_SETS = [
     {"split_rows": 1}, {"split_rows": 2},
 ]
 OPTION_CASES = ["c1_ragged", "c2_ragged", "c3_ragged", "c4_ragged", "c4_small", "c5a_small", "c5b_ragged_c", "c2b_ragged",
-                "c3b_ragged", "c4b_ragged"]
+                "c3b_ragged", "c4b_ragged", "bn_ragged"]
 
 
 @pytest.mark.parametrize("case", OPTION_CASES)

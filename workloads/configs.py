@@ -403,6 +403,35 @@ def c4_bias_relu_chansum_backward(n: int = 128, c: int = 64, h: int = 112, w: in
                     _nbytes(bufs) + ne * 4 + 2 * c * 4, oracle_spec=r)
 
 
+# --------------------------------------------------------------------------- a plan in stages
+#
+# Batch normalisation of a matrix over its rows (the paper's convnets normalise activations this
+# way; section 2.2.1 states what fusion is for: not to loop over a tensor several times).  The
+# statistics are reductions over the outer axis and the normalised tensor needs them at every
+# element, so no single kernel covers it: the evaluator has to split it into passes.
+
+def batch_norm_axis0(rows: int = 65536, cols: int = 1024, storage: str = "f32") -> Workload:
+    """mean and (biased) variance over axis 0 and the normalised tensor, float32 [rows, cols] N(0.5, 2)."""
+    g = _gen(SEED0 + 21)
+    X = _normal(g, (rows, cols), 2.0)
+    if _DATA:
+        X = (X + np.float32(0.5)).astype(np.float16 if storage == "f16" else np.float32)
+    elif storage == "f16":
+        X = Placeholder((rows, cols), np.float16)
+    s = GraphSpec(2)
+    x = s.input(storage, (False, False))
+    inv_n = s.const(1.0 / rows)
+    mean = s.mul(s.reduce("sum", x, (0,), keep=True), inv_n)
+    cen = s.sub(x, mean)
+    var = s.mul(s.reduce("sum", s.mul(cen, cen), (0,), keep=True), inv_n)
+    s.output(s.mul(cen, s.apply("recip", s.apply("sqrt", s.add(var, s.const(1e-5))))), storage)
+    s.output(mean, "f32"); s.output(var, "f32")
+    n = rows * cols
+    return Workload(f"batch_norm_axis0_{storage}", s, [X], [_full_view(0, (rows, cols))], [], ["normalised", "mean", "var"],
+                    [TOL_F32_REDUCE if storage == "f32" else TOL_F16, TOL_F32_REDUCE, TOL_F32_REDUCE], n,
+                    2 * X.nbytes + 2 * cols * 4)
+
+
 BACKWARD = {"c2b": c2_lstm_cell_backward, "c3b": c3_softmax_xent_backward, "c4b": c4_bias_relu_chansum_backward}
 
 FULL_SIZE = {
