@@ -138,7 +138,7 @@ class Case:
         return [a.elapsed_time(b) for a, b in ev]
 
 
-def copy_ceiling(nbytes, steps, warmup):
+def copy_ceiling(nbytes, steps, warmup, identity=True):
     """What plain streaming reaches on this chip, in the same run and measured the same way as
     the headline: (a) an identity expression through the library's own element-wise kernel class
     on a float32 tensor of `nbytes` (a generated copy: same tiling, same non-temporal accesses),
@@ -150,6 +150,25 @@ def copy_ceiling(nbytes, steps, warmup):
     n = nbytes // 4
     src = torch.empty(n, dtype=torch.float32, device="cuda").fill_(1.0)
     dst = torch.empty_like(src)
+    st = torch.cuda.current_stream().cuda_stream
+    res = {}
+    if identity:
+        res["identity_expression_gbps"] = round(_identity_rate(src, dst, n, steps, warmup), 1)
+    for _ in range(3):
+        ewf.copy_bytes(dst.data_ptr(), src.data_ptr(), n * 4, st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ewf.copy_bytes(dst.data_ptr(), src.data_ptr(), n * 4, st)
+    torch.cuda.synchronize()
+    res["copy_kernel_gbps"] = round(2 * n * 4 * steps / (time.perf_counter() - t0) / 1e9, 1)
+    return res
+
+
+def _identity_rate(src, dst, n, steps, warmup):
+    import torch
+    from paper_1605_02688_amd import ewf
+    from workloads import GraphSpec
     st = torch.cuda.current_stream().cuda_stream
     s = GraphSpec(1)
     s.output(s.input("f32", (False,)), "f32")
@@ -164,15 +183,7 @@ def copy_ceiling(nbytes, steps, warmup):
     torch.cuda.synchronize()
     ident = 2 * n * 4 * steps / (time.perf_counter() - t0) / 1e9
     assert bool(torch.equal(src, dst))
-    for _ in range(3):
-        ewf.copy_bytes(dst.data_ptr(), src.data_ptr(), n * 4, st)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        ewf.copy_bytes(dst.data_ptr(), src.data_ptr(), n * 4, st)
-    torch.cuda.synchronize()
-    plain = 2 * n * 4 * steps / (time.perf_counter() - t0) / 1e9
-    return {"identity_expression_gbps": round(ident, 1), "copy_kernel_gbps": round(plain, 1)}
+    return ident
 
 
 def torch_elementwise_rate(nbytes, steps=20):
@@ -292,6 +303,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--profile", action="store_true",
+                    help="for runs under a profiler: skip the identity expression of the copy ceiling (its generated kernel has the "
+                         "same name as the workload's) and PyTorch's own kernel")
     ap.add_argument("--only", default="", help="time one workload (c1,c2,c3,c4,c5a,c5b,c2b,c3b,c4b,c3_long,bn) as the headline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -343,12 +357,13 @@ def main():
                      "kernel_avg_us": round(st["avg_us"], 2), "kernel_median_us": round(st["median_us"], 2),
                      "kernel_min_us": round(st["min_us"], 2)},
     }
-    cc = copy_ceiling(w.algorithmic_bytes // 2 // 16 * 16, min(args.steps, 50), args.warmup)
+    cc = copy_ceiling(w.algorithmic_bytes // 2 // 16 * 16, min(args.steps, 50), args.warmup, identity=not args.profile)
     out["copy_ceiling_gbps"] = max(cc.values())
     out["copy_ceiling"] = cc
     out["pct_of_copy_ceiling"] = round(100 * gbps / out["copy_ceiling_gbps"], 1)
     # context only: PyTorch's element-wise y = x + 1 on tensors of the same size (same read/write mix)
-    out["torch_elementwise_gbps"] = round(torch_elementwise_rate(w.algorithmic_bytes // 2 // 16 * 16), 1)
+    if not args.profile:
+        out["torch_elementwise_gbps"] = round(torch_elementwise_rate(w.algorithmic_bytes // 2 // 16 * 16), 1)
     fl = launch_floor()
     out["launch_floor_us"] = {"avg": round(fl["avg_us"], 2), "min": round(fl["min_us"], 2)}
     del head
