@@ -120,6 +120,8 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // along the operand's fastest dimension with wide accesses, scatters it into an LDS copy
     // of the tile laid out in the output's order, and the compute phase reads it back with
     // one wide LDS access per vector.  The tile is shaped so that both sides see long runs.
+    int64_t stage_patch_a = 0;                         // pieces per index of the patch dimension (0: plain memory order)
+    std::vector<int> stage_order;                      // digits of a staged piece's number, fastest first
     std::vector<int> staged;                           // operand numbers
     std::vector<int> sdims;                            // dims ordered by the staged operand's stride
     int VS = 1;
@@ -201,7 +203,15 @@ ewf_status Gen::gen_tile(bool with_reduce)
         // 512 threads 93-94 us, 1024 threads 101-108 us)
         int64_t te = 1;
         for (int d = 0; d < R; d++) te *= T[d];
-        if (te * isz(c.ops[staged[0]].storage) > 40 * 1024) block = 768;
+        if (te * isz(c.ops[staged[0]].storage) > 40 * 1024) {
+            block = 768;
+            // ... unless that leaves a nearly empty last trip: eight wavefronts have the registers
+            // to take such a trip's items along with the trip before (below), twelve have not
+            // (NCHW reading of the stress workload, 49 wavefronts of items per tile: 768 threads
+            // 91.7-93.0 us, 512 threads with the two last trips in one 89.7-90.0 us)
+            auto last_fill = [&](int64_t b) { const int64_t s_ = b * VEC * U, n_ = ceil_div(te, s_); return (double)(te - (n_ - 1) * s_) / (double)s_; };
+            if (e.opts.no_prefetch != 1 && last_fill(768) <= 0.25 && last_fill(512) <= 0.25) block = 512;
+        }
     }
     p.block = block;
 
@@ -216,6 +226,33 @@ ewf_status Gen::gen_tile(bool with_reduce)
         const int szS = isz(c.ops[staged[0]].storage);
         std::vector<int> st;
         for (int d : sdims) if (T[d] > 1) st.push_back(d);
+        // Which 16-byte piece of the staged tile a lane loads.  Taken in the operand's memory
+        // order, the 64 lanes of a wavefront may differ only along dimensions that are slow in the
+        // LDS copy, and their scattered writes then fall into a few banks whatever the padding
+        // (every lane writes the same position of the copy's fastest dimension: 82 % of the LDS's
+        // active cycles were bank conflicts on the float16 stress workload's NHWC reading).  So
+        // a wavefront takes an 8 x 8 patch: eight neighbouring pieces in memory order (128
+        // contiguous bytes where a run of the operand's fastest dimension holds eight) at each of
+        // eight neighbouring indices of the copy's fastest dimension.  The pieces are numbered
+        // with that dimension as the slowest digit to get there.
+        {
+            const int pd = R - 1;
+            auto at = std::find(st.begin(), st.end(), pd);
+            int64_t A = 1;
+            for (int d : st) if (d != pd) A *= T[d];
+            A /= VS;
+            if (at != st.end() && pd != s0 && st.size() >= 2 && A % 8 == 0 && T[pd] % 8 == 0) {
+                st.erase(at);
+                st.push_back(pd);
+                stage_patch_a = A;
+            }
+            stage_order = st;
+        }
+        auto piece_of = [&](int64_t q) {
+            if (!stage_patch_a) return q;
+            const int64_t b = q / 64, l = q % 64, na = stage_patch_a / 8;
+            return (b % na) * 8 + (l & 7) + stage_patch_a * ((b / na) * 8 + (l >> 3));
+        };
         auto conflicts = [&](int64_t pad) {
             // passes one scattered write of a wavefront needs: the LDS has 32 banks of 4 bytes
             // and takes the 64 lanes as two halves; a half needs as many passes as the largest
@@ -224,7 +261,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
             for (int half = 0; half < 2; half++) {
                 std::map<int64_t, std::vector<int64_t>> bank;
                 for (int lane = half * 32; lane < half * 32 + 32; lane++) {
-                    int64_t j = (int64_t)lane * VS, addr = 0;
+                    int64_t j = piece_of(lane) * VS, addr = 0;
                     for (size_t i = 0; i < st.size(); i++) {
                         int d = st[i];
                         int64_t cd = (i + 1 < st.size()) ? j % T[d] : j; j /= T[d];
@@ -299,13 +336,23 @@ ewf_status Gen::gen_tile(bool with_reduce)
     for (int k : used_inputs) load_ops.push_back(k);
 
     // what one trip of a thread holds in registers between its loads and its arithmetic
-    o << "struct Item {\n    bool ok[" << U << "];\n    int L[" << U << "];\n";
-    if (ragged) o << "    int nv[" << U << "];\n";              // elements of the vector that lie inside the row
-    for (int d : tiled) o << "    int c" << d << "[" << U << "];\n";
+    // When the tile's last trip would be nearly empty (a few wavefronts with work, the others
+    // waiting at the barrier for a whole round of memory latency), its items ride with the trip
+    // before: those wavefronts issue both trips' loads together.
+    const int64_t ntrips = ceil_div(TE, step);
+    const bool prefetch = TE > step && !(e.opts.no_prefetch == 1 || (heavy >= 4 && e.opts.no_prefetch == 0));
+    const bool fused_tail = !staged.empty() && !prefetch && e.opts.no_prefetch != 1 && U == 1 && block <= 512 && ntrips >= 2 && (TE - (ntrips - 1) * step) * 4 <= step;
+    const int UI = fused_tail ? 2 : U;                 // items a thread may hold at once
+    // (two items in flight take about a hundred registers: room for four wavefronts per SIMD, and
+    // the register allocator is told so that it does not spill to keep more resident)
+    if (fused_tail) auto_waves_per_simd = 4;
+    o << "struct Item {\n    bool ok[" << UI << "];\n    int L[" << UI << "];\n";
+    if (ragged) o << "    int nv[" << UI << "];\n";              // elements of the vector that lie inside the row
+    for (int d : tiled) o << "    int c" << d << "[" << UI << "];\n";
     for (int k : load_ops) {
         const Operand &op = c.ops[k];
-        if (op.access == Access::Splat && !is_staged(k)) o << "    " << ctype(op.storage) << " x_" << opname(k) << "[" << U << "];\n";
-        else o << "    ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << U << "];\n";
+        if (op.access == Access::Splat && !is_staged(k)) o << "    " << ctype(op.storage) << " x_" << opname(k) << "[" << UI << "];\n";
+        else o << "    ewf_vec<" << ctype(op.storage) << ", EWF_VEC> x_" << opname(k) << "[" << UI << "];\n";
     }
     o << "};\n";
 
@@ -362,11 +409,17 @@ ewf_status Gen::gen_tile(bool with_reduce)
     if (!staged.empty()) {
         const int s0 = sdims[0];
         o << ind << "for (int J0 = 0; J0 < " << TE << "; J0 += " << (int64_t)block * VS << ") {\n";
-        o << ind << "    int j_ = J0 + tid * " << VS << ";\n";
+        if (stage_patch_a) {
+            o << ind << "    int j_;\n";
+            o << ind << "    { const int q_ = J0 / " << VS << " + tid, b_ = q_ >> 6, l_ = q_ & 63;    // an 8 x 8 patch of pieces per wavefront\n";
+            o << ind << "      j_ = ((b_ % " << stage_patch_a / 8 << ") * 8 + (l_ & 7) + " << stage_patch_a << " * ((b_ / " << stage_patch_a / 8
+              << ") * 8 + (l_ >> 3))) * " << VS << "; }\n";
+        } else {
+            o << ind << "    int j_ = J0 + tid * " << VS << ";\n";
+        }
         o << ind << "    bool k_ = j_ < " << TE << ";\n";
         o << ind << "    int lm_ = 0; ioff_t g_ = 0;\n";
-        std::vector<int> st;                           // staged-order dims with T > 1
-        for (int d : sdims) if (T[d] > 1) st.push_back(d);
+        const std::vector<int> &st = stage_order;      // the staged operand's dims with T > 1, fastest digit first
         for (size_t i = 0; i < st.size(); i++) {
             int d = st[i];
             o << ind << "    { const int c_ = " << (i + 1 < st.size() ? "j_ % " + std::to_string(T[d]) + "; j_ /= " + std::to_string(T[d]) : std::string("j_")) << ";\n";
@@ -541,7 +594,6 @@ ewf_status Gen::gen_tile(bool with_reduce)
         }
     });
 
-    const bool prefetch = looped && !(e.opts.no_prefetch == 1 || (heavy >= 4 && e.opts.no_prefetch == 0));
     if (prefetch) {
         o << ind << "auto load_item = [&](const int L0, Item &it) {\n";
         o << ind2 << "#pragma unroll\n" << ind2 << "for (int u = 0; u < " << U << "; ++u) {\n";
@@ -576,7 +628,22 @@ ewf_status Gen::gen_tile(bool with_reduce)
         o << text_b << text_c;
         o << ind2 << "}\n";
         o << ind << "};\n";
-        if (!looped) o << ind << "run_item(0);\n";
+        if (fused_tail) {
+            o << ind << "auto run_last_two = [&](const int L0) {\n";
+            o << ind2 << "Item it;\n";
+            o << ind2 << "#pragma unroll\n" << ind2 << "for (int u = 0; u < 2; ++u) {\n";
+            o << text_a;
+            o << ind2 << "    it.ok[u] = k_;\n";
+            o << ind2 << "    if (k_) {\n" << text_b << ind2 << "    }\n" << ind2 << "}\n";
+            o << ind2 << "#pragma unroll\n" << ind2 << "for (int u = 0; u < 2; ++u) {\n";
+            o << ind2 << "    if (!it.ok[u]) continue;\n";
+            o << text_c;
+            o << ind2 << "}\n";
+            o << ind << "};\n";
+            if (ntrips > 2) o << ind << "for (int L0 = 0; L0 < " << (ntrips - 2) * step << "; L0 += " << step << ") run_item(L0);\n";
+            o << ind << "run_last_two(" << (ntrips - 2) * step << ");\n";
+        }
+        else if (!looped) o << ind << "run_item(0);\n";
         else o << ind << "for (int L0 = 0; L0 < " << TE << "; L0 += " << step << ") run_item(L0);\n";
     }
     if (!staged.empty()) o << ind << "__syncthreads();\n";
