@@ -218,6 +218,7 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
     ewf_status st;
     const Canon &c = plan->canon;
     bool row_only = false;                     // only the row class covers the expression
+    bool cross_only = false;                   // ... and only because of reductions over the rows
     if (!plan->red.has_reduce) {
         plan->kclass = KernelClass::Tile;
     } else {
@@ -261,6 +262,7 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
             }
             plan->kclass = KernelClass::Row;
             row_only = true;
+            cross_only = plan->red.max_depth <= 1 && !full_dep_out && rows <= 8192;
         } else if (inner_only && rows >= 512 && c.extent[c.rank - 1] <= 65536) {
             plan->kclass = KernelClass::Row;
         } else {
@@ -332,11 +334,14 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
         }
     }
     if (plan->kclass != KernelClass::Lane) st = generate(e, *plan);
-    if (st == EWF_EUNSUPPORTED && plan->row_refused && plan->kclass == KernelClass::Row && !row_only) {
-        // plain row reductions do not need the row class
-        plan->row_refused = false;
+    if (st == EWF_EUNSUPPORTED && plan->row_refused && plan->kclass == KernelClass::Row && (!row_only || cross_only)) {
+        // plain row reductions do not need the row class, nor does a single level of them followed
+        // by reductions over the rows (those are folded by the finish kernel)
+        const std::string why = get_error();
         plan->kclass = KernelClass::TileReduce;
         st = generate(e, *plan);
+        if (st == EWF_OK) plan->row_refused = false;
+        else if (row_only) { plan->kclass = KernelClass::Row; set_error_str(why); }
     }
     if (st != EWF_OK) return st;
     bool cached = false;

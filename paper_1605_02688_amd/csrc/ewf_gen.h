@@ -64,6 +64,9 @@ struct Gen {
     // the worst case (exp: at most 6e-8 * (1 + |x| log2 e) relative, under 6e-6 wherever the
     // result is finite), so under the automatic math mode these nodes use that flavour.
     std::vector<char> sum_only;
+    // Values that feed a product, an extreme value or an arg-max (see the constructor): these keep
+    // the accurate routines throughout.
+    std::vector<char> strict;
 
     // A small sign analysis over the scalar graph, in the spirit of the specialisation stage
     // of paper section 2.2.1: when the base of a power is provably positive (x*x + 1, exp(u),
@@ -137,16 +140,17 @@ struct Gen {
         for (const OutputDecl &od : g.outputs) if (!below_reduce[od.value]) direct[od.value] = 1;
         // (what a product, maximum, minimum or arg-max folds stays accurate: a product compounds
         // the error of its factors, and an extreme value or its index can flip on a rounding)
+        strict.assign(N, 0);
         for (int n = 0; n < N; n++) {
             const Node &nd = g.nodes[n];
             if (live[n] && nd.kind == NodeKind::Reduce && real_reduce(n) && !(nd.op == EWF_RSUM && nd.vtype == EWF_F32) &&
-                nd.op != kRSumExpShifted) direct[nd.args[0]] = 1;
+                nd.op != kRSumExpShifted) direct[nd.args[0]] = strict[nd.args[0]] = 1;
         }
         for (int n = N - 1; n >= 0; n--) {
             if (!direct[n]) continue;
             const Node &nd = g.nodes[n];
             if (nd.kind == NodeKind::Reduce && nd.op == EWF_RSUM && nd.vtype == EWF_F32 && real_reduce(n)) continue;
-            for (int a = 0; a < nd.nargs; a++) direct[nd.args[a]] = 1;
+            for (int a = 0; a < nd.nargs; a++) { direct[nd.args[a]] = 1; if (strict[n]) strict[nd.args[a]] = 1; }
         }
         sum_only.assign(N, 0);
         for (int n = 0; n < N; n++) sum_only[n] = live[n] && !direct[n];
@@ -191,7 +195,12 @@ struct Gen {
         for (size_t n = 0; n < need.size(); n++) {
             if (!need[n]) continue;
             const Node &nd = g.nodes[n];
-            const int fl = (e.auto_math && e.math_flavour == 1 && sum_only[n]) ? 2 : e.math_flavour;
+            // Under the automatic math mode the sigmoid and the hyperbolic tangent of a float32
+            // result take the native-rate routines too: both are bounded, their relative error
+            // stays under 1.5e-6 (the exponential's argument is never large where its value
+            // matters) and their absolute error under 1.2e-7, inside the element-wise bar.
+            const bool bounded = nd.kind == NodeKind::Apply && (nd.op == EWF_TANH || nd.op == EWF_SIGMOID) && !strict[n];
+            const int fl = (e.auto_math && e.math_flavour == 1 && (sum_only[n] || bounded)) ? 2 : e.math_flavour;
             const char *M = fl == 3 ? "ewf_bare" : fl == 2 ? "ewf_fast" : "ewf_acc";
             std::string a0 = nd.nargs > 0 ? "v" + std::to_string(nd.args[0]) : "";
             std::string a1 = nd.nargs > 1 ? "v" + std::to_string(nd.args[1]) : "";
@@ -407,12 +416,14 @@ struct Gen {
     // in increasing order: a later element then replaces the running maximum only when it is
     // strictly greater (or the first NaN), and the index comparison falls away.  The
     // identity index (no element taken yet) must then be resolved by emit_first_index.
+    // `only` (one flag per position of `nodes`, or null for all) restricts it to some slots.
     void emit_accumulate(const std::string &acc, const std::vector<int> &nodes,
                          const std::function<std::string(int)> &argmax_index, const std::string &ind,
-                         bool ascending = false)
+                         bool ascending = false, const std::vector<char> *only = nullptr)
     {
         for (size_t i = 0; i < nodes.size(); i++) {
             if (shared_slot(nodes, i) >= 0) continue;
+            if (only && !(*only)[i]) continue;
             const Node &nd = g.nodes[nodes[i]];
             const bool isint = g.nodes[nd.args[0]].vtype == EWF_I32;
             std::string a = acc + ".a" + std::to_string(i), v = "v" + std::to_string(nd.args[0]);
@@ -461,6 +472,77 @@ struct Gen {
             }
             }
         }
+    }
+
+    // Slots that can take a whole vector of elements at once (float32 arguments): the running
+    // maximum of a sum of shifted exponentials, of a maximum and -- met in ascending order -- of an
+    // arg-max.  Returns one flag per position of `nodes`.
+    std::vector<char> vector_slots(const std::vector<int> &nodes, bool ascending) const
+    {
+        std::vector<char> f(nodes.size(), 0);
+        for (size_t i = 0; i < nodes.size(); i++) {
+            if (shared_slot(nodes, i) >= 0) continue;
+            const Node &nd = g.nodes[nodes[i]];
+            if (g.nodes[nd.args[0]].vtype != EWF_F32) continue;
+            f[i] = nd.op == kRSumExpShifted || nd.op == EWF_RMAX || (nd.op == EWF_RARGMAX && ascending);
+        }
+        return f;
+    }
+
+    // Folds the VEC values xs[0..VEC) of argument `arg` into the slots flagged in `slots` that
+    // take this argument.  When all of them are finite (and no slot holds a NaN) a vector costs
+    // one hardware maximum per element, and per slot: for a maximum or arg-max a comparison (the
+    // index is looked up only when the maximum moves, which becomes rare quickly); for a sum of
+    // shifted exponentials one rescaling of the sum and one exponential per element, all against
+    // the same new maximum.  Anything else -- a NaN or an infinity among the values, a NaN held,
+    // a vector cut short by the row's end (`full` false) -- goes element by element through
+    // emit_accumulate, whose rules for those cases the fast path never has to reproduce.
+    void emit_vector_accumulate(const std::string &acc, const std::vector<int> &nodes, const std::vector<char> &slots, int arg,
+                                const std::string &xs, const std::string &full, const std::string &skip_element,
+                                const std::function<std::string(int)> &argmax_index, const std::string &ind)
+    {
+        std::vector<char> mine(nodes.size(), 0);
+        bool any = false;
+        for (size_t i = 0; i < nodes.size(); i++) if (slots[i] && g.nodes[nodes[i]].args[0] == arg) { mine[i] = 1; any = true; }
+        if (!any) return;
+        o << ind << "{ float t_ = 0.0f;\n";
+        o << ind << "  _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) t_ = __builtin_fmaf(" << xs << "[e_], 0.0f, t_);     // NaN iff a value is NaN or infinite\n";
+        o << ind << "  bool fast_ = (t_ == 0.0f)";
+        if (!full.empty()) o << " & (" << full << ")";
+        for (size_t i = 0; i < nodes.size(); i++) if (mine[i]) o << " & (" << acc << ".a" << i << " == " << acc << ".a" << i << ")";
+        o << ";\n";
+        o << ind << "  if (fast_) {\n";
+        o << ind << "      float vm_ = " << xs << "[0];\n";
+        o << ind << "      _Pragma(\"unroll\") for (int e_ = 1; e_ < EWF_VEC; ++e_) vm_ = __builtin_fmaxf(vm_, " << xs << "[e_]);\n";
+        for (size_t i = 0; i < nodes.size(); i++) {
+            if (!mine[i]) continue;
+            const Node &nd = g.nodes[nodes[i]];
+            const std::string a = acc + ".a" + std::to_string(i);
+            if (nd.op == EWF_RMAX) {
+                o << ind << "      " << a << " = __builtin_fmaxf(" << a << ", vm_);\n";
+            } else if (nd.op == EWF_RARGMAX) {
+                o << ind << "      if (vm_ > " << a << ") {\n";
+                o << ind << "          int k_ = 0;\n";
+                o << ind << "          _Pragma(\"unroll\") for (int e_ = EWF_VEC - 1; e_ >= 0; --e_) k_ = (" << xs << "[e_] == vm_) ? e_ : k_;\n";
+                o << ind << "          const int e_ = k_;\n";
+                o << ind << "          " << a << " = vm_; " << acc << ".i" << i << " = (int)(" << argmax_index(nodes[i]) << ");\n";
+                o << ind << "      }\n";
+            } else {
+                const std::string b = acc + ".b" + std::to_string(i);
+                o << ind << "      { const float mn_ = __builtin_fmaxf(" << a << ", vm_);\n";
+                o << ind << "        float s_ = " << b << " * " << sum_math() << "::exp(" << a << " - mn_);\n";
+                o << ind << "        _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) s_ += " << sum_math() << "::exp(" << xs << "[e_] - mn_);\n";
+                o << ind << "        " << b << " = s_; " << a << " = mn_; }\n";
+            }
+        }
+        o << ind << "  } else {\n";
+        o << ind << "      _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
+        if (!skip_element.empty()) o << ind << "          if (" << skip_element << ") continue;\n";
+        o << ind << "          const float v" << arg << " = " << xs << "[e_];\n";
+        emit_accumulate(acc, nodes, argmax_index, ind + "          ", true, &mine);
+        o << ind << "      }\n";
+        o << ind << "  }\n";
+        o << ind << "}\n";
     }
 
     // After an `ascending` accumulation: a thread whose elements all equal the identity value
@@ -594,6 +676,17 @@ struct Gen {
         o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
         o << "    const idx_t nparts = " << nparts_expr << ";\n";
         o << "    for (idx_t group = blockIdx.x; group < p.nrows; group += gridDim.x) {\n";
+        // The single-term sums read an element whose position comes from the inputs alone: those
+        // loads (an index, then the element it names -- two round trips to memory) are issued
+        // before the partials are folded instead of after.
+        bool early = !gathers.empty();
+        {
+            std::vector<int> it;
+            for (const Gather &ga : gathers) it.push_back(ga.index_value);
+            const std::vector<char> ineed = needed(it);
+            for (size_t n = 0; n < ineed.size(); n++) if (ineed[n] && g.nodes[n].kind == NodeKind::Reduce && real_reduce((int)n)) early = false;
+        }
+        if (early) emit_group_epilogue(level, group_out_ops, gathers, "        ", nullptr, nullptr, 1);
         o << "        const Acc *const gpart = partials + (size_t)group * (size_t)nparts;\n";
         o << "        Acc tot = Acc_identity();\n";
         if (inflight <= 1) {
@@ -611,8 +704,91 @@ struct Gen {
         }
         o << "        tot = ewf_block_reduce<" << fin_block / 64 << ">(tot, Acc_combine(), sm_fin, lane);\n";
         o << "        if (lane != 0) continue;\n";
-        emit_group_epilogue(level, group_out_ops, gathers, "        ");
+        emit_group_epilogue(level, group_out_ops, gathers, "        ", nullptr, nullptr, early ? 2 : 0);
         o << "    }\n}\n";
+    }
+
+    // The same fold when reductions over the kept axes follow (a mean over the rows of per-row
+    // values): one workgroup takes all groups, a wavefront per group in turn -- its lanes fold the
+    // group's partials, its first lane evaluates the group's values, stores the per-group outputs
+    // and adds the group's term to the wavefront's running cross-group accumulator -- and at the
+    // end folds the wavefronts' accumulators in a fixed order and writes the final outputs.  One
+    // launch instead of a fold per group followed by a kernel for the second reduction.
+    // With few partials per group (`per_thread`) a thread takes a whole group instead: all groups
+    // are then in flight at once, which matters when there are hundreds of them.
+    int emit_finish_all(const std::vector<int> &level, const std::vector<int> &group_out_ops, const std::vector<int> &final_out_ops,
+                        const std::string &nparts_expr, int64_t ngroups, const std::vector<Gather> &gathers, bool per_thread)
+    {
+        const int waves = (int)std::min<int64_t>(16, std::max<int64_t>(1, per_thread ? (ngroups + 63) / 64 : ngroups));
+        const int fb = waves * 64;
+        o << "\n// folds the partials of every reduction group, then the groups' values, in a fixed order\n";
+        o << "extern \"C\" __global__ void __launch_bounds__(" << fb << ") ewf_finish(const Params p)\n{\n";
+        o << "    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;\n";
+        o << "    (void)lane;\n";
+        o << "    __shared__ AccX sm_accx[" << waves << "];\n";
+        o << "    const Acc *const partials = (const Acc *)p.ws_partials;\n";
+        o << "    const idx_t nparts = " << nparts_expr << ";\n";
+        o << "    AccX totx = AccX_identity();\n";
+        if (per_thread) o << "    for (idx_t group = threadIdx.x; group < p.nrows; group += " << fb << ") {\n";
+        else o << "    for (idx_t group = wave; group < p.nrows; group += " << waves << ") {\n";
+        bool early = !gathers.empty();
+        {
+            std::vector<int> it;
+            for (const Gather &ga : gathers) it.push_back(ga.index_value);
+            const std::vector<char> ineed = needed(it);
+            for (size_t n = 0; n < ineed.size(); n++) if (ineed[n] && g.nodes[n].kind == NodeKind::Reduce && real_reduce((int)n)) early = false;
+        }
+        epilogue_extra_targets.clear();
+        for (int n : red.cross_nodes) epilogue_extra_targets.push_back(g.nodes[n].args[0]);
+        if (early) emit_group_epilogue(level, group_out_ops, gathers, "        ", nullptr, nullptr, 1);
+        if (per_thread) o << "        const Acc *const gpart = partials + (size_t)group;          // partial i of a group at [i][group]\n";
+        else o << "        const Acc *const gpart = partials + (size_t)group * (size_t)nparts;\n";
+        o << "        Acc tot = Acc_identity();\n";
+        if (per_thread) {
+            // eight partials in flight per thread, folded in their order
+            o << "        for (idx_t i0 = 0; i0 < nparts; i0 += 8) {\n";
+            o << "            Acc part_[8];\n";
+            o << "            #pragma unroll\n            for (int u = 0; u < 8; ++u) {\n";
+            o << "                part_[u] = Acc_identity();\n";
+            o << "                if (i0 + u < nparts) part_[u] = gpart[(size_t)(i0 + u) * (size_t)p.nrows];\n";
+            o << "            }\n";
+            o << "            #pragma unroll\n            for (int u = 0; u < 8; ++u) tot = Acc_combine()(tot, part_[u]);\n";
+            o << "        }\n";
+        } else {
+            o << "        for (idx_t i = lane; i < nparts; i += 64) tot = Acc_combine()(tot, gpart[i]);\n";
+            o << "        tot = ewf_wave_reduce(tot, Acc_combine());\n";
+            o << "        if (lane != 0) continue;\n";
+        }
+        emit_group_epilogue(level, group_out_ops, gathers, "        ", nullptr, nullptr, early ? 2 : 0);
+        emit_cross_partial("        ", "totx = AccX_combine()(totx, ax);");
+        epilogue_extra_targets.clear();
+        o << "    }\n";
+        if (per_thread) {
+            o << "    totx = ewf_block_reduce<" << waves << ">(totx, AccX_combine(), sm_accx, (int)threadIdx.x);\n";
+            o << "    if (threadIdx.x == 0) {\n";
+            o << "        const AccX tot = totx;\n";
+        } else {
+            o << "    if (lane == 0) sm_accx[wave] = totx;\n";
+            o << "    __syncthreads();\n";
+            o << "    if (threadIdx.x == 0) {\n";
+            o << "        AccX tot = sm_accx[0];\n";
+            o << "        for (int w = 1; w < " << waves << "; ++w) tot = AccX_combine()(tot, sm_accx[w]);\n";
+        }
+        emit_results("tot", red.cross_nodes, "        ");
+        std::vector<int> tg;
+        for (int k : final_out_ops) tg.push_back(g.outputs[c.ops[k].index].value);
+        std::vector<char> need = needed(tg);
+        EmitCtx fx;
+        fx.input = [&](int k) { return "ewf_in(((const " + std::string(ctype(c.ops[k].storage)) + " *)p." + opname(k) + ")[0])"; };
+        fx.coord = [&](int) { return std::string("0"); };
+        emit_values(need, fx, "        ");
+        for (int k : final_out_ops) {
+            const Operand &op = c.ops[k];
+            const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";
+            o << "        ((" << ctype(op.storage) << " *)p." << opname(k) << ")[0] = " << cv << "(v" << g.outputs[op.index].value << ");\n";
+        }
+        o << "    }\n}\n";
+        return fb;
     }
 
     // What one thread does with the folded accumulator `tot` of reduction group `group`: the
@@ -622,13 +798,18 @@ struct Gen {
     // dimension, read for the kept ones) and spares the divisions; `store`, when given, emits
     // the store of output operand k instead of the plain scalar store.
     typedef std::function<void(int k, const std::string &value, const std::string &ind)> GroupStore;
+    std::vector<char> epilogue_based;          // operands whose base pointer the epilogue has declared
+    std::vector<int> epilogue_extra_targets;   // values the epilogue computes besides the group outputs
     void emit_group_epilogue(const std::vector<int> &level, const std::vector<int> &group_out_ops,
                              const std::vector<Gather> &gathers, const std::string &ind,
-                             const std::vector<std::string> *coords = nullptr, const GroupStore *store = nullptr)
+                             const std::vector<std::string> *coords = nullptr, const GroupStore *store = nullptr, int part = 0)
     {
+        // part 1: the group's coordinates and the single-term sums only (nothing that needs `tot`);
+        // part 2: the rest, in a scope that part 1 was emitted into; 0: both
         std::vector<int> all_dims;
         for (int d = 0; d < R; d++) all_dims.push_back(d);
-        if (coords) {
+        if (part == 2) {}
+        else if (coords) {
             for (int d = 0; d < R; d++)
                 o << ind << "const idx_t o" << d << " = " << (c.reduced[d] ? std::string("0") : (*coords)[d]) << ";\n";
         }
@@ -643,15 +824,17 @@ struct Gen {
             }
             o << ind << "(void)g_;\n";
         }
-        for (int d = 0; d < R; d++) o << ind << "(void)o" << d << ";\n";
-        emit_results("tot", level, ind);
+        if (part != 2) for (int d = 0; d < R; d++) o << ind << "(void)o" << d << ";\n";
+        if (part != 1) emit_results("tot", level, ind);
         std::vector<int> gt;
         for (int k : group_out_ops) gt.push_back(g.outputs[c.ops[k].index].value);
+        for (int n : epilogue_extra_targets) gt.push_back(n);
         std::vector<char> gneed = needed(gt);
         EmitCtx gx;
         gx.input = [&](int k) { return "ewf_in(q_" + opname(k) + "[0])"; };
         gx.coord = [&](int d) { return "o" + std::to_string(d); };
-        std::vector<char> based(c.ops.size(), 0);
+        if (part != 2) epilogue_based.assign(c.ops.size(), 0);
+        std::vector<char> &based = epilogue_based;
         auto base_once = [&](int k) {
             if (based[k]) return;
             based[k] = 1;
@@ -661,10 +844,13 @@ struct Gen {
             std::vector<int> it;
             for (const Gather &ga : gathers) it.push_back(ga.index_value);
             std::vector<char> ineed = needed(it);
-            for (int k : inputs_of(ineed)) base_once(k);
-            emit_values(ineed, gx, ind);
+            if (part != 2) {
+                for (int k : inputs_of(ineed)) base_once(k);
+                emit_values(ineed, gx, ind);
+            }
             for (size_t n = 0; n < ineed.size(); n++) if (ineed[n]) gneed[n] = 0;
             for (const Gather &ga : gathers) {
+                if (part == 2) break;
                 base_once(ga.input);
                 const std::string nm = opname(ga.input);
                 o << ind << "float r" << ga.node << ";\n" << ind << "{\n";
@@ -674,6 +860,7 @@ struct Gen {
                 o << ind << "    r" << ga.node << " = in_ ? x_ + 0.0f : 0.0f;\n" << ind << "}\n";
             }
         }
+        if (part == 1) return;
         for (int k : inputs_of(gneed)) base_once(k);
         emit_values(gneed, gx, ind);
         for (int k : group_out_ops) {
@@ -689,7 +876,7 @@ struct Gen {
 
     // One row's contribution to the cross-row reductions (the value of their arguments for this
     // row, already emitted as v<n>) goes to partials[row].
-    void emit_cross_partial(const std::string &ind)
+    void emit_cross_partial(const std::string &ind, const std::string &sink = "partials[row] = ax;")
     {
         o << ind << "AccX ax = AccX_identity();\n";
         for (size_t i = 0; i < red.cross_nodes.size(); i++) {
@@ -703,7 +890,7 @@ struct Gen {
                 o << ind << "ax.i" << i << " = (int)(" << (cd < 0 ? std::string("0") : "o" + std::to_string(cd)) << ");\n";
             }
         }
-        o << ind << "partials[row] = ax;\n";
+        o << ind << sink << "\n";
     }
 
     // The per-row values are folded by a second, single-workgroup kernel: ordered by the kernel

@@ -41,11 +41,16 @@ ewf_status Gen::gen_tile(bool with_reduce)
     if (block % 64 || block > 1024) return fail("block_threads must be a multiple of 64, at most 1024");
 
     // ---- outputs by role
-    std::vector<int> ew_out_ops, group_out_ops;        // operand numbers
+    std::vector<int> ew_out_ops, group_out_ops, final_out_ops;        // operand numbers
     const int nin = g.ninputs;
+    // reductions over the kept axes of per-group values (the mean of per-row losses): folded by
+    // the finish kernel, a single workgroup then
+    const bool has_cross = with_reduce && !red.cross_nodes.empty();
+    if (has_cross && red.max_depth > 1) return fail("chained reductions along the rows need the row-resident class");
     for (size_t k = nin; k < c.ops.size(); k++) {
         const Node &v = g.nodes[g.outputs[c.ops[k].index].value];
         const int vn = g.outputs[c.ops[k].index].value;
+        if (has_cross && after_cross[vn]) { final_out_ops.push_back((int)k); continue; }
         bool group = with_reduce && ((v.bcast & red.axes) == red.axes);
         if (with_reduce && red.edepth[vn] >= 1 && !group) return fail("an output depends on a reduction and varies along the reduced axes; only the row-resident class covers that");
         (group ? group_out_ops : ew_out_ops).push_back((int)k);
@@ -86,6 +91,17 @@ ewf_status Gen::gen_tile(bool with_reduce)
         int in_sz = 4;
         for (int k = 0; k < nin; k++) in_sz = std::min(in_sz, isz(c.ops[k].storage));
         if (c.total * in_sz >= ((int64_t)1 << 28)) target = std::max<int64_t>(target, 131072 / in_sz);
+    }
+    // Reductions over the groups follow: with few partials per group (at most 32) a thread of the
+    // finish kernel folds a whole group, and hundreds of groups are in flight at once -- as long
+    // as that leaves enough tiles for the chip.
+    if (has_cross) {
+        int64_t per_group = 1, ngroups_ = 1;
+        for (int d = 0; d < R; d++) (c.reduced[d] ? per_group : ngroups_) *= c.extent[d];
+        // (softmax cross-entropy on float32 [512, 131072]: 16 tiles per row 52.2-53.0 us a step,
+        // 8 tiles 48.6-50.1 us, 4 tiles 51.6-52.0 us, 2 tiles 56.8-57.4 us)
+        const int64_t slots = 8;
+        if (ngroups_ * slots >= (int64_t)4 * device_cu_count()) target = std::max(target, ceil_div(per_group, slots));
     }
     if (e.opts.tile_elems > 0) target = e.opts.tile_elems;
     {
@@ -330,6 +346,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     emit_header(block);
     build_layout();
     if (with_reduce) emit_acc_struct("Acc", level);
+    if (has_cross) emit_acc_struct("AccX", red.cross_nodes);
     std::vector<int> all_dims;
     for (int d = 0; d < R; d++) all_dims.push_back(d);
     std::vector<int> load_ops;                         // operand numbers read per element
@@ -363,8 +380,16 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // its wavefronts through LDS and writes the results itself -- one launch, no workspace.
     bool one_tile = with_reduce;
     for (int d = 0; d < R; d++) if (c.reduced[d] && ntile[d] != 1) one_tile = false;
+    if (has_cross) one_tile = false;
+    // With reductions over the groups to follow and few tiles per group, a thread of the finish
+    // kernel takes a whole group: the workgroup then leaves one partial per tile (its wavefronts
+    // folded through LDS), stored with the group as the fastest index so that neighbouring threads
+    // of the finish kernel read neighbouring partials.
+    int64_t nslots_host = 1;
+    for (int d = 0; d < R; d++) if (c.reduced[d]) nslots_host *= ntile[d];
+    const bool cross_per_thread = has_cross && nslots_host <= 32;
     if (with_reduce && !one_tile) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
-    if (one_tile) o << "    __shared__ Acc sm_one[EWF_NWAVES];\n";
+    if (one_tile || cross_per_thread) o << "    __shared__ Acc sm_one[EWF_NWAVES];\n";
     for (int k : staged)
         o << "    __shared__ __attribute__((aligned(16))) " << ctype(c.ops[k].storage) << " lds_" << opname(k) << "[" << lds_elems << "];\n";
     // tiles are numbered in canonical (memory) order so that the workgroups resident at any
@@ -548,6 +573,20 @@ ewf_status Gen::gen_tile(bool with_reduce)
     const std::string text_c = capture([&]() {
         const std::string &ind = ind2;
         for (int k : ew_out_ops) o << ind << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
+        // slots that take a vector of elements at once keep the element loop's values of their
+        // argument and are folded after it
+        std::vector<char> vslots(level.size(), 0), eslots(level.size(), 1);
+        std::vector<int> vargs;
+        if (with_reduce && VEC >= 2 && !e.opts.plain_extremes) {
+            vslots = vector_slots(level, ascending);
+            for (size_t i = 0; i < level.size(); i++) {
+                if (!vslots[i]) continue;
+                eslots[i] = 0;
+                const int a = g.nodes[level[i]].args[0];
+                if (std::find(vargs.begin(), vargs.end(), a) == vargs.end()) vargs.push_back(a);
+            }
+        }
+        for (int a : vargs) o << ind << "    float xs" << a << "_[EWF_VEC]" << (ragged ? " = {}" : "") << ";\n";
         o << ind << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
         EmitCtx cx;
         cx.input = [&](int k) {
@@ -565,7 +604,8 @@ ewf_status Gen::gen_tile(bool with_reduce)
         if (ragged) o << ind << "        if (e_ >= it.nv[u]) continue;\n";
         emit_values(need, cx, ind + "        ");
         if (with_reduce)
-            emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ", ascending);
+            emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ", ascending, &eslots);
+        for (int a : vargs) o << ind << "        xs" << a << "_[e_] = v" << a << ";\n";
         for (int k : ew_out_ops) {
             const Operand &op = c.ops[k];
             int v = g.outputs[op.index].value;
@@ -573,6 +613,9 @@ ewf_status Gen::gen_tile(bool with_reduce)
             o << ind << "        y_" << opname(k) << ".e[e_] = " << cv << "(v" << v << ");\n";
         }
         o << ind << "    }\n";
+        for (int a : vargs)
+            emit_vector_accumulate("acc", level, vslots, a, "xs" + std::to_string(a) + "_", ragged ? "it.nv[u] == EWF_VEC" : "",
+                                   ragged ? "e_ >= it.nv[u]" : "", [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "    ");
         for (int k : ew_out_ops) {
             const Operand &op = c.ops[k];
             std::string nm = opname(k);
@@ -677,6 +720,9 @@ ewf_status Gen::gen_tile(bool with_reduce)
             o << ind << "    const Acc tot = acc;\n";
             emit_group_epilogue(level, group_out_ops, gathers, ind + "    ");
             o << ind << "}\n";
+        } else if (cross_per_thread) {
+            o << ind << "acc = ewf_block_reduce<EWF_NWAVES>(acc, Acc_combine(), sm_one, tid);\n";
+            o << ind << "if (tid == 0) partials[(size_t)slot * (size_t)p.nrows + (size_t)group] = acc;\n";
         } else {
             o << ind << "acc = ewf_wave_reduce(acc, Acc_combine());\n";
             o << ind << "if ((tid & 63) == 0) partials[((size_t)group * (size_t)p.nslots + (size_t)slot) * EWF_NWAVES + (tid >> 6)] = acc;\n";
@@ -693,7 +739,14 @@ ewf_status Gen::gen_tile(bool with_reduce)
         const int fin_block = nparts_host > 4096 ? 1024 : nparts_host > 256 ? 256 : 64;
         fin_block_out = fin_block;
         const int inflight = (int)std::min<int64_t>(8, std::max<int64_t>(1, ceil_div(nparts_host, fin_block)));
-        emit_finish_lanes(level, group_out_ops, "p.nslots * EWF_NWAVES", fin_block, inflight, gathers);
+        if (has_cross) {
+            int64_t ngroups_ = 1;
+            for (int d = 0; d < R; d++) if (!c.reduced[d]) ngroups_ *= c.extent[d];
+            if (ngroups_ > 8192) return fail("too many groups for the single-workgroup fold of a cross-group reduction");
+            fin_block_out = emit_finish_all(level, group_out_ops, final_out_ops, cross_per_thread ? "p.nslots" : "p.nslots * EWF_NWAVES", ngroups_,
+                                            gathers, cross_per_thread);
+        }
+        else emit_finish_lanes(level, group_out_ops, "p.nslots * EWF_NWAVES", fin_block, inflight, gathers);
     }
 
     // ---- launch geometry and argument block
@@ -708,8 +761,8 @@ ewf_status Gen::gen_tile(bool with_reduce)
     p.finish_grid = 0;
     if (with_reduce && !one_tile) {
         if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31)) return fail("too many reduction groups");
-        p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(block / 64) * acc_bytes(level);
-        p.finish_grid = std::min<int64_t>(ngroups, (int64_t)1 << 20);
+        p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(cross_per_thread ? 1 : block / 64) * acc_bytes(level);
+        p.finish_grid = has_cross ? 1 : std::min<int64_t>(ngroups, (int64_t)1 << 20);
         p.finish_block = fin_block_out;
     }
     p.args.assign(p.layout.size, 0);

@@ -78,6 +78,44 @@ def test_full_size_parity(case, oracle, H):
     torch.cuda.empty_cache()
 
 
+# Rows split over workgroups with a reduction over the rows to follow (the mean of the per-row
+# losses): one stage of two launches -- the kernel that folds the rows' partials also folds the
+# rows.  Many rows: a thread of that kernel per row; few, long rows: a wavefront per row.  Rows
+# that hold NaN or infinities take the element-by-element rules inside the streaming kernel.
+@pytest.mark.parametrize("rows,vocab,opts,per_thread", [
+    (600, 40000, {"split_rows": 1}, True), (512, 131072, {}, True), (3, 1 << 20, {}, False), (37, 1003, {"split_rows": 1}, True),
+    (70, 300000, {}, False),
+])
+def test_split_rows_fold_the_mean_in_the_finish_kernel(rows, vocab, opts, per_thread, oracle, H):
+    import gc
+    import torch
+    w = wl.c3_softmax_xent(rows=rows, vocab=vocab)
+    x = w.buffers[0]
+    inf = np.float32(np.inf)
+    if rows >= 37:
+        x[1, 5] = -inf; x[1, vocab - 3] = -inf
+        x[2, :] = -inf
+        x[3, 0] = -inf; x[3, 1] = 2.0
+        x[4, 77] = inf
+        x[5, vocab // 2] = np.nan; x[5, vocab // 2 + 9] = np.nan
+        x[6, :] = 1.5
+        x[7, vocab - 1] = 80.0
+        x[8, 3] = 50.0; x[8, vocab - 2] = 50.0          # the maximum twice: the first index counts
+    print(f"[case] split xent rows={rows} vocab={vocab} {opts}", flush=True)
+    expr, got = H.run_gpu(w, **opts)
+    info = expr.info()
+    assert info["kernel_class"] == "multi" and info["grid_blocks"] == 1, info
+    src = expr.source(0)
+    assert "totx = AccX_combine()(totx, ax);" in src
+    assert ("group = threadIdx.x" in src) == per_thread
+    want = oracle.evaluate(w.spec, wl.host_inputs(w), w.scalars, nthreads=16)
+    for name, g, o, (rtol, atol) in zip(w.out_names, got, want, w.tol):
+        H.compare(f"{name}", g, o, rtol, atol)
+    del w, expr, got
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
 # Tuning options change how a kernel is generated and launched, never what it computes: every
 # workload under every option still has to match the oracle.
 OPTION_SETS = [
