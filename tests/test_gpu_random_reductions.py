@@ -191,3 +191,78 @@ def test_random_column_plans_with_few_or_odd_columns(seed, oracle):
     if len(axes) == 1:
         s.output(s.reduce("argmax", xi, axes), "i32"); tols.append((0, 0))
     _check(G, oracle, f"narrow columns seed{seed} {storage} shape{shape} axes{axes}", s, [x], tols)
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_row_reductions_followed_by_reductions_over_the_rows(seed, oracle):
+    """Per-row sums, extremes, arg-max and log-sum-exp, then a sum / maximum / minimum of those
+    over the rows: rows held by a workgroup, several rows per wavefront, rows split over
+    workgroups with the second reduction folded by the finish kernel (a thread or a wavefront per
+    row), with NaN and infinities in some inputs."""
+    import tests.test_gpu_ops_and_layouts as T
+    G = _ctx()
+    rng = np.random.default_rng(515000 + seed)
+    mode = seed % 4
+    if mode == 0: rows, cols = int(rng.choice([1, 3, 17, 100])), int(rng.choice([40000, 70001, 200000]))
+    elif mode == 1: rows, cols = int(rng.choice([300, 600, 1500])), int(rng.choice([9000, 20000, 33000]))
+    elif mode == 2: rows, cols = int(rng.choice([5, 64, 700])), int(rng.choice([7, 100, 1003, 4096]))
+    else: rows, cols = int(rng.choice([2000, 9000])), int(rng.choice([600, 2048]))
+    storage = "f16" if rng.integers(0, 4) == 0 else "f32"
+    x = (rng.standard_normal((rows, cols)) * 2).astype(np.float16 if storage == "f16" else np.float32)
+    if rng.integers(0, 3) == 0 and rows > 2:
+        x[int(rng.integers(rows)), int(rng.integers(cols))] = np.nan
+        x[int(rng.integers(rows)), int(rng.integers(cols))] = -np.inf
+    s = GraphSpec(2)
+    xi = s.input(storage, (False, False))
+    affine = bool(rng.integers(0, 2))
+    f = s.add(s.mul(xi, s.const(0.5)), s.const(0.25)) if affine else xi
+    fx = x.astype(np.float64) * 0.5 + 0.25 if affine else x.astype(np.float64)
+    per_row, tols = [], []
+    kinds = rng.choice(["sum", "max", "argmax", "lse", "min", "sumsq"], size=int(rng.integers(1, 4)), replace=False).tolist()
+    for k in kinds:
+        if k == "sum":
+            v = s.reduce("sum", f, (1,)); per_row.append((v, (0,), len(tols))); s.output(v, "f32")
+            mag = np.abs(fx).sum(axis=1)
+            tols.append((1e-5, 1e-6, np.where(np.isfinite(mag), mag, 0.0)))
+        elif k in ("max", "min"):
+            v = s.reduce(k, f, (1,)); per_row.append((v, (0,), len(tols))); s.output(v, "f32"); tols.append((2e-6, 1e-6))
+        elif k == "argmax":
+            v = s.reduce("argmax", f, (1,)); per_row.append((s.cast(v, "f32"), (0,), len(tols))); s.output(v, "i32"); tols.append((0, 0))
+        elif k == "sumsq":
+            v = s.reduce("sum", s.mul(f, f), (1,)); per_row.append((v, (0,), len(tols))); s.output(v, "f32"); tols.append((1e-5, 1e-6))
+        else:
+            m = s.reduce("max", f, (1,), keep=True)
+            lse = s.add(m, s.apply("log", s.reduce("sum", s.apply("exp", s.sub(f, m)), (1,), keep=True)))
+            per_row.append((lse, (0, 1), len(tols))); s.output(lse, "f32"); tols.append((1e-5, 1e-6))
+    for _ in range(int(rng.integers(1, 3))):
+        v, axes, src = per_row[int(rng.integers(len(per_row)))]
+        op = ["sum", "max", "min"][int(rng.integers(3))]
+        r = s.reduce(op, v, axes)
+        div = float(rows) if rng.integers(0, 2) else 1.0
+        if div != 1.0:
+            r = s.div(r, s.const(div))
+        s.output(r, "f32")
+        # the bar for reductions; a sum over the rows relative to the sum of the magnitudes of the
+        # per-row values (each of which carries its own rounding error)
+        tols.append((1e-5, 1e-6, ("rows", src, div)) if op == "sum" else (1e-5, 1e-6))
+    opts = [{}, {}, {"split_rows": 1}, {"split_rows": 2}][int(rng.integers(4))]
+    tag = f"seed={seed} rows={rows} cols={cols} {storage} kinds={kinds} opts={opts}"
+    print(f"[case] {tag}", flush=True)
+    try:
+        expr, got = T.run_spec(G, s, [x], **opts)
+    except G.ewf.EwfError as e:
+        assert e.status == G.ewf.EUNSUPPORTED, e         # an option that does not fit is refused, never run wrongly
+        expr, got = T.run_spec(G, s, [x])
+    want = oracle.evaluate(s, [x], nthreads=8)
+    for k, (g_, w_, tol) in enumerate(zip(got, want, tols)):
+        if tol[:2] == (0, 0):
+            assert np.array_equal(g_, w_), f"{tag} output {k}"
+            continue
+        scale = tol[2] if len(tol) > 2 else None
+        if isinstance(scale, tuple):
+            terms = np.abs(want[scale[1]].astype(np.float64))
+            total = np.where(np.isfinite(terms), terms, 0.0).sum() / scale[2]
+            scale = np.maximum(total, np.abs(np.where(np.isfinite(w_), w_, 0.0)))
+        elif scale is not None:
+            scale = np.maximum(scale, np.abs(np.where(np.isfinite(w_), w_, 0.0))).reshape(w_.shape)
+        G.h.compare(f"{tag}.out{k}", g_, w_, tol[0], tol[1], scale=scale)
