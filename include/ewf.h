@@ -96,7 +96,10 @@ typedef struct {
                                output is stored as float16, else 1 -- except for values that
                                reach the outputs only as terms of a float32 sum, which use 2
                                (worst-case relative error of a term under 6e-6, inside the 1e-5
-                               bar of reduction outputs)                                      */
+                               bar of reduction outputs), and for sigmoid and tanh, which use 2
+                               wherever they do not feed a product, an extreme value or an
+                               arg-max (bounded results: relative error under 1.5e-6, absolute
+                               under 1.2e-7, inside the 2e-6 / 1e-6 bar of element-wise outputs) */
     int32_t force_scalar;   /* 1: never use vector (multi-element) memory accesses           */
     int32_t force_index64;  /* 1: 64-bit offset arithmetic even when 32 bits suffice         */
     int32_t block_threads;  /* 0 = library default                                           */
@@ -109,7 +112,8 @@ typedef struct {
     int32_t waves_per_simd; /* register budget hint: resident wavefronts per SIMD to aim for
                                (1..8); 0 = compiler default                                   */
     int32_t no_prefetch;    /* the next trip's loads ahead of the current trip's arithmetic:
-                               0 automatic, 1 never, 2 always                                 */
+                               0 automatic, 1 never (nor a nearly empty last trip taken along
+                               with the trip before it), 2 always                              */
     int32_t xcd_remap;      /* 1: neighbouring tiles go to the same accelerator die, whose L2
                                they then share (default 0: workgroup w takes tile w, which
                                measured faster on streaming workloads)                       */
@@ -122,10 +126,12 @@ typedef struct {
                                level that is rescaled as the maximum grows).  0 automatic: split
                                when a row does not fit the registers or the rows are too few to
                                occupy the chip; 1 always split; 2 never                       */
-    int32_t plain_extremes; /* 1: a row's maximum and arg-max are always folded with the rules that
-                               rank NaN (default 0: rows held in registers take the hardware
-                               maximum first, find the index afterwards, and fall back on those
-                               rules only for rows that hold a NaN or an infinity)             */
+    int32_t plain_extremes; /* 1: maxima, arg-maxima and sums of shifted exponentials are always
+                               folded element by element with the rules that rank NaN (default
+                               0: rows held in registers take the hardware maximum first and find
+                               the index afterwards, streaming kernels fold a vector of finite
+                               values at once; both fall back on those rules only for rows or
+                               vectors that hold a NaN or an infinity)                         */
     int32_t reserved[1];
 } ewf_options;
 
