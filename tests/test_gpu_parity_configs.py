@@ -84,7 +84,7 @@ def test_full_size_parity(case, oracle, H):
 # that hold NaN or infinities take the element-by-element rules inside the streaming kernel.
 @pytest.mark.parametrize("rows,vocab,opts,per_thread", [
     (600, 40000, {"split_rows": 1}, True), (512, 131072, {}, True), (3, 1 << 20, {}, False), (37, 1003, {"split_rows": 1}, True),
-    (70, 300000, {}, False),
+    (70, 300000, {}, False), (600, 40000, {"split_rows": 1, "plain_extremes": 1}, True),
 ])
 def test_split_rows_fold_the_mean_in_the_finish_kernel(rows, vocab, opts, per_thread, oracle, H):
     import gc
@@ -108,6 +108,7 @@ def test_split_rows_fold_the_mean_in_the_finish_kernel(rows, vocab, opts, per_th
     src = expr.source(0)
     assert "totx = AccX_combine()(totx, ax);" in src
     assert ("group = threadIdx.x" in src) == per_thread
+    assert ("__builtin_fmaxf(vm_, xs" in src) == (not opts.get("plain_extremes"))
     want = oracle.evaluate(w.spec, wl.host_inputs(w), w.scalars, nthreads=16)
     for name, g, o, (rtol, atol) in zip(w.out_names, got, want, w.tol):
         H.compare(f"{name}", g, o, rtol, atol)
@@ -122,7 +123,7 @@ OPTION_SETS = [
     {"force_scalar": 1}, {"force_index64": 1}, {"no_lds_staging": 1}, {"no_prefetch": 1}, {"no_prefetch": 2},
     {"xcd_remap": 1}, {"streaming": 1}, {"streaming": 2}, {"unroll": 1}, {"unroll": 4}, {"block_threads": 64},
     {"block_threads": 1024}, {"tile_elems": 1024}, {"waves_per_simd": 2}, {"max_blocks": 3}, {"no_rewrite": 1},
-    {"split_rows": 1}, {"split_rows": 2},
+    {"split_rows": 1}, {"split_rows": 2}, {"plain_extremes": 1}, {"split_rows": 1, "plain_extremes": 1},
 ]
 OPTION_CASES = ["c1_ragged", "c2_ragged", "c3_ragged", "c4_ragged", "c4_small", "c5a_small", "c5b_ragged_c", "c2b_ragged",
                 "c3b_ragged", "c4b_ragged", "bn_ragged"]
