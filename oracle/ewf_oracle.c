@@ -167,7 +167,6 @@ static int analyse(orc_ctx *c)
         case K_REDUCE: {
             if (nd->nargs != 1) return ORC_EINVAL;
             if (nd->axes == 0 || (nd->axes & ~all)) return ORC_EINVAL;
-            if (nd->op == R_ARGMAX && (nd->axes & (nd->axes - 1))) return ORC_EINVAL; /* one axis */
             c->vtype[n] = (nd->op == R_ARGMAX) ? T_INT : c->vtype[nd->args[0]];
             c->vbc[n] = c->vbc[nd->args[0]] | nd->axes;
             break;
@@ -406,9 +405,11 @@ static int materialise_reduce(orc_ctx *c, int n, int nthreads)
                 if (r == 0) acc = v;
                 else if (!isnan(acc) && (isnan(v) || v < acc)) acc = v;
                 break;
-            case R_ARGMAX:                      /* first occurrence of the maximum */
+            case R_ARGMAX:                      /* first occurrence of the maximum: its position in the
+                                                   row-major order of the reduced axes (r walks them in
+                                                   that order; with one axis it is the coordinate) */
                 if (r == 0) { acc = v; best = 0; }
-                else if (!isnan(acc) && (isnan(v) || v > acc)) { acc = v; best = coord[rd[0]]; }
+                else if (!isnan(acc) && (isnan(v) || v > acc)) { acc = v; best = r; }
                 break;
             }
         }

@@ -737,3 +737,40 @@ def test_multi_axis_reductions_without_keep_have_the_rank_of_the_kept_axes(oracl
     # axis 0: dropped by a, kept (as extent 1) by c, constant in the sum -> stays dropped
     assert ac.shape == (3, 4) and np.array_equal(ac, (Y64.sum((0, 2), keepdims=True) + Y64.sum(0, keepdims=True))[0])
     assert ax.shape == (2, 3, 4) and np.array_equal(ax, Y64.sum((0, 2), keepdims=True) + Y64)
+
+
+# Arg-max over several axes: the position of the first maximum in the row-major order of the
+# reduced axes, in axis order (what numpy gives after moving those axes last and flattening them).
+@pytest.mark.parametrize("axes", [(0, 1), (1, 2), (0, 2), (0, 1, 2), (2,), (0, 3), (1, 2, 3)])
+@pytest.mark.parametrize("keep", [False, True])
+def test_argmax_over_several_axes_vs_numpy(oracle, axes, keep):
+    rng = np.random.default_rng(77 + sum(axes))
+    shape = (3, 4, 5, 2)
+    x = rng.integers(-3, 4, shape).astype(np.float32)          # few distinct values: many ties
+    x[1, 2, 3, 0] = np.nan
+    x[2, 0, 0, 1] = np.nan
+    s = GraphSpec(4)
+    xi = s.input("f32", (False,) * 4)
+    s.output(s.reduce("argmax", xi, axes, keep=keep), "i32")
+    s.output(s.reduce("max", xi, axes, keep=keep), "f32")
+    got, mx = oracle.evaluate(s, [x])
+    kept = [d for d in range(4) if d not in axes]
+    moved = np.transpose(x, kept + list(axes)).reshape([shape[d] for d in kept] + [-1])
+    want = np.argmax(moved, axis=-1)                            # numpy: first occurrence, NaN counts as the maximum
+    if keep:
+        want = want.reshape([1 if d in axes else shape[d] for d in range(4)])
+    assert got.shape == want.shape and np.array_equal(got, want)
+    # and the value found there is the maximum
+    flat_max = np.take_along_axis(moved, np.argmax(moved, axis=-1)[..., None], axis=-1)[..., 0]
+    assert np.array_equal(mx.reshape(flat_max.shape), flat_max, equal_nan=True)
+
+
+def test_argmax_over_two_axes_by_hand(oracle):
+    x = np.array([[[1, 9], [9, 2]], [[3, 3], [3, 3]]], np.float32)      # [2, 2, 2]
+    s = GraphSpec(3)
+    xi = s.input("f32", (False,) * 3)
+    s.output(s.reduce("argmax", xi, (1, 2)), "i32")         # per leading index: positions in a 2 x 2 block
+    s.output(s.reduce("argmax", xi, (0, 2)), "i32")         # per middle index: positions in [2 (axis 0), 2 (axis 2)]
+    a12, a02 = oracle.evaluate(s, [x])
+    assert a12.tolist() == [1, 0]                           # 9 first at (0, 1) -> 1; all equal -> 0
+    assert a02.tolist() == [1, 0]                           # middle 0: values 1 9 3 3 -> 1; middle 1: 9 2 3 3 -> 0
