@@ -79,8 +79,9 @@ typedef enum {
     EWF_LT, EWF_LE, EWF_EQ, EWF_NE, EWF_EXPM1, EWF_SQR, EWF_RECIP, EWF_OP_COUNT
 } ewf_op;
 
-/* Reductions.  EWF_ARGMAX takes exactly one axis and returns the int32 index of the first
- * occurrence of the maximum along it. */
+/* Reductions.  EWF_RARGMAX returns the int32 index of the first occurrence of the maximum (a NaN
+ * ranks above every number): along one axis the coordinate, over several axes the position in
+ * their row-major order, taken in axis order (fewer than 2^31 positions). */
 typedef enum { EWF_RSUM = 0, EWF_RMAX, EWF_RMIN, EWF_RPROD, EWF_RARGMAX } ewf_redop;
 
 typedef int32_t ewf_value;

@@ -130,6 +130,14 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
     uint32_t unit = 0;
     bool empty = false;
     for (int d = 0; d < e.g.ndim; d++) { if (full[d] == 1) unit |= 1u << d; if (full[d] == 0) empty = true; }
+    // an arg-max is an int32 position among the elements it ranks
+    for (const Node &nd : e.g.nodes) {
+        if (nd.kind != NodeKind::Reduce || nd.op != EWF_RARGMAX) continue;
+        int64_t positions = 1;
+        for (int d = 0; d < e.g.ndim; d++)
+            if ((nd.axes >> d & 1u) && !(e.g.nodes[nd.args[0]].bcast >> d & 1u)) positions *= std::max<int64_t>(full[d], 1);
+        if (positions > 2147483647) { set_error("arg-max over %lld positions does not fit its int32 result", (long long)positions); return EWF_ESHAPE; }
+    }
     plan->red = analyse_reductions(e.g, unit);
     st = canonicalize(e, plan->red, in, nin, out, nout, true, plan->canon, full, &plan->raw);
     if (st != EWF_OK) return st;

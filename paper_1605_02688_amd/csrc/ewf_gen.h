@@ -585,11 +585,36 @@ struct Gen {
         return false;
     }
 
+    // The canonical dimension of an arg-max axis; with several axes, of the first one that
+    // has more than one element (-1 when there is none).
     int argmax_canon_dim(int node) const
     {
         const Node &nd = g.nodes[node];
-        for (int d = 0; d < g.ndim; d++) if (nd.axes & (1u << d)) return c.orig_of_axis[d];
+        for (int d = 0; d < g.ndim; d++) if ((nd.axes & (1u << d)) && c.orig_of_axis[d] >= 0) return c.orig_of_axis[d];
         return -1;
+    }
+    // Number of arg-max axes with more than one element.
+    int argmax_rank(int node) const
+    {
+        const Node &nd = g.nodes[node];
+        int r = 0;
+        for (int d = 0; d < g.ndim; d++) if ((nd.axes & (1u << d)) && c.orig_of_axis[d] >= 0) r++;
+        return r;
+    }
+    // The index an arg-max returns for the element whose canonical coordinates `coord` names:
+    // its position in the row-major order of the reduced axes, in axis order (one axis: the
+    // coordinate itself).  An arg-max axis is never merged with a neighbour, so each has a
+    // canonical dimension of its own whose extent is a kernel argument.
+    std::string argmax_index(int node, const std::function<std::string(int)> &coord) const
+    {
+        const Node &nd = g.nodes[node];
+        std::string s;
+        for (int d = 0; d < g.ndim; d++) {
+            if (!(nd.axes & (1u << d)) || c.orig_of_axis[d] < 0) continue;
+            const std::string x = "(int)(" + coord(c.orig_of_axis[d]) + ")";
+            s = s.empty() ? x : "(" + s + ") * (int)p.ext[" + std::to_string(c.orig_of_axis[d]) + "] + " + x;
+        }
+        return s.empty() ? std::string("0") : s;
     }
 
     // ---- common pieces ------------------------------------------------------------------
@@ -885,10 +910,8 @@ struct Gen {
             o << ind << "ax.a" << i << " = v" << nd.args[0] << ";\n";
             if (nd.op == kRSumExpShifted) o << ind << "ax.b" << i << " = 1.0f;\n";
             if (nd.op == kRSumSqCentred) o << ind << "ax.n" << i << " = 1.0f;\n" << ind << "ax.b" << i << " = 0.0f;\n";
-            if (nd.op == EWF_RARGMAX) {
-                int cd = argmax_canon_dim(red.cross_nodes[i]);
-                o << ind << "ax.i" << i << " = (int)(" << (cd < 0 ? std::string("0") : "o" + std::to_string(cd)) << ");\n";
-            }
+            if (nd.op == EWF_RARGMAX)
+                o << ind << "ax.i" << i << " = " << argmax_index(red.cross_nodes[i], [](int d) { return "o" + std::to_string(d); }) << ";\n";
         }
         o << ind << sink << "\n";
     }

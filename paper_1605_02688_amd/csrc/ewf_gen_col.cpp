@@ -286,7 +286,7 @@ ewf_status Gen::gen_col()
         for (int k : ew_out_ops) o << in2 << "    ewf_vec<" << ctype(c.ops[k].storage) << ", EWF_VEC> y_" << opname(k) << ";\n";
         o << in2 << "    _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
         emit_values(need, cx, in2 + "        ");
-        emit_accumulate("acc[e_]", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, in2 + "        ");
+        emit_accumulate("acc[e_]", level, [&](int node) { return argmax_index(node, cx.coord); }, in2 + "        ");
         for (int k : ew_out_ops) {
             const Operand &op = c.ops[k];
             const char *cv = op.storage == EWF_F16 ? "ewf_out_f16" : op.storage == EWF_I32 ? "ewf_out_i32" : "ewf_out_f32";

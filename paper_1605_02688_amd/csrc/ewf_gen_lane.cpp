@@ -189,7 +189,7 @@ ewf_status Gen::gen_lane()
         o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
         emit_values(need, cx, "                ");
         // a lane walks its columns in increasing order
-        emit_accumulate(av, lvl[l], [&](int node) { return cx.coord(argmax_canon_dim(node)); }, "                ", true);
+        emit_accumulate(av, lvl[l], [&](int node) { return argmax_index(node, cx.coord); }, "                ", true);
         o << "            }\n        }\n";
         emit_first_index(av, lvl[l], "lr * EWF_VEC < " + std::to_string(cols), "lr * EWF_VEC", "        ");
         // the lanes of a row fold with a fixed butterfly; afterwards each holds the row's result

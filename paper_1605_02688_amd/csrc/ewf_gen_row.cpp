@@ -309,7 +309,7 @@ ewf_status Gen::gen_row()
                 o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
                 if (ragged) o << "                if (u >= " << NFULL << " && col + e_ >= cols) continue;\n";
                 emit_values(need, cx, "                ");
-                emit_accumulate(av, fastn[l], [&](int node) { return cx.coord(argmax_canon_dim(node)); }, "                ", true);
+                emit_accumulate(av, fastn[l], [&](int node) { return argmax_index(node, cx.coord); }, "                ", true);
                 o << "            }\n";
                 close_pass();
                 emit_first_index(av, fastn[l], "(idx_t)tid * EWF_VEC < cols", "tid * EWF_VEC", "        ");
@@ -337,7 +337,7 @@ ewf_status Gen::gen_row()
         o << "            _Pragma(\"unroll\") for (int e_ = 0; e_ < EWF_VEC; ++e_) {\n";
         if (ragged) o << "                if (u >= " << NFULL << " && col + e_ >= cols) continue;\n";
         emit_values(need, cx, "                ");
-        emit_accumulate(av, lvl[l], [&](int node) { return cx.coord(argmax_canon_dim(node)); }, "                ", true);
+        emit_accumulate(av, lvl[l], [&](int node) { return argmax_index(node, cx.coord); }, "                ", true);
         o << "            }\n";
         close_pass();
         // every thread walks its columns in increasing order, starting at tid * EWF_VEC

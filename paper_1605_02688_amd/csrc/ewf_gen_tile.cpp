@@ -339,7 +339,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     // tile extends along the arg-max axis only, that is increasing order of the arg-max index.
     bool ascending = with_reduce && tiled.size() <= 1;
     for (int n : level)
-        if (g.nodes[n].op == EWF_RARGMAX && !tiled.empty() && argmax_canon_dim(n) != tiled[0]) ascending = false;
+        if (g.nodes[n].op == EWF_RARGMAX && ((!tiled.empty() && argmax_canon_dim(n) != tiled[0]) || argmax_rank(n) > 1)) ascending = false;
     std::vector<char> need = needed(targets);
     std::vector<int> used_inputs = inputs_of(need);
 
@@ -604,7 +604,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         if (ragged) o << ind << "        if (e_ >= it.nv[u]) continue;\n";
         emit_values(need, cx, ind + "        ");
         if (with_reduce)
-            emit_accumulate("acc", level, [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "        ", ascending, &eslots);
+            emit_accumulate("acc", level, [&](int node) { return argmax_index(node, cx.coord); }, ind + "        ", ascending, &eslots);
         for (int a : vargs) o << ind << "        xs" << a << "_[e_] = v" << a << ";\n";
         for (int k : ew_out_ops) {
             const Operand &op = c.ops[k];
@@ -615,7 +615,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         o << ind << "    }\n";
         for (int a : vargs)
             emit_vector_accumulate("acc", level, vslots, a, "xs" + std::to_string(a) + "_", ragged ? "it.nv[u] == EWF_VEC" : "",
-                                   ragged ? "e_ >= it.nv[u]" : "", [&](int node) { return cx.coord(argmax_canon_dim(node)); }, ind + "    ");
+                                   ragged ? "e_ >= it.nv[u]" : "", [&](int node) { return argmax_index(node, cx.coord); }, ind + "    ");
         for (int k : ew_out_ops) {
             const Operand &op = c.ops[k];
             std::string nm = opname(k);

@@ -87,10 +87,6 @@ static ewf_status infer_node(Graph &g, int n)
             set_error("reduce node %d: bad axes", n);
             return EWF_EINVAL;
         }
-        if (nd.op == EWF_RARGMAX && (nd.axes & (nd.axes - 1))) {
-            set_error("argmax takes exactly one axis");
-            return EWF_EINVAL;
-        }
         nd.vtype = (nd.op == EWF_RARGMAX) ? EWF_I32 : arg(0).vtype;
         nd.bcast = arg(0).bcast | nd.axes;
         nd.dropped = (arg(0).dropped | (nd.keep ? 0u : nd.axes)) & nd.bcast;

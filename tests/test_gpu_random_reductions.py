@@ -266,3 +266,68 @@ def test_random_row_reductions_followed_by_reductions_over_the_rows(seed, oracle
         elif scale is not None:
             scale = np.maximum(scale, np.abs(np.where(np.isfinite(w_), w_, 0.0))).reshape(w_.shape)
         G.h.compare(f"{tag}.out{k}", g_, w_, tol[0], tol[1], scale=scale)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_argmax_over_several_axes(seed, oracle):
+    """The position of the first maximum in the row-major order of any set of reduced axes, on
+    contiguous, permuted and sliced inputs of every storage type, with many ties, NaN and
+    infinities; exact."""
+    import tests.test_gpu_ops_and_layouts as T
+    G = _ctx()
+    rng = np.random.default_rng(880000 + seed)
+    nd = int(rng.integers(2, 5))
+    shape = [int(rng.choice([1, 2, 3, 5, 8, 17, 64])) for _ in range(nd)]
+    if seed % 2:
+        shape[int(rng.integers(nd))] = int(rng.choice([257, 1000, 4099, 20000]))
+    while np.prod(shape) > 4e6:
+        shape[int(np.argmax(shape))] //= 2
+    storage = ["f32", "f16", "i32"][seed % 3]
+    dt = {"f32": np.float32, "f16": np.float16, "i32": np.int32}[storage]
+    x = rng.integers(-4, 5, shape).astype(dt)
+    if storage != "i32" and rng.integers(0, 2) and x.size > 4:
+        flat = x.reshape(-1)
+        flat[int(rng.integers(x.size))] = np.nan
+        flat[int(rng.integers(x.size))] = np.inf
+    style = int(rng.integers(0, 3))
+    if style == 1:
+        perm = rng.permutation(nd)
+        x = np.ascontiguousarray(x.transpose(perm)).transpose(np.argsort(perm))
+    elif style == 2:
+        big = np.zeros([e + 2 for e in shape], dt)
+        inner = tuple(slice(1, 1 + e) for e in shape)
+        big[inner] = x
+        x = big[inner]
+    axes = tuple(sorted(rng.choice(nd, size=int(rng.integers(1, nd + 1)), replace=False).tolist()))
+    keep = bool(rng.integers(0, 2))
+    s = GraphSpec(nd)
+    xi = s.input(storage, (False,) * nd)
+    s.output(s.reduce("argmax", xi, axes, keep=keep), "i32")
+    s.output(s.reduce("max", xi, axes, keep=keep), "i32" if storage == "i32" else "f32")
+    opts = [{}, {}, {}, {"force_scalar": 1}, {"block_threads": 64}, {"tile_elems": 512}, {"max_blocks": 5}, {"plain_extremes": 1}][int(rng.integers(8))]
+    print(f"[case] seed={seed} shape={shape} {storage} style={style} axes={axes} keep={keep} opts={opts}", flush=True)
+    expr, got = T.run_spec(G, s, [x], **opts)
+    want = oracle.evaluate(s, [x], nthreads=8)
+    assert np.array_equal(got[0], want[0]), (expr.info()["kernel_class"], np.argwhere(got[0] != want[0])[:3].tolist())
+    assert np.array_equal(got[1], want[1], equal_nan=True)
+
+
+@pytest.mark.parametrize("shape,axes", [((8, 700, 3000), (1, 2)), ((700, 8, 3000), (0, 2)), ((3000, 700, 8), (0, 1)), ((40, 50, 60, 70), (0, 1, 2, 3))])
+def test_argmax_over_several_axes_of_large_tensors(shape, axes, oracle):
+    """Groups that span many tiles: the partial results carry flattened positions and are folded
+    by value, then by position."""
+    import tests.test_gpu_ops_and_layouts as T
+    G = _ctx()
+    rng = np.random.default_rng(4242)
+    x = rng.integers(-50, 51, shape).astype(np.float32)
+    s = GraphSpec(len(shape))
+    xi = s.input("f32", (False,) * len(shape))
+    s.output(s.reduce("argmax", xi, axes), "i32")
+    s.output(s.reduce("max", xi, axes), "f32")
+    print(f"[case] argmax shape={shape} axes={axes}", flush=True)
+    expr, got = T.run_spec(G, s, [x])
+    kept = [d for d in range(len(shape)) if d not in axes]
+    moved = np.transpose(x, kept + list(axes)).reshape([shape[d] for d in kept] + [-1])
+    want = oracle.evaluate(s, [x], nthreads=16)
+    assert np.array_equal(want[0], np.argmax(moved, axis=-1).astype(np.int32))       # the oracle against numpy, at this size too
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])

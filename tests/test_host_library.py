@@ -94,8 +94,8 @@ def test_type_rules():
     ewf.graph_destroy(g)
     g = ewf.graph_create(2)
     x = ewf.input(g, ewf.F32, [0, 0])
-    with pytest.raises(ewf.EwfError):
-        ewf.reduce(g, ewf.REDOPS["argmax"], x, [0, 1], False)      # argmax: one axis
+    am = ewf.reduce(g, ewf.REDOPS["argmax"], x, [0, 1], False)    # arg-max over several axes: an int32 position
+    assert am >= 0
     with pytest.raises(ewf.EwfError) as e:
         ewf.compile(g)                                            # no output declared
     assert e.value.status == ewf.EINVAL
@@ -292,6 +292,18 @@ def test_long_or_few_rows_are_split_over_workgroups():
     e = ewf.Expression(s, split_rows=1)
     e.plan([ref(BASE, (1000, 4096))], [ref(BASE + (1 << 30), (1000,))])
     assert e.info()["kernel_class"] == "tile_reduce"
+
+
+def test_argmax_positions_must_fit_int32():
+    s = GraphSpec(2)
+    s.output(s.reduce("argmax", s.input("f16", (False, False)), (0, 1)), "i32")
+    e = ewf.Expression(s)
+    with pytest.raises(ewf.EwfError) as err:
+        e.plan([ref(BASE, (70000, 40000))], [ref(BASE + (1 << 40), ())])
+    assert err.value.status == ewf.ESHAPE and "int32" in err.value.message
+    e.plan([ref(BASE, (7000, 40000))], [ref(BASE + (1 << 40), ())])          # 2.8e8 positions: fine
+    src = e.source() or e.source(0)
+    assert "p.ext[" in src and "i0" in src
 
 
 def test_chains_that_passes_cannot_shorten_stay_with_the_row_class():
