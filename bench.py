@@ -165,6 +165,40 @@ def copy_ceiling(nbytes, steps, warmup, identity=True):
     return res
 
 
+def copy_same_bytes_us(total_bytes, launches=60):
+    """Microseconds per launch of the library's copy kernel moving `total_bytes` (half read, half
+    written), back to back over rotating buffer sets like the workloads: what plain streaming
+    costs at this size, where a launch's ramp-up and drain (about 2.6 us) no longer vanish."""
+    import torch
+    from paper_1605_02688_amd import ewf
+    half = max(4096, int(total_bytes) // 2 // 4096 * 4096)
+    nsets = max(1, int(700e6 // (2 * half)) + 1) if half < 300e6 else 1
+    src = [torch.empty(half // 4, dtype=torch.float32, device="cuda").fill_(1.0) for _ in range(nsets)]
+    dst = [torch.empty(half // 4, dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    st = torch.cuda.current_stream().cuda_stream
+    best = float("inf")
+    for _ in range(3):
+        for i in range(10):
+            ewf.copy_bytes(dst[i % nsets].data_ptr(), src[i % nsets].data_ptr(), half, st)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(launches):
+            ewf.copy_bytes(dst[i % nsets].data_ptr(), src[i % nsets].data_ptr(), half, st)
+        torch.cuda.synchronize()
+        best = min(best, (time.perf_counter() - t0) / launches)
+    del src, dst
+    torch.cuda.empty_cache()
+    return best * 1e6 * (total_bytes / (2.0 * half))
+
+
+def _with_copy_reference(res, total_bytes):
+    """Adds the copy kernel's time on the same number of bytes and the share of it a step takes."""
+    us = copy_same_bytes_us(total_bytes)
+    res["copy_same_bytes_us"] = round(us, 2)
+    res["pct_of_copy_same_bytes"] = round(100 * us / res["us_per_step"], 1)
+    return res
+
+
 def _identity_rate(src, dst, n, steps, warmup):
     import torch
     from paper_1605_02688_amd import ewf
@@ -403,9 +437,9 @@ def main():
             if name in ("c1", "c3"):
                 # the same launches (one per buffer set) replayed from a captured HIP graph
                 res["graph_replay_us_per_step"] = round(case.graph_replay_us(), 2)
-            per_config[name] = res
             del case
             torch.cuda.empty_cache()
+            per_config[name] = _with_copy_reference(res, wk.algorithmic_bytes)
         out["per_config"] = per_config
         # the same C1 / C2 kernels on 64 times the rows, and the C3 expression on rows of 131072
         # logits (rows split over workgroups): supplementary bandwidth points, not among the five
@@ -425,6 +459,7 @@ def main():
                             "pct_of_peak": round(100 * wk.algorithmic_bytes / (us_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 1)}
             del case
             torch.cuda.empty_cache()
+            _with_copy_reference(scaled[name], wk.algorithmic_bytes)
         out["scaled"] = scaled
         # backward passes (kernels generated from the library's own differentiation of the forward
         # descriptions): supplementary, not among the five headline workloads
@@ -443,6 +478,7 @@ def main():
                               "pct_of_peak": round(100 * wk.algorithmic_bytes / (us_step * 1e-6) / 1e9 / PEAK_HBM_GBPS, 1)}
             del case
             torch.cuda.empty_cache()
+            _with_copy_reference(backward[name], wk.algorithmic_bytes)
         out["backward"] = backward
 
     if not args.no_cpu:
