@@ -146,6 +146,20 @@ struct Gen {
             if (live[n] && nd.kind == NodeKind::Reduce && real_reduce(n) && !(nd.op == EWF_RSUM && nd.vtype == EWF_F32) &&
                 nd.op != kRSumExpShifted) direct[nd.args[0]] = strict[nd.args[0]] = 1;
         }
+        // (likewise what a comparison or a conversion to an integer reads: the outcome is discrete.
+        // A plan in several kernels evaluates such a value in more than one of them -- the
+        // elements equal to a maximum that an earlier kernel folded -- and they must agree to the
+        // last bit, so all of them take the accurate routines.)
+        for (int n = 0; n < N; n++) {
+            const Node &nd = g.nodes[n];
+            if (!live[n] || nd.vtype != EWF_I32) continue;
+            const bool cmp = nd.kind == NodeKind::Apply && (nd.op == EWF_GT || nd.op == EWF_GE || nd.op == EWF_LT || nd.op == EWF_LE ||
+                                                            nd.op == EWF_EQ || nd.op == EWF_NE);
+            const bool to_int = nd.kind == NodeKind::Cast && nd.op == EWF_I32;
+            if (!cmp && !to_int) continue;
+            for (int a = 0; a < nd.nargs; a++)
+                if (g.nodes[nd.args[a]].vtype == EWF_F32) direct[nd.args[a]] = strict[nd.args[a]] = 1;
+        }
         for (int n = N - 1; n >= 0; n--) {
             if (!direct[n]) continue;
             const Node &nd = g.nodes[n];

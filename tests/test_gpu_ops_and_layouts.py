@@ -646,6 +646,36 @@ def test_gradient_through_a_sum_reaches_operands_constant_along_it(oracle, G):
     G.h.compare("db", got[2], want[2], 1e-5, 1e-6)
 
 
+@pytest.mark.parametrize("shape,ops", [((64, 3000), ("tanh", "sigmoid")), ((64, 7), ("sigmoid", "exp")), ((5, 3000), ("tanh", "log"))])
+def test_gradient_of_a_maximum_finds_its_element_in_every_kernel(shape, ops, oracle, G):
+    # The cotangent of max goes to the elements equal to it.  A plan in two kernels folds the maximum
+    # in the first and compares every element with it in the second: both must evaluate the
+    # expression with the same routines, to the last bit, or the comparison finds nothing.
+    rng = np.random.default_rng(2049)
+    R, C = shape
+    a = rng.uniform(0.5, 1.5, (R, C)).astype(np.float32); b = rng.uniform(0.5, 1.5, (1, C)).astype(np.float32)
+    cot = rng.standard_normal((R, 1)).astype(np.float32)
+    s = GraphSpec(2)
+    ai = s.input("f32", (False, False)); bi = s.input("f32", (True, False)); ci = s.input("f32", (False, True))
+    v = s.add(s.apply(ops[0], s.mul(ai, bi)), s.apply(ops[1], ai))
+    red = s.reduce("max", s.mul(v, s.const(0.5)), (1,), keep=True)
+    ga, gb = s.grad([red], [ci], [ai, bi])
+    s.output(ga, "f32"); s.output(gb, "f32")
+    print(f"[case] gradient of a row maximum {shape} {ops}", flush=True)
+    for opts in ({}, {"split_rows": 1}, {"tile_elems": 1024}):
+        try:
+            expr, got = run_spec(G, s, [a, b, cot], **opts)
+        except G.ewf.EwfError as e:
+            assert e.status == G.ewf.EUNSUPPORTED
+            continue
+        want = oracle.evaluate(G.ewf.export_spec(s), [a, b, cot])
+        hit = want[0] != 0                                  # one element per row (no ties in this data)
+        assert hit.sum() == R and (got[0] != 0).sum() == R, (opts, expr.info()["kernel_class"], int((got[0] != 0).sum()))
+        assert np.array_equal(got[0] != 0, hit)
+        G.h.compare("da", got[0], want[0], 1e-5, 1e-6)
+        G.h.compare("db", got[1], want[1], 1e-5, 1e-6, scale=np.abs(want[0].astype(np.float64)).sum(0, keepdims=True) * 2 + 1e-3)
+
+
 def test_argmax_ties_take_the_first_index(oracle, G):
     x = np.zeros((70, 5000), np.float32)
     x[:, 4000] = 3.0; x[:, 123] = 3.0; x[5, 7] = 3.0
