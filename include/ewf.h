@@ -98,9 +98,10 @@ typedef struct {
                                reach the outputs only as terms of a float32 sum, which use 2
                                (worst-case relative error of a term under 6e-6, inside the 1e-5
                                bar of reduction outputs), and for sigmoid and tanh, which use 2
-                               wherever they do not feed a product, an extreme value or an
-                               arg-max (bounded results: relative error under 1.5e-6, absolute
-                               under 1.2e-7, inside the 2e-6 / 1e-6 bar of element-wise outputs) */
+                               wherever they do not feed a product, an extreme value, an
+                               arg-max, a comparison or a conversion to an integer (bounded
+                               results: relative error under 1.5e-6, absolute under 1.2e-7,
+                               inside the 2e-6 / 1e-6 bar of element-wise outputs)             */
     int32_t force_scalar;   /* 1: never use vector (multi-element) memory accesses           */
     int32_t force_index64;  /* 1: 64-bit offset arithmetic even when 32 bits suffice         */
     int32_t block_threads;  /* 0 = library default                                           */
