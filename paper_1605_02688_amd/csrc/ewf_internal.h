@@ -234,6 +234,9 @@ struct Exec {
     // reduces an index, say): the whole expression's extents, for the axes its own inputs leave open.
     bool has_forced_full = false;
     int64_t forced_full[kMaxDims] = {0};
+    // Inputs (by index) that a later stage of the same plan reads again: while such a tensor fits
+    // the memory-side cache it is loaded with ordinary accesses so that it is still there.
+    std::vector<char> read_again;
     Graph g;
     ewf_options opts{};
     int math_flavour = 1;                // 1 accurate, 2 native rate with fix-ups, 3 native rate

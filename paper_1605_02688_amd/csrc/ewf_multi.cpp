@@ -318,6 +318,31 @@ ewf_status plan_multi(Exec &e, const Graph &g, bool strict_rows, const ewf_tenso
         }
         if (round == 15) { set_error("too many reduction levels"); return EWF_EUNSUPPORTED; }
     }
+    // A caller's input that a later stage reads again: the earlier stage is planned once more
+    // knowing that (its loads of that tensor then leave it in the memory-side cache, see the
+    // streaming hint of the canonical layout).
+    for (size_t i = 0; i + 1 < plan.stages.size(); i++) {
+        Stage &sg = plan.stages[i];
+        std::vector<char> again(sg.in_src.size(), 0);
+        bool any = false;
+        for (size_t a = 0; a < sg.in_src.size(); a++) {
+            if (sg.in_src[a] < 0) continue;
+            for (size_t j = i + 1; j < plan.stages.size(); j++)
+                if (std::find(plan.stages[j].in_src.begin(), plan.stages[j].in_src.end(), sg.in_src[a]) != plan.stages[j].in_src.end()) again[a] = 1;
+            any = any || again[a];
+        }
+        if (!any || e.opts.streaming != 0) continue;
+        sg.exec->read_again = again;
+        sg.exec->plans.clear();
+        sg.exec->last = nullptr;
+        if (try_stage(sg) != EWF_OK) {
+            sg.exec->read_again.clear();
+            sg.exec->plans.clear();
+            sg.exec->last = nullptr;
+            st = try_stage(sg);
+            if (st != EWF_OK) return st;
+        }
+    }
     for (Stage &sg : plan.stages) {
         sg.ws_offset = ws;
         ws = align_up(ws + sg.ws_bytes);

@@ -294,6 +294,23 @@ def test_long_or_few_rows_are_split_over_workgroups():
     assert e.info()["kernel_class"] == "tile_reduce"
 
 
+def test_an_input_that_a_later_stage_reads_again_is_left_in_the_cache():
+    # batch normalisation over axis 0: statistics in one kernel, the normalised tensor in a second.
+    # While X fits the memory-side cache the first kernel loads it with ordinary accesses; the
+    # second one, its last reader, streams it; a tensor beyond the cache is streamed by both.
+    def sources(rows, **opts):
+        e, _, info = plan_workload(wl.layout_only(wl.batch_norm_axis0, rows=rows, cols=1024), **opts)
+        assert info["kernel_class"] == "multi" and info["grid_blocks"] == 2
+        return e.source(0), e.source(1)
+    first, second = sources(32768)                       # 134 MB
+    assert "ewf_ld<float, EWF_VEC>" in first and "ewf_ld_nt<float, EWF_VEC>" not in first
+    assert "ewf_ld_nt<float, EWF_VEC>" in second and "ewf_st_nt<float, EWF_VEC>" in second
+    first, second = sources(65536)                       # 268 MB: more than the cache holds
+    assert "ewf_ld_nt<float, EWF_VEC>" in first and "ewf_ld_nt<float, EWF_VEC>" in second
+    first, _ = sources(32768, streaming=1)               # the caller's choice stands
+    assert "ewf_ld_nt<float, EWF_VEC>" in first
+
+
 def test_argmax_positions_must_fit_int32():
     s = GraphSpec(2)
     s.output(s.reduce("argmax", s.input("f16", (False, False)), (0, 1)), "i32")
