@@ -334,13 +334,16 @@ ewf_status canonicalize(const Exec &e, const ReduceInfo &red, const ewf_tensor *
         op.stream = op.access == Access::Vector && once &&
                     (e.opts.streaming == 1 ||
                      (e.opts.streaming == 0 && (footprint >= ((int64_t)32 << 20) || (moved_once >= ((int64_t)64 << 20) && footprint >= ((int64_t)4 << 20)))));
-        // ... unless a later stage of the plan reads the tensor again and it fits the 256 MB
-        // memory-side cache with room to spare: a non-temporal load would not leave it there
-        // (batch normalisation over axis 0, statistics then the normalised tensor: float16
-        // [65536, 1024] 86.8 -> 76.6 us, float32 [32768, 1024] 75.9 -> 68.1 us; float32 [65536, 1024],
-        // 268 MB, 138 us either way and 150 us with ordinary loads throughout)
+        // ... unless a later stage of the plan reads the tensor again: a non-temporal load would not
+        // leave it in the 256 MB memory-side cache.  Ordinary loads are slower in a kernel that only
+        // reads (a sum over 268 MB: 47.6 against 44.9 us), but what the later stage then finds
+        // cached outweighs that, also for tensors larger than the cache, of which a part survives
+        // (batch normalisation over axis 0, statistics then the normalised tensor, rotating
+        // buffers: float16 [65536, 1024] 87.3 -> 83.6 us, float32 [32768, 1024] 77.9 -> 72.1 us,
+        // [65536, 1024] (268 MB) 138.4 -> 132.3 us, [131072, 1024] 269.0 -> 255.8 us, [262144, 1024]
+        // (1.07 GB) 534.1 -> 526.9 us; not tried beyond)
         const size_t k_ = (size_t)(&op - c.ops.data());
-        if (e.opts.streaming == 0 && !op.is_output && k_ < e.read_again.size() && e.read_again[k_] && footprint <= ((int64_t)192 << 20))
+        if (e.opts.streaming == 0 && !op.is_output && k_ < e.read_again.size() && e.read_again[k_] && footprint <= ((int64_t)1 << 30))
             op.stream = false;
     }
     return EWF_OK;

@@ -234,8 +234,8 @@ struct Exec {
     // reduces an index, say): the whole expression's extents, for the axes its own inputs leave open.
     bool has_forced_full = false;
     int64_t forced_full[kMaxDims] = {0};
-    // Inputs (by index) that a later stage of the same plan reads again: while such a tensor fits
-    // the memory-side cache it is loaded with ordinary accesses so that it is still there.
+    // Inputs (by index) that a later stage of the same plan reads again: such a tensor is loaded
+    // with ordinary accesses so that the memory-side cache still holds it, or part of it.
     std::vector<char> read_again;
     Graph g;
     ewf_options opts{};

@@ -3,6 +3,8 @@ device array inside the library, nothing is compiled, loaded or allocated by the
 through the C ABI against ewf_run with a caller's workspace and against the CPU oracle: two calls
 in a row per workload, the second on a smaller input, so that the second call finds the array as
 the first one left it."""
+import gc
+
 import numpy as np
 import pytest
 
@@ -64,9 +66,12 @@ def test_static_workspace_matches_caller_workspace(case, oracle):
         # ewf_run with a caller's workspace full of NaN patterns: nothing needs clearing
         ws = torch.full(((nbytes + 3) // 4,), -1, dtype=torch.int32, device="cuda") if nbytes else None
         expr.run(ins, ref, w.scalars, ws, stream)
-        before = torch.cuda.memory_allocated()
+        # (the allocator's count of allocations made so far: frees of earlier tests' tensors,
+        # whenever the collector gets to them, do not move it)
+        gc.collect()
+        before = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
         expr.run_static(ins, got, w.scalars, stream)
-        assert torch.cuda.memory_allocated() == before
+        assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == before
         torch.cuda.synchronize()
         want = oracle.evaluate(w.oracle_spec or w.spec, wl.host_inputs(w), w.scalars, nthreads=4)
         for name, g, r, o, (rtol, atol) in zip(w.out_names, got, ref, want, w.tol):
