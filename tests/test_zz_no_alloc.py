@@ -37,6 +37,7 @@ CASES = {
     "c3": (lambda: wl.c3_softmax_xent(rows=600, vocab=5000), lambda: wl.c3_softmax_xent(rows=520, vocab=1000), "row"),
     "c4b": (lambda: wl.c4_bias_relu_chansum_backward(n=8, c=16, h=28, w=28), lambda: wl.c4_bias_relu_chansum_backward(n=2, c=8, h=14, w=14), "tile_reduce"),
     "c3_long_rows": (lambda: wl.c3_softmax_xent(rows=9, vocab=150001), lambda: wl.c3_softmax_xent(rows=5, vocab=70001), "multi"),
+    "c3_many_long_rows": (lambda: wl.c3_softmax_xent(rows=640, vocab=100000), lambda: wl.c3_softmax_xent(rows=600, vocab=70001), "multi"),
     "batch_norm": (lambda: _batch_norm(300, 70), lambda: _batch_norm(120, 30), "multi"),
     "c1_no_workspace": (lambda: wl.c1_affine_tanh(rows=64, cols=256), lambda: wl.c1_affine_tanh(rows=16, cols=64), "tile"),
 }
