@@ -389,7 +389,13 @@ ewf_status Gen::gen_tile(bool with_reduce)
     for (int d = 0; d < R; d++) if (c.reduced[d]) nslots_host *= ntile[d];
     const bool cross_per_thread = has_cross && nslots_host <= 32;
     if (with_reduce && !one_tile) o << "    Acc *const partials = (Acc *)p.ws_partials;\n";
-    if (one_tile || cross_per_thread) o << "    __shared__ Acc sm_one[EWF_NWAVES];\n";
+    // A kernel that also streams element-wise outputs takes one trip per tile and ends right after
+    // it: folding its wavefronts through LDS first costs a wait for the slowest of them and leaves
+    // the finish kernel a quarter of the partials (bias + ReLU + channel sums on float32
+    // [128,64,112,112]: 133.3 -> 131.5 us a step, [128,256,56,56] 131.5 -> 130.4, [32,64,112,112]
+    // 36.8 -> 36.0; its backward pass and pure reductions the same within 0.3 %).
+    const bool wg_partials = with_reduce && !one_tile && !cross_per_thread && !ew_out_ops.empty() && TE <= step && block > 64;
+    if (one_tile || cross_per_thread || wg_partials) o << "    __shared__ Acc sm_one[EWF_NWAVES];\n";
     for (int k : staged)
         o << "    __shared__ __attribute__((aligned(16))) " << ctype(c.ops[k].storage) << " lds_" << opname(k) << "[" << lds_elems << "];\n";
     // tiles are numbered in canonical (memory) order so that the workgroups resident at any
@@ -723,6 +729,9 @@ ewf_status Gen::gen_tile(bool with_reduce)
         } else if (cross_per_thread) {
             o << ind << "acc = ewf_block_reduce<EWF_NWAVES>(acc, Acc_combine(), sm_one, tid);\n";
             o << ind << "if (tid == 0) partials[(size_t)slot * (size_t)p.nrows + (size_t)group] = acc;\n";
+        } else if (wg_partials) {
+            o << ind << "acc = ewf_block_reduce<EWF_NWAVES>(acc, Acc_combine(), sm_one, tid);\n";
+            o << ind << "if (tid == 0) partials[(size_t)group * (size_t)p.nslots + (size_t)slot] = acc;\n";
         } else {
             o << ind << "acc = ewf_wave_reduce(acc, Acc_combine());\n";
             o << ind << "if ((tid & 63) == 0) partials[((size_t)group * (size_t)p.nslots + (size_t)slot) * EWF_NWAVES + (tid >> 6)] = acc;\n";
@@ -732,7 +741,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
 
     if (with_reduce && !one_tile) {
         // one workgroup per group: a wavefront when a group has few partials, four otherwise
-        int64_t nparts_host = (int64_t)(block / 64);
+        int64_t nparts_host = wg_partials ? 1 : (int64_t)(block / 64);
         for (int d = 0; d < R; d++) if (c.reduced[d]) nparts_host *= ntile[d];
         // (1024 threads and eight partials in flight per thread when there are thousands: a total
         // over a large tensor is one group, and its finish is otherwise a chain of dependent loads)
@@ -746,7 +755,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
             fin_block_out = emit_finish_all(level, group_out_ops, final_out_ops, cross_per_thread ? "p.nslots" : "p.nslots * EWF_NWAVES", ngroups_,
                                             gathers, cross_per_thread);
         }
-        else emit_finish_lanes(level, group_out_ops, "p.nslots * EWF_NWAVES", fin_block, inflight, gathers);
+        else emit_finish_lanes(level, group_out_ops, wg_partials ? "p.nslots" : "p.nslots * EWF_NWAVES", fin_block, inflight, gathers);
     }
 
     // ---- launch geometry and argument block
@@ -761,7 +770,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
     p.finish_grid = 0;
     if (with_reduce && !one_tile) {
         if (ngroups >= ((int64_t)1 << 31) || nslots >= ((int64_t)1 << 31)) return fail("too many reduction groups");
-        p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(cross_per_thread ? 1 : block / 64) * acc_bytes(level);
+        p.workspace_bytes = (size_t)ngroups * (size_t)nslots * (size_t)(cross_per_thread || wg_partials ? 1 : block / 64) * acc_bytes(level);
         p.finish_grid = has_cross ? 1 : std::min<int64_t>(ngroups, (int64_t)1 << 20);
         p.finish_block = fin_block_out;
     }

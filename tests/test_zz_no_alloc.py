@@ -86,7 +86,7 @@ def test_static_workspace_refuses_what_does_not_fit():
     from paper_1605_02688_amd import ewf
     from paper_1605_02688_amd.selfcheck import plan_layout
     # planned on made-up addresses: the call must fail before anything is launched
-    w = wl.layout_only(wl.c4_bias_relu_chansum, n=1024)
+    w = wl.layout_only(wl.c4_bias_relu_chansum_backward, n=1216)
     expr = ewf.Expression(w.spec)
     nbytes, _ = plan_layout(expr, w.spec, w.views, [w.buffers[v.buffer].itemsize for v in w.views])
     assert nbytes > ewf.STATIC_WORKSPACE_BYTES
