@@ -113,6 +113,37 @@ def test_tanh_and_sigmoid_accurate_mode_whole_range(oracle, G):
     G.h.compare("sigmoid specials", gs[:k], ws[:k], 4e-7, 1.2e-38)
 
 
+def test_tanh_and_sigmoid_automatic_mode_whole_range(oracle, G):
+    # under the automatic math mode float32 results take the native-rate sigmoid and tanh: held to
+    # the element-wise bar over the whole range, dense around the switch to the series of tanh
+    # (|x| = 2^-5) and where the exponential's argument is large, alone and as factors of a product
+    rng = np.random.default_rng(79)
+    x = np.concatenate([rng.uniform(-1, 1, 200000), rng.uniform(-20, 20, 100000), np.linspace(-0.3, 0.3, 60001),
+                        np.linspace(0.03, 0.0325, 20001), -np.linspace(0.03, 0.0325, 20001),
+                        rng.uniform(-100, 100, 20000), rng.uniform(-1e-4, 1e-4, 2000)]).astype(np.float32)
+    sp = np.float32([0.0, -0.0, np.inf, -np.inf, np.nan, 1e30, -1e30, 15.0, -15.0, 88.0, -88.0, 89.0, -104.0, 1e-30, -1e-38])
+    x = np.concatenate([sp, x])
+    y = rng.uniform(-3, 3, x.shape).astype(np.float32)
+    s = GraphSpec(1)
+    xi = s.input("f32", (False,)); yi = s.input("f32", (False,))
+    t = s.apply("tanh", xi); g = s.apply("sigmoid", xi)
+    s.output(t, "f32"); s.output(g, "f32")
+    s.output(s.add(s.mul(g, yi), s.mul(s.apply("sigmoid", yi), t)), "f32")        # f * c + i * g of an LSTM cell
+    expr, (gt, gs, gc) = run_spec(G, s, [x, y])
+    assert "ewf_fast::tanh" in expr.source() and "ewf_fast::sigmoid" in expr.source()
+    wt, ws, wc = oracle.evaluate(s, [x, y])
+    assert gt[2] == 1 and gt[3] == -1 and np.isnan(gt[4]) and gs[2] == 1 and gs[3] == 0 and np.isnan(gs[4])
+    G.h.compare("tanh", gt, wt, 2e-6, 1e-6)
+    G.h.compare("sigmoid", gs, ws, 2e-6, 1e-6)
+    terms = np.nan_to_num(np.abs(ws.astype(np.float64) * y) + np.abs(wt.astype(np.float64)), nan=0.0, posinf=0.0)
+    G.h.compare("cell", gc, wc, 2e-6, 1e-6, scale=np.maximum(terms, np.abs(np.where(np.isfinite(wc), wc, 0.0))))
+    # the relative error alone, away from the flush to zero of tiny sigmoids: under 1.5e-6 as stated
+    fin = np.isfinite(wt) & (wt != 0)
+    assert np.max(np.abs(gt[fin].astype(np.float64) - wt[fin]) / np.abs(wt[fin])) < 1.5e-6
+    big = np.isfinite(ws) & (ws > 1e-30)
+    assert np.max(np.abs(gs[big].astype(np.float64) - ws[big]) / ws[big]) < 1.5e-5     # exp of up to -69: |x| * 6e-8
+
+
 def test_log1p_keeps_small_arguments(oracle, G):
     x = np.float32([1e-7, -1e-7, 3e-10, 1e-5, -1e-5])
     s = GraphSpec(1)
