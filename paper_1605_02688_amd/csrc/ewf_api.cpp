@@ -223,7 +223,7 @@ ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *o
 
 static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
 {
-    ewf_status st;
+    ewf_status st = EWF_OK;
     const Canon &c = plan->canon;
     bool row_only = false;                     // only the row class covers the expression
     bool cross_only = false;                   // ... and only because of reductions over the rows
