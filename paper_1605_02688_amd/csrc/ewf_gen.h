@@ -599,6 +599,33 @@ struct Gen {
         return false;
     }
 
+    // x / d for 0 <= x < n, d a literal that is not a power of two: the compiler's own
+    // multiply-high runs at a quarter of the rate of the 24-bit multiply, and inside a tile every
+    // index is small.  (x * m) >> s with m = ceil(2^s / d) is exact as long as x * (m * d - 2^s) <
+    // 2^s; the smallest s for which that holds for all x < n with the product below 2^32 and both
+    // factors below 2^24 is taken (none: the plain division).  The workgroups of the float16
+    // stress workload's NCHW reading spent an eighth of their vector cycles on such divisions.
+    std::string div_small(const std::string &x, int64_t d, int64_t n) const
+    {
+        if (d <= 1) return x;
+        if ((d & (d - 1)) == 0) { int sh = 0; while (((int64_t)1 << sh) < d) sh++; return "(" + x + " >> " + std::to_string(sh) + ")"; }
+        if (n <= (int64_t)1 << 24)
+            for (int sft = 1; sft < 32; sft++) {
+                const int64_t m = (((int64_t)1 << sft) + d - 1) / d;
+                if (m >= ((int64_t)1 << 24) || (n - 1) * m >= ((int64_t)1 << 32)) continue;
+                if ((n - 1) * (m * d - ((int64_t)1 << sft)) < ((int64_t)1 << sft))
+                    return "(int)(ewf_mul24(" + x + ", " + std::to_string(m) + ") >> " + std::to_string(sft) + ")";
+            }
+        return "(" + x + " / " + std::to_string(d) + ")";
+    }
+    // Statements that split `var` (below n) into `rem` = var % d and var /= d.
+    std::string divmod_small(const std::string &rem, const std::string &var, int64_t d, int64_t n) const
+    {
+        if ((d & (d - 1)) == 0 || d >= ((int64_t)1 << 24))
+            return rem + " = " + var + " % " + std::to_string(d) + "; " + var + " /= " + std::to_string(d) + ";";
+        return "{ const int q_ = " + div_small(var, d, n) + "; " + rem + " = " + var + " - (int)ewf_mul24(q_, " + std::to_string(d) + "); " + var + " = q_; }";
+    }
+
     // The canonical dimension of an arg-max axis; with several axes, of the first one that
     // has more than one element (-1 when there is none).
     int argmax_canon_dim(int node) const
