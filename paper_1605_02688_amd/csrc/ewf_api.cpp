@@ -81,6 +81,7 @@ struct KernelTiming {
 };
 
 static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full);
+constexpr int kMaxKernelArgBytes = 4096;           // what the hardware's kernel-argument segment holds
 
 ewf_status make_plan(Exec &e, const ewf_tensor *in, int nin, const ewf_tensor *out, int nout, Plan **result, bool lookup_only)
 {
@@ -352,6 +353,11 @@ static ewf_status single_kernel_plan(Exec &e, Plan *plan, const int64_t *full)
         else if (row_only) { plan->kclass = KernelClass::Row; set_error_str(why); }
     }
     if (st != EWF_OK) return st;
+    if (plan->args.size() > kMaxKernelArgBytes) {
+        set_error("unsupported: the kernel's argument block would take %zu bytes (at most %d): too many operands or dimensions for one kernel",
+                  plan->args.size(), kMaxKernelArgBytes);
+        return EWF_EUNSUPPORTED;
+    }
     bool cached = false;
     st = compile_source(plan->source, plan->code, &cached);
     if (st != EWF_OK) return st;
@@ -597,11 +603,11 @@ ewf_status run_exec(Exec &x, const ewf_tensor *in, int32_t nin, const double *sc
     }
 
     // patch pointers and scalars into a copy of the prepared argument block
-    uint8_t stack_args[1024];
-    std::vector<uint8_t> heap_args;
-    uint8_t *args = stack_args;
-    if (p->args.size() > sizeof stack_args) { heap_args = p->args; args = heap_args.data(); }
-    else memcpy(args, p->args.data(), p->args.size());
+    // (a kernel takes at most 4 KiB of arguments: layouts beyond that are refused when planned,
+    // so the copy always fits the stack and a launch allocates nothing)
+    uint8_t args[kMaxKernelArgBytes];
+    if (p->args.size() > sizeof args) { set_error("argument block of %zu bytes", p->args.size()); return EWF_EUNSUPPORTED; }
+    memcpy(args, p->args.data(), p->args.size());
     const ParamLayout &L = p->layout;
     size_t f = 0;
     for (int k = 0; k < nin; k++, f++) memcpy(args + L.offsets[f], &in[k].ptr, 8);
