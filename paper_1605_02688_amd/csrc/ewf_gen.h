@@ -604,7 +604,7 @@ struct Gen {
     // index is small.  (x * m) >> s with m = ceil(2^s / d) is exact as long as x * (m * d - 2^s) <
     // 2^s; the smallest s for which that holds for all x < n with the product below 2^32 and both
     // factors below 2^24 is taken (none: the plain division).  The workgroups of the float16
-    // stress workload's NCHW reading spent an eighth of their vector cycles on such divisions.
+    // stress workload's reading "B" spent an eighth of their vector cycles on such divisions.
     std::string div_small(const std::string &x, int64_t d, int64_t n) const
     {
         if (d <= 1) return x;

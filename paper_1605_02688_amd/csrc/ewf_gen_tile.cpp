@@ -223,7 +223,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
             block = 768;
             // ... unless that leaves a nearly empty last trip: eight wavefronts have the registers
             // to take such a trip's items along with the trip before (below), twelve have not
-            // (NCHW reading of the stress workload, 49 wavefronts of items per tile: 768 threads
+            // (reading "B" of the float16 stress workload, 49 wavefronts of items per tile: 768 threads
             // 91.7-93.0 us, 512 threads with the two last trips in one 89.7-90.0 us)
             auto last_fill = [&](int64_t b) { const int64_t s_ = b * VEC * U, n_ = ceil_div(te, s_); return (double)(te - (n_ - 1) * s_) / (double)s_; };
             if (e.opts.no_prefetch != 1 && last_fill(768) <= 0.25 && last_fill(512) <= 0.25) block = 512;
@@ -246,7 +246,7 @@ ewf_status Gen::gen_tile(bool with_reduce)
         // order, the 64 lanes of a wavefront may differ only along dimensions that are slow in the
         // LDS copy, and their scattered writes then fall into a few banks whatever the padding
         // (every lane writes the same position of the copy's fastest dimension: 82 % of the LDS's
-        // active cycles were bank conflicts on the float16 stress workload's NHWC reading).  So
+        // active cycles were bank conflicts on reading "B" of the float16 stress workload).  So
         // a wavefront takes an 8 x 8 patch: eight neighbouring pieces in memory order (128
         // contiguous bytes where a run of the operand's fastest dimension holds eight) at each of
         // eight neighbouring indices of the copy's fastest dimension.  The pieces are numbered
