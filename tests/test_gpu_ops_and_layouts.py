@@ -704,7 +704,7 @@ def test_gradient_of_a_maximum_finds_its_element_in_every_kernel(shape, ops, ora
         assert hit.sum() == R and (got[0] != 0).sum() == R, (opts, expr.info()["kernel_class"], int((got[0] != 0).sum()))
         assert np.array_equal(got[0] != 0, hit)
         G.h.compare("da", got[0], want[0], 1e-5, 1e-6)
-        G.h.compare("db", got[1], want[1], 1e-5, 1e-6, scale=np.abs(want[0].astype(np.float64)).sum(0, keepdims=True) * 2 + 1e-3)
+        G.h.compare("db", got[1], want[1], 1e-5, 1e-6)          # a column sums the few rows whose maximum lies in it
 
 
 def test_argmax_ties_take_the_first_index(oracle, G):
