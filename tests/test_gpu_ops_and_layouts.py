@@ -144,6 +144,26 @@ def test_tanh_and_sigmoid_automatic_mode_whole_range(oracle, G):
     assert np.max(np.abs(gs[big].astype(np.float64) - ws[big]) / ws[big]) < 1.5e-5     # exp of up to -69: |x| * 6e-8
 
 
+def test_run_time_scalars_of_both_types(oracle, G):
+    rng = np.random.default_rng(81)
+    x = rng.standard_normal((37, 1003)).astype(np.float32)
+    k = rng.integers(-100, 100, (37, 1003)).astype(np.int32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False)); ki = s.input("i32", (False, False))
+    a = s.scalar("f32"); n = s.scalar("i32")
+    s.output(s.mul(xi, a), "f32")
+    s.output(s.add(ki, n), "i32")
+    s.output(s.mul(s.cast(n, "f32"), xi), "f32")
+    s.output(s.reduce("sum", s.apply("where", s.apply("gt", ki, n), xi, s.const(0.0)), (1,)), "f32")
+    for scal in ([0.1, 7.9], [-2.5, -7.9], [16777217.0, 0.0]):
+        expr, got = run_spec(G, s, [x, k], scal)
+        want = oracle.evaluate(s, [x, k], scal)
+        G.h.compare("x*a", got[0], want[0], 2e-6, 1e-6)
+        assert np.array_equal(got[1], want[1])
+        G.h.compare("n*x", got[2], want[2], 2e-6, 1e-6)
+        G.h.compare("sum", got[3], want[3], 1e-5, 1e-6, scale=np.abs(x.astype(np.float64)).sum(1))
+
+
 def test_log1p_keeps_small_arguments(oracle, G):
     x = np.float32([1e-7, -1e-7, 3e-10, 1e-5, -1e-5])
     s = GraphSpec(1)

@@ -774,3 +774,25 @@ def test_argmax_over_two_axes_by_hand(oracle):
     a12, a02 = oracle.evaluate(s, [x])
     assert a12.tolist() == [1, 0]                           # 9 first at (0, 1) -> 1; all equal -> 0
     assert a02.tolist() == [1, 0]                           # middle 0: values 1 9 3 3 -> 1; middle 1: 9 2 3 3 -> 0
+
+
+def test_run_time_scalars_have_their_declared_type(oracle):
+    # a float32 scalar is rounded to float32 before use, an int32 scalar is truncated toward zero
+    x = np.array([[1.0, 2.0, 4.0]], np.float32)
+    k = np.array([[3, -3, 10]], np.int32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False)); ki = s.input("i32", (False, False))
+    a = s.scalar("f32"); n = s.scalar("i32")
+    s.output(s.mul(xi, a), "f32")
+    s.output(s.add(ki, n), "i32")
+    s.output(s.mul(s.cast(n, "f32"), xi), "f32")
+    s.output(s.add(s.mul(xi, s.const(0.0)), s.sub(a, s.const(16777216.0))), "f32")
+    got = oracle.evaluate(s, [x, k], [0.1, 7.9])
+    assert np.array_equal(got[0], (x.astype(np.float64) * np.float64(np.float32(0.1))).astype(np.float32))
+    assert got[1].tolist() == [[10, 4, 17]]
+    assert got[2].tolist() == [[7.0, 14.0, 28.0]]
+    got = oracle.evaluate(s, [x, k], [-2.5, -7.9])
+    assert got[0].tolist() == [[-2.5, -5.0, -10.0]] and got[1].tolist() == [[-4, -10, 3]] and got[2].tolist() == [[-7.0, -14.0, -28.0]]
+    # 2^24 + 1 is not a float32: the scalar is 2^24 by the time it is used
+    got = oracle.evaluate(s, [x, k], [16777217.0, 0.0])
+    assert got[3].tolist() == [[0.0, 0.0, 0.0]]
