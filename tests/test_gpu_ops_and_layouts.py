@@ -260,6 +260,52 @@ def test_native_rate_math_meets_the_f16_bar(oracle, G):
             G.h.compare(f"mode{mode}.out{k}", g_, w_, 2e-3, 1e-3)
 
 
+def test_every_operation_folds_on_literals_like_it_evaluates(oracle, G):
+    # op(literal, literal) is folded on the host when an expression is compiled; the oracle
+    # evaluates it like any other node.  Every operation, float32 and int32, special values included.
+    x = np.linspace(-1, 1, 513).astype(np.float32)
+    k = np.arange(513, dtype=np.int32)
+    fl = [(0.75, 1.5), (-2.25, 0.5), (3.0, -1.25), (0.0, 2.0), (1e-3, 1e-3)]
+    unary = ["neg", "abs", "sqr", "exp", "tanh", "sigmoid", "recip", "expm1"]
+    positive = ["log", "log1p", "sqrt"]
+    binary = ["add", "sub", "mul", "div", "max", "min"]
+    compare = ["gt", "ge", "lt", "le", "eq", "ne"]
+    for a, b in fl:
+        s = GraphSpec(1)
+        xi = s.input("f32", (False,)); ki = s.input("i32", (False,))
+        zero = s.mul(xi, s.const(0.0))
+        izero = s.mul(ki, s.const(0, "i32"))
+        ca, cb = s.const(a), s.const(b)
+        vals = [s.apply(op, ca) for op in unary] + [s.apply(op, s.apply("abs", ca)) for op in positive]
+        vals += [s.apply(op, ca, cb) for op in binary] + [s.apply("pow", s.apply("abs", ca), cb)]
+        vals += [s.apply("where", s.apply(op, ca, cb), ca, cb) for op in compare]
+        total = zero
+        for v in vals:
+            total = s.add(total, v)
+        s.output(total, "f32")
+        for v in vals[:6]:
+            s.output(s.add(zero, v), "f32")
+        ia, ib = s.const(int(a * 4), "i32"), s.const(int(b * 4) - 7, "i32")
+        ivals = [s.apply(op, ia) for op in ("neg", "abs", "sqr")] + [s.apply(op, ia, ib) for op in ("add", "sub", "mul", "max", "min")]
+        ivals += [s.apply("where", s.apply(op, ia, ib), ia, ib) for op in compare]
+        ivals += [s.cast(s.mul(ca, s.const(3.7)), "i32"), s.mul(s.const(46341, "i32"), s.const(46341, "i32"))]
+        itotal = izero
+        for v in ivals:
+            itotal = s.add(itotal, v)
+        s.output(itotal, "i32")
+        s.output(s.add(zero, s.cast(s.cast(cb, "f16"), "f32")), "f32")
+        expr, got = run_spec(G, s, [x, k])
+        before, after = expr.graph_size()
+        assert after <= before - 30, (before, after)          # the operations on literals are gone (the sums of them stay)
+        want = oracle.evaluate(s, [x, k])
+        terms = len(vals)
+        G.h.compare(f"sum of folds {a},{b}", got[0], want[0], 2e-6 * terms, 1e-6 * terms)
+        for i in range(1, 7):
+            G.h.compare(f"fold {i} {a},{b}", got[i], want[i], 2e-6, 1e-6)
+        assert np.array_equal(got[7], want[7]), (a, b, got[7][:3], want[7][:3])
+        assert np.array_equal(got[8], want[8])
+
+
 def test_rewritten_graph_matches_the_graph_as_described(oracle, G):
     # the oracle evaluates the description node by node; the library first merges duplicates,
     # folds constants and applies the stabilising rewrites
