@@ -260,6 +260,30 @@ def test_native_rate_math_meets_the_f16_bar(oracle, G):
             G.h.compare(f"mode{mode}.out{k}", g_, w_, 2e-3, 1e-3)
 
 
+def test_run_time_scalars_reach_every_stage_of_a_plan(oracle, G):
+    # a temperature and an offset, used before and after the reductions of a plan in several kernels
+    rng = np.random.default_rng(82)
+    x = rng.standard_normal((40, 70001)).astype(np.float32)
+    s = GraphSpec(2)
+    xi = s.input("f32", (False, False))
+    t = s.scalar("f32"); off = s.scalar("f32"); n = s.scalar("i32")
+    z = s.mul(xi, t)
+    m = s.reduce("max", z, (1,), keep=True)
+    S = s.reduce("sum", s.apply("exp", s.sub(z, m)), (1,), keep=True)
+    lse = s.add(s.add(m, s.apply("log", S)), off)
+    s.output(lse, "f32")
+    s.output(s.div(s.apply("exp", s.sub(z, m)), S), "f32")                      # probabilities: a second sweep
+    s.output(s.mul(s.reduce("sum", lse, (0, 1)), s.cast(n, "f32")), "f32")     # over the rows, times an integer scalar
+    for scal in ([0.5, 3.0, 2.0], [2.0, -1.0, -3.0]):
+        expr, got = run_spec(G, s, [x], scal)
+        info = expr.info()
+        assert info["kernel_class"] == "multi" and info["grid_blocks"] >= 2, info
+        want = oracle.evaluate(s, [x], scal)
+        G.h.compare("lse", got[0], want[0], 1e-5, 1e-6)
+        G.h.compare("p", got[1], want[1], 1e-5, 1e-9)
+        G.h.compare("total", got[2], want[2], 1e-5, 1e-6, scale=np.abs(want[0].astype(np.float64)).sum() * abs(scal[2]))
+
+
 def test_every_operation_folds_on_literals_like_it_evaluates(oracle, G):
     # op(literal, literal) is folded on the host when an expression is compiled; the oracle
     # evaluates it like any other node.  Every operation, float32 and int32, special values included.
