@@ -58,6 +58,17 @@ ewf_status Gen::gen_row()
         std::vector<int> under = inputs_of(lneed);
         for (int k : row_ops) if (std::find(under.begin(), under.end(), k) == under.end()) late[k] = 1;
     }
+    // With such operands the last pass issues loads of its own next to the arithmetic, and more
+    // threads with fewer vectors each hide them better: two vectors of the row per thread (layer
+    // normalisation with scale and shift rows, 134 MB: float16 [4096, 16384] 256 threads 67.2 us,
+    // 1024 threads 55.5 us; [8192, 8192] 256 threads 59.5 us, 512 threads 54.4 us; float32
+    // [8192, 8192] 99.4 -> 93.0 us, [4096, 16384] 99.3 -> 91.1 us; softmax, which has none, runs
+    // best as it is).
+    if (e.opts.block_threads <= 0 && std::find(late.begin(), late.end(), (char)1) != late.end()) {
+        int want = 64;
+        while (want < 1024 && (int64_t)want * VEC * 2 < cols) want *= 2;
+        if (want > block) { block = want; p.block = block; }
+    }
     // ---- residency: keep the row in registers when it fits
     const int64_t per_iter = (int64_t)block * VEC;
     const int64_t NV = ceil_div(cols, per_iter);
