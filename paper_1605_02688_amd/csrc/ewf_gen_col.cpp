@@ -101,6 +101,11 @@ ewf_status Gen::gen_col()
         int narrowest = 4;
         for (const Operand &op : c.ops) if (!op.is_output && op.stride[in_d] != 0) narrowest = std::min(narrowest, isz(op.storage));
         if (e.opts.unroll <= 0 && ew_out_ops.empty() && !small && VEC * narrowest < 16) U = 8;
+        // (... and one whose accesses are 16 bytes wide a single one: as for a plain copy, one wide
+        // access per thread and more workgroup trips stream best.  Sums over axis 0, 268 MB: float32
+        // [65536, 1024] 45.6 -> 43.0 us, [16384, 4096] 46.2 -> 42.8 us, [262144, 256] 48.4 -> 45.0 us,
+        // float16 [131072, 1024] 49.5 -> 48.2 us; two in flight 43.4-46.9 us, three 46.9-55.2 us)
+        else if (e.opts.unroll <= 0 && ew_out_ops.empty() && !small && TZ == 1 && heavy < 4) U = 1;
     }
     // Outer-index lanes whose rows need fewer loads than that take further outer indices, UZ in
     // all, so that a thread still has U loads in flight: with one 16-byte load per thread and
