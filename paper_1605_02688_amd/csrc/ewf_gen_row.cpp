@@ -85,7 +85,12 @@ ewf_status Gen::gen_row()
         // (a chain that a plan in passes cannot shorten -- layer normalisation of float32
         // [4096, 16384] with its scale and shift rows: 96 registers of row data, 91 us here against
         // 185 us in three passes -- keeps the row class as long as the row fits at all)
-        const bool too_long = !resident || (regs > 48 && p.fused_depth <= 1);
+        // (without outputs that vary along the row, from 32 registers of 1024 threads on: softmax cross-entropy on
+        // float32 [1280, 32768] 40.0 us with 1024 threads a row -- two workgroups per compute unit,
+        // two and a half rounds of them -- against 35.6 us split; [3000, 32768] 84.1 against 78.1 us,
+        // [1280, 49152] 54.6 against 49.9 us, [20000, 32768] 450 against 411 us; [512, 40000] 22.1 against 23.3 us)
+        const bool too_long = !resident || (regs > 48 && p.fused_depth <= 1) ||
+                              (block == 1024 && regs >= 32 && p.fused_depth <= 1 && full_out_ops.empty());
         if (too_long || (nr * 2 < device_cu_count() && cols >= 16384) || e.opts.split_rows == 1) {
             p.row_refused = true;
             return fail(too_long ? "a row does not fit the registers of a workgroup well: the row class would read it once per reduction level or run one workgroup per compute unit"
